@@ -1,0 +1,168 @@
+/*
+ * moe.h -- C ABI of the MI355X (gfx950) Sparsely-Gated Mixture-of-Experts layer library.
+ *
+ * The layer (Section 2 of "Outrageously Large Neural Networks: The Sparsely-Gated
+ * Mixture-of-Experts Layer"):
+ *     y = sum_i G(x)_i E_i(x)                                   Eq.(1)
+ *     G(x) = Softmax(KeepTopK(H(x), k))                         Eq.(3),(5)
+ *     H(x)_i = (x W_g)_i + eps_i * Softplus((x W_noise)_i)      Eq.(4), eps ~ N(0,1) passed in
+ *     E_i(x) = relu(x W1_i) W2_i                                Appendix C (no biases)
+ *     L_importance = w_importance * CV(sum_x G(x))^2            Eq.(6),(7)
+ *     L_load = w_load * CV(sum_x P(x,.))^2,                     Eq.(8)-(11), Appendix A
+ *         P(x,i) = Phi((clean_i - kth_excluding(H,k,i)) / Softplus(raw_i))
+ *
+ * Conventions for every entry point
+ *  - extern "C"; returns 0 (MOE_OK) or a negative moe_status; no exception crosses the ABI.
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller, dense row-major, 16-byte
+ *    aligned, non-overlapping unless stated.  Outputs are fully overwritten.
+ *  - The library allocates nothing and never synchronises with the host: all work is
+ *    enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *  - Arguments are validated on the host before anything is launched; on error nothing runs.
+ *  - Index tensors are int32.  "bf16" tensors are uint16 bit patterns of bfloat16.
+ *  - Calls that share a workspace or an output on different streams race; distinct buffers
+ *    on distinct streams are safe.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum moe_status {
+    MOE_OK = 0,
+    MOE_EINVAL = -1,        /* null pointer, bad shape, k out of range, misaligned pointer */
+    MOE_EUNSUPPORTED = -2,  /* valid request outside what the kernels were built for */
+    MOE_EWORKSPACE = -3,    /* workspace smaller than moe_workspace_bytes() */
+    MOE_EHIP = -4           /* a HIP runtime call failed; see moe_last_hip_error() */
+} moe_status;
+
+enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
+
+/* Shape of one layer call.  Flat MoE: a = b = k_primary = k_secondary = 0.
+ * Hierarchical MoE (Appendix B): a groups of b experts, n = a*b, k = k_primary*k_secondary.
+ * Supported: d % 64 == 0, h % 128 == 0 for the bf16 experts; 1 <= k <= min(n, 8)
+ * (per level when hierarchical); n <= 16384, at most 2048 experts per gating level;
+ * T*k < 2^31. */
+typedef struct moe_config {
+    int32_t T;             /* tokens in the batch */
+    int32_t d;             /* model width: expert input and output size */
+    int32_t h;             /* expert hidden size */
+    int32_t n;             /* number of experts */
+    int32_t k;             /* experts per token */
+    int32_t a, b;          /* hierarchical: groups, experts per group */
+    int32_t k_primary, k_secondary;
+    int32_t expert_dtype;  /* MOE_DTYPE_F32 or MOE_DTYPE_BF16: storage type of W1, W2 */
+    float w_importance;    /* Eq.(7) */
+    float w_load;          /* Eq.(11) */
+} moe_config;
+
+int moe_version(void);
+const char *moe_strerror(int status);
+/* hipError_t (as int) of the most recent failing HIP call on this thread, 0 if none. */
+int moe_last_hip_error(void);
+
+/* ---- sizes the caller needs to allocate buffers ------------------------------------ */
+
+/* Rows of the per-block partial sums moe_gate writes: partials is float [rows][2][n]. */
+int64_t moe_gate_partial_rows(const moe_config *cfg);
+/* Bytes of scratch moe_route needs (chunk histograms). */
+size_t moe_route_workspace_bytes(const moe_config *cfg);
+/* Row-tile height of the expert kernel and the capacity of the tile table moe_route fills:
+ * tile_expert and tile_row0 must hold moe_max_tiles() int32 each. */
+int32_t moe_tile_rows(const moe_config *cfg);
+int64_t moe_max_tiles(const moe_config *cfg);
+/* Bytes of scratch moe_expert_ffn needs (fp32 experts keep the hidden layer there; 0 for bf16). */
+size_t moe_ffn_workspace_bytes(const moe_config *cfg);
+/* Bytes of scratch moe_aux_losses needs. */
+size_t moe_aux_workspace_bytes(const moe_config *cfg);
+/* Bytes of the single workspace of moe_layer_forward / moe_layer_forward_hier. */
+size_t moe_workspace_bytes(const moe_config *cfg);
+
+/* Where moe_layer_forward keeps its intermediates inside the workspace (byte offsets), so a
+ * caller can inspect them or hand them to moe_layer_backward. */
+typedef struct moe_workspace_layout {
+    size_t cleanb, sp, next_idx, partials, counts, offsets, perm, inv_perm, tile_expert,
+        tile_row0, num_tiles, route_ws, out_sorted, ffn_ws, aux_ws, total;
+    /* hierarchical only */
+    size_t p_cleanb, p_sp, p_next_idx, p_partials, p_idx, p_gate, p_counts, p_offsets, p_perm,
+        p_inv_perm, p_tile_group, p_tile_row0, p_num_tiles, s_idx, s_gate, s_load;
+} moe_workspace_layout;
+int moe_get_workspace_layout(const moe_config *cfg, moe_workspace_layout *out);
+
+/* ---- a1: noisy top-k gating, Eq.(3)-(5) -------------------------------------------- */
+/*
+ * x [T,d] f32; W_g, W_noise [d,n] f32; gate_bias [n] f32 or NULL (added to the clean logits;
+ * the paper's gate has none); eps [T,n] f32 standard-normal draws, or NULL for the noise-free
+ * gate H = x W_g.
+ * Outputs: topk_idx [T,k] i32 (descending H; equal H: lower index first), topk_gate [T,k] f32
+ * (softmax over the kept logits); cleanb [T,n] f32 = x W_g (+ bias); sp [T,n] f32 =
+ * Softplus(x W_noise); next_idx [T] i32 = index of the (k+1)-th largest H (-1 when k = n);
+ * partials f32 [moe_gate_partial_rows][2][n] = per-block sums of G(x) and of P(x,.) that
+ * moe_aux_losses finishes.
+ * Arithmetic of H (what makes top-k reproducible): each logit is one fp32 accumulator,
+ * acc = fma(x[t][j], W[j][i], acc) for j ascending from +0; Softplus is evaluated in
+ * binary64 from a fixed sequence of fused operations and rounded once to fp32;
+ * H = fma(eps, sp, clean + bias).  Inputs must be finite.
+ */
+int moe_gate(const moe_config *cfg, const float *x, const float *W_g, const float *W_noise,
+             const float *gate_bias, const float *eps, int32_t *topk_idx, float *topk_gate,
+             float *cleanb, float *sp, int32_t *next_idx, float *partials, void *stream);
+
+/* ---- a2: dispatch bookkeeping (Section 2: skip experts with G = 0; Section 3.1: one
+ *      combined batch per expert) ------------------------------------------------------ */
+/*
+ * topk_idx [T,k] -> counts [n] (assignments per expert), offsets [n+1] (exclusive prefix
+ * sum), perm [T*k] (sorted row -> assignment id a = t*k+s; stable: rows of one expert in
+ * ascending a), inv_perm [T*k] (assignment id -> sorted row), and the row-tile table for the
+ * expert kernel: tile_expert/tile_row0 [moe_max_tiles] and num_tiles [1] (tiles never straddle
+ * experts; experts without tokens get no tile).  Deterministic: no position atomics.
+ * workspace: moe_route_workspace_bytes() bytes.
+ */
+int moe_route(const moe_config *cfg, const int32_t *topk_idx, int32_t *counts, int32_t *offsets,
+              int32_t *perm, int32_t *inv_perm, int32_t *tile_expert, int32_t *tile_row0,
+              int32_t *num_tiles, void *workspace, void *stream);
+
+/* ---- a3: the experts, E_i(x) = relu(x W1_i) W2_i (Appendix C) ------------------------ */
+/*
+ * x [T,d] f32; W1 [n,d,h] and W2 [n,h,d] in the paper's plain layout (input x hidden,
+ * hidden x output), fp32 or bf16 per cfg->expert_dtype.  Rows are gathered through perm
+ * (token = perm[row] / k).  out_sorted [T*k, d] f32, row r = E_{expert of r}(x_{token of r}).
+ * bf16 experts: x and the hidden activations are rounded to bf16 (nearest-even), products
+ * accumulate in fp32 on the matrix cores; the hidden layer never leaves the chip.
+ * Experts with no rows are never read.
+ */
+int moe_expert_ffn(const moe_config *cfg, const float *x, const int32_t *perm,
+                   const int32_t *offsets, const int32_t *tile_expert, const int32_t *tile_row0,
+                   const int32_t *num_tiles, const void *W1, const void *W2, float *out_sorted,
+                   void *workspace, void *stream);
+
+/* ---- a4: y = sum_s gate[t,s] * E_{idx[t,s]}(x_t), Eq.(1) (Eq.(12) when the gates are the
+ *      products of primary and secondary gates) ----------------------------------------- */
+/* out_sorted [T*k,d] f32, topk_gate [T,k] f32, inv_perm [T*k] -> y [T,d] f32; slots are
+ * accumulated in ascending s with fused multiply-adds. */
+int moe_combine(const moe_config *cfg, const float *out_sorted, const float *topk_gate,
+                const int32_t *inv_perm, float *y, void *stream);
+
+/* ---- a5: balancing losses, Eq.(6),(7),(10),(11) ---------------------------------------- */
+/* partials from moe_gate -> importance [n] f32, load [n] f32, losses [4] f32 =
+ * {w_importance*CV^2(importance), w_load*CV^2(load), CV^2(importance), CV^2(load)}; CV^2 uses
+ * the population variance and is evaluated in fp64.  workspace: moe_aux_workspace_bytes()
+ * bytes (the fp64 sums). */
+int moe_aux_losses(const moe_config *cfg, const float *partials, float *importance, float *load,
+                   float *losses, void *workspace, void *stream);
+
+/* ---- the whole forward pass of the flat layer: a1..a5 on one stream ------------------- */
+int moe_layer_forward(const moe_config *cfg, const float *x, const float *W_g,
+                      const float *W_noise, const float *gate_bias, const float *eps,
+                      const void *W1, const void *W2, float *y, int32_t *topk_idx,
+                      float *topk_gate, float *importance, float *load, float *losses,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

@@ -1,0 +1,42 @@
+// Internal helpers of the HIP library (host-side checks, launch error capture, small device
+// utilities).  Not part of the ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/moe.h"
+
+namespace moe {
+
+extern thread_local int g_last_hip_error;
+
+inline int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return MOE_EHIP;
+}
+
+#define MOE_HIP_TRY(expr)                                   \
+    do {                                                    \
+        hipError_t e__ = (expr);                            \
+        if (e__ != hipSuccess) return ::moe::hip_fail(e__); \
+    } while (0)
+
+// after a kernel launch: catches bad launch configurations without synchronising
+#define MOE_LAUNCH_CHECK() MOE_HIP_TRY(hipGetLastError())
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape checks shared by every entry point.  Returns MOE_OK or the status to report.
+int check_config(const moe_config *cfg);
+// Checks of one gating level (n experts, k kept).
+int check_gate_level(int64_t T, int d, int n, int k);
+
+constexpr int kGateBM = 128;       // rows per block tile of the logits kernel
+constexpr int kGateRowsPerBlock = 32;  // rows per block of the top-k kernel
+constexpr int kMaxK = 8;
+constexpr int kMaxExperts = 16384;   // route histograms live in 64 KB of LDS
+constexpr int kMaxGateExperts = 2048;  // experts of one gating level (top-k kernel accumulators)
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace moe

@@ -1,0 +1,433 @@
+// a1: noisy top-k gating (Section 2.1, Eq.(3)-(5)) and the per-block partial sums of
+// Importance (Eq.(6)) and Load (Eq.(8)-(10), Appendix A).
+//
+// Two kernels:
+//  * gate_logits_kernel  -- clean = x W_g (+bias), sp = Softplus(x W_noise) as an fp32 GEMM on
+//    the matrix cores.  v_mfma_f32_32x32x2f32 accumulates its two k-slices one after the other
+//    with a single rounding each, i.e. exactly acc = fma(x_j, W_ji, acc) for ascending j, so
+//    as long as every output keeps ONE accumulator chain over the whole of d the result has
+//    the bits of the sequential fused chain that defines the gate's arithmetic.
+//  * gate_topk_kernel    -- one wavefront per row: H = fma(eps, sp, clean), per-lane sorted
+//    candidate lists merged by k+1 wave-wide arg-max rounds (ties to the lower index), softmax
+//    over the kept logits, then P(x,i) for every expert and the block's partial sums.
+#include "stages.h"
+
+namespace moe {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------------------
+// Softplus in binary64, rounded once to fp32.  Fixed operation sequence:
+//   a = min(|z|, 64); q = rint(a*log2e); r = fma(-q, ln2, a); E = 2^-q * T13(-r)
+//   (T13 = degree-13 Taylor polynomial of exp, Horner with fma);
+//   v = 2 + E; y = reciprocal of v by a linear guess (5/6 - v/6) and four Newton steps;
+//   s = E*y; L = 2*s*A13(s*s) with A13 = sum_{j<=13} u^j/(2j+1) (Horner with fma);
+//   result = (float)(max(z,0) + L).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ float softplus_spec(float zf) {
+    const double z = (double)zf;
+    double a = fabs(z);
+    a = a > 64.0 ? 64.0 : a;
+    const double q = rint(a * 1.4426950408889634);
+    const double m = -__fma_rn(-q, 0.6931471805599453, a);
+    double p = 1.0 / 6227020800.0;
+    p = __fma_rn(p, m, 1.0 / 479001600.0);
+    p = __fma_rn(p, m, 1.0 / 39916800.0);
+    p = __fma_rn(p, m, 1.0 / 3628800.0);
+    p = __fma_rn(p, m, 1.0 / 362880.0);
+    p = __fma_rn(p, m, 1.0 / 40320.0);
+    p = __fma_rn(p, m, 1.0 / 5040.0);
+    p = __fma_rn(p, m, 1.0 / 720.0);
+    p = __fma_rn(p, m, 1.0 / 120.0);
+    p = __fma_rn(p, m, 1.0 / 24.0);
+    p = __fma_rn(p, m, 1.0 / 6.0);
+    p = __fma_rn(p, m, 0.5);
+    p = __fma_rn(p, m, 1.0);
+    p = __fma_rn(p, m, 1.0);
+    const double E = ldexp(p, -(int)q);
+    const double v = 2.0 + E;
+    double y = __fma_rn(-1.0 / 6.0, v, 5.0 / 6.0);
+    double e;
+    e = __fma_rn(-v, y, 1.0); y = __fma_rn(y, e, y);
+    e = __fma_rn(-v, y, 1.0); y = __fma_rn(y, e, y);
+    e = __fma_rn(-v, y, 1.0); y = __fma_rn(y, e, y);
+    e = __fma_rn(-v, y, 1.0); y = __fma_rn(y, e, y);
+    const double s = __dmul_rn(E, y);
+    const double s2 = __dmul_rn(s, s);
+    double t = 1.0 / 27.0;
+    t = __fma_rn(t, s2, 1.0 / 25.0);
+    t = __fma_rn(t, s2, 1.0 / 23.0);
+    t = __fma_rn(t, s2, 1.0 / 21.0);
+    t = __fma_rn(t, s2, 1.0 / 19.0);
+    t = __fma_rn(t, s2, 1.0 / 17.0);
+    t = __fma_rn(t, s2, 1.0 / 15.0);
+    t = __fma_rn(t, s2, 1.0 / 13.0);
+    t = __fma_rn(t, s2, 1.0 / 11.0);
+    t = __fma_rn(t, s2, 1.0 / 9.0);
+    t = __fma_rn(t, s2, 1.0 / 7.0);
+    t = __fma_rn(t, s2, 1.0 / 5.0);
+    t = __fma_rn(t, s2, 1.0 / 3.0);
+    t = __fma_rn(t, s2, 1.0);
+    const double L = __dmul_rn(2.0, __dmul_rn(s, t));
+    const double zpos = z > 0.0 ? z : 0.0;
+    return (float)__dadd_rn(zpos, L);
+}
+
+// ---------------------------------------------------------------------------------------
+// logits GEMM
+// ---------------------------------------------------------------------------------------
+
+constexpr int BM = kGateBM;  // 128 rows: 4 waves x 32
+constexpr int KC = 32;       // k-slab staged in LDS
+constexpr int ASTR = KC + 4; // floats per LDS row of the x tile: [parity][KC/2] + pad
+
+template <int RN>  // the block tile is BM x (32*RN) columns of ONE of the two matrices
+__global__ __launch_bounds__(256, 2) void gate_logits_kernel(LogitsArgs p) {
+    constexpr int BN = 32 * RN;
+    __shared__ __attribute__((aligned(16))) float As[2][BM][ASTR];
+    __shared__ __attribute__((aligned(16))) float Bs[2][KC][BN];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+
+    int group = 0;
+    int64_t row0 = (int64_t)blockIdx.x * BM;
+    int rows;
+    if (p.tile_row0) {
+        if ((int)blockIdx.x >= *p.num_tiles) return;
+        group = p.tile_group[blockIdx.x];
+        row0 = p.tile_row0[blockIdx.x];
+        rows = (int)min((int64_t)BM, (int64_t)p.group_offsets[group + 1] - row0);
+    } else {
+        rows = (int)min((int64_t)BM, p.R - row0);
+    }
+    const int NT = (p.n + BN - 1) / BN;
+    const int which = blockIdx.y / NT;
+    const int col0 = (blockIdx.y % NT) * BN;
+    const int d = p.d, n = p.n;
+    const float *W = (which ? p.Wn : p.Wg) + (size_t)group * d * n;
+
+    // global -> register staging
+    const int a_r = tid >> 3, a_k = (tid & 7) * 4;       // + 32*i rows
+    const float *a_src[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = a_r + 32 * i;
+        if (r < rows) {
+            const int64_t tok = p.row_src ? (int64_t)(p.row_src[row0 + r] / p.row_div) : row0 + r;
+            a_src[i] = p.x + tok * d + a_k;
+        } else {
+            a_src[i] = nullptr;
+        }
+    }
+    constexpr int BQ = BN / 4;                  // float4 per B row
+    constexpr int BROWS = 256 / BQ;             // B rows covered per pass
+    constexpr int BPASS = KC / BROWS;
+    const int b_k = tid / BQ, b_c = (tid % BQ) * 4;
+    const bool vec_ok = (n % 4) == 0;
+
+    float4 a_reg[4], b_reg[BPASS];
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            a_reg[i] = a_src[i] ? *reinterpret_cast<const float4 *>(a_src[i] + k0)
+                                : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int i = 0; i < BPASS; ++i) {
+            const float *src = W + (size_t)(k0 + b_k + BROWS * i) * n + col0 + b_c;
+            const int col = col0 + b_c;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (vec_ok && col + 3 < n) {
+                v = *reinterpret_cast<const float4 *>(src);
+            } else {
+                if (col + 0 < n) v.x = src[0];
+                if (col + 1 < n) v.y = src[1];
+                if (col + 2 < n) v.z = src[2];
+                if (col + 3 < n) v.w = src[3];
+            }
+            b_reg[i] = v;
+        }
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float *row = &As[buf][a_r + 32 * i][0];
+            // k parity 0 -> first half of the row, parity 1 -> second half
+            *reinterpret_cast<float2 *>(row + a_k / 2) = make_float2(a_reg[i].x, a_reg[i].z);
+            *reinterpret_cast<float2 *>(row + KC / 2 + a_k / 2) = make_float2(a_reg[i].y, a_reg[i].w);
+        }
+#pragma unroll
+        for (int i = 0; i < BPASS; ++i)
+            *reinterpret_cast<float4 *>(&Bs[buf][b_k + BROWS * i][b_c]) = b_reg[i];
+    };
+
+    v16f acc[RN];
+#pragma unroll
+    for (int c = 0; c < RN; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int k0 = 0; k0 < d; k0 += KC) {
+        const int buf = (k0 / KC) & 1;
+        const bool more = k0 + KC < d;
+        if (more) load_global(k0 + KC);
+        const float *a_row = &As[buf][wave * 32 + l32][half * (KC / 2)];
+#pragma unroll
+        for (int kk4 = 0; kk4 < KC / 2; kk4 += 4) {
+            const float4 a4 = *reinterpret_cast<const float4 *>(a_row + kk4);
+            const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int k = 2 * (kk4 + u) + half;
+#pragma unroll
+                for (int c = 0; c < RN; ++c)
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], Bs[buf][k][32 * c + l32],
+                                                                  acc[c], 0, 0, 0);
+            }
+        }
+        if (more) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    float *out = which ? p.sp : p.cleanb;
+#pragma unroll
+    for (int c = 0; c < RN; ++c) {
+        const int col = col0 + 32 * c + l32;
+        if (col >= n) continue;
+        const float bias = (!which && p.bias) ? p.bias[col] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = wave * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            if (i >= rows) continue;
+            float v = acc[c][r];
+            if (which) v = softplus_spec(v);
+            else if (p.bias) v = __fadd_rn(v, bias);
+            out[(row0 + i) * (int64_t)n + col] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// top-k, softmax, P(x,i) and partial sums
+// ---------------------------------------------------------------------------------------
+
+__device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
+    return v1 > v2 || (v1 == v2 && i1 < i2);
+}
+
+template <int L>
+__global__ __launch_bounds__(256) void gate_topk_kernel(TopkArgs p) {
+    extern __shared__ float lds_acc[];  // [4][2][n]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = p.n, k = p.k;
+    constexpr int RPB = kGateRowsPerBlock;
+    constexpr int SUB = kGateBM / RPB;
+
+    int64_t rb, re;
+    if (p.tile_row0) {
+        const int tile = blockIdx.x / SUB;
+        if (tile >= *p.num_tiles) return;
+        const int g = p.tile_group[tile];
+        const int64_t t0 = p.tile_row0[tile];
+        const int64_t tend = min(t0 + kGateBM, (int64_t)p.group_offsets[g + 1]);
+        rb = min(t0 + (int64_t)(blockIdx.x % SUB) * RPB, tend);
+        re = min(rb + RPB, tend);
+    } else {
+        rb = (int64_t)blockIdx.x * RPB;
+        re = min(rb + RPB, p.R);
+    }
+
+    for (int i = tid; i < 8 * n; i += 256) lds_acc[i] = 0.f;
+    __syncthreads();
+    float *acc_imp = lds_acc + (size_t)wave * 2 * n;
+    float *acc_load = acc_imp + n;
+    const int kp1 = (k < n) ? k + 1 : k;
+
+    for (int64_t r = rb + wave; r < re; r += 4) {
+        const float *c_row = p.cleanb + r * n;
+        const float *s_row = p.sp + r * n;
+        const int64_t orow = p.row_map ? p.row_map[r] : r;
+        const float *e_row = p.eps ? p.eps + orow * n : nullptr;
+
+        float lv[L];
+        int li[L];
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            lv[j] = -INFINITY;
+            li[j] = 0x7fffffff;
+        }
+        for (int i = lane; i < n; i += 64) {
+            const float c = c_row[i];
+            float v = e_row ? __fmaf_rn(e_row[i], s_row[i], c) : c;
+            int id = i;
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                if (better(v, id, lv[j], li[j])) {
+                    const float tv = lv[j];
+                    const int ti = li[j];
+                    lv[j] = v;
+                    li[j] = id;
+                    v = tv;
+                    id = ti;
+                }
+            }
+        }
+        float tv[L];
+        int ti[L];
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            tv[j] = -INFINITY;
+            ti[j] = 0x7fffffff;
+            if (j < kp1) {
+                float v = lv[0];
+                int id = li[0];
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const float ov = __shfl_xor(v, off);
+                    const int oi = __shfl_xor(id, off);
+                    if (better(ov, oi, v, id)) {
+                        v = ov;
+                        id = oi;
+                    }
+                }
+                tv[j] = v;
+                ti[j] = id;
+                if (li[0] == id) {
+#pragma unroll
+                    for (int q = 0; q + 1 < L; ++q) {
+                        lv[q] = lv[q + 1];
+                        li[q] = li[q + 1];
+                    }
+                    lv[L - 1] = -INFINITY;
+                    li[L - 1] = 0x7fffffff;
+                }
+            }
+        }
+        // Eq.(3): softmax over the kept logits
+        float g[L];
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            g[j] = (j < k) ? expf(tv[j] - tv[0]) : 0.f;
+            sum += g[j];
+        }
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (int j = 0; j < L; ++j) g[j] *= inv;
+        if (lane == 0) {
+#pragma unroll
+            for (int j = 0; j < L; ++j)
+                if (j < k) {
+                    p.idx[orow * k + j] = ti[j];
+                    p.gate[orow * k + j] = g[j];
+                }
+        }
+        // Eq.(9): P(x,i) for every expert; threshold = (k+1)-th H for kept experts, k-th otherwise
+        float thr_in = 0.f, thr_out = 0.f;
+        int nxt = -1;
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            if (j == k && k < n) {
+                thr_in = tv[j];
+                nxt = ti[j];
+            }
+            if (j == k - 1) thr_out = tv[j];
+        }
+        if (lane == 0 && p.next_idx) p.next_idx[orow] = nxt;
+        for (int i = lane; i < n; i += 64) {
+            float gi = 0.f;
+            bool kept = false;
+#pragma unroll
+            for (int j = 0; j < L; ++j)
+                if (j < k && ti[j] == i) {
+                    kept = true;
+                    gi = g[j];
+                }
+            float P = 1.0f;
+            if (k < n) {
+                const float u = (c_row[i] - (kept ? thr_in : thr_out)) / s_row[i];
+                P = 0.5f * erfcf(-0.70710678118654752f * u);
+            }
+            acc_load[i] += P;
+            acc_imp[i] += gi;
+        }
+    }
+    __syncthreads();
+    float *out = p.partials + (size_t)blockIdx.x * 2 * n;
+    for (int i = tid; i < 2 * n; i += 256)
+        out[i] = (lds_acc[i] + lds_acc[2 * n + i]) + (lds_acc[4 * n + i] + lds_acc[6 * n + i]);
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
+    if (row_tiles <= 0) return MOE_OK;
+    if (a.n <= 32) {
+        dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 32));
+        hipLaunchKernelGGL(gate_logits_kernel<1>, grid, dim3(256), 0, st, a);
+    } else if (a.n <= 64) {
+        dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 64));
+        hipLaunchKernelGGL(gate_logits_kernel<2>, grid, dim3(256), 0, st, a);
+    } else {
+        dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 128));
+        hipLaunchKernelGGL(gate_logits_kernel<4>, grid, dim3(256), 0, st, a);
+    }
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st) {
+    if (blocks <= 0) return MOE_OK;
+    const size_t lds = (size_t)8 * a.n * sizeof(float);
+    if (a.k + 1 <= 3) {
+        hipLaunchKernelGGL(gate_topk_kernel<3>, dim3((unsigned)blocks), dim3(256), lds, st, a);
+    } else if (a.k + 1 <= 5) {
+        hipLaunchKernelGGL(gate_topk_kernel<5>, dim3((unsigned)blocks), dim3(256), lds, st, a);
+    } else {
+        hipLaunchKernelGGL(gate_topk_kernel<9>, dim3((unsigned)blocks), dim3(256), lds, st, a);
+    }
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" int64_t moe_gate_partial_rows(const moe_config *cfg) {
+    if (!cfg || cfg->T <= 0) return 0;
+    return ceil_div(cfg->T, kGateRowsPerBlock);
+}
+
+extern "C" int moe_gate(const moe_config *cfg, const float *x, const float *W_g,
+                        const float *W_noise, const float *gate_bias, const float *eps,
+                        int32_t *topk_idx, float *topk_gate, float *cleanb, float *sp,
+                        int32_t *next_idx, float *partials, void *stream) {
+    int st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (cfg->a != 0) return MOE_EINVAL;  // flat entry point; hierarchical layers use moe_gate_hier
+    if (!x || !W_g || !W_noise || !topk_idx || !topk_gate || !cleanb || !sp || !partials)
+        return MOE_EINVAL;
+    if (!aligned16(x) || !aligned16(W_g) || !aligned16(W_noise) || !aligned16(cleanb) ||
+        !aligned16(sp) || (eps && !aligned16(eps)))
+        return MOE_EINVAL;
+    st = check_gate_level(cfg->T, cfg->d, cfg->n, cfg->k);
+    if (st != MOE_OK) return st;
+
+    LogitsArgs la{};
+    la.x = x; la.Wg = W_g; la.Wn = W_noise; la.bias = gate_bias;
+    la.cleanb = cleanb; la.sp = sp;
+    la.R = cfg->T; la.d = cfg->d; la.n = cfg->n;
+    st = launch_gate_logits(la, ceil_div(cfg->T, kGateBM), (hipStream_t)stream);
+    if (st != MOE_OK) return st;
+
+    TopkArgs ta{};
+    ta.cleanb = cleanb; ta.sp = sp; ta.eps = eps;
+    ta.R = cfg->T; ta.n = cfg->n; ta.k = cfg->k;
+    ta.idx = topk_idx; ta.gate = topk_gate; ta.next_idx = next_idx; ta.partials = partials;
+    return launch_gate_topk(ta, moe_gate_partial_rows(cfg), (hipStream_t)stream);
+}

@@ -1,0 +1,193 @@
+// a2: dispatch bookkeeping -- a deterministic stable counting sort of the T*k assignments by
+// expert id.  Skipping experts with G(x)_i = 0 (Section 2) and giving each expert one combined
+// batch (Section 3.1) both come down to this permutation.
+//
+//   route_hist_kernel    chunk c of the assignment list -> LDS histogram -> hist[c][e]
+//   route_colscan_kernel per expert: exclusive scan over chunks (in place), counts[e]
+//   route_offsets_kernel one block: offsets = scan(counts); row-tile table for the expert kernel
+//   route_scatter_kernel one wavefront per chunk walks its assignments in order; the rank of an
+//                        assignment among equal experts inside a 64-wide step comes from
+//                        ballots over the bits of the expert id, so no atomics decide positions
+#include "stages.h"
+
+namespace moe {
+
+
+void route_chunking(int64_t A, int *chunk, int *num_chunks) {
+    int64_t c = ceil_div(ceil_div(A, 512), 64) * 64;
+    if (c < 64) c = 64;
+    if (c > 4096) c = 4096;
+    *chunk = (int)c;
+    *num_chunks = (int)ceil_div(A, c);
+}
+
+size_t route_ws_bytes(int64_t A, int n) {
+    int chunk, nc;
+    route_chunking(A, &chunk, &nc);
+    return (size_t)(nc > 0 ? nc : 1) * n * sizeof(int32_t);
+}
+
+__global__ __launch_bounds__(256) void route_hist_kernel(RouteArgs p) {
+    extern __shared__ int lds_hist[];
+    const int n = p.n;
+    for (int e = threadIdx.x; e < n; e += 256) lds_hist[e] = 0;
+    __syncthreads();
+    const int64_t a0 = (int64_t)blockIdx.x * p.chunk;
+    const int64_t a1 = min(a0 + p.chunk, p.A);
+    for (int64_t a = a0 + threadIdx.x; a < a1; a += 256) {
+        const int e = p.idx[a];
+        if (e >= 0 && e < n) atomicAdd(&lds_hist[e], 1);  // integer counts: order-independent
+    }
+    __syncthreads();
+    int32_t *out = p.hist + (size_t)blockIdx.x * n;
+    for (int e = threadIdx.x; e < n; e += 256) out[e] = lds_hist[e];
+}
+
+__global__ __launch_bounds__(256) void route_colscan_kernel(RouteArgs p) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= p.n) return;
+    int run = 0;
+    for (int c = 0; c < p.num_chunks; ++c) {
+        int32_t *cell = p.hist + (size_t)c * p.n + e;
+        const int v = *cell;
+        *cell = run;
+        run += v;
+    }
+    p.counts[e] = run;
+}
+
+// Block-wide inclusive scan of one int per thread (1024 threads = 16 waves).
+__device__ __forceinline__ int block_inclusive_scan(int v, int *wave_sums) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(v, off);
+        if (lane >= off) v += o;
+    }
+    if (lane == 63) wave_sums[wave] = v;
+    __syncthreads();
+    int add = 0;
+    for (int w = 0; w < wave; ++w) add += wave_sums[w];
+    __syncthreads();
+    return v + add;
+}
+
+__global__ __launch_bounds__(1024) void route_offsets_kernel(RouteArgs p) {
+    __shared__ int wave_sums[16];
+    __shared__ int carry[2];
+    const int n = p.n, TM = p.tile_rows;
+    if (threadIdx.x == 0) {
+        carry[0] = 0;
+        carry[1] = 0;
+    }
+    __syncthreads();
+    for (int base = 0; base < n; base += 1024) {
+        const int e = base + threadIdx.x;
+        const int cnt = e < n ? p.counts[e] : 0;
+        const int tiles = (cnt + TM - 1) / TM;
+        const int c0 = carry[0], c1 = carry[1];
+        const int inc_rows = block_inclusive_scan(cnt, wave_sums);
+        const int inc_tiles = block_inclusive_scan(tiles, wave_sums);
+        if (e < n) {
+            const int off = c0 + inc_rows - cnt;
+            const int toff = c1 + inc_tiles - tiles;
+            p.offsets[e] = off;
+            if (p.tile_offsets) p.tile_offsets[e] = toff;
+            for (int j = 0; j < tiles; ++j) {
+                p.tile_expert[toff + j] = e;
+                p.tile_row0[toff + j] = off + j * TM;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 1023) {
+            carry[0] = c0 + inc_rows;
+            carry[1] = c1 + inc_tiles;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        p.offsets[n] = carry[0];
+        if (p.tile_offsets) p.tile_offsets[n] = carry[1];
+        p.num_tiles[0] = carry[1];
+    }
+}
+
+__global__ __launch_bounds__(64) void route_scatter_kernel(RouteArgs p, int nbits) {
+    extern __shared__ int lds_cursor[];
+    const int n = p.n, lane = threadIdx.x;
+    for (int e = lane; e < n; e += 64) lds_cursor[e] = 0;
+    __syncthreads();
+    const int32_t *base_row = p.hist + (size_t)blockIdx.x * n;
+    const int64_t a0 = (int64_t)blockIdx.x * p.chunk;
+    const int64_t a1 = min(a0 + p.chunk, p.A);
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int64_t s = a0; s < a1; s += 64) {
+        const int64_t a = s + lane;
+        int e = (a < a1) ? p.idx[a] : -1;
+        const bool active = e >= 0 && e < n;
+        unsigned long long same = __ballot(active);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (e >> b) & 1;
+            const unsigned long long bal = __ballot(active && bit);
+            same &= bit ? bal : ~bal;
+        }
+        if (active) {
+            const int rank = __popcll(same & lt_mask);
+            const int cnt = __popcll(same);
+            const int before = lds_cursor[e];
+            const int pos = p.offsets[e] + base_row[e] + before + rank;
+            p.perm[pos] = (int32_t)a;
+            p.inv_perm[a] = pos;
+            if (rank == cnt - 1) lds_cursor[e] = before + cnt;  // issued after every lane's read
+        }
+    }
+}
+
+int launch_route(RouteArgs a, hipStream_t st) {
+    route_chunking(a.A, &a.chunk, &a.num_chunks);
+    const size_t lds = (size_t)a.n * sizeof(int);
+    if (a.num_chunks > 0) {
+        hipLaunchKernelGGL(route_hist_kernel, dim3(a.num_chunks), dim3(256), lds, st, a);
+        MOE_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(route_colscan_kernel, dim3((unsigned)ceil_div(a.n, 256)), dim3(256), 0, st, a);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(route_offsets_kernel, dim3(1), dim3(1024), 0, st, a);
+    MOE_LAUNCH_CHECK();
+    if (a.num_chunks > 0) {
+        int nbits = 0;
+        while ((1 << nbits) < a.n) ++nbits;
+        hipLaunchKernelGGL(route_scatter_kernel, dim3(a.num_chunks), dim3(64), lds, st, a, nbits);
+        MOE_LAUNCH_CHECK();
+    }
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" size_t moe_route_workspace_bytes(const moe_config *cfg) {
+    if (check_config(cfg) != MOE_OK) return 0;
+    return route_ws_bytes((int64_t)cfg->T * cfg->k, cfg->n);
+}
+
+extern "C" int moe_route(const moe_config *cfg, const int32_t *topk_idx, int32_t *counts,
+                         int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *tile_expert,
+                         int32_t *tile_row0, int32_t *num_tiles, void *workspace, void *stream) {
+    int st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (!topk_idx || !counts || !offsets || !perm || !inv_perm || !tile_expert || !tile_row0 ||
+        !num_tiles || !workspace)
+        return MOE_EINVAL;
+    RouteArgs a{};
+    a.idx = topk_idx;
+    a.A = (int64_t)cfg->T * cfg->k;
+    a.n = cfg->n;
+    a.tile_rows = moe_tile_rows(cfg);
+    a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm;
+    a.tile_expert = tile_expert; a.tile_row0 = tile_row0; a.num_tiles = num_tiles;
+    a.tile_offsets = nullptr;
+    a.hist = (int32_t *)workspace;
+    return launch_route(a, (hipStream_t)stream);
+}

@@ -1,0 +1,71 @@
+// Argument blocks and launchers of the individual stages (internal; shared by the stage
+// files and by the layer composition).
+#pragma once
+#include "common.h"
+
+namespace moe {
+
+struct LogitsArgs {
+    const float *x;            // [*, d]
+    const float *Wg, *Wn;      // [groups][d][n]
+    const float *bias;         // [n] or null
+    float *cleanb, *sp;        // [R][n]
+    int64_t R;                 // rows
+    int d, n;
+    // row gather (hierarchical secondary gate): token = row_src[r] / row_div; null = identity
+    const int32_t *row_src;
+    int row_div;
+    // row tiles that never straddle a group; null = one group, tile t covers rows 128t..
+    const int32_t *tile_group, *tile_row0, *num_tiles, *group_offsets;
+};
+
+struct TopkArgs {
+    const float *cleanb, *sp;  // [R][n]
+    const float *eps;          // [*][n] or null
+    int64_t R;
+    int n, k;
+    // row r reads eps row / writes output row row_map[r] (null: r)
+    const int32_t *row_map;
+    const int32_t *tile_row0, *num_tiles, *tile_group, *group_offsets;  // null = flat
+    int32_t *idx;              // [*][k]
+    float *gate;               // [*][k]
+    int32_t *next_idx;         // [*] or null
+    float *partials;           // [gridDim.x][2][n]
+};
+
+struct RouteArgs {
+    const int32_t *idx;  // [A]
+    int64_t A;
+    int n;
+    int tile_rows;
+    int chunk;           // assignments per chunk (multiple of 64)
+    int num_chunks;
+    int32_t *counts, *offsets, *perm, *inv_perm;
+    int32_t *tile_expert, *tile_row0, *num_tiles;
+    int32_t *tile_offsets;  // [n+1] or null: exclusive scan of tiles per expert
+    int32_t *hist;          // workspace [num_chunks][n]
+};
+
+struct FfnArgs {
+    const float *x;           // [T,d]
+    const int32_t *perm;      // [A]
+    const int32_t *offsets;   // [n+1]
+    const int32_t *tile_expert, *tile_row0, *num_tiles;
+    const void *W1, *W2;
+    float *out;               // [A,d]
+    float *hidden;            // fp32 path workspace [A,h]
+    int d, h, k;
+};
+
+int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st);
+int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st);
+size_t route_ws_bytes(int64_t A, int n);
+int launch_route(RouteArgs a, hipStream_t st);
+int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles, hipStream_t st);
+int launch_combine(const float *out_sorted, const float *gate, const int32_t *inv_perm, float *y,
+                   int64_t T, int d, int k, hipStream_t st);
+int launch_aux_losses(const float *partials, int64_t rows, int n, float w_imp, float w_load,
+                      float *importance, float *load, float *losses, double *sums64,
+                      hipStream_t st);
+
+}  // namespace moe

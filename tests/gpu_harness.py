@@ -1,0 +1,125 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C ABI binding and the oracle
+on the same seeded inputs.  (Test infrastructure; the product never imports this.)"""
+import numpy as np
+import torch
+
+import moe_workloads as W
+from oracle import moe_oracle as O
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+class FlatRun:
+    """One forward pass of the flat layer on the GPU, stage by stage or fused."""
+
+    def __init__(self, api, shape, x, W_g, W_noise, eps, bias, W1, W2):
+        self.api = api
+        self.shape = shape
+        self.cfg = api.make_config(shape)
+        c = self.cfg
+        self.x, self.W_g, self.W_noise = dev(x), dev(W_g), dev(W_noise)
+        self.eps = None if eps is None else dev(eps)
+        self.bias = None if bias is None else dev(bias)
+        self.W1, self.W2 = W1, W2                     # device tensors [n,d,h], [n,h,d]
+        T, n, k, d = c.T, c.n, c.k, c.d
+        A = T * k
+        i32 = dict(dtype=torch.int32, device="cuda")
+        f32 = dict(dtype=torch.float32, device="cuda")
+        self.topk_idx = torch.full((T, k), -7, **i32)
+        self.topk_gate = torch.full((T, k), float("nan"), **f32)
+        self.cleanb = torch.full((T, n), float("nan"), **f32)
+        self.sp = torch.full((T, n), float("nan"), **f32)
+        self.next_idx = torch.full((T,), -7, **i32)
+        self.partials = torch.full((max(1, api.moe_gate_partial_rows(c)), 2, n), float("nan"), **f32)
+        self.counts = torch.full((n,), -7, **i32)
+        self.offsets = torch.full((n + 1,), -7, **i32)
+        self.perm = torch.full((max(A, 1),), -7, **i32)
+        self.inv_perm = torch.full((max(A, 1),), -7, **i32)
+        mt = api.moe_max_tiles(c) + 8
+        self.tile_expert = torch.full((mt,), -7, **i32)
+        self.tile_row0 = torch.full((mt,), -7, **i32)
+        self.num_tiles = torch.full((4,), -7, **i32)
+        self.route_ws = torch.empty(max(16, api.moe_route_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
+        self.out_sorted = torch.full((max(A, 1), d), float("nan"), **f32)
+        self.ffn_ws = torch.empty(max(16, api.moe_ffn_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
+        self.aux_ws = torch.empty(max(16, api.moe_aux_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
+        self.y = torch.full((max(T, 1), d), float("nan"), **f32)
+        self.importance = torch.full((n,), float("nan"), **f32)
+        self.load = torch.full((n,), float("nan"), **f32)
+        self.losses = torch.full((4,), float("nan"), **f32)
+
+    def gate(self):
+        self.api.moe_gate(self.cfg, self.x, self.W_g, self.W_noise, self.bias, self.eps, self.topk_idx,
+                          self.topk_gate, self.cleanb, self.sp, self.next_idx, self.partials)
+
+    def route(self, idx=None):
+        self.api.moe_route(self.cfg, self.topk_idx if idx is None else idx, self.counts, self.offsets,
+                           self.perm, self.inv_perm, self.tile_expert, self.tile_row0, self.num_tiles,
+                           self.route_ws)
+
+    def ffn(self):
+        self.api.moe_expert_ffn(self.cfg, self.x, self.perm, self.offsets, self.tile_expert, self.tile_row0,
+                                self.num_tiles, self.W1, self.W2, self.out_sorted, self.ffn_ws)
+
+    def combine(self):
+        self.api.moe_combine(self.cfg, self.out_sorted, self.topk_gate, self.inv_perm, self.y)
+
+    def losses_(self):
+        self.api.moe_aux_losses(self.cfg, self.partials, self.importance, self.load, self.losses, self.aux_ws)
+
+    def stages(self):
+        self.gate(); self.route(); self.ffn(); self.combine(); self.losses_()
+        torch.cuda.synchronize()
+
+    def fused(self):
+        ws = torch.empty(self.api.moe_workspace_bytes(self.cfg), dtype=torch.uint8, device="cuda")
+        self.workspace = ws
+        self.api.moe_layer_forward(self.cfg, self.x, self.W_g, self.W_noise, self.bias, self.eps, self.W1,
+                                   self.W2, self.y, self.topk_idx, self.topk_gate, self.importance,
+                                   self.load, self.losses, ws)
+        torch.cuda.synchronize()
+
+
+def flat_inputs(shape, with_bias=False, gate_std=0.02):
+    x, W_g, W_noise, eps = W.gate_inputs(shape, gate_std)
+    bias = W.zipf_gate_bias(shape) if with_bias else None
+    return x, W_g, W_noise, eps, bias
+
+
+def device_weights(shape, chunk=64):
+    """Expert weights generated on the GPU in the paper's plain layout."""
+    outs = []
+    for which in (0, 1):
+        parts = [W.expert_weights_all(shape, which, range(e0, min(shape.n, e0 + chunk)), device="cuda")
+                 for e0 in range(0, shape.n, chunk)]
+        outs.append(torch.cat(parts, dim=0).contiguous())
+    return outs
+
+
+def oracle_weight_fn(shape):
+    def fn(e):
+        w1 = W.expert_weights(shape, 0, e).to(torch.float64).numpy()
+        w2 = W.expert_weights(shape, 1, e).to(torch.float64).numpy()
+        return w1, w2
+    return fn
+
+
+def oracle_flat(shape, x, W_g, W_noise, eps, bias):
+    lg = O.noisy_logits_f32(x, W_g, W_noise, eps, bias)
+    return O.gate_and_losses(lg, shape.k, shape.w_importance, shape.w_load)
+
+
+def rel_errors(got, ref):
+    """(max per-row relative L2 error, max-abs error / max-abs ref)."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    num = np.linalg.norm(got - ref, axis=-1)
+    den = np.linalg.norm(ref, axis=-1)
+    row = float(np.max(num / np.maximum(den, 1e-300))) if ref.size else 0.0
+    mx = float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300)) if ref.size else 0.0
+    return row, mx

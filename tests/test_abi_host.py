@@ -1,0 +1,93 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments before touching the GPU (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "moe.h")
+LIB = os.path.join(ROOT, "paper_1701_06538_amd", "libmoe_hip.so")
+
+
+@pytest.fixture(scope="module")
+def api():
+    if not os.path.exists(LIB):
+        from paper_1701_06538_amd import build
+        build.build()
+    from paper_1701_06538_amd import api as _api
+    return _api
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_header_declares_the_named_entry_points():
+    names = declared_functions()
+    for must in ("moe_gate", "moe_route", "moe_expert_ffn", "moe_combine", "moe_aux_losses",
+                 "moe_layer_forward"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(api):
+    lib = ctypes.CDLL(LIB)
+    for name in declared_functions():
+        assert hasattr(lib, name), "missing export: " + name
+
+
+def test_python_binding_has_the_same_names(api):
+    for name in declared_functions():
+        assert hasattr(api, name), "binding lacks " + name
+
+
+def test_status_strings_and_version(api):
+    assert api.moe_version() >= 100
+    for st in (0, -1, -2, -3, -4):
+        assert api.moe_strerror(st)
+    assert "unknown" in api.moe_strerror(-99)
+
+
+def test_bad_shapes_are_rejected_on_the_host(api):
+    ok = dict(T=64, d=512, h=1024, n=16, k=4)
+    assert api.moe_workspace_bytes(api.make_config(**ok)) > 0
+    bad = [dict(ok, k=0), dict(ok, k=17, n=32), dict(ok, k=9, n=32), dict(ok, n=0), dict(ok, d=0),
+           dict(ok, T=-1), dict(ok, k=5, n=4), dict(ok, expert_dtype=7), dict(ok, a=4, b=3),
+           dict(ok, a=4, b=4, k_primary=2, k_secondary=3), dict(ok, n=20000), dict(ok, d=500)]
+    for kw in bad:
+        cfg = api.make_config(**kw)
+        assert api.moe_workspace_bytes(cfg) == 0, kw
+        with pytest.raises(api.MoeError):
+            api.moe_get_workspace_layout(cfg)
+    hier = api.make_config(T=64, d=512, h=1024, n=64, k=4, a=8, b=8, k_primary=2, k_secondary=2)
+    assert api.moe_workspace_bytes(hier) > 0
+
+
+def test_null_pointers_are_rejected_before_any_launch(api):
+    cfg = api.make_config(T=64, d=512, h=1024, n=16, k=4)
+    for call, nargs in ((api._moe_gate, 12), (api._moe_route, 10), (api._moe_expert_ffn, 11),
+                        (api._moe_combine, 5), (api._moe_aux_losses, 6)):
+        st = call(ctypes.byref(cfg), *([None] * nargs))
+        assert st == api.MOE_EINVAL
+    st = api._moe_layer_forward(ctypes.byref(cfg), *([None] * 14), 0, None)
+    assert st == api.MOE_EINVAL
+
+
+def test_workspace_layout_is_ordered_aligned_and_sized(api):
+    cfg = api.make_config(T=8192, d=512, h=1024, n=256, k=4)
+    L = api.moe_get_workspace_layout(cfg)
+    offs = [L.cleanb, L.sp, L.next_idx, L.partials, L.counts, L.offsets, L.perm, L.inv_perm,
+            L.tile_expert, L.tile_row0, L.num_tiles, L.route_ws, L.out_sorted, L.ffn_ws, L.aux_ws]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    assert L.sp - L.cleanb >= 8192 * 256 * 4
+    assert L.total == api.moe_workspace_bytes(cfg)
+    assert L.total >= L.out_sorted + 8192 * 4 * 512 * 4
+    assert api.moe_max_tiles(cfg) == 8192 * 4 // api.moe_tile_rows(cfg) + 256
+    assert api.moe_gate_partial_rows(cfg) == 8192 // 32
+    f32 = api.make_config(T=256, d=512, h=1024, n=16, k=4, expert_dtype=api.MOE_DTYPE_F32)
+    assert api.moe_ffn_workspace_bytes(f32) == 256 * 4 * 1024 * 4
+    assert api.moe_ffn_workspace_bytes(cfg) == 0

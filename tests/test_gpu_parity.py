@@ -1,0 +1,211 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: top-k indices, counts, offsets, permutations bit-exact; the fp32 logits the selection is
+taken on bit-exact (same pinned arithmetic on both sides); gate values, fp32 outputs and losses
+within 1e-5 relative; bf16-expert outputs within 2e-2 relative."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import moe_workloads as W
+from oracle import moe_oracle as O
+from tests import gpu_harness as G
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-2
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def api():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_1701_06538_amd import api as _api
+    return _api
+
+
+def _shape(base, **kw):
+    return W.scaled_config(W.CONFIGS[base], **kw)
+
+
+def check_gate(run, fw, shape):
+    k, n = shape.k, shape.n
+    assert np.array_equal(run.cleanb.cpu().numpy(), fw.logits.cleanb), "clean logits differ in bits"
+    assert np.array_equal(run.sp.cpu().numpy(), fw.logits.sp), "softplus differs in bits"
+    assert np.array_equal(run.topk_idx.cpu().numpy(), fw.idx), "top-k indices differ"
+    g = run.topk_gate.cpu().numpy().astype(np.float64)
+    assert np.abs(g - fw.gates).max() <= TOL_F32 * 1.0
+    if k < n:
+        order = np.argsort(-fw.logits.H, axis=1, kind="stable")
+        assert np.array_equal(run.next_idx.cpu().numpy(), order[:, k].astype(np.int32))
+    else:
+        assert np.all(run.next_idx.cpu().numpy() == -1)
+
+
+def check_losses(run, fw):
+    imp = run.importance.cpu().numpy().astype(np.float64)
+    ld = run.load.cpu().numpy().astype(np.float64)
+    assert np.abs(imp - fw.importance).max() <= TOL_F32 * np.abs(fw.importance).max()
+    assert np.abs(ld - fw.load).max() <= TOL_F32 * np.abs(fw.load).max()
+    L = run.losses.cpu().numpy().astype(np.float64)
+    for got, ref in ((L[0], fw.loss_importance), (L[1], fw.loss_load)):
+        assert abs(got - ref) <= TOL_F32 * abs(ref) + 1e-8, (got, ref)
+    w_i, w_l = run.cfg.w_importance, run.cfg.w_load
+    assert abs(L[2] * w_i - L[0]) <= 1e-6 * abs(L[0]) + 1e-9
+    assert abs(L[3] * w_l - L[1]) <= 1e-6 * abs(L[1]) + 1e-9
+
+
+def check_route(run, idx, n):
+    counts, offsets, perm, inv = O.routing(idx, n)
+    assert np.array_equal(run.counts.cpu().numpy(), counts)
+    assert np.array_equal(run.offsets.cpu().numpy(), offsets)
+    A = idx.size
+    assert np.array_equal(run.perm.cpu().numpy()[:A], perm)
+    assert np.array_equal(run.inv_perm.cpu().numpy()[:A], inv)
+    # tile table: covers every non-empty expert's rows exactly once, in order
+    TM = run.api.moe_tile_rows(run.cfg)
+    nt = int(run.num_tiles.cpu().numpy()[0])
+    te = run.tile_expert.cpu().numpy()[:nt]
+    tr = run.tile_row0.cpu().numpy()[:nt]
+    want_e, want_r = [], []
+    for e in range(n):
+        for j in range(0, counts[e], TM):
+            want_e.append(e)
+            want_r.append(offsets[e] + j)
+    assert list(te) == want_e and list(tr) == want_r
+    assert nt <= run.api.moe_max_tiles(run.cfg)
+
+
+GATE_CASES = [
+    # name, base, overrides, with_bias, noise
+    ("cfg0", 0, dict(), False, True),
+    ("ragged_T_n", 1, dict(T=1000, n=200, k=4), False, True),
+    ("odd_n_k3", 1, dict(T=333, n=37, k=3), True, True),
+    ("k_equals_n", 1, dict(T=130, n=8, k=8), False, True),
+    ("noise_free_k1", 1, dict(T=257, n=64, k=1), False, False),
+    ("n2048_k4", 2, dict(T=192), False, True),
+    ("k2_n64", 1, dict(T=500, n=64, k=2), False, True),
+]
+
+
+@pytest.mark.parametrize("name,base,ov,with_bias,noise", GATE_CASES, ids=[c[0] for c in GATE_CASES])
+def test_gate_route_losses_parity(api, name, base, ov, with_bias, noise):
+    shape = _shape(base, **ov)
+    if with_bias:
+        shape = W.scaled_config(shape, zipf_beta=0.5)
+    say("case", name, shape)
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias)
+    if not noise:
+        eps = None
+    fw = G.oracle_flat(shape, x, W_g, W_noise, eps, bias)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, None, None)
+    run.gate(); run.route(); run.losses_()
+    torch.cuda.synchronize()
+    check_gate(run, fw, shape)
+    check_route(run, fw.idx, shape.n)
+    check_losses(run, fw)
+
+
+def test_gate_zero_initialised_matrices(api):
+    """W_g = W_noise = 0 (the paper's initialisation): selection = top-k of the noise."""
+    shape = _shape(1, T=512, n=256)
+    say("case zero-init", shape)
+    x, _, _, eps, _ = G.flat_inputs(shape)
+    Z = np.zeros((shape.d, shape.n), np.float32)
+    run = G.FlatRun(api, shape, x, Z, Z, eps, None, None, None)
+    run.gate()
+    torch.cuda.synchronize()
+    fw = G.oracle_flat(shape, x, Z, Z, eps, None)
+    assert np.array_equal(run.topk_idx.cpu().numpy(), fw.idx)
+    assert np.all(run.sp.cpu().numpy() == np.float32(np.log(2.0)))
+
+
+def test_route_extreme_imbalance_and_empty_experts(api):
+    shape = _shape(1, T=777, n=300, k=4)
+    say("case route-extremes", shape)
+    rng = np.random.default_rng(5)
+    x, W_g, W_noise, eps, _ = G.flat_inputs(shape)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, None, None, None)
+    # (a) every token picks experts 0..3 ; (b) zipf-skewed random picks with many empty experts
+    idx_a = np.tile(np.arange(4, dtype=np.int32), (shape.T, 1))
+    p = 1.0 / np.arange(1, 101) ** 1.5
+    idx_b = np.stack([rng.choice(100, size=4, replace=False, p=p / p.sum()) for _ in range(shape.T)]).astype(np.int32) * 3
+    for idx in (idx_a, idx_b):
+        run.route(G.dev(idx))
+        torch.cuda.synchronize()
+        check_route(run, idx, shape.n)
+
+
+def _ffn_case(api, shape, tol, name):
+    say("case", name, shape)
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape)
+    fw = G.oracle_flat(shape, x, W_g, W_noise, eps, bias)
+    W1, W2 = G.device_weights(shape)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+    run.stages()
+    check_gate(run, fw, shape)
+    check_route(run, fw.idx, shape.n)
+    wf = G.oracle_weight_fn(shape)
+    y_ref = O.moe_output(x, fw.idx, fw.gates, wf, shape.n)
+    # per-assignment expert outputs
+    out = run.out_sorted.cpu().numpy()
+    inv = run.inv_perm.cpu().numpy()
+    for t in (0, shape.T // 2, shape.T - 1):
+        for s in range(shape.k):
+            e = int(fw.idx[t, s])
+            ref = O.expert_ffn(x[t:t + 1], *wf(e))[0]
+            row, mx = G.rel_errors(out[inv[t * shape.k + s]], ref)
+            assert row <= tol, (t, s, row)
+    row, mx = G.rel_errors(run.y.cpu().numpy(), y_ref)
+    say("  y errors: row-rel %.3e  max-abs-rel %.3e" % (row, mx))
+    assert row <= tol and mx <= tol
+    check_losses(run, fw)
+    # fused entry point gives the same bits as the stage-by-stage calls
+    y_stage = run.y.clone()
+    run.y.fill_(float("nan"))
+    run.fused()
+    assert torch.equal(run.y, y_stage)
+    return run
+
+
+def test_layer_cfg0_fp32(api):
+    _ffn_case(api, W.CONFIGS[0], TOL_F32, "cfg0 full")
+
+
+def test_layer_fp32_ragged_small_dims(api):
+    _ffn_case(api, _shape(0, T=150, d=64, h=96, n=5, k=2), TOL_F32, "fp32 ragged small")
+
+
+def test_layer_bf16_small(api):
+    _ffn_case(api, _shape(1, T=300, n=8, k=2), TOL_BF16, "bf16 T=300 n=8")
+
+
+def test_layer_bf16_one_token_per_expert_tail(api):
+    _ffn_case(api, _shape(1, T=65, n=70, k=1), TOL_BF16, "bf16 tiny tiles")
+
+
+def test_layer_cfg1_full(api):
+    run = _ffn_case(api, W.CONFIGS[1], TOL_BF16, "cfg1 full")
+    # determinism: a second fused run reproduces every bit
+    y1 = run.y.clone()
+    imp1 = run.importance.clone()
+    run.fused()
+    assert torch.equal(run.y, y1) and torch.equal(run.importance, imp1)
+
+
+def test_error_paths(api):
+    c = api.make_config(W.CONFIGS[0])
+    t = torch.zeros(16, device="cuda")
+    with pytest.raises(api.MoeError) as ei:
+        api.moe_combine(c, None, t, t, t)
+    assert ei.value.status == api.MOE_EINVAL
+    bad = api.make_config(W.CONFIGS[0], k=17)
+    with pytest.raises(api.MoeError):
+        api.moe_combine(bad, t, t, t, t)
