@@ -1,0 +1,205 @@
+"""Benchmark of the MoE-layer forward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path (gate -> route -> expert FFN -> combine -> losses,
+i.e. moe_layer_forward) over one batch of seeded synthetic input that is already resident in
+HBM.  Prints ONE JSON line: tokens/s, the roofline of the dominant kernel (the expert FFN,
+timed live with HIP events recorded on the launch stream inside the timed region) and the CPU
+oracle's throughput on a bounded sample of the same workload.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+STAGES = ["gate", "route", "expert_ffn", "combine", "aux_losses"]
+
+
+class HipEvents:
+    """hipEvent_t handles made with the HIP runtime that torch already loaded."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        err = self.hip.hipEventCreate(ctypes.byref(ev))
+        assert err == 0, "hipEventCreate failed: %d" % err
+        return ev.value
+
+    def elapsed_ms(self, a, b):
+        out = ctypes.c_float()
+        err = self.hip.hipEventElapsedTime(ctypes.byref(out), a, b)
+        assert err == 0, "hipEventElapsedTime failed: %d" % err
+        return out.value
+
+    def destroy(self, ev):
+        self.hip.hipEventDestroy(ev)
+
+
+def read_traffic(name):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (profiles/<name>), or None when no summary has been recorded."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def cpu_baseline(shape, sample_tokens):
+    """The oracle as it stands, timed on the host on the first `sample_tokens` tokens of the same
+    seeded workload (same gate matrices, noise and expert weights).  Expert weights are inputs:
+    they are generated before the clock starts."""
+    import numpy as np
+    import torch
+
+    import moe_workloads as W
+    from oracle import moe_oracle as O
+
+    x, W_g, W_noise, eps = W.gate_inputs(shape)
+    x, eps = x[:sample_tokens], eps[:sample_tokens]
+    w1 = W.expert_weights_all(shape, 0, range(shape.n))
+    w2 = W.expert_weights_all(shape, 1, range(shape.n))
+
+    def wf(e):
+        return w1[e].to(torch.float64).numpy(), w2[e].to(torch.float64).numpy()
+
+    t0 = time.perf_counter()
+    lg = O.noisy_logits_f32(x, W_g, W_noise, eps)
+    fw = O.gate_and_losses(lg, shape.k, shape.w_importance, shape.w_load)
+    O.routing(fw.idx, shape.n)
+    y = O.moe_output(x, fw.idx, fw.gates, wf, shape.n)
+    dt = time.perf_counter() - t0
+    assert np.isfinite(y).all()
+    try:
+        import threadpoolctl
+        threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "first %d of %d tokens of the same seeded workload, full forward "
+                      "(gate, routing, experts in fp64, combine, losses), %.1f s" % (sample_tokens, shape.T, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default 1)")
+    ap.add_argument("--cpu-sample", type=int, default=2048)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel, so that rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs the MoE layer on ONE GPU (one GPU's share of the batch at its "
+                 "real shape); --gpus %d is not available. Sharding is described in DESIGN.md." % args.gpus)
+
+    import numpy as np
+    import torch
+
+    import moe_workloads as W
+    from paper_1701_06538_amd import api     # raises if the HIP library is missing: no fallback
+    from tests import gpu_harness as G
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    shape = W.CONFIGS[args.config]
+    assert not shape.hierarchical and not shape.backward, "bench covers the flat forward workloads"
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape)
+    W1, W2 = G.device_weights(shape)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+    ws = torch.empty(api.moe_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+    hip = HipEvents()
+
+    def step(events=None):
+        api.moe_layer_forward_profiled(run.cfg, run.x, run.W_g, run.W_noise, run.bias, run.eps, run.W1,
+                                       run.W2, run.y, run.topk_idx, run.topk_gate, run.importance,
+                                       run.load, run.losses, ws, events)
+
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                                      # one elementwise copy kernel
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: K steps, each with one event pair around the expert kernel
+    K = args.steps
+    ffn_ev = [(hip.create(), hip.create()) for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step([0, 0, 0, 0, ffn_ev[i][0], ffn_ev[i][1], 0, 0, 0, 0])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ffn_ms = float(np.mean([hip.elapsed_ms(a, b) for a, b in ffn_ev]))
+
+    # second, untimed pass with every stage bracketed (diagnostics only)
+    all_ev = [[hip.create() for _ in range(10)] for _ in range(min(K, 50))]
+    for evs in all_ev:
+        step(evs)
+    torch.cuda.synchronize()
+    stage_ms = {name: float(np.mean([hip.elapsed_ms(evs[2 * i], evs[2 * i + 1]) for evs in all_ev]))
+                for i, name in enumerate(STAGES)}
+
+    counts = run.api.moe_get_workspace_layout(run.cfg)
+    lay = counts
+    cnt = ws[lay.counts:lay.counts + 4 * shape.n].view(torch.int32).cpu().numpy()
+    used = int((cnt > 0).sum())
+    A = shape.T * shape.k
+    wbytes = 2 if shape.expert_dtype == "bf16" else 4
+    # algorithmic bytes of one expert-kernel launch: every used expert's two matrices once, the
+    # gathered fp32 token rows once, the fp32 expert outputs once
+    ffn_bytes = used * 2 * shape.d * shape.h * wbytes + A * shape.d * 4 + A * shape.d * 4
+    ffn_flops = 4.0 * shape.d * shape.h * A
+    achieved = ffn_bytes / (ffn_ms * 1e-3) / 1e9
+    ms_per_step = elapsed / K * 1e3
+
+    out = {
+        "metric": "MoE-layer tokens/sec (fwd) at d=512,h=1024",
+        "value": shape.T / (elapsed / K),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.expert_dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": shape.name, "T": shape.T, "d": shape.d, "h": shape.h, "n": shape.n,
+                   "k": shape.k, "experts_used": used, "gating": "fp32 noisy top-k",
+                   "expert_math": "bf16 MFMA, fp32 accumulate" if wbytes == 2 else "fp32"},
+        "roofline": {"kernel": "ffn_bf16_kernel" if wbytes == 2 else "ffn_f32_kernel",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic("ffn_bf16_%s_pmc.txt" % shape.name.split("_")[0]),
+                     "kernel_ms": ffn_ms, "algorithmic_bytes": ffn_bytes,
+                     "mfma_tflops": ffn_flops / (ffn_ms * 1e-3) / 1e12},
+        "stage_ms": stage_ms,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, min(args.cpu_sample, shape.T))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -162,6 +162,17 @@ int moe_layer_forward(const moe_config *cfg, const float *x, const float *W_g,
                       float *topk_gate, float *importance, float *load, float *losses,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* Same as moe_layer_forward, with optional timing hooks: stage_events is a HOST array of 10
+ * hipEvent_t (as void*), or NULL; entry 2i is recorded on `stream` just before stage i and entry
+ * 2i+1 just after it, for i = 0 gate, 1 route, 2 experts, 3 combine, 4 losses.  NULL entries
+ * are skipped.  The events belong to the caller. */
+int moe_layer_forward_profiled(const moe_config *cfg, const float *x, const float *W_g,
+                               const float *W_noise, const float *gate_bias, const float *eps,
+                               const void *W1, const void *W2, float *y, int32_t *topk_idx,
+                               float *topk_gate, float *importance, float *load, float *losses,
+                               void *workspace, size_t workspace_bytes, void *const *stage_events,
+                               void *stream);
+
 #ifdef __cplusplus
 }
 #endif

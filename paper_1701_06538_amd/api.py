@@ -69,6 +69,10 @@ _moe_layer_forward = _proto("moe_layer_forward", ctypes.c_int,
                             [_cfgp] + [_vp] * 14 + [ctypes.c_size_t, _vp])
 
 
+_moe_layer_forward_profiled = _proto("moe_layer_forward_profiled", ctypes.c_int,
+                                     [_cfgp] + [_vp] * 14 + [ctypes.c_size_t, ctypes.POINTER(_vp), _vp])
+
+
 class MoeError(RuntimeError):
     def __init__(self, status):
         self.status = status
@@ -196,3 +200,16 @@ def moe_layer_forward(cfg, x, W_g, W_noise, gate_bias, eps, W1, W2, y, topk_idx,
                               _ptr(gate_bias), _ptr(eps), _ptr(W1), _ptr(W2), _ptr(y),
                               _ptr(topk_idx), _ptr(topk_gate), _ptr(importance), _ptr(load),
                               _ptr(losses), _ptr(workspace), nbytes, _stream(stream)))
+
+
+def moe_layer_forward_profiled(cfg, x, W_g, W_noise, gate_bias, eps, W1, W2, y, topk_idx, topk_gate,
+                               importance, load, losses, workspace, stage_events, stream=None):
+    """stage_events: None or a sequence of 10 hipEvent_t handles (ints, 0/None to skip)."""
+    nbytes = workspace.numel() * workspace.element_size()
+    ev = None
+    if stage_events is not None:
+        ev = (_vp * 10)(*[(e or None) for e in stage_events])
+    _check(_moe_layer_forward_profiled(ctypes.byref(cfg), _ptr(x), _ptr(W_g), _ptr(W_noise),
+                                       _ptr(gate_bias), _ptr(eps), _ptr(W1), _ptr(W2), _ptr(y),
+                                       _ptr(topk_idx), _ptr(topk_gate), _ptr(importance), _ptr(load),
+                                       _ptr(losses), _ptr(workspace), nbytes, ev, _stream(stream)))

@@ -6,19 +6,41 @@
 
 namespace moe {
 
-// out[which][i] = sum over rows r in [row_begin(i-group), row_end) of partials[r][which][i]
+// sums64[which*n + i] = sum over rows r of partials[r][which][i], added in a fixed order:
+// a block covers 32 columns x 8 row groups; each thread adds rows rg, rg+8, ... in fp64 and the
+// eight group sums are added in ascending group order.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partials,
                                                               int64_t rows, int n,
                                                               float *__restrict__ importance,
                                                               float *__restrict__ load,
                                                               double *__restrict__ sums64) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= 2 * n) return;
+    __shared__ double part[8][33];
+    const int cx = threadIdx.x & 31, rg = threadIdx.x >> 5;
+    const int i = blockIdx.x * 32 + cx;
     double acc = 0.0;
-    for (int64_t r = 0; r < rows; ++r) acc += (double)partials[r * 2 * n + i];
-    sums64[i] = acc;
-    if (i < n) importance[i] = (float)acc;
-    else load[i - n] = (float)acc;
+    if (i < 2 * n) {
+        const float *col = partials + i;
+        int64_t r = rg;
+        for (; r + 24 < rows; r += 32) {
+            const float v0 = col[r * 2 * n], v1 = col[(r + 8) * 2 * n];
+            const float v2 = col[(r + 16) * 2 * n], v3 = col[(r + 24) * 2 * n];
+            acc += (double)v0;
+            acc += (double)v1;
+            acc += (double)v2;
+            acc += (double)v3;
+        }
+        for (; r < rows; r += 8) acc += (double)col[r * 2 * n];
+    }
+    part[rg][cx] = acc;
+    __syncthreads();
+    if (rg == 0 && i < 2 * n) {
+        double s = part[0][cx];
+#pragma unroll
+        for (int q = 1; q < 8; ++q) s += part[q][cx];
+        sums64[i] = s;
+        if (i < n) importance[i] = (float)s;
+        else load[i - n] = (float)s;
+    }
 }
 
 // one block: CV^2 of v[0..n) in fp64
@@ -65,7 +87,7 @@ __global__ __launch_bounds__(256) void cv2_kernel(const double *__restrict__ sum
 int launch_aux_losses(const float *partials, int64_t rows, int n, float w_imp, float w_load,
                       float *importance, float *load, float *losses, double *sums64,
                       hipStream_t st) {
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(2 * n, 256)), dim3(256), 0,
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(2 * n, 32)), dim3(256), 0,
                        st, partials, rows, n, importance, load, sums64);
     MOE_LAUNCH_CHECK();
     hipLaunchKernelGGL(cv2_kernel, dim3(1), dim3(256), 0, st, sums64, n, w_imp, w_load, losses);

@@ -32,7 +32,6 @@ int check_config(const moe_config *cfg);
 int check_gate_level(int64_t T, int d, int n, int k);
 
 constexpr int kGateBM = 128;       // rows per block tile of the logits kernel
-constexpr int kGateRowsPerBlock = 32;  // rows per block of the top-k kernel
 constexpr int kMaxK = 8;
 constexpr int kMaxExperts = 16384;   // route histograms live in 64 KB of LDS
 constexpr int kMaxGateExperts = 2048;  // experts of one gating level (top-k kernel accumulators)

@@ -15,10 +15,14 @@
 
 namespace moe {
 
-typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 constexpr int kFfnTM = 64;  // rows per tile
+#ifndef FFN_STAGES1
+#define FFN_STAGES1 2
+#define FFN_STAGES2 2
+#endif
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
     uint32_t u = __float_as_uint(f);
@@ -32,41 +36,33 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 // XCD-aware tile order: consecutive workgroup ids go to different XCDs (one L2 each), so
 // workgroup b takes tile (b % 8) * ceil(num/8) + b / 8: tiles of one expert, which are adjacent
-// in the table, then share an L2.
+// in the table, then run at the same time behind the same L2 and the expert's weights cross
+// the fabric once.
 __device__ __forceinline__ int xcd_tile(int bid, int num_tiles) {
     const int per = (num_tiles + 7) >> 3;
     const int tile = (bid & 7) * per + (bid >> 3);
     return ((bid >> 3) < per && tile < num_tiles) ? tile : -1;
 }
 
-// One 16-deep k-step of B-operand data for BW adjacent columns: rows k0+8g .. k0+8g+7.
-template <int BW>
+// One 32-deep k-step of B-operand data for 8 adjacent columns of a row-major [K, N] bf16
+// matrix: lane (c = lane % 16, g = lane / 16) holds rows k0+8g .. k0+8g+7, columns col .. col+7,
+// fetched as eight 16-byte loads (the vector memory pipe moves 16 B per lane per instruction at
+// the same address-processing cost as 4 B, so nothing narrower is ever issued for weights).
 struct BFrag {
-    uint32_t r[8][BW / 2];
+    uint32_t r[8][4];
 };
 
-template <int BW>
-__device__ __forceinline__ void load_bfrag(BFrag<BW> &f, const uint16_t *W, int ld, int k0, int g,
-                                           int col) {
-    const uint16_t *src = W + (size_t)(k0 + 8 * g) * ld + col;
+__device__ __forceinline__ void load_bfrag(BFrag &f, const uint16_t *src, int ld, int k0) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        if constexpr (BW == 2) {
-            f.r[i][0] = *reinterpret_cast<const uint32_t *>(src + (size_t)i * ld);
-        } else if constexpr (BW == 4) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(src + (size_t)i * ld);
-            f.r[i][0] = v.x;
-            f.r[i][1] = v.y;
-        } else {
-            const uint4 v = *reinterpret_cast<const uint4 *>(src + (size_t)i * ld);
-            f.r[i][0] = v.x; f.r[i][1] = v.y; f.r[i][2] = v.z; f.r[i][3] = v.w;
-        }
+        const uint4 v = *reinterpret_cast<const uint4 *>(src + (size_t)(k0 + i) * ld);
+        f.r[i][0] = v.x; f.r[i][1] = v.y; f.r[i][2] = v.z; f.r[i][3] = v.w;
     }
 }
 
-// Column j of the block as an MFMA B operand: 8 consecutive k in one lane.
-template <int BW>
-__device__ __forceinline__ v8bf bfrag_column(const BFrag<BW> &f, int j) {
+// Column j of the block as a v_mfma_f32_16x16x32_bf16 B operand (8 consecutive k in one lane):
+// a register transpose done with byte permutes.
+__device__ __forceinline__ v8bf bfrag_column(const BFrag &f, int j) {
     const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
     uint4 o;
     o.x = __builtin_amdgcn_perm(f.r[1][j >> 1], f.r[0][j >> 1], sel);
@@ -76,44 +72,69 @@ __device__ __forceinline__ v8bf bfrag_column(const BFrag<BW> &f, int j) {
     return __builtin_bit_cast(v8bf, o);
 }
 
-// acc[rt][j] += A[rows 32rt.., K] * W[K, col0 + BW*q + j]   (A bf16 in LDS, row stride lda)
-template <int BW, int K>
-__device__ __forceinline__ void wave_gemm(v16f (&acc)[2][BW], const uint16_t *A_lds, int lda,
-                                          const uint16_t *W, int ldw, int col, int q, int g) {
-    BFrag<BW> f0, f1;
-    load_bfrag<BW>(f0, W, ldw, 0, g, col);
-    load_bfrag<BW>(f1, W, ldw, 16, g, col);
-    const uint16_t *a0p = A_lds + (size_t)q * lda + 8 * g;
-    const uint16_t *a1p = a0p + (size_t)32 * lda;
-    auto step = [&](BFrag<BW> &f, int k0) {
-        const v8bf a0 = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(a0p + k0));
-        const v8bf a1 = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(a1p + k0));
-        v8bf b[BW];
+// A software-pipelined stream of weight fragments: STAGES k-steps of 32 stay in flight per
+// wave, so the weights (read once per tile) arrive ahead of the matrix cores.  The k loop is
+// fully unrolled: with no loop-carried registers the compiler's wait counts stay exact.
+template <int K, int STAGES>
+struct WeightStream {
+    static_assert(K % (32 * STAGES) == 0, "k extent must be a multiple of the pipeline depth");
+    BFrag f[STAGES];
+    const uint16_t *src;  // this lane's first element: row 8g of the k range, column col
+    int ld;
+
+    __device__ __forceinline__ void start(const uint16_t *W, int ldw, int col, int g) {
+        src = W + (size_t)(8 * g) * ldw + col;
+        ld = ldw;
 #pragma unroll
-        for (int j = 0; j < BW; ++j) b[j] = bfrag_column<BW>(f, j);
-        if (k0 + 32 < K) load_bfrag<BW>(f, W, ldw, k0 + 32, g, col);
-#pragma unroll
-        for (int j = 0; j < BW; ++j) {
-            acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, b[j], acc[0][j], 0, 0, 0);
-            acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b[j], acc[1][j], 0, 0, 0);
-        }
-    };
-#pragma unroll 1
-    for (int k0 = 0; k0 < K; k0 += 32) {
-        step(f0, k0);
-        step(f1, k0 + 16);
+        for (int s = 0; s < STAGES; ++s) load_bfrag(f[s], src, ld, 32 * s);
     }
-}
+
+    // acc[rt][j] += A[16rt + c, 0:K] * W[0:K, col + j]   (A bf16 in LDS, row stride lda)
+    __device__ __forceinline__ void run(v4f (&acc)[4][8], const uint16_t *A_lds, int lda, int c,
+                                        int g) {
+        const uint16_t *ap = A_lds + (size_t)c * lda + 8 * g;
+        auto step = [&](int s, int kk, bool reload) {
+            v8bf a[4];
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt)
+                a[rt] = __builtin_bit_cast(
+                    v8bf, *reinterpret_cast<const uint4 *>(ap + (size_t)(16 * rt) * lda + kk));
+            v8bf b[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) b[j] = bfrag_column(f[s], j);
+            if (reload) load_bfrag(f[s], src, ld, kk + 32 * STAGES);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int rt = 0; rt < 4; ++rt)
+                    acc[rt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b[j], acc[rt][j], 0, 0, 0);
+        };
+#pragma unroll
+        for (int k0 = 0; k0 < K - 32 * STAGES; k0 += 32 * STAGES) {
+#pragma unroll
+            for (int s = 0; s < STAGES; ++s) step(s, k0 + 32 * s, true);
+        }
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s) step(s, K - 32 * STAGES + 32 * s, false);
+    }
+};
+
+#ifdef MOE_FFN_TIMING
+__device__ long long g_ffn_timing[1024 * 8 * 8];
+#define FFN_STAMP(i) do { if (lane == 0 && tile < 1024) g_ffn_timing[(tile * 8 + wave) * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define FFN_STAMP(i) do { } while (0)
+#endif
 
 template <int D, int H>
 __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
     constexpr int TM = kFfnTM;
     constexpr int XS = D + 8;   // bf16 elements per LDS row of the x tile
     constexpr int HS = H + 8;   // ... of the hidden tile (aliases the x tile)
-    constexpr int BW1 = H / 256;  // 8 waves x 32 lanes x BW1 columns = H
-    constexpr int BW2 = D / 256;
-    static_assert(BW1 == 2 || BW1 == 4 || BW1 == 8, "hidden size");
-    static_assert(BW2 == 2 || BW2 == 4 || BW2 == 8, "model width");
+    constexpr int PS = D + 4;   // fp32 elements per LDS row of the split-k partial sums
+    static_assert(H == 8 * 128, "eight waves own 128 hidden columns each");
+    static_assert(D == 4 * 128, "four column groups of 128 outputs, two k halves");
+    static_assert(TM * PS * 4 <= TM * HS * 2, "partial sums reuse the hidden tile's LDS");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
 
     const int tile = xcd_tile(blockIdx.x, *p.num_tiles);
@@ -122,88 +143,130 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
     const int row0 = p.tile_row0[tile];
     const int rows = min(TM, p.offsets[e + 1] - row0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int q = lane & 31, g = lane >> 5;
-
-    // gather the tile's token rows, round to bf16 (nearest even)
-    {
-        constexpr int F4 = D / 4;                 // float4 per row
-        constexpr int RPP = 512 / F4;             // rows per pass
-        const int c4 = tid % F4, rr = tid / F4;
-#pragma unroll 4
-        for (int r = rr; r < TM; r += RPP) {
-            uint2 packed = make_uint2(0u, 0u);
-            if (r < rows) {
-                const int tok = p.perm[row0 + r] / p.k;
-                const float4 v = *reinterpret_cast<const float4 *>(p.x + (size_t)tok * D + 4 * c4);
-                packed.x = pack_bf16x2(v.x, v.y);
-                packed.y = pack_bf16x2(v.z, v.w);
-            }
-            *reinterpret_cast<uint2 *>(lds + (size_t)r * XS + 4 * c4) = packed;
-        }
-    }
-    __syncthreads();
+    const int c = lane & 15, g = lane >> 4;
 
     const uint16_t *W1 = (const uint16_t *)p.W1 + (size_t)e * D * H;
     const uint16_t *W2 = (const uint16_t *)p.W2 + (size_t)e * H * D;
 
-    // hidden = relu(x W1): wave owns hidden columns [32*BW1*wave, +32*BW1)
+    FFN_STAMP(0);
+    // gather the tile's token rows (rounded to bf16, nearest even).  Order of issue: row ids,
+    // then the first weight fragments (they do not depend on x), then the token rows, so the
+    // two dependent round trips of the gather overlap the weights' first trip.
+    WeightStream<D, FFN_STAGES1> s1;
+    const int col1 = 128 * wave + 8 * c;
     {
-        v16f acc[2][BW1];
+        constexpr int F4 = D / 4;                 // float4 per row
+        constexpr int RPP = 512 / F4;             // rows per pass
+        constexpr int PASSES = TM / RPP;
+        const int c4 = tid % F4, rr = tid / F4;
+        int tok[PASSES];
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+        for (int i = 0; i < PASSES; ++i) {
+            const int r = min(rr + i * RPP, rows - 1);      // clamped: padding rows re-read a valid row
+            tok[i] = p.perm[row0 + r];
+        }
+        s1.start(W1, H, col1, g);
+        float4 v[PASSES];
 #pragma unroll
-            for (int j = 0; j < BW1; ++j)
+        for (int i = 0; i < PASSES; ++i) {
+            const int t = p.k_shift >= 0 ? (tok[i] >> p.k_shift) : (tok[i] / p.k);
+            v[i] = *reinterpret_cast<const float4 *>(p.x + (size_t)t * D + 4 * c4);
+        }
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[rt][j][r] = 0.f;
-        const int col = 32 * BW1 * wave + BW1 * q;
-        wave_gemm<BW1, D>(acc, lds, XS, W1, H, col, q, g);
+        for (int i = 0; i < PASSES; ++i) {
+            const int r = rr + i * RPP;
+            const bool live = r < rows;
+            *reinterpret_cast<uint2 *>(lds + (size_t)r * XS + 4 * c4) =
+                make_uint2(live ? pack_bf16x2(v[i].x, v[i].y) : 0u, live ? pack_bf16x2(v[i].z, v[i].w) : 0u);
+        }
+    }
+    __syncthreads();
+    FFN_STAMP(1);
+
+    // hidden = relu(x W1): wave w owns hidden columns [128w, 128w+128)
+    const int cg = wave & 3, kh = wave >> 2;
+    WeightStream<H / 2, FFN_STAGES2> s2;
+    const int col2 = 128 * cg + 8 * c;
+    {
+        v4f acc[4][8];
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[rt][j] = v4f{0.f, 0.f, 0.f, 0.f};
+        s1.run(acc, lds, XS, c, g);
+        FFN_STAMP(2);
+        // second matrix starts streaming during the hand-over below
+        s2.start(W2 + (size_t)(H / 2) * kh * D, D, col2, g);
         __syncthreads();  // every wave is done reading the x tile; the hidden tile overwrites it
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+        for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = 32 * rt + 8 * (r / 4) + 4 * g + (r % 4);
-                uint32_t w[BW1 / 2];
-#pragma unroll
-                for (int j = 0; j < BW1; j += 2)
-                    w[j / 2] = pack_bf16x2(fmaxf(acc[rt][j][r], 0.f), fmaxf(acc[rt][j + 1][r], 0.f));
-                uint16_t *dst = lds + (size_t)row * HS + col;
-                if constexpr (BW1 == 2) *reinterpret_cast<uint32_t *>(dst) = w[0];
-                else if constexpr (BW1 == 4) *reinterpret_cast<uint2 *>(dst) = make_uint2(w[0], w[1]);
-                else *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+            for (int r = 0; r < 4; ++r) {
+                const int row = 16 * rt + 4 * g + r;
+                uint4 w;
+                w.x = pack_bf16x2(fmaxf(acc[rt][0][r], 0.f), fmaxf(acc[rt][1][r], 0.f));
+                w.y = pack_bf16x2(fmaxf(acc[rt][2][r], 0.f), fmaxf(acc[rt][3][r], 0.f));
+                w.z = pack_bf16x2(fmaxf(acc[rt][4][r], 0.f), fmaxf(acc[rt][5][r], 0.f));
+                w.w = pack_bf16x2(fmaxf(acc[rt][6][r], 0.f), fmaxf(acc[rt][7][r], 0.f));
+                *reinterpret_cast<uint4 *>(lds + (size_t)row * HS + col1) = w;
             }
         __syncthreads();
+        FFN_STAMP(3);
     }
 
-    // out = hidden W2: wave owns output columns [32*BW2*wave, +32*BW2)
+    // out = hidden W2: wave (cg, kh) owns output columns [128cg, +128) and hidden units
+    // [512kh, +512); the two k halves are added through LDS.
     {
-        v16f acc[2][BW2];
+        v4f acc[4][8];
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+        for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
-            for (int j = 0; j < BW2; ++j)
+            for (int j = 0; j < 8; ++j) acc[rt][j] = v4f{0.f, 0.f, 0.f, 0.f};
+        s2.run(acc, lds + (H / 2) * kh, HS, c, g);
+        FFN_STAMP(4);
+        __syncthreads();  // the hidden tile is dead; its LDS now carries the partial sums
+        float *part = reinterpret_cast<float *>(lds);
+        if (kh == 1) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[rt][j][r] = 0.f;
-        const int col = 32 * BW2 * wave + BW2 * q;
-        wave_gemm<BW2, H>(acc, lds, HS, W2, D, col, q, g);
+            for (int rt = 0; rt < 4; ++rt)
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = 32 * rt + 8 * (r / 4) + 4 * g + (r % 4);
-                if (row >= rows) continue;
-                float *dst = p.out + (size_t)(row0 + row) * D + col;
-                if constexpr (BW2 == 2) {
-                    *reinterpret_cast<float2 *>(dst) = make_float2(acc[rt][0][r], acc[rt][1][r]);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < BW2; j += 4)
-                        *reinterpret_cast<float4 *>(dst + j) = make_float4(
-                            acc[rt][j][r], acc[rt][j + 1][r], acc[rt][j + 2][r], acc[rt][j + 3][r]);
+                for (int r = 0; r < 4; ++r) {
+                    float *dst = part + (size_t)(16 * rt + 4 * g + r) * PS + col2;
+                    *reinterpret_cast<float4 *>(dst) =
+                        make_float4(acc[rt][0][r], acc[rt][1][r], acc[rt][2][r], acc[rt][3][r]);
+                    *reinterpret_cast<float4 *>(dst + 4) =
+                        make_float4(acc[rt][4][r], acc[rt][5][r], acc[rt][6][r], acc[rt][7][r]);
                 }
-            }
+        }
+        __syncthreads();
+        FFN_STAMP(5);
+        if (kh == 0) {
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = 16 * rt + 4 * g + r;
+                    if (row >= rows) continue;
+                    const float *src = part + (size_t)row * PS + col2;
+                    const float4 p0 = *reinterpret_cast<const float4 *>(src);
+                    const float4 p1 = *reinterpret_cast<const float4 *>(src + 4);
+                    float *dst = p.out + (size_t)(row0 + row) * D + col2;
+                    *reinterpret_cast<float4 *>(dst) =
+                        make_float4(acc[rt][0][r] + p0.x, acc[rt][1][r] + p0.y, acc[rt][2][r] + p0.z,
+                                    acc[rt][3][r] + p0.w);
+                    *reinterpret_cast<float4 *>(dst + 4) =
+                        make_float4(acc[rt][4][r] + p1.x, acc[rt][5][r] + p1.y, acc[rt][6][r] + p1.z,
+                                    acc[rt][7][r] + p1.w);
+                }
+        }
+        FFN_STAMP(6);
     }
 }
+#ifdef MOE_FFN_TIMING
+extern "C" int moe_debug_read_ffn_timing(long long *host_out) {
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_ffn_timing), sizeof(long long) * 1024 * 8 * 8);
+}
+#endif
 
 // ---------------------------------------------------------------------------------------
 // fp32 experts: C[rows, N] = act(A[rows, K] W_e[K, N]) per row tile; A rows either gathered
@@ -337,5 +400,6 @@ extern "C" int moe_expert_ffn(const moe_config *cfg, const float *x, const int32
     a.tile_expert = tile_expert; a.tile_row0 = tile_row0; a.num_tiles = num_tiles;
     a.W1 = W1; a.W2 = W2; a.out = out_sorted; a.hidden = (float *)workspace;
     a.d = cfg->d; a.h = cfg->h; a.k = cfg->k;
+    a.k_shift = (cfg->k & (cfg->k - 1)) == 0 ? __builtin_ctz(cfg->k) : -1;
     return launch_expert_ffn(cfg, a, moe_max_tiles(cfg), (hipStream_t)stream);
 }

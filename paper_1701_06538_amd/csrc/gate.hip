@@ -223,8 +223,8 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(TopkArgs p) {
     extern __shared__ float lds_acc[];  // [4][2][n]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = p.n, k = p.k;
-    constexpr int RPB = kGateRowsPerBlock;
-    constexpr int SUB = kGateBM / RPB;
+    const int RPB = p.rows_per_block;
+    const int SUB = kGateBM / RPB;
 
     int64_t rb, re;
     if (p.tile_row0) {
@@ -398,9 +398,18 @@ int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st) {
 
 using namespace moe;
 
+namespace moe {
+// Rows one top-k workgroup (4 waves) walks: few rows per block when the batch is small, so that
+// every CU holds several blocks and row latency is hidden; more when the partial-sum traffic
+// (one [2][n] row per block) would otherwise rival the logits themselves.
+int gate_rows_per_block(int64_t rows, int n) {
+    return (rows * (int64_t)n <= ((int64_t)1 << 22)) ? 8 : 32;
+}
+}  // namespace moe
+
 extern "C" int64_t moe_gate_partial_rows(const moe_config *cfg) {
     if (!cfg || cfg->T <= 0) return 0;
-    return ceil_div(cfg->T, kGateRowsPerBlock);
+    return ceil_div(cfg->T, gate_rows_per_block(cfg->T, cfg->n));
 }
 
 extern "C" int moe_gate(const moe_config *cfg, const float *x, const float *W_g,
@@ -429,5 +438,6 @@ extern "C" int moe_gate(const moe_config *cfg, const float *x, const float *W_g,
     ta.cleanb = cleanb; ta.sp = sp; ta.eps = eps;
     ta.R = cfg->T; ta.n = cfg->n; ta.k = cfg->k;
     ta.idx = topk_idx; ta.gate = topk_gate; ta.next_idx = next_idx; ta.partials = partials;
+    ta.rows_per_block = gate_rows_per_block(cfg->T, cfg->n);
     return launch_gate_topk(ta, moe_gate_partial_rows(cfg), (hipStream_t)stream);
 }

@@ -24,7 +24,7 @@ int workspace_layout(const moe_config *cfg, moe_workspace_layout *L) {
     L->cleanb = take(gate_rows * gate_n * 4);
     L->sp = take(gate_rows * gate_n * 4);
     L->next_idx = take(gate_rows * 4);
-    L->partials = take((size_t)(ceil_div((int64_t)gate_rows, kGateRowsPerBlock) + 4 * (cfg->a > 0 ? cfg->a : 0)) * 2 * gate_n * 4);
+    L->partials = take((size_t)(ceil_div((int64_t)gate_rows, gate_rows_per_block((int64_t)gate_rows, (int)gate_n)) + 16 * (cfg->a > 0 ? cfg->a : 0)) * 2 * gate_n * 4);
     L->counts = take(n * 4);
     L->offsets = take((n + 1) * 4);
     L->perm = take(A * 4);
@@ -71,11 +71,19 @@ extern "C" size_t moe_workspace_bytes(const moe_config *cfg) {
     return L.total;
 }
 
-extern "C" int moe_layer_forward(const moe_config *cfg, const float *x, const float *W_g,
-                                 const float *W_noise, const float *gate_bias, const float *eps,
-                                 const void *W1, const void *W2, float *y, int32_t *topk_idx,
-                                 float *topk_gate, float *importance, float *load, float *losses,
-                                 void *workspace, size_t workspace_bytes, void *stream) {
+static int record(void *const *ev, int i, void *stream) {
+    if (!ev || !ev[i]) return MOE_OK;
+    MOE_HIP_TRY(hipEventRecord((hipEvent_t)ev[i], (hipStream_t)stream));
+    return MOE_OK;
+}
+
+extern "C" int moe_layer_forward_profiled(const moe_config *cfg, const float *x, const float *W_g,
+                                          const float *W_noise, const float *gate_bias,
+                                          const float *eps, const void *W1, const void *W2,
+                                          float *y, int32_t *topk_idx, float *topk_gate,
+                                          float *importance, float *load, float *losses,
+                                          void *workspace, size_t workspace_bytes,
+                                          void *const *stage_events, void *stream) {
     moe_workspace_layout L;
     int st = workspace_layout(cfg, &L);
     if (st != MOE_OK) return st;
@@ -95,17 +103,31 @@ extern "C" int moe_layer_forward(const moe_config *cfg, const float *x, const fl
     int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
     int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
     float *out_sorted = (float *)(ws + L.out_sorted);
+    void *const *ev = stage_events;
 
-    st = moe_gate(cfg, x, W_g, W_noise, gate_bias, eps, topk_idx, topk_gate, cleanb, sp, next_idx,
-                  partials, stream);
-    if (st != MOE_OK) return st;
-    st = moe_route(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0, num_tiles,
-                   ws + L.route_ws, stream);
-    if (st != MOE_OK) return st;
-    st = moe_expert_ffn(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2, out_sorted,
-                        ws + L.ffn_ws, stream);
-    if (st != MOE_OK) return st;
-    st = moe_combine(cfg, out_sorted, topk_gate, inv_perm, y, stream);
-    if (st != MOE_OK) return st;
-    return moe_aux_losses(cfg, partials, importance, load, losses, ws + L.aux_ws, stream);
+#define MOE_STAGE(i, call)                                        \
+    if ((st = record(ev, 2 * (i), stream)) != MOE_OK) return st;  \
+    if ((st = (call)) != MOE_OK) return st;                       \
+    if ((st = record(ev, 2 * (i) + 1, stream)) != MOE_OK) return st;
+
+    MOE_STAGE(0, moe_gate(cfg, x, W_g, W_noise, gate_bias, eps, topk_idx, topk_gate, cleanb, sp,
+                          next_idx, partials, stream))
+    MOE_STAGE(1, moe_route(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0,
+                           num_tiles, ws + L.route_ws, stream))
+    MOE_STAGE(2, moe_expert_ffn(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2,
+                                out_sorted, ws + L.ffn_ws, stream))
+    MOE_STAGE(3, moe_combine(cfg, out_sorted, topk_gate, inv_perm, y, stream))
+    MOE_STAGE(4, moe_aux_losses(cfg, partials, importance, load, losses, ws + L.aux_ws, stream))
+#undef MOE_STAGE
+    return MOE_OK;
+}
+
+extern "C" int moe_layer_forward(const moe_config *cfg, const float *x, const float *W_g,
+                                 const float *W_noise, const float *gate_bias, const float *eps,
+                                 const void *W1, const void *W2, float *y, int32_t *topk_idx,
+                                 float *topk_gate, float *importance, float *load, float *losses,
+                                 void *workspace, size_t workspace_bytes, void *stream) {
+    return moe_layer_forward_profiled(cfg, x, W_g, W_noise, gate_bias, eps, W1, W2, y, topk_idx,
+                                      topk_gate, importance, load, losses, workspace,
+                                      workspace_bytes, nullptr, stream);
 }

@@ -143,7 +143,87 @@ __global__ __launch_bounds__(64) void route_scatter_kernel(RouteArgs p, int nbit
     }
 }
 
+// Whole route in one workgroup (16 waves) for small problems: per-wave LDS histograms over
+// contiguous slices of the assignment list, a scan over (expert, wave), then the same ordered
+// ballot-ranked scatter.  One launch instead of four.
+__global__ __launch_bounds__(1024) void route_small_kernel(RouteArgs p, int nbits, int slice) {
+    extern __shared__ int lds_h[];  // [16][n]
+    __shared__ int wave_sums[16];
+    const int n = p.n, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < 16 * n; i += 1024) lds_h[i] = 0;
+    __syncthreads();
+    int *my = lds_h + wave * n;
+    const int64_t a0 = (int64_t)wave * slice;
+    const int64_t a1 = min(a0 + slice, p.A);
+    for (int64_t a = a0 + lane; a < a1; a += 64) {
+        const int e = p.idx[a];
+        if (e >= 0 && e < n) atomicAdd(&my[e], 1);
+    }
+    __syncthreads();
+    // one expert per thread (n <= 512 here): exclusive scan over the 16 waves, then over experts
+    const int e = tid;
+    int cnt = 0;
+    if (e < n) {
+        for (int w = 0; w < 16; ++w) {
+            const int v = lds_h[w * n + e];
+            lds_h[w * n + e] = cnt;
+            cnt += v;
+        }
+    }
+    const int TM = p.tile_rows;
+    const int tiles = (cnt + TM - 1) / TM;
+    const int inc_rows = block_inclusive_scan(cnt, wave_sums);
+    const int inc_tiles = block_inclusive_scan(tiles, wave_sums);
+    if (e < n) {
+        const int off = inc_rows - cnt, toff = inc_tiles - tiles;
+        p.counts[e] = cnt;
+        p.offsets[e] = off;
+        if (p.tile_offsets) p.tile_offsets[e] = toff;
+        for (int w = 0; w < 16; ++w) lds_h[w * n + e] += off;
+        for (int j = 0; j < tiles; ++j) {
+            p.tile_expert[toff + j] = e;
+            p.tile_row0[toff + j] = off + j * TM;
+        }
+    }
+    if (tid == 1023) {
+        p.offsets[n] = inc_rows;
+        if (p.tile_offsets) p.tile_offsets[n] = inc_tiles;
+        p.num_tiles[0] = inc_tiles;
+    }
+    __syncthreads();
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int64_t s = a0; s < a1; s += 64) {
+        const int64_t a = s + lane;
+        int ex = (a < a1) ? p.idx[a] : -1;
+        const bool active = ex >= 0 && ex < n;
+        unsigned long long same = __ballot(active);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (ex >> b) & 1;
+            const unsigned long long bal = __ballot(active && bit);
+            same &= bit ? bal : ~bal;
+        }
+        if (active) {
+            const int rank = __popcll(same & lt_mask);
+            const int c = __popcll(same);
+            const int before = my[ex];
+            const int pos = before + rank;
+            p.perm[pos] = (int32_t)a;
+            p.inv_perm[a] = pos;
+            if (rank == c - 1) my[ex] = before + c;  // issued after every lane's read
+        }
+    }
+}
+
 int launch_route(RouteArgs a, hipStream_t st) {
+    int nbits = 0;
+    while ((1 << nbits) < a.n) ++nbits;
+    if (a.n <= 512 && a.A <= 65536) {
+        const int slice = (int)(ceil_div(ceil_div(a.A, 16), 64) * 64);
+        hipLaunchKernelGGL(route_small_kernel, dim3(1), dim3(1024), (size_t)16 * a.n * sizeof(int),
+                           st, a, nbits, slice);
+        MOE_LAUNCH_CHECK();
+        return MOE_OK;
+    }
     route_chunking(a.A, &a.chunk, &a.num_chunks);
     const size_t lds = (size_t)a.n * sizeof(int);
     if (a.num_chunks > 0) {
@@ -155,8 +235,6 @@ int launch_route(RouteArgs a, hipStream_t st) {
     hipLaunchKernelGGL(route_offsets_kernel, dim3(1), dim3(1024), 0, st, a);
     MOE_LAUNCH_CHECK();
     if (a.num_chunks > 0) {
-        int nbits = 0;
-        while ((1 << nbits) < a.n) ++nbits;
         hipLaunchKernelGGL(route_scatter_kernel, dim3(a.num_chunks), dim3(64), lds, st, a, nbits);
         MOE_LAUNCH_CHECK();
     }

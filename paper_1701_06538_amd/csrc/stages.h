@@ -31,6 +31,7 @@ struct TopkArgs {
     float *gate;               // [*][k]
     int32_t *next_idx;         // [*] or null
     float *partials;           // [gridDim.x][2][n]
+    int rows_per_block;        // 8 or 32 (divides the 128-row logits tile)
 };
 
 struct RouteArgs {
@@ -55,10 +56,12 @@ struct FfnArgs {
     float *out;               // [A,d]
     float *hidden;            // fp32 path workspace [A,h]
     int d, h, k;
+    int k_shift;              // log2(k) when k is a power of two, else -1
 };
 
 int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st);
 int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st);
+int gate_rows_per_block(int64_t rows, int n);
 size_t route_ws_bytes(int64_t A, int n);
 int launch_route(RouteArgs a, hipStream_t st);
 int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles, hipStream_t st);

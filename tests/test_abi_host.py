@@ -87,7 +87,7 @@ def test_workspace_layout_is_ordered_aligned_and_sized(api):
     assert L.total == api.moe_workspace_bytes(cfg)
     assert L.total >= L.out_sorted + 8192 * 4 * 512 * 4
     assert api.moe_max_tiles(cfg) == 8192 * 4 // api.moe_tile_rows(cfg) + 256
-    assert api.moe_gate_partial_rows(cfg) == 8192 // 32
+    assert api.moe_gate_partial_rows(cfg) == 8192 // 8
     f32 = api.make_config(T=256, d=512, h=1024, n=16, k=4, expert_dtype=api.MOE_DTYPE_F32)
     assert api.moe_ffn_workspace_bytes(f32) == 256 * 4 * 1024 * 4
     assert api.moe_ffn_workspace_bytes(cfg) == 0
