@@ -6,30 +6,29 @@
 
 namespace moe {
 
-// sums64[which*n + i] = sum over rows r of partials[r][which][i], added in a fixed order:
-// a block covers 32 columns x 8 row groups; each thread adds rows rg, rg+8, ... in fp64 and the
-// eight group sums are added in ascending group order.
+// Level 1: level2[chunk][i] = sum of partials[r][i] over the chunk's 128 rows (i runs over the
+// 2n importance|load columns).  A block covers 32 columns x 8 row groups, every thread adds its
+// 16 rows (all loads independent) in fp64, the eight group sums are added in ascending order.
+constexpr int kAuxChunkRows = 128;
+
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partials,
                                                               int64_t rows, int n,
-                                                              float *__restrict__ importance,
-                                                              float *__restrict__ load,
-                                                              double *__restrict__ sums64) {
+                                                              double *__restrict__ level2) {
     __shared__ double part[8][33];
     const int cx = threadIdx.x & 31, rg = threadIdx.x >> 5;
     const int i = blockIdx.x * 32 + cx;
+    const int64_t r0 = (int64_t)blockIdx.y * kAuxChunkRows;
     double acc = 0.0;
     if (i < 2 * n) {
         const float *col = partials + i;
-        int64_t r = rg;
-        for (; r + 24 < rows; r += 32) {
-            const float v0 = col[r * 2 * n], v1 = col[(r + 8) * 2 * n];
-            const float v2 = col[(r + 16) * 2 * n], v3 = col[(r + 24) * 2 * n];
-            acc += (double)v0;
-            acc += (double)v1;
-            acc += (double)v2;
-            acc += (double)v3;
+        float v[kAuxChunkRows / 8];
+#pragma unroll
+        for (int q = 0; q < kAuxChunkRows / 8; ++q) {
+            const int64_t r = r0 + rg + 8 * q;
+            v[q] = r < rows ? col[r * 2 * n] : 0.f;
         }
-        for (; r < rows; r += 8) acc += (double)col[r * 2 * n];
+#pragma unroll
+        for (int q = 0; q < kAuxChunkRows / 8; ++q) acc += (double)v[q];
     }
     part[rg][cx] = acc;
     __syncthreads();
@@ -37,10 +36,24 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
         double s = part[0][cx];
 #pragma unroll
         for (int q = 1; q < 8; ++q) s += part[q][cx];
-        sums64[i] = s;
-        if (i < n) importance[i] = (float)s;
-        else load[i - n] = (float)s;
+        level2[(size_t)blockIdx.y * 2 * n + i] = s;
     }
+}
+
+// Level 2 (one block): add the chunk sums in ascending chunk order, publish Importance and Load,
+// then the two CV^2.
+__global__ __launch_bounds__(256) void finish_sums_kernel(const double *__restrict__ level2,
+                                                          int chunks, int n,
+                                                          double *__restrict__ sums64,
+                                                          float *__restrict__ importance,
+                                                          float *__restrict__ load) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= 2 * n) return;
+    double s = 0.0;
+    for (int c = 0; c < chunks; ++c) s += level2[(size_t)c * 2 * n + i];
+    sums64[i] = s;
+    if (i < n) importance[i] = (float)s;
+    else load[i - n] = (float)s;
 }
 
 // one block: CV^2 of v[0..n) in fp64
@@ -85,14 +98,24 @@ __global__ __launch_bounds__(256) void cv2_kernel(const double *__restrict__ sum
 }
 
 int launch_aux_losses(const float *partials, int64_t rows, int n, float w_imp, float w_load,
-                      float *importance, float *load, float *losses, double *sums64,
-                      hipStream_t st) {
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(2 * n, 32)), dim3(256), 0,
-                       st, partials, rows, n, importance, load, sums64);
+                      float *importance, float *load, float *losses, double *ws, hipStream_t st) {
+    const int chunks = (int)ceil_div(rows > 0 ? rows : 1, kAuxChunkRows);
+    double *sums64 = ws;                  // [2n]
+    double *level2 = ws + 2 * (size_t)n;  // [chunks][2n]
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(2 * n, 32), (unsigned)chunks),
+                       dim3(256), 0, st, partials, rows, n, level2);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(finish_sums_kernel, dim3((unsigned)ceil_div(2 * n, 256)), dim3(256), 0, st,
+                       level2, chunks, n, sums64, importance, load);
     MOE_LAUNCH_CHECK();
     hipLaunchKernelGGL(cv2_kernel, dim3(1), dim3(256), 0, st, sums64, n, w_imp, w_load, losses);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
+}
+
+size_t aux_ws_bytes(int64_t rows, int n) {
+    const int64_t chunks = ceil_div(rows > 0 ? rows : 1, kAuxChunkRows);
+    return (size_t)(2 * (size_t)n * (1 + chunks)) * sizeof(double);
 }
 
 }  // namespace moe

@@ -372,6 +372,10 @@ int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
     } else if (a.n <= 64) {
         dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 64));
         hipLaunchKernelGGL(gate_logits_kernel<2>, grid, dim3(256), 0, st, a);
+    } else if (row_tiles * 2 * ceil_div(a.n, 128) < 1024) {
+        // few tiles: narrower column tiles so that every CU holds at least two workgroups
+        dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 64));
+        hipLaunchKernelGGL(gate_logits_kernel<2>, grid, dim3(256), 0, st, a);
     } else {
         dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 128));
         hipLaunchKernelGGL(gate_logits_kernel<4>, grid, dim3(256), 0, st, a);

@@ -35,7 +35,7 @@ int workspace_layout(const moe_config *cfg, moe_workspace_layout *L) {
     L->route_ws = take(route_ws_bytes((int64_t)A, cfg->n));
     L->out_sorted = take(A * (size_t)cfg->d * 4);
     L->ffn_ws = take(moe_ffn_workspace_bytes(cfg));
-    L->aux_ws = take(2 * n * 8);
+    L->aux_ws = take(aux_ws_bytes(cfg->a > 0 ? (int64_t)T * cfg->k_primary : moe_gate_partial_rows(cfg), cfg->n));
     L->total = off;
     return MOE_OK;
 }
@@ -46,7 +46,7 @@ using namespace moe;
 
 extern "C" size_t moe_aux_workspace_bytes(const moe_config *cfg) {
     if (check_config(cfg) != MOE_OK) return 0;
-    return (size_t)2 * cfg->n * sizeof(double);
+    return aux_ws_bytes(moe_gate_partial_rows(cfg), cfg->n);
 }
 
 extern "C" int moe_aux_losses(const moe_config *cfg, const float *partials, float *importance,

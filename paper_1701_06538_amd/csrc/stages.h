@@ -68,7 +68,8 @@ int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles
 int launch_combine(const float *out_sorted, const float *gate, const int32_t *inv_perm, float *y,
                    int64_t T, int d, int k, hipStream_t st);
 int launch_aux_losses(const float *partials, int64_t rows, int n, float w_imp, float w_load,
-                      float *importance, float *load, float *losses, double *sums64,
+                      float *importance, float *load, float *losses, double *ws,
                       hipStream_t st);
+size_t aux_ws_bytes(int64_t rows, int n);
 
 }  // namespace moe
