@@ -52,10 +52,14 @@ struct BFrag {
     uint32_t r[8][4];
 };
 
-__device__ __forceinline__ void load_bfrag(BFrag &f, const uint16_t *src, int ld, int k0) {
+template <int LD_BYTES>
+__device__ __forceinline__ void load_bfrag(BFrag &f, const char *base, uint32_t lane_off, int k0) {
+    // uniform base + compile-time row offset + 32-bit lane offset: scalar-base addressing, so
+    // the whole stream needs one address VGPR
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(src + (size_t)(k0 + i) * ld);
+        const char *row = base + (size_t)(k0 + i) * LD_BYTES;
+        const uint4 v = *reinterpret_cast<const uint4 *>(row + lane_off);
         f.r[i][0] = v.x; f.r[i][1] = v.y; f.r[i][2] = v.z; f.r[i][3] = v.w;
     }
 }
@@ -75,39 +79,51 @@ __device__ __forceinline__ v8bf bfrag_column(const BFrag &f, int j) {
 // A software-pipelined stream of weight fragments: STAGES k-steps of 32 stay in flight per
 // wave, so the weights (read once per tile) arrive ahead of the matrix cores.  The k loop is
 // fully unrolled: with no loop-carried registers the compiler's wait counts stay exact.
-template <int K, int STAGES>
+template <int K, int LD, int STAGES>   // LD: elements per row of the weight matrix
 struct WeightStream {
     static_assert(K % (32 * STAGES) == 0, "k extent must be a multiple of the pipeline depth");
     BFrag f[STAGES];
-    const uint16_t *src;  // this lane's first element: row 8g of the k range, column col
-    int ld;
+    const char *base;    // the matrix (uniform)
+    uint32_t lane_off;   // this lane's first element: row 8g of the k range, column col (bytes)
 
-    __device__ __forceinline__ void start(const uint16_t *W, int ldw, int col, int g) {
-        src = W + (size_t)(8 * g) * ldw + col;
-        ld = ldw;
+    __device__ __forceinline__ void start(const uint16_t *W, int col, int g) {
+        base = reinterpret_cast<const char *>(W);
+        lane_off = (uint32_t)((8 * g) * LD + col) * 2u;
 #pragma unroll
-        for (int s = 0; s < STAGES; ++s) load_bfrag(f[s], src, ld, 32 * s);
+        for (int s = 0; s < STAGES; ++s) load_bfrag<LD * 2>(f[s], base, lane_off, 32 * s);
     }
 
     // acc[rt][j] += A[16rt + c, 0:K] * W[0:K, col + j]   (A bf16 in LDS, row stride lda)
     __device__ __forceinline__ void run(v4f (&acc)[4][8], const uint16_t *A_lds, int lda, int c,
                                         int g) {
         const uint16_t *ap = A_lds + (size_t)c * lda + 8 * g;
-        auto step = [&](int s, int kk, bool reload) {
-            v8bf a[4];
+        auto mma_half = [&](const v8bf (&b)[4], int j0, int kk) {
 #pragma unroll
-            for (int rt = 0; rt < 4; ++rt)
-                a[rt] = __builtin_bit_cast(
+            for (int rt = 0; rt < 4; ++rt) {
+                const v8bf a = __builtin_bit_cast(
                     v8bf, *reinterpret_cast<const uint4 *>(ap + (size_t)(16 * rt) * lda + kk));
-            v8bf b[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) b[j] = bfrag_column(f[s], j);
-            if (reload) load_bfrag(f[s], src, ld, kk + 32 * STAGES);
+                for (int j = 0; j < 4; ++j)
+                    acc[rt][j0 + j] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[j], acc[rt][j0 + j], 0, 0, 0);
+            }
+        };
+        auto step = [&](int s, int kk, bool reload) {
+            // first four columns: transpose, multiply
+            v8bf b[4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int j = 0; j < 4; ++j) b[j] = bfrag_column(f[s], j);
+            mma_half(b, 0, kk);
+            // last four columns: transpose (the fragment's last reads), refill the fragment's
+            // registers at once so the loads have ~STAGES k-steps of matrix work to arrive,
+            // then multiply
 #pragma unroll
-                for (int rt = 0; rt < 4; ++rt)
-                    acc[rt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b[j], acc[rt][j], 0, 0, 0);
+            for (int j = 0; j < 4; ++j) b[j] = bfrag_column(f[s], 4 + j);
+            __builtin_amdgcn_sched_barrier(0);
+            if (reload) load_bfrag<LD * 2>(f[s], base, lane_off, kk + 32 * STAGES);
+            __builtin_amdgcn_sched_barrier(0);
+            mma_half(b, 4, kk);
+            __builtin_amdgcn_sched_barrier(0);
         };
 #pragma unroll
         for (int k0 = 0; k0 < K - 32 * STAGES; k0 += 32 * STAGES) {
@@ -152,7 +168,7 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
     // gather the tile's token rows (rounded to bf16, nearest even).  Order of issue: row ids,
     // then the first weight fragments (they do not depend on x), then the token rows, so the
     // two dependent round trips of the gather overlap the weights' first trip.
-    WeightStream<D, FFN_STAGES1> s1;
+    WeightStream<D, H, FFN_STAGES1> s1;
     const int col1 = 128 * wave + 8 * c;
     {
         constexpr int F4 = D / 4;                 // float4 per row
@@ -165,7 +181,7 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
             const int r = min(rr + i * RPP, rows - 1);      // clamped: padding rows re-read a valid row
             tok[i] = p.perm[row0 + r];
         }
-        s1.start(W1, H, col1, g);
+        s1.start(W1, col1, g);
         float4 v[PASSES];
 #pragma unroll
         for (int i = 0; i < PASSES; ++i) {
@@ -185,7 +201,7 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
 
     // hidden = relu(x W1): wave w owns hidden columns [128w, 128w+128)
     const int cg = wave & 3, kh = wave >> 2;
-    WeightStream<H / 2, FFN_STAGES2> s2;
+    WeightStream<H / 2, D, FFN_STAGES2> s2;
     const int col2 = 128 * cg + 8 * c;
     {
         v4f acc[4][8];
@@ -196,7 +212,7 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
         s1.run(acc, lds, XS, c, g);
         FFN_STAMP(2);
         // second matrix starts streaming during the hand-over below
-        s2.start(W2 + (size_t)(H / 2) * kh * D, D, col2, g);
+        s2.start(W2 + (size_t)(H / 2) * kh * D, col2, g);
         __syncthreads();  // every wave is done reading the x tile; the hidden tile overwrites it
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt)
