@@ -89,7 +89,8 @@ typedef struct moe_workspace_layout {
         tile_row0, num_tiles, route_ws, out_sorted, ffn_ws, aux_ws, total;
     /* hierarchical only */
     size_t p_cleanb, p_sp, p_next_idx, p_partials, p_idx, p_gate, p_counts, p_offsets, p_perm,
-        p_inv_perm, p_tile_group, p_tile_row0, p_num_tiles, s_idx, s_gate, s_load;
+        p_inv_perm, p_tile_group, p_tile_row0, p_num_tiles, p_tile_offsets, p_route_ws, p_aux_ws,
+        s_idx, s_gate;
 } moe_workspace_layout;
 int moe_get_workspace_layout(const moe_config *cfg, moe_workspace_layout *out);
 
@@ -161,6 +162,42 @@ int moe_layer_forward(const moe_config *cfg, const float *x, const float *W_g,
                       const void *W1, const void *W2, float *y, int32_t *topk_idx,
                       float *topk_gate, float *importance, float *load, float *losses,
                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- hierarchical MoE (Appendix B, Eq.(12)-(14)) ---------------------------------------- */
+/*
+ * Two-level noisy top-k gating: a primary gate over the a groups (k_primary kept), then for every
+ * kept group i the secondary gate G_i over its b experts (k_secondary kept), evaluated only on
+ * X^(i) = {x : G_primary(x)_i > 0}.
+ * x [T,d]; Wg_p, Wn_p [d,a]; eps_p [T,a]; Wg_s, Wn_s [a,d,b]; eps_s [T,k_primary,b] (noise of the
+ * secondary gate reached through primary slot p); any eps may be NULL (noise-free level).
+ * Outputs: topk_idx [T,k] = global expert id i*b + j, slot-major (primary slot, then secondary
+ * slot, each in descending logit order); topk_gate [T,k] = G_primary(x)_i * G_i(x)_j.
+ * workspace: moe_workspace_bytes(); it keeps every intermediate (primary and secondary logits,
+ * per-level indices and gates, the grouping of rows by primary group) at the offsets
+ * moe_get_workspace_layout reports, for moe_aux_losses_hier.
+ * Same logit arithmetic as moe_gate at both levels.
+ */
+int moe_gate_hier(const moe_config *cfg, const float *x, const float *Wg_p, const float *Wn_p,
+                  const float *eps_p, const float *Wg_s, const float *Wn_s, const float *eps_s,
+                  int32_t *topk_idx, float *topk_gate, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
+/* Importance_H (Eq.(13)) = sum of the gate products per expert; Load_H (Eq.(14)) =
+ * Load_primary_i * Load_i(X^(i))_j / |X^(i)| (0 for an empty X^(i)); losses as in moe_aux_losses
+ * with CV^2 taken over all a*b experts.  Needs the workspace moe_gate_hier filled and the
+ * permutation moe_route built from topk_idx (perm, offsets). */
+int moe_aux_losses_hier(const moe_config *cfg, const float *topk_gate, const int32_t *perm,
+                        const int32_t *offsets, void *workspace, size_t workspace_bytes,
+                        float *importance, float *load, float *losses, void *stream);
+
+/* Whole forward pass of the hierarchical layer, Eq.(12): moe_gate_hier, moe_route,
+ * moe_expert_ffn, moe_combine, moe_aux_losses_hier on one stream. */
+int moe_layer_forward_hier(const moe_config *cfg, const float *x, const float *Wg_p,
+                           const float *Wn_p, const float *eps_p, const float *Wg_s,
+                           const float *Wn_s, const float *eps_s, const void *W1, const void *W2,
+                           float *y, int32_t *topk_idx, float *topk_gate, float *importance,
+                           float *load, float *losses, void *workspace, size_t workspace_bytes,
+                           void *stream);
 
 /* Same as moe_layer_forward, with optional timing hooks: stage_events is a HOST array of 10
  * hipEvent_t (as void*), or NULL; entry 2i is recorded on `stream` just before stage i and entry

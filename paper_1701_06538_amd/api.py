@@ -30,7 +30,8 @@ _LAYOUT_FIELDS = ["cleanb", "sp", "next_idx", "partials", "counts", "offsets", "
                   "tile_expert", "tile_row0", "num_tiles", "route_ws", "out_sorted", "ffn_ws",
                   "aux_ws", "total", "p_cleanb", "p_sp", "p_next_idx", "p_partials", "p_idx",
                   "p_gate", "p_counts", "p_offsets", "p_perm", "p_inv_perm", "p_tile_group",
-                  "p_tile_row0", "p_num_tiles", "s_idx", "s_gate", "s_load"]
+                  "p_tile_row0", "p_num_tiles", "p_tile_offsets", "p_route_ws", "p_aux_ws",
+                  "s_idx", "s_gate"]
 
 
 class MoeWorkspaceLayout(ctypes.Structure):
@@ -71,6 +72,13 @@ _moe_layer_forward = _proto("moe_layer_forward", ctypes.c_int,
 
 _moe_layer_forward_profiled = _proto("moe_layer_forward_profiled", ctypes.c_int,
                                      [_cfgp] + [_vp] * 14 + [ctypes.c_size_t, ctypes.POINTER(_vp), _vp])
+
+
+_moe_gate_hier = _proto("moe_gate_hier", ctypes.c_int, [_cfgp] + [_vp] * 10 + [ctypes.c_size_t, _vp])
+_moe_aux_losses_hier = _proto("moe_aux_losses_hier", ctypes.c_int,
+                              [_cfgp] + [_vp] * 4 + [ctypes.c_size_t] + [_vp] * 4)
+_moe_layer_forward_hier = _proto("moe_layer_forward_hier", ctypes.c_int,
+                                 [_cfgp] + [_vp] * 16 + [ctypes.c_size_t, _vp])
 
 
 class MoeError(RuntimeError):
@@ -213,3 +221,28 @@ def moe_layer_forward_profiled(cfg, x, W_g, W_noise, gate_bias, eps, W1, W2, y, 
                                        _ptr(gate_bias), _ptr(eps), _ptr(W1), _ptr(W2), _ptr(y),
                                        _ptr(topk_idx), _ptr(topk_gate), _ptr(importance), _ptr(load),
                                        _ptr(losses), _ptr(workspace), nbytes, ev, _stream(stream)))
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def moe_gate_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, topk_idx, topk_gate, workspace,
+                  stream=None):
+    _check(_moe_gate_hier(ctypes.byref(cfg), _ptr(x), _ptr(Wg_p), _ptr(Wn_p), _ptr(eps_p), _ptr(Wg_s),
+                          _ptr(Wn_s), _ptr(eps_s), _ptr(topk_idx), _ptr(topk_gate), _ptr(workspace),
+                          _nbytes(workspace), _stream(stream)))
+
+
+def moe_aux_losses_hier(cfg, topk_gate, perm, offsets, workspace, importance, load, losses, stream=None):
+    _check(_moe_aux_losses_hier(ctypes.byref(cfg), _ptr(topk_gate), _ptr(perm), _ptr(offsets),
+                                _ptr(workspace), _nbytes(workspace), _ptr(importance), _ptr(load),
+                                _ptr(losses), _stream(stream)))
+
+
+def moe_layer_forward_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, W1, W2, y, topk_idx, topk_gate,
+                           importance, load, losses, workspace, stream=None):
+    _check(_moe_layer_forward_hier(ctypes.byref(cfg), _ptr(x), _ptr(Wg_p), _ptr(Wn_p), _ptr(eps_p),
+                                   _ptr(Wg_s), _ptr(Wn_s), _ptr(eps_s), _ptr(W1), _ptr(W2), _ptr(y),
+                                   _ptr(topk_idx), _ptr(topk_gate), _ptr(importance), _ptr(load),
+                                   _ptr(losses), _ptr(workspace), _nbytes(workspace), _stream(stream)))

@@ -52,6 +52,7 @@ __global__ __launch_bounds__(256) void finish_sums_kernel(const double *__restri
     double s = 0.0;
     for (int c = 0; c < chunks; ++c) s += level2[(size_t)c * 2 * n + i];
     sums64[i] = s;
+    if (!importance) return;
     if (i < n) importance[i] = (float)s;
     else load[i - n] = (float)s;
 }
@@ -109,6 +110,50 @@ int launch_aux_losses(const float *partials, int64_t rows, int n, float w_imp, f
                        level2, chunks, n, sums64, importance, load);
     MOE_LAUNCH_CHECK();
     hipLaunchKernelGGL(cv2_kernel, dim3(1), dim3(256), 0, st, sums64, n, w_imp, w_load, losses);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+int launch_partial_sums(const float *partials, int64_t rows, int n, double *ws, hipStream_t st) {
+    const int chunks = (int)ceil_div(rows > 0 ? rows : 1, kAuxChunkRows);
+    double *sums64 = ws;
+    double *level2 = ws + 2 * (size_t)n;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)ceil_div(2 * n, 32), (unsigned)chunks),
+                       dim3(256), 0, st, partials, rows, n, level2);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(finish_sums_kernel, dim3((unsigned)ceil_div(2 * n, 256)), dim3(256), 0, st,
+                       level2, chunks, n, sums64, (float *)nullptr, (float *)nullptr);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+// Eq.(13)-(14), one thread per expert e = i*b + j:
+//   Importance_H = sum of the gate products routed to e (rows offsets[e]..offsets[e+1], in order)
+//   Load_H       = Load_primary_i * Load_i(X^(i))_j / |X^(i)|, the secondary load being the sum of
+//                  the partial rows of group i's tiles, in order.
+__global__ __launch_bounds__(256) void hier_losses_kernel(HierLossArgs p) {
+    const int n = p.a * p.b;
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= n) return;
+    const int i = e / p.b, j = e % p.b;
+    double imp = 0.0;
+    for (int r = p.offsets[e]; r < p.offsets[e + 1]; ++r) imp += (double)p.gate[p.perm[r]];
+    double ls = 0.0;
+    const int blk0 = p.p_tile_offsets[i] * p.sub, blk1 = p.p_tile_offsets[i + 1] * p.sub;
+    for (int blk = blk0; blk < blk1; ++blk) ls += (double)p.s_partials[((size_t)blk * 2 + 1) * p.b + j];
+    const int cnt = p.p_counts[i];
+    const double ld = cnt > 0 ? p.p_sums[p.a + i] * ls / (double)cnt : 0.0;
+    p.sums64[e] = imp;
+    p.sums64[n + e] = ld;
+    p.importance[e] = (float)imp;
+    p.load[e] = (float)ld;
+}
+
+int launch_hier_losses(const HierLossArgs &a, float w_imp, float w_load, float *losses, hipStream_t st) {
+    const int n = a.a * a.b;
+    hipLaunchKernelGGL(hier_losses_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, a);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(cv2_kernel, dim3(1), dim3(256), 0, st, a.sums64, n, w_imp, w_load, losses);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
 }

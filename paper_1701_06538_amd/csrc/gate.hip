@@ -361,6 +361,32 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(TopkArgs p) {
         out[i] = (lds_acc[i] + lds_acc[2 * n + i]) + (lds_acc[4 * n + i] + lds_acc[6 * n + i]);
 }
 
+// Eq.(12): global expert id and gate product for every (token, primary slot, secondary slot)
+__global__ __launch_bounds__(256) void hier_compose_kernel(const int32_t *__restrict__ p_idx,
+                                                           const float *__restrict__ p_gate,
+                                                           const int32_t *__restrict__ s_idx,
+                                                           const float *__restrict__ s_gate,
+                                                           int64_t T, int k_p, int k_s, int b,
+                                                           int32_t *__restrict__ idx,
+                                                           float *__restrict__ gate) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over T*k_p*k_s
+    if (i >= T * k_p * k_s) return;
+    const int64_t ap = i / k_s;                                  // primary assignment t*k_p + p
+    idx[i] = p_idx[ap] * b + s_idx[i];
+    gate[i] = p_gate[ap] * s_gate[i];
+}
+
+int launch_hier_compose(const int32_t *p_idx, const float *p_gate, const int32_t *s_idx,
+                        const float *s_gate, int64_t T, int k_p, int k_s, int b, int32_t *idx,
+                        float *gate, hipStream_t st) {
+    const int64_t total = T * k_p * k_s;
+    if (total <= 0) return MOE_OK;
+    hipLaunchKernelGGL(hier_compose_kernel, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, st,
+                       p_idx, p_gate, s_idx, s_gate, T, k_p, k_s, b, idx, gate);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------

@@ -11,6 +11,7 @@ int workspace_layout(const moe_config *cfg, moe_workspace_layout *L) {
     int st = check_config(cfg);
     if (st != MOE_OK) return st;
     *L = moe_workspace_layout{};
+    const bool hier = cfg->a > 0;
     const size_t T = (size_t)cfg->T, n = (size_t)cfg->n, A = T * (size_t)cfg->k;
     const size_t MT = (size_t)moe_max_tiles(cfg) + 8;
     size_t off = 0;
@@ -19,12 +20,17 @@ int workspace_layout(const moe_config *cfg, moe_workspace_layout *L) {
         off = align_up(off + (bytes ? bytes : 1));
         return at;
     };
-    const size_t gate_n = cfg->a > 0 ? (size_t)cfg->b : n;   // columns of the (secondary) gate
-    const size_t gate_rows = cfg->a > 0 ? T * (size_t)cfg->k_primary : T;
+    // the gate whose [rows, cols] logits feed the final top-k: the flat gate, or the secondary one
+    const size_t gate_n = hier ? (size_t)cfg->b : n;
+    const size_t gate_rows = hier ? T * (size_t)cfg->k_primary : T;
+    const size_t MTp = hier ? (size_t)ceil_div((int64_t)gate_rows, kGateBM) + cfg->a + 8 : 0;
+    size_t part_rows;
+    if (hier) part_rows = MTp * (size_t)(kGateBM / gate_rows_per_block((int64_t)gate_rows, (int)gate_n));
+    else part_rows = (size_t)moe_gate_partial_rows(cfg);
     L->cleanb = take(gate_rows * gate_n * 4);
     L->sp = take(gate_rows * gate_n * 4);
     L->next_idx = take(gate_rows * 4);
-    L->partials = take((size_t)(ceil_div((int64_t)gate_rows, gate_rows_per_block((int64_t)gate_rows, (int)gate_n)) + 16 * (cfg->a > 0 ? cfg->a : 0)) * 2 * gate_n * 4);
+    L->partials = take(part_rows * 2 * gate_n * 4);
     L->counts = take(n * 4);
     L->offsets = take((n + 1) * 4);
     L->perm = take(A * 4);
@@ -35,7 +41,30 @@ int workspace_layout(const moe_config *cfg, moe_workspace_layout *L) {
     L->route_ws = take(route_ws_bytes((int64_t)A, cfg->n));
     L->out_sorted = take(A * (size_t)cfg->d * 4);
     L->ffn_ws = take(moe_ffn_workspace_bytes(cfg));
-    L->aux_ws = take(aux_ws_bytes(cfg->a > 0 ? (int64_t)T * cfg->k_primary : moe_gate_partial_rows(cfg), cfg->n));
+    L->aux_ws = take(hier ? 2 * n * 8 : aux_ws_bytes(moe_gate_partial_rows(cfg), cfg->n));
+    if (hier) {
+        const size_t a = (size_t)cfg->a, kp = (size_t)cfg->k_primary, ks = (size_t)cfg->k_secondary;
+        const size_t Ap = T * kp;
+        const int64_t prow = ceil_div((int64_t)T, gate_rows_per_block((int64_t)T, cfg->a));
+        L->p_cleanb = take(T * a * 4);
+        L->p_sp = take(T * a * 4);
+        L->p_next_idx = take(T * 4);
+        L->p_partials = take((size_t)prow * 2 * a * 4);
+        L->p_idx = take(Ap * 4);
+        L->p_gate = take(Ap * 4);
+        L->p_counts = take(a * 4);
+        L->p_offsets = take((a + 1) * 4);
+        L->p_perm = take(Ap * 4);
+        L->p_inv_perm = take(Ap * 4);
+        L->p_tile_group = take(MTp * 4);
+        L->p_tile_row0 = take(MTp * 4);
+        L->p_num_tiles = take(16);
+        L->p_tile_offsets = take((a + 1) * 4);
+        L->p_route_ws = take(route_ws_bytes((int64_t)Ap, cfg->a));
+        L->p_aux_ws = take(aux_ws_bytes(prow, cfg->a));
+        L->s_idx = take(Ap * ks * 4);
+        L->s_gate = take(Ap * ks * 4);
+    }
     L->total = off;
     return MOE_OK;
 }
@@ -130,4 +159,144 @@ extern "C" int moe_layer_forward(const moe_config *cfg, const float *x, const fl
     return moe_layer_forward_profiled(cfg, x, W_g, W_noise, gate_bias, eps, W1, W2, y, topk_idx,
                                       topk_gate, importance, load, losses, workspace,
                                       workspace_bytes, nullptr, stream);
+}
+
+// ---------------------------------------------------------------------------------------
+// hierarchical layer (Appendix B)
+// ---------------------------------------------------------------------------------------
+extern "C" int moe_gate_hier(const moe_config *cfg, const float *x, const float *Wg_p,
+                             const float *Wn_p, const float *eps_p, const float *Wg_s,
+                             const float *Wn_s, const float *eps_s, int32_t *topk_idx,
+                             float *topk_gate, void *workspace, size_t workspace_bytes,
+                             void *stream) {
+    moe_workspace_layout L;
+    int st = workspace_layout(cfg, &L);
+    if (st != MOE_OK) return st;
+    if (cfg->a <= 0) return MOE_EINVAL;
+    if (!x || !Wg_p || !Wn_p || !Wg_s || !Wn_s || !topk_idx || !topk_gate || !workspace)
+        return MOE_EINVAL;
+    if (!aligned16(x) || !aligned16(Wg_p) || !aligned16(Wn_p) || !aligned16(Wg_s) ||
+        !aligned16(Wn_s) || !aligned16(workspace) || (eps_p && !aligned16(eps_p)) ||
+        (eps_s && !aligned16(eps_s)))
+        return MOE_EINVAL;
+    if (workspace_bytes < L.total) return MOE_EWORKSPACE;
+    if ((st = check_gate_level(cfg->T, cfg->d, cfg->a, cfg->k_primary)) != MOE_OK) return st;
+    if ((st = check_gate_level((int64_t)cfg->T * cfg->k_primary, cfg->d, cfg->b, cfg->k_secondary)) != MOE_OK)
+        return st;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const int64_t T = cfg->T, Ap = T * cfg->k_primary;
+    float *p_cleanb = (float *)(ws + L.p_cleanb), *p_sp = (float *)(ws + L.p_sp);
+    int32_t *p_idx = (int32_t *)(ws + L.p_idx);
+    float *p_gate = (float *)(ws + L.p_gate);
+    int32_t *p_offsets = (int32_t *)(ws + L.p_offsets), *p_perm = (int32_t *)(ws + L.p_perm);
+    int32_t *p_tile_group = (int32_t *)(ws + L.p_tile_group), *p_tile_row0 = (int32_t *)(ws + L.p_tile_row0);
+    int32_t *p_num_tiles = (int32_t *)(ws + L.p_num_tiles);
+
+    // primary gate over the a groups
+    LogitsArgs la{};
+    la.x = x; la.Wg = Wg_p; la.Wn = Wn_p; la.cleanb = p_cleanb; la.sp = p_sp;
+    la.R = T; la.d = cfg->d; la.n = cfg->a;
+    if ((st = launch_gate_logits(la, ceil_div(T, kGateBM), s)) != MOE_OK) return st;
+    TopkArgs ta{};
+    ta.cleanb = p_cleanb; ta.sp = p_sp; ta.eps = eps_p; ta.R = T; ta.n = cfg->a; ta.k = cfg->k_primary;
+    ta.idx = p_idx; ta.gate = p_gate; ta.next_idx = (int32_t *)(ws + L.p_next_idx);
+    ta.partials = (float *)(ws + L.p_partials);
+    ta.rows_per_block = gate_rows_per_block(T, cfg->a);
+    if ((st = launch_gate_topk(ta, ceil_div(T, ta.rows_per_block), s)) != MOE_OK) return st;
+
+    // X^(i): rows grouped by primary group, in 128-row tiles that never straddle groups
+    RouteArgs ra{};
+    ra.idx = p_idx; ra.A = Ap; ra.n = cfg->a; ra.tile_rows = kGateBM;
+    ra.counts = (int32_t *)(ws + L.p_counts); ra.offsets = p_offsets; ra.perm = p_perm;
+    ra.inv_perm = (int32_t *)(ws + L.p_inv_perm);
+    ra.tile_expert = p_tile_group; ra.tile_row0 = p_tile_row0; ra.num_tiles = p_num_tiles;
+    ra.tile_offsets = (int32_t *)(ws + L.p_tile_offsets);
+    ra.hist = (int32_t *)(ws + L.p_route_ws);
+    if ((st = launch_route(ra, s)) != MOE_OK) return st;
+
+    // secondary gates, each on its own rows and with its own matrices
+    const int64_t max_tiles_p = ceil_div(Ap, kGateBM) + cfg->a;
+    float *s_cleanb = (float *)(ws + L.cleanb), *s_sp = (float *)(ws + L.sp);
+    LogitsArgs lb{};
+    lb.x = x; lb.Wg = Wg_s; lb.Wn = Wn_s; lb.cleanb = s_cleanb; lb.sp = s_sp;
+    lb.R = Ap; lb.d = cfg->d; lb.n = cfg->b;
+    lb.row_src = p_perm; lb.row_div = cfg->k_primary;
+    lb.tile_group = p_tile_group; lb.tile_row0 = p_tile_row0; lb.num_tiles = p_num_tiles;
+    lb.group_offsets = p_offsets;
+    if ((st = launch_gate_logits(lb, max_tiles_p, s)) != MOE_OK) return st;
+    TopkArgs tb{};
+    tb.cleanb = s_cleanb; tb.sp = s_sp; tb.eps = eps_s; tb.R = Ap; tb.n = cfg->b; tb.k = cfg->k_secondary;
+    tb.row_map = p_perm;
+    tb.tile_row0 = p_tile_row0; tb.num_tiles = p_num_tiles; tb.tile_group = p_tile_group;
+    tb.group_offsets = p_offsets;
+    tb.idx = (int32_t *)(ws + L.s_idx); tb.gate = (float *)(ws + L.s_gate);
+    tb.next_idx = (int32_t *)(ws + L.next_idx); tb.partials = (float *)(ws + L.partials);
+    tb.rows_per_block = gate_rows_per_block(Ap, cfg->b);
+    if ((st = launch_gate_topk(tb, max_tiles_p * (kGateBM / tb.rows_per_block), s)) != MOE_OK) return st;
+
+    return launch_hier_compose(p_idx, p_gate, tb.idx, tb.gate, T, cfg->k_primary, cfg->k_secondary,
+                               cfg->b, topk_idx, topk_gate, s);
+}
+
+extern "C" int moe_aux_losses_hier(const moe_config *cfg, const float *topk_gate, const int32_t *perm,
+                                   const int32_t *offsets, void *workspace, size_t workspace_bytes,
+                                   float *importance, float *load, float *losses, void *stream) {
+    moe_workspace_layout L;
+    int st = workspace_layout(cfg, &L);
+    if (st != MOE_OK) return st;
+    if (cfg->a <= 0) return MOE_EINVAL;
+    if (!topk_gate || !perm || !offsets || !workspace || !importance || !load || !losses)
+        return MOE_EINVAL;
+    if (workspace_bytes < L.total) return MOE_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const int64_t T = cfg->T, Ap = T * cfg->k_primary;
+    const int64_t prow = ceil_div(T, gate_rows_per_block(T, cfg->a));
+    double *p_sums = (double *)(ws + L.p_aux_ws);
+    st = launch_partial_sums((const float *)(ws + L.p_partials), prow, cfg->a, p_sums, s);
+    if (st != MOE_OK) return st;
+    HierLossArgs ha{};
+    ha.gate = topk_gate; ha.perm = perm; ha.offsets = offsets;
+    ha.p_sums = p_sums; ha.s_partials = (const float *)(ws + L.partials);
+    ha.p_counts = (const int32_t *)(ws + L.p_counts);
+    ha.p_tile_offsets = (const int32_t *)(ws + L.p_tile_offsets);
+    ha.a = cfg->a; ha.b = cfg->b; ha.sub = kGateBM / gate_rows_per_block(Ap, cfg->b);
+    ha.sums64 = (double *)(ws + L.aux_ws);
+    ha.importance = importance; ha.load = load;
+    return launch_hier_losses(ha, cfg->w_importance, cfg->w_load, losses, s);
+}
+
+extern "C" int moe_layer_forward_hier(const moe_config *cfg, const float *x, const float *Wg_p,
+                                      const float *Wn_p, const float *eps_p, const float *Wg_s,
+                                      const float *Wn_s, const float *eps_s, const void *W1,
+                                      const void *W2, float *y, int32_t *topk_idx, float *topk_gate,
+                                      float *importance, float *load, float *losses, void *workspace,
+                                      size_t workspace_bytes, void *stream) {
+    moe_workspace_layout L;
+    int st = workspace_layout(cfg, &L);
+    if (st != MOE_OK) return st;
+    if (cfg->a <= 0) return MOE_EINVAL;
+    if (!W1 || !W2 || !y || !importance || !load || !losses || !workspace) return MOE_EINVAL;
+    if (!aligned16(y) || !aligned16(W1) || !aligned16(W2)) return MOE_EINVAL;
+    if (workspace_bytes < L.total) return MOE_EWORKSPACE;
+    char *ws = (char *)workspace;
+    st = moe_gate_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, topk_idx, topk_gate, workspace,
+                       workspace_bytes, stream);
+    if (st != MOE_OK) return st;
+    int32_t *counts = (int32_t *)(ws + L.counts), *offsets = (int32_t *)(ws + L.offsets);
+    int32_t *perm = (int32_t *)(ws + L.perm), *inv_perm = (int32_t *)(ws + L.inv_perm);
+    int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
+    int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
+    float *out_sorted = (float *)(ws + L.out_sorted);
+    st = moe_route(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0, num_tiles,
+                   ws + L.route_ws, stream);
+    if (st != MOE_OK) return st;
+    st = moe_expert_ffn(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2, out_sorted,
+                        ws + L.ffn_ws, stream);
+    if (st != MOE_OK) return st;
+    st = moe_combine(cfg, out_sorted, topk_gate, inv_perm, y, stream);
+    if (st != MOE_OK) return st;
+    return moe_aux_losses_hier(cfg, topk_gate, perm, offsets, workspace, workspace_bytes, importance,
+                               load, losses, stream);
 }

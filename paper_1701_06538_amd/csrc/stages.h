@@ -71,5 +71,21 @@ int launch_aux_losses(const float *partials, int64_t rows, int n, float w_imp, f
                       float *importance, float *load, float *losses, double *ws,
                       hipStream_t st);
 size_t aux_ws_bytes(int64_t rows, int n);
+int launch_hier_compose(const int32_t *p_idx, const float *p_gate, const int32_t *s_idx,
+                        const float *s_gate, int64_t T, int k_p, int k_s, int b, int32_t *idx,
+                        float *gate, hipStream_t st);
+// fixed-order fp64 column sums of float partials [rows][2][n] -> sums64 [2n] (ws as in aux_ws_bytes)
+int launch_partial_sums(const float *partials, int64_t rows, int n, double *ws, hipStream_t st);
+struct HierLossArgs {
+    const float *gate;          // [T*k] gate products
+    const int32_t *perm, *offsets;  // route over all a*b experts
+    const double *p_sums;       // [2a]: primary importance | load
+    const float *s_partials;    // [blocks][2][b] secondary partial sums, blocks grouped by tile
+    const int32_t *p_counts, *p_tile_offsets;
+    int a, b, sub;              // sub = top-k blocks per 128-row tile
+    double *sums64;             // out [2n]: importance | load
+    float *importance, *load;   // out [n]
+};
+int launch_hier_losses(const HierLossArgs &a, float w_imp, float w_load, float *losses, hipStream_t st);
 
 }  // namespace moe

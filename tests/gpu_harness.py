@@ -123,3 +123,44 @@ def rel_errors(got, ref):
     row = float(np.max(num / np.maximum(den, 1e-300))) if ref.size else 0.0
     mx = float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300)) if ref.size else 0.0
     return row, mx
+
+
+class HierRun:
+    """One forward pass of the hierarchical layer on the GPU through the C ABI."""
+
+    def __init__(self, api, shape, inputs, W1, W2):
+        self.api, self.shape = api, shape
+        self.cfg = api.make_config(shape)
+        x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s = inputs
+        self.x = dev(x)
+        self.Wg_p, self.Wn_p, self.eps_p = dev(Wg_p), dev(Wn_p), dev(eps_p)
+        self.Wg_s, self.Wn_s, self.eps_s = dev(Wg_s), dev(Wn_s), dev(eps_s)
+        self.W1, self.W2 = W1, W2
+        T, n, k, d = shape.T, shape.n, shape.k, shape.d
+        i32 = dict(dtype=torch.int32, device="cuda")
+        f32 = dict(dtype=torch.float32, device="cuda")
+        self.topk_idx = torch.full((T, k), -7, **i32)
+        self.topk_gate = torch.full((T, k), float("nan"), **f32)
+        self.y = torch.full((T, d), float("nan"), **f32)
+        self.importance = torch.full((n,), float("nan"), **f32)
+        self.load = torch.full((n,), float("nan"), **f32)
+        self.losses = torch.full((4,), float("nan"), **f32)
+        self.workspace = torch.empty(api.moe_workspace_bytes(self.cfg), dtype=torch.uint8, device="cuda")
+        self.layout = api.moe_get_workspace_layout(self.cfg)
+
+    def ws_view(self, field, count, dtype):
+        off = getattr(self.layout, field)
+        nbytes = count * torch.tensor([], dtype=dtype).element_size()
+        return self.workspace[off:off + nbytes].view(dtype)
+
+    def gate(self):
+        self.api.moe_gate_hier(self.cfg, self.x, self.Wg_p, self.Wn_p, self.eps_p, self.Wg_s, self.Wn_s,
+                               self.eps_s, self.topk_idx, self.topk_gate, self.workspace)
+        torch.cuda.synchronize()
+
+    def forward(self):
+        self.api.moe_layer_forward_hier(self.cfg, self.x, self.Wg_p, self.Wn_p, self.eps_p, self.Wg_s,
+                                        self.Wn_s, self.eps_s, self.W1, self.W2, self.y, self.topk_idx,
+                                        self.topk_gate, self.importance, self.load, self.losses,
+                                        self.workspace)
+        torch.cuda.synchronize()
