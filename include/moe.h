@@ -199,6 +199,28 @@ int moe_layer_forward_hier(const moe_config *cfg, const float *x, const float *W
                            float *load, float *losses, void *workspace, size_t workspace_bytes,
                            void *stream);
 
+/* ---- a6: backward pass of the flat layer (Section 2.1, "Training the Gating Network";
+ *      Appendix D: hidden activations are recomputed) ------------------------------------ */
+/*
+ * Gradients of J = <dy, y> + w_importance*CV^2(Importance) + w_load*CV^2(Load) with respect to
+ * x, W_g, W_noise and every expert's W1, W2.  The top-k selection is piecewise constant: gradient
+ * flows through the kept softmax values, through P(x,i) of Eq.(9) -- including the element
+ * kth_excluding picks as threshold -- and through the experts; relu'(0) = 0.
+ * Inputs: the forward call's inputs, dy [T,d] f32, its outputs topk_idx/topk_gate and its
+ * workspace exactly as moe_layer_forward left it (logits, permutation, expert outputs, loss sums).
+ * Outputs (overwritten): dx [T,d], dW_g, dW_noise [d,n], dW1 [n,d,h], dW2 [n,h,d], all f32
+ * (fp32 master gradients; experts that received no token get zeros).
+ * bf16 experts only, d and h multiples of 128, n a multiple of 32; expert math in bf16 MFMA with
+ * fp32 accumulation, gate math in fp32.  workspace: moe_backward_workspace_bytes().
+ */
+size_t moe_backward_workspace_bytes(const moe_config *cfg);
+int moe_layer_backward(const moe_config *cfg, const float *x, const float *W_g,
+                       const float *W_noise, const float *eps, const void *W1, const void *W2,
+                       const float *dy, const int32_t *topk_idx, const float *topk_gate,
+                       const void *fwd_workspace, float *dx, float *dW_g, float *dW_noise,
+                       float *dW1, float *dW2, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
 /* Same as moe_layer_forward, with optional timing hooks: stage_events is a HOST array of 10
  * hipEvent_t (as void*), or NULL; entry 2i is recorded on `stream` just before stage i and entry
  * 2i+1 just after it, for i = 0 gate, 1 route, 2 experts, 3 combine, 4 losses.  NULL entries

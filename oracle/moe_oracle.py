@@ -347,6 +347,13 @@ def hier_gate_and_losses(x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, k_p, k_s,
 # recomputed, nothing but gate quantities is kept from the forward pass)
 # --------------------------------------------------------------------------------------
 
+def round_to_bf16(a):
+    """Round fp32 values to the nearest bfloat16 (ties to even), returned as float32."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32)
+
+
 def dcv_squared(v):
     """Gradient of cv_squared with respect to v (population variance)."""
     v = np.asarray(v, np.float64)
@@ -366,15 +373,20 @@ class Grads:
 
 
 def flat_backward(x, W_g, W_noise, fwd: FlatForward, k, weight_fn, dy,
-                  w_importance=0.1, w_load=0.1, experts_for_dW=None) -> Grads:
+                  w_importance=0.1, w_load=0.1, experts_for_dW=None, expert_input=None) -> Grads:
     """Gradients of J = <dy, y> + L_importance + L_load for the flat layer.
 
     The top-k selection is piecewise constant, so no gradient flows through *which* experts
     are kept; it flows through the kept softmax values, through P(x,i) of Eq.(9) (including
     the threshold element kth_excluding picks, as differentiating Eq.(9) as printed gives) and
     through the experts.  relu'(0) is taken as 0.
-    experts_for_dW: optional iterable restricting which experts' dW1/dW2 are returned."""
+    experts_for_dW: optional iterable restricting which experts' dW1/dW2 are returned.
+    expert_input: optional [T,d] array the experts see instead of x.  For the bf16 workloads the
+    experts' input activations are bf16(x); the sign test z > 0 of the ReLU derivative is a binary
+    decision, so it has to be taken on the same rounded input on both sides of a parity test
+    (a flipped unit changes dz by its full size).  The gating path always uses x itself."""
     x = np.asarray(x, np.float64)
+    xe_all = x if expert_input is None else np.asarray(expert_input, np.float64)
     dy = np.asarray(dy, np.float64)
     W_g = np.asarray(W_g, np.float64)
     W_noise = np.asarray(W_noise, np.float64)
@@ -397,7 +409,7 @@ def flat_backward(x, W_g, W_noise, fwd: FlatForward, k, weight_fn, dy,
     for e in np.unique(idx):
         r, s = np.nonzero(idx == e)
         W1, W2 = (np.asarray(w, np.float64) for w in weight_fn(int(e)))
-        xe = x[r]
+        xe = xe_all[r]
         z = xe @ W1
         hid = np.maximum(z, 0.0)
         out = hid @ W2

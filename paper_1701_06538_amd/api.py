@@ -81,6 +81,11 @@ _moe_layer_forward_hier = _proto("moe_layer_forward_hier", ctypes.c_int,
                                  [_cfgp] + [_vp] * 16 + [ctypes.c_size_t, _vp])
 
 
+_moe_backward_workspace_bytes = _proto("moe_backward_workspace_bytes", ctypes.c_size_t, [_cfgp])
+_moe_layer_backward = _proto("moe_layer_backward", ctypes.c_int,
+                             [_cfgp] + [_vp] * 16 + [ctypes.c_size_t, _vp])
+
+
 class MoeError(RuntimeError):
     def __init__(self, status):
         self.status = status
@@ -246,3 +251,15 @@ def moe_layer_forward_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, W1, W2,
                                    _ptr(Wg_s), _ptr(Wn_s), _ptr(eps_s), _ptr(W1), _ptr(W2), _ptr(y),
                                    _ptr(topk_idx), _ptr(topk_gate), _ptr(importance), _ptr(load),
                                    _ptr(losses), _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def moe_backward_workspace_bytes(cfg):
+    return _moe_backward_workspace_bytes(ctypes.byref(cfg))
+
+
+def moe_layer_backward(cfg, x, W_g, W_noise, eps, W1, W2, dy, topk_idx, topk_gate, fwd_workspace, dx,
+                       dW_g, dW_noise, dW1, dW2, workspace, stream=None):
+    _check(_moe_layer_backward(ctypes.byref(cfg), _ptr(x), _ptr(W_g), _ptr(W_noise), _ptr(eps), _ptr(W1),
+                               _ptr(W2), _ptr(dy), _ptr(topk_idx), _ptr(topk_gate), _ptr(fwd_workspace),
+                               _ptr(dx), _ptr(dW_g), _ptr(dW_noise), _ptr(dW1), _ptr(dW2), _ptr(workspace),
+                               _nbytes(workspace), _stream(stream)))

@@ -1,0 +1,739 @@
+// a6: backward pass of the flat layer (Section 2.1 "Training the Gating Network": plain
+// back-propagation through the kept gate values, the experts and both balancing losses;
+// Appendix D: the experts' hidden activations are recomputed, not stored).
+//
+// Objective: J = <dy, y> + w_importance CV^2(Importance) + w_load CV^2(Load).
+//
+//   bwd_prepare_kernel   per routed row: dout = gate * dy (bf16), x row (bf16), dgate = <dy, E(x)>
+//   gg_rows_kernel       grouped bf16 MFMA GEMM over the ragged rows of each expert:
+//                          hid = relu(xs W1)            dz = (dout W2^T) * [hid > 0]
+//                          dxs = dz W1^T
+//   gg_wgrad_kernel      per expert, contraction over its rows: dW2 = hid^T dout, dW1 = xs^T dz
+//   gate_bwd_rows_kernel per token: softmax-over-k backward, d/dclean and d/draw of Eq.(9) incl.
+//                        the threshold element, H = clean + eps * sp
+//   sg_kernel            fp32 MFMA GEMMs of the gate: dW_g = x^T dclean, dW_noise = x^T draw
+//                        (split over tokens, partial sums added in a fixed order) and
+//                        dx = dclean W_g^T + draw W_noise^T
+//   dx_gather_add_kernel dx[t] += sum_s dxs[row of (t,s)]
+#include "stages.h"
+
+namespace moe {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return bf16_rne(lo) | (bf16_rne(hi) << 16); }
+__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// ---------------------------------------------------------------------------------------
+// per routed row: dout, xs, dgate
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bwd_prepare_kernel(const float *__restrict__ x,
+                                                          const float *__restrict__ dy,
+                                                          const float *__restrict__ out_sorted,
+                                                          const float *__restrict__ gate,
+                                                          const int32_t *__restrict__ perm, int64_t A,
+                                                          int d, int k, uint16_t *__restrict__ xs,
+                                                          uint16_t *__restrict__ dout,
+                                                          float *__restrict__ dgate) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= A) return;
+    const int a = perm[r];
+    const int64_t t = a / k;
+    const float g = gate[a];
+    float dot = 0.f;
+    for (int c = lane * 4; c < d; c += 256) {
+        const float4 vy = *reinterpret_cast<const float4 *>(dy + t * d + c);
+        const float4 vo = *reinterpret_cast<const float4 *>(out_sorted + r * d + c);
+        const float4 vx = *reinterpret_cast<const float4 *>(x + t * d + c);
+        dot = fmaf(vy.x, vo.x, dot); dot = fmaf(vy.y, vo.y, dot);
+        dot = fmaf(vy.z, vo.z, dot); dot = fmaf(vy.w, vo.w, dot);
+        *reinterpret_cast<uint2 *>(dout + r * d + c) = make_uint2(pack2(g * vy.x, g * vy.y), pack2(g * vy.z, g * vy.w));
+        *reinterpret_cast<uint2 *>(xs + r * d + c) = make_uint2(pack2(vx.x, vx.y), pack2(vx.z, vx.w));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+    if (lane == 0) dgate[a] = dot;
+}
+
+// ---------------------------------------------------------------------------------------
+// bf16 MFMA block GEMM shared by the expert backward kernels: 128 x 128 tile, 4 waves (2 x 2),
+// k-slabs of 32 staged in LDS with k contiguous for both operands.
+// ---------------------------------------------------------------------------------------
+constexpr int GBM = 128, GBN = 128, GKC = 32, GLD = GKC + 8;  // LDS row = 32 k + pad (bf16)
+
+struct Tile16 {
+    uint4 v[2];
+};
+
+// operand rows have k contiguous in memory: element (row, k) at src[row * ld + k]
+__device__ __forceinline__ void load_kcontig(Tile16 &t, const uint16_t *src, int64_t ld, int row0,
+                                             int rows_valid, int k0, int tid) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = (tid >> 2) + 64 * i, kq = (tid & 3) * 8;
+        t.v[i] = r < rows_valid
+                     ? *reinterpret_cast<const uint4 *>(src + (int64_t)(row0 + r) * ld + k0 + kq)
+                     : make_uint4(0u, 0u, 0u, 0u);
+    }
+}
+__device__ __forceinline__ void store_kcontig(const Tile16 &t, uint16_t (*S)[GLD], int tid) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = (tid >> 2) + 64 * i, kq = (tid & 3) * 8;
+        *reinterpret_cast<uint4 *>(&S[r][kq]) = t.v[i];
+    }
+}
+// operand rows are strided in k: element (row, k) at src[k * ld + row]
+__device__ __forceinline__ void load_kstrided(Tile16 &t, const uint16_t *src, int64_t ld, int row0,
+                                              int k0, int k_valid, int tid) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int k = (tid >> 4) + 16 * i, rs = (tid & 15) * 8;
+        t.v[i] = (k0 + k) < k_valid
+                     ? *reinterpret_cast<const uint4 *>(src + (int64_t)(k0 + k) * ld + row0 + rs)
+                     : make_uint4(0u, 0u, 0u, 0u);
+    }
+}
+__device__ __forceinline__ void store_kstrided(const Tile16 &t, uint16_t (*S)[GLD], int tid) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int k = (tid >> 4) + 16 * i, rs = (tid & 15) * 8;
+        const uint32_t w[4] = {t.v[i].x, t.v[i].y, t.v[i].z, t.v[i].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            S[rs + 2 * j][k] = (uint16_t)(w[j] & 0xffffu);
+            S[rs + 2 * j + 1][k] = (uint16_t)(w[j] >> 16);
+        }
+    }
+}
+
+__device__ __forceinline__ void mma_slab(v16f (&acc)[2][2], uint16_t (*As)[GLD], uint16_t (*Bs)[GLD],
+                                         int wm, int wn, int lane) {
+    const int l32 = lane & 31, kg = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        v8bf a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            a[i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(&As[wm * 64 + 32 * i + l32][16 * ks + 8 * kg]));
+            b[i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(&Bs[wn * 64 + 32 * i + l32][16 * ks + 8 * kg]));
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+}
+
+enum { EPI_RELU_BF16 = 0, EPI_MASK_BF16 = 1, EPI_F32 = 2 };
+
+struct GGRows {
+    const uint16_t *A;     // [A_rows, K] sorted rows, k contiguous
+    const uint16_t *B;     // per expert: B_KN ? [K, N] : [N, K]
+    void *C;               // [A_rows, N] bf16 or fp32
+    const uint16_t *mask;  // [A_rows, N] (EPI_MASK_BF16)
+    int K, N;
+    const int32_t *offsets, *tile_expert, *tile_row0, *num_tiles;
+};
+
+// C[rows of expert e, N] = A[rows, K] * B_e   over the row tiles of a 128-row tile table
+template <bool B_KN, int EPI>
+__global__ __launch_bounds__(256) void gg_rows_kernel(GGRows p) {
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][GBM][GLD];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][GBN][GLD];
+    const int tile = blockIdx.x;
+    if (tile >= *p.num_tiles) return;
+    const int e = p.tile_expert[tile];
+    const int row0 = p.tile_row0[tile];
+    const int rows = min(GBM, p.offsets[e + 1] - row0);
+    const int col0 = blockIdx.y * GBN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+    const uint16_t *Bw = p.B + (size_t)e * p.K * p.N;
+
+    v16f acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    Tile16 ta, tb;
+    auto load = [&](int k0) {
+        load_kcontig(ta, p.A, p.K, row0, rows, k0, tid);
+        if (B_KN) load_kstrided(tb, Bw, p.N, col0, k0, p.K, tid);
+        else load_kcontig(tb, Bw, p.K, col0, GBN, k0, tid);
+    };
+    auto store = [&](int buf) {
+        store_kcontig(ta, As[buf], tid);
+        if (B_KN) store_kstrided(tb, Bs[buf], tid);
+        else store_kcontig(tb, Bs[buf], tid);
+    };
+    load(0);
+    store(0);
+    __syncthreads();
+    for (int k0 = 0; k0 < p.K; k0 += GKC) {
+        const int buf = (k0 / GKC) & 1;
+        const bool more = k0 + GKC < p.K;
+        if (more) load(k0 + GKC);
+        mma_slab(acc, As[buf], Bs[buf], wm, wn, lane);
+        if (more) store(buf ^ 1);
+        __syncthreads();
+    }
+    const int l32 = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = wm * 64 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
+            if (row >= rows) continue;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = col0 + wn * 64 + 32 * j + l32;
+                const size_t at = (size_t)(row0 + row) * p.N + col;
+                float v = acc[i][j][r];
+                if (EPI == EPI_RELU_BF16) {
+                    reinterpret_cast<uint16_t *>(p.C)[at] = (uint16_t)bf16_rne(fmaxf(v, 0.f));
+                } else if (EPI == EPI_MASK_BF16) {
+                    // relu'(z) with relu'(0) = 0: the stored hidden value is positive iff z > 0
+                    const bool on = (p.mask[at] & 0x7fffu) != 0 && (p.mask[at] & 0x8000u) == 0;
+                    reinterpret_cast<uint16_t *>(p.C)[at] = (uint16_t)bf16_rne(on ? v : 0.f);
+                } else {
+                    reinterpret_cast<float *>(p.C)[at] = v;
+                }
+            }
+        }
+}
+
+struct GGWgrad {
+    const uint16_t *A;   // [A_rows, M] sorted rows
+    const uint16_t *B;   // [A_rows, N] sorted rows
+    float *C;            // [n, M, N]
+    int M, N;
+    const int32_t *offsets;
+};
+
+// C_e[M, N] = sum over the rows r of expert e of A[r, :]^T B[r, :]
+__global__ __launch_bounds__(256) void gg_wgrad_kernel(GGWgrad p) {
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][GBM][GLD];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][GBN][GLD];
+    const int e = blockIdx.z;
+    const int r0 = p.offsets[e], r1 = p.offsets[e + 1];
+    const int m0 = blockIdx.x * GBM, n0 = blockIdx.y * GBN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
+    v16f acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    Tile16 ta, tb;
+    const uint16_t *Ab = p.A + (size_t)r0 * p.M;
+    const uint16_t *Bb = p.B + (size_t)r0 * p.N;
+    const int K = r1 - r0;
+    auto load = [&](int k0) {
+        load_kstrided(ta, Ab, p.M, m0, k0, K, tid);
+        load_kstrided(tb, Bb, p.N, n0, k0, K, tid);
+    };
+    auto store = [&](int buf) {
+        store_kstrided(ta, As[buf], tid);
+        store_kstrided(tb, Bs[buf], tid);
+    };
+    if (K > 0) {
+        load(0);
+        store(0);
+    }
+    __syncthreads();
+    for (int k0 = 0; k0 < K; k0 += GKC) {
+        const int buf = (k0 / GKC) & 1;
+        const bool more = k0 + GKC < K;
+        if (more) load(k0 + GKC);
+        mma_slab(acc, As[buf], Bs[buf], wm, wn, lane);
+        if (more) store(buf ^ 1);
+        __syncthreads();
+    }
+    const int l32 = lane & 31, half = lane >> 5;
+    float *Ce = p.C + (size_t)e * p.M * p.N;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm * 64 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = n0 + wn * 64 + 32 * j + l32;
+                Ce[(size_t)row * p.N + col] = acc[i][j][r];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------------------
+// gate: gradients of the two CV^2 losses with respect to Importance and Load
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void loss_grad_kernel(const double *__restrict__ sums64, int n,
+                                                        float w_imp, float w_load,
+                                                        float *__restrict__ gI, float *__restrict__ gL) {
+    __shared__ double red[2][256];
+    for (int which = 0; which < 2; ++which) {
+        const double *v = sums64 + (size_t)which * n;
+        double s = 0.0, s2 = 0.0;
+        for (int i = threadIdx.x; i < n; i += 256) {
+            s += v[i];
+            s2 += v[i] * v[i];
+        }
+        red[0][threadIdx.x] = s;
+        red[1][threadIdx.x] = s2;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if ((int)threadIdx.x < o) {
+                red[0][threadIdx.x] += red[0][threadIdx.x + o];
+                red[1][threadIdx.x] += red[1][threadIdx.x + o];
+            }
+            __syncthreads();
+        }
+        const double S = red[0][0], Q = red[1][0];
+        __syncthreads();
+        const double w = which ? (double)w_load : (double)w_imp;
+        float *out = which ? gL : gI;
+        // d CV^2 / d v_i = 2 n v_i / S^2 - 2 n sum(v^2) / S^3   (population variance)
+        for (int i = threadIdx.x; i < n; i += 256)
+            out[i] = (float)(w * (2.0 * n * v[i] / (S * S) - 2.0 * n * Q / (S * S * S)));
+    }
+}
+
+struct GateBwdArgs {
+    const float *cleanb, *sp, *eps;   // [T, n]
+    const int32_t *idx;               // [T, k]
+    const float *gate, *dgate;        // [T, k]
+    const int32_t *next_idx;          // [T]
+    const float *gI, *gL;             // [n]
+    float *dclean, *draw;             // [T, n]
+    int64_t T;
+    int n, k;
+};
+
+__global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= p.T) return;
+    const int n = p.n, k = p.k;
+    const float *c_row = p.cleanb + t * n, *s_row = p.sp + t * n;
+    const float *e_row = p.eps ? p.eps + t * n : nullptr;
+    int ki[kMaxK];
+    float g[kMaxK], dH[kMaxK];
+    float inner = 0.f;
+#pragma unroll
+    for (int s = 0; s < kMaxK; ++s) {
+        ki[s] = s < k ? p.idx[t * k + s] : -1;
+        g[s] = s < k ? p.gate[t * k + s] : 0.f;
+        const float dg = s < k ? p.dgate[t * k + s] + p.gI[ki[s]] : 0.f;
+        dH[s] = dg;
+        inner = fmaf(g[s], dg, inner);
+    }
+#pragma unroll
+    for (int s = 0; s < kMaxK; ++s) dH[s] = g[s] * (dH[s] - inner);   // softmax over the kept logits
+
+    const bool with_load = k < n;
+    int j_in = -1, j_out = -1;
+    float thr_in = 0.f, thr_out = 0.f;
+    if (with_load) {
+        j_in = p.next_idx[t];
+#pragma unroll
+        for (int s = 0; s < kMaxK; ++s)
+            if (s == k - 1) j_out = ki[s];
+        thr_in = e_row ? __fmaf_rn(e_row[j_in], s_row[j_in], c_row[j_in]) : c_row[j_in];
+        thr_out = e_row ? __fmaf_rn(e_row[j_out], s_row[j_out], c_row[j_out]) : c_row[j_out];
+    }
+    // first pass: sums of c = gL * phi(u) / sp over the kept and the other experts
+    float S_in = 0.f, S_out = 0.f;
+    if (with_load) {
+        for (int i = lane; i < n; i += 64) {
+            bool kept = false;
+#pragma unroll
+            for (int s = 0; s < kMaxK; ++s) kept |= (ki[s] == i);
+            const float sp = s_row[i];
+            const float u = (c_row[i] - (kept ? thr_in : thr_out)) / sp;
+            const float c = p.gL[i] * 0.3989422804014327f * expf(-0.5f * u * u) / sp;
+            if (kept) S_in += c;
+            else S_out += c;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            S_in += __shfl_xor(S_in, off);
+            S_out += __shfl_xor(S_out, off);
+        }
+    }
+    // second pass: dclean, draw
+    for (int i = lane; i < n; i += 64) {
+        bool kept = false;
+        float dh = 0.f;
+#pragma unroll
+        for (int s = 0; s < kMaxK; ++s)
+            if (ki[s] == i) {
+                kept = true;
+                dh = dH[s];
+            }
+        const float sp = s_row[i];
+        float c = 0.f, u = 0.f;
+        if (with_load) {
+            u = (c_row[i] - (kept ? thr_in : thr_out)) / sp;
+            c = p.gL[i] * 0.3989422804014327f * expf(-0.5f * u * u) / sp;
+            if (i == j_in) dh -= S_in;     // the threshold of the kept experts
+            if (i == j_out) dh -= S_out;   // the threshold of all the others
+        }
+        const float ev = e_row ? e_row[i] : 0.f;
+        const float dsp = fmaf(dh, ev, -c * u);
+        p.dclean[t * n + i] = c + dh;
+        p.draw[t * n + i] = dsp * (1.0f - expf(-sp));   // softplus' = sigmoid(raw) = 1 - exp(-sp)
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// fp32 MFMA GEMM for the gate: C[M,N] (+)= sum over segments of A_s * B_s
+// ---------------------------------------------------------------------------------------
+struct SGArgs {
+    const float *A[2];
+    const float *B[2];
+    float *C;
+    int M, N, K;      // K per segment
+    int lda, ldb, ldc;
+    int nseg;
+    int ksplit;       // blockIdx.z = which * ksplit + split (A_MK only)
+    size_t c_which_stride, c_split_stride;
+};
+
+constexpr int SBM = 128, SBN = 128, SKC = 32, SAS = SKC + 4;
+
+// A_MK: A(m,k) = A[k*lda + m] (m contiguous; used for x^T), else A(m,k) = A[m*lda + k].
+// B_NK: B(k,n) = B[n*ldb + k] (k contiguous; used for W^T), else B(k,n) = B[k*ldb + n].
+template <bool A_MK, bool B_NK>
+__global__ __launch_bounds__(256, 2) void sg_kernel(SGArgs p) {
+    __shared__ __attribute__((aligned(16))) float As[2][SBM][SAS];  // [row][k parity][k/2]
+    __shared__ __attribute__((aligned(16))) float Bs[2][SKC][SBN];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int m0 = blockIdx.x * SBM, n0 = blockIdx.y * SBN;
+    int which = 0, split = 0;
+    if (A_MK) {
+        which = blockIdx.z / p.ksplit;
+        split = blockIdx.z % p.ksplit;
+    }
+    const int kper = A_MK ? ((p.K + p.ksplit - 1) / p.ksplit + SKC - 1) / SKC * SKC : p.K;
+    const int kbeg = split * kper, kend = min(p.K, kbeg + kper);
+
+    v16f acc[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+
+    float4 a_reg[4], b_reg[4];
+    auto load = [&](const float *A, const float *B, int k0) {
+        if (A_MK) {   // 32 k x 128 m, float4 along m
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = (tid >> 5) + 8 * i, m4 = (tid & 31) * 4;
+                a_reg[i] = (k0 + k) < kend ? *reinterpret_cast<const float4 *>(A + (size_t)(k0 + k) * p.lda + m0 + m4)
+                                           : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        } else {      // 128 m x 32 k, float4 along k
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = (tid >> 3) + 32 * i, kq = (tid & 7) * 4;
+                a_reg[i] = (m0 + r) < p.M ? *reinterpret_cast<const float4 *>(A + (size_t)(m0 + r) * p.lda + k0 + kq)
+                                          : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        if (B_NK) {   // 128 n x 32 k, float4 along k
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = (tid >> 3) + 32 * i, kq = (tid & 7) * 4;
+                b_reg[i] = (n0 + c) < p.N ? *reinterpret_cast<const float4 *>(B + (size_t)(n0 + c) * p.ldb + k0 + kq)
+                                          : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        } else {      // 32 k x 128 n, float4 along n
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = (tid >> 5) + 8 * i, c4 = (tid & 31) * 4;
+                b_reg[i] = ((k0 + k) < kend && (n0 + c4) < p.N) ? *reinterpret_cast<const float4 *>(B + (size_t)(k0 + k) * p.ldb + n0 + c4)
+                                           : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    };
+    auto store = [&](int buf) {
+        if (A_MK) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = (tid >> 5) + 8 * i, m4 = (tid & 31) * 4;
+                const int pos = (k & 1) * (SKC / 2) + (k >> 1);
+                As[buf][m4 + 0][pos] = a_reg[i].x; As[buf][m4 + 1][pos] = a_reg[i].y;
+                As[buf][m4 + 2][pos] = a_reg[i].z; As[buf][m4 + 3][pos] = a_reg[i].w;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = (tid >> 3) + 32 * i, kq = (tid & 7) * 4;
+                float *row = &As[buf][r][0];
+                *reinterpret_cast<float2 *>(row + kq / 2) = make_float2(a_reg[i].x, a_reg[i].z);
+                *reinterpret_cast<float2 *>(row + SKC / 2 + kq / 2) = make_float2(a_reg[i].y, a_reg[i].w);
+            }
+        }
+        if (B_NK) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = (tid >> 3) + 32 * i, kq = (tid & 7) * 4;
+                Bs[buf][kq + 0][c] = b_reg[i].x; Bs[buf][kq + 1][c] = b_reg[i].y;
+                Bs[buf][kq + 2][c] = b_reg[i].z; Bs[buf][kq + 3][c] = b_reg[i].w;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = (tid >> 5) + 8 * i, c4 = (tid & 31) * 4;
+                *reinterpret_cast<float4 *>(&Bs[buf][k][c4]) = b_reg[i];
+            }
+        }
+    };
+
+    const int nseg = A_MK ? 1 : p.nseg;
+    int buf = 0;
+    bool first = true;
+    for (int sgm = 0; sgm < nseg; ++sgm) {
+        const float *A = p.A[A_MK ? 0 : sgm];
+        const float *B = p.B[A_MK ? which : sgm];
+        for (int k0 = kbeg; k0 < kend; k0 += SKC) {
+            // single-buffered in time (two LDS buffers avoid one barrier): load, store, barrier, multiply
+            load(A, B, k0);
+            store(buf);
+            __syncthreads();
+            const float *a_row = &As[buf][wave * 32 + l32][half * (SKC / 2)];
+#pragma unroll
+            for (int kk4 = 0; kk4 < SKC / 2; kk4 += 4) {
+                const float4 a4 = *reinterpret_cast<const float4 *>(a_row + kk4);
+                const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int k = 2 * (kk4 + u) + half;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], Bs[buf][k][32 * c + l32], acc[c], 0, 0, 0);
+                }
+            }
+            buf ^= 1;
+            first = false;
+        }
+    }
+    (void)first;
+    float *C = p.C + (A_MK ? which * p.c_which_stride + split * p.c_split_stride : 0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int col = n0 + 32 * c + l32;
+        if (col >= p.N) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wave * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+            if (row < p.M) C[(size_t)row * p.ldc + col] = acc[c][r];
+        }
+    }
+}
+
+// out[i] = sum over splits (ascending) of part[split][i]
+__global__ __launch_bounds__(256) void split_sum_kernel(const float *__restrict__ part, int splits,
+                                                        size_t stride, size_t count,
+                                                        float *__restrict__ out) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    float s = 0.f;
+    for (int q = 0; q < splits; ++q) s += part[(size_t)q * stride + i];
+    out[i] = s;
+}
+
+__global__ __launch_bounds__(256) void dx_gather_add_kernel(float4 *__restrict__ dx,
+                                                            const float4 *__restrict__ dxs,
+                                                            const int32_t *__restrict__ inv_perm,
+                                                            int64_t T, int d4, int k) {
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    int rows[kMaxK];
+#pragma unroll
+    for (int s = 0; s < kMaxK; ++s) rows[s] = s < k ? inv_perm[t * k + s] : 0;
+    for (int c = lane; c < d4; c += 64) {
+        float4 acc = dx[t * d4 + c];
+#pragma unroll
+        for (int s = 0; s < kMaxK; ++s)
+            if (s < k) {
+                const float4 v = dxs[(int64_t)rows[s] * d4 + c];
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+        dx[t * d4 + c] = acc;
+    }
+}
+
+static size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct BwdLayout {
+    size_t xs, dout, hid, dz, dxs, dgate, dclean, draw, gI, gL, wpart, tile_expert, tile_row0,
+        num_tiles, total;
+    int ksplit;
+};
+
+static int bwd_layout(const moe_config *cfg, BwdLayout *L) {
+    const size_t T = cfg->T, n = cfg->n, A = T * (size_t)cfg->k, d = cfg->d, h = cfg->h;
+    size_t off = 0;
+    auto take = [&](size_t b) {
+        const size_t at = off;
+        off = up256(off + (b ? b : 1));
+        return at;
+    };
+    L->xs = take(A * d * 2);
+    L->dout = take(A * d * 2);
+    L->hid = take(A * h * 2);
+    L->dz = take(A * h * 2);
+    L->dxs = take(A * d * 4);
+    L->dgate = take(A * 4);
+    L->dclean = take(T * n * 4);
+    L->draw = take(T * n * 4);
+    L->gI = take(n * 4);
+    L->gL = take(n * 4);
+    // tokens per split of the weight-gradient GEMM: enough workgroups to fill the chip
+    const int64_t tiles = ceil_div(cfg->d, SBM) * ceil_div(cfg->n, SBN) * 2;
+    int ks = (int)ceil_div(1024, tiles);
+    const int maxks = (int)ceil_div(cfg->T > 0 ? cfg->T : 1, 256);
+    if (ks > maxks) ks = maxks;
+    if (ks < 1) ks = 1;
+    L->ksplit = ks;
+    L->wpart = take((size_t)ks * 2 * d * n * 4);
+    const size_t MT = (size_t)ceil_div((int64_t)A, GBM) + n + 8;
+    L->tile_expert = take(MT * 4);
+    L->tile_row0 = take(MT * 4);
+    L->num_tiles = take(16);
+    L->total = off;
+    return MOE_OK;
+}
+
+int launch_build_tiles(const int32_t *offsets, int n, int tile_rows, int32_t *tile_expert,
+                       int32_t *tile_row0, int32_t *num_tiles, hipStream_t st);
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" size_t moe_backward_workspace_bytes(const moe_config *cfg) {
+    if (check_config(cfg) != MOE_OK || cfg->a != 0) return 0;
+    BwdLayout L;
+    bwd_layout(cfg, &L);
+    return L.total;
+}
+
+extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const float *W_g,
+                                  const float *W_noise, const float *eps, const void *W1,
+                                  const void *W2, const float *dy, const int32_t *topk_idx,
+                                  const float *topk_gate, const void *fwd_workspace, float *dx,
+                                  float *dW_g, float *dW_noise, float *dW1, float *dW2,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+    moe_workspace_layout F;
+    int st = moe_get_workspace_layout(cfg, &F);
+    if (st != MOE_OK) return st;
+    if (cfg->a != 0) return MOE_EUNSUPPORTED;           // flat layer only
+    if (cfg->expert_dtype != MOE_DTYPE_BF16) return MOE_EUNSUPPORTED;
+    if (cfg->d % 128 != 0 || cfg->h % 128 != 0 || cfg->n % 32 != 0) return MOE_EUNSUPPORTED;
+    if (!x || !W_g || !W_noise || !W1 || !W2 || !dy || !topk_idx || !topk_gate || !fwd_workspace ||
+        !dx || !dW_g || !dW_noise || !dW1 || !dW2 || !workspace)
+        return MOE_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(W1) || !aligned16(W2) ||
+        !aligned16(dW1) || !aligned16(dW2) || !aligned16(dW_g) || !aligned16(dW_noise) ||
+        !aligned16(workspace) || !aligned16(fwd_workspace) || (eps && !aligned16(eps)))
+        return MOE_EINVAL;
+    BwdLayout L;
+    bwd_layout(cfg, &L);
+    if (workspace_bytes < L.total) return MOE_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t T = cfg->T, A = T * cfg->k;
+    const int d = cfg->d, h = cfg->h, n = cfg->n, k = cfg->k;
+    if (T == 0) return MOE_OK;
+    const char *fw = (const char *)fwd_workspace;
+    char *ws = (char *)workspace;
+    const float *cleanb = (const float *)(fw + F.cleanb), *sp = (const float *)(fw + F.sp);
+    const int32_t *next_idx = (const int32_t *)(fw + F.next_idx);
+    const int32_t *offsets = (const int32_t *)(fw + F.offsets);
+    const int32_t *perm = (const int32_t *)(fw + F.perm), *inv_perm = (const int32_t *)(fw + F.inv_perm);
+    const float *out_sorted = (const float *)(fw + F.out_sorted);
+    const double *sums64 = (const double *)(fw + F.aux_ws);
+    uint16_t *xs = (uint16_t *)(ws + L.xs), *dout = (uint16_t *)(ws + L.dout);
+    uint16_t *hid = (uint16_t *)(ws + L.hid), *dz = (uint16_t *)(ws + L.dz);
+    float *dxs = (float *)(ws + L.dxs), *dgate = (float *)(ws + L.dgate);
+    float *dclean = (float *)(ws + L.dclean), *draw = (float *)(ws + L.draw);
+    float *gI = (float *)(ws + L.gI), *gL = (float *)(ws + L.gL), *wpart = (float *)(ws + L.wpart);
+    int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
+    int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
+
+    // Eq.(1) backward per routed row
+    hipLaunchKernelGGL(bwd_prepare_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, s, x, dy,
+                       out_sorted, topk_gate, perm, A, d, k, xs, dout, dgate);
+    MOE_LAUNCH_CHECK();
+    if ((st = launch_build_tiles(offsets, n, GBM, tile_expert, tile_row0, num_tiles, s)) != MOE_OK) return st;
+    const unsigned max_tiles = (unsigned)(ceil_div(A, GBM) + n);
+
+    // experts (hidden layer recomputed)
+    GGRows g1{xs, (const uint16_t *)W1, hid, nullptr, d, h, offsets, tile_expert, tile_row0, num_tiles};
+    hipLaunchKernelGGL((gg_rows_kernel<true, EPI_RELU_BF16>), dim3(max_tiles, h / GBN), dim3(256), 0, s, g1);
+    MOE_LAUNCH_CHECK();
+    GGRows g2{dout, (const uint16_t *)W2, dz, hid, d, h, offsets, tile_expert, tile_row0, num_tiles};
+    hipLaunchKernelGGL((gg_rows_kernel<false, EPI_MASK_BF16>), dim3(max_tiles, h / GBN), dim3(256), 0, s, g2);
+    MOE_LAUNCH_CHECK();
+    GGWgrad w2{hid, dout, dW2, h, d, offsets};
+    hipLaunchKernelGGL(gg_wgrad_kernel, dim3(h / GBM, d / GBN, n), dim3(256), 0, s, w2);
+    MOE_LAUNCH_CHECK();
+    GGWgrad w1{xs, dz, dW1, d, h, offsets};
+    hipLaunchKernelGGL(gg_wgrad_kernel, dim3(d / GBM, h / GBN, n), dim3(256), 0, s, w1);
+    MOE_LAUNCH_CHECK();
+    GGRows g5{dz, (const uint16_t *)W1, dxs, nullptr, h, d, offsets, tile_expert, tile_row0, num_tiles};
+    hipLaunchKernelGGL((gg_rows_kernel<false, EPI_F32>), dim3(max_tiles, d / GBN), dim3(256), 0, s, g5);
+    MOE_LAUNCH_CHECK();
+
+    // gate
+    hipLaunchKernelGGL(loss_grad_kernel, dim3(1), dim3(256), 0, s, sums64, n, cfg->w_importance,
+                       cfg->w_load, gI, gL);
+    MOE_LAUNCH_CHECK();
+    GateBwdArgs gb{cleanb, sp, eps, topk_idx, topk_gate, dgate, next_idx, gI, gL, dclean, draw, T, n, k};
+    hipLaunchKernelGGL(gate_bwd_rows_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s, gb);
+    MOE_LAUNCH_CHECK();
+
+    // dW_g = x^T dclean, dW_noise = x^T draw: split over tokens, then a fixed-order sum
+    SGArgs wa{};
+    wa.A[0] = x; wa.B[0] = dclean; wa.B[1] = draw; wa.C = wpart;
+    wa.M = d; wa.N = n; wa.K = (int)T; wa.lda = d; wa.ldb = n; wa.ldc = n; wa.nseg = 1;
+    wa.ksplit = L.ksplit;
+    wa.c_split_stride = (size_t)2 * d * n;
+    wa.c_which_stride = (size_t)d * n;
+    hipLaunchKernelGGL((sg_kernel<true, false>), dim3(ceil_div(d, SBM), ceil_div(n, SBN), 2 * L.ksplit),
+                       dim3(256), 0, s, wa);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)ceil_div((int64_t)d * n, 256)), dim3(256), 0, s,
+                       wpart, L.ksplit, (size_t)2 * d * n, (size_t)d * n, dW_g);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)ceil_div((int64_t)d * n, 256)), dim3(256), 0, s,
+                       wpart + (size_t)d * n, L.ksplit, (size_t)2 * d * n, (size_t)d * n, dW_noise);
+    MOE_LAUNCH_CHECK();
+
+    // dx = dclean W_g^T + draw W_noise^T  (+ the experts' part)
+    SGArgs xa{};
+    xa.A[0] = dclean; xa.A[1] = draw; xa.B[0] = W_g; xa.B[1] = W_noise; xa.C = dx;
+    xa.M = (int)T; xa.N = d; xa.K = n; xa.lda = n; xa.ldb = n; xa.ldc = d; xa.nseg = 2; xa.ksplit = 1;
+    hipLaunchKernelGGL((sg_kernel<false, true>), dim3((unsigned)ceil_div(T, SBM), ceil_div(d, SBN), 1),
+                       dim3(256), 0, s, xa);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(dx_gather_add_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s,
+                       (float4 *)dx, (const float4 *)dxs, inv_perm, T, d / 4, k);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}

@@ -291,6 +291,44 @@ __global__ __launch_bounds__(256) void route_small_kernel(RouteArgs p, int nbits
     }
 }
 
+// Row-tile table for another tile height, from an existing offsets array (one workgroup).
+__global__ __launch_bounds__(1024) void build_tiles_kernel(const int32_t *__restrict__ offsets, int n,
+                                                           int TM, int32_t *__restrict__ tile_expert,
+                                                           int32_t *__restrict__ tile_row0,
+                                                           int32_t *__restrict__ num_tiles) {
+    __shared__ int wave_sums[16];
+    __shared__ int carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < n; base += 1024) {
+        const int e = base + threadIdx.x;
+        const int off = e < n ? offsets[e] : 0;
+        const int cnt = e < n ? offsets[e + 1] - off : 0;
+        const int tiles = (cnt + TM - 1) / TM;
+        const int c0 = carry;
+        const int inc = block_inclusive_scan(tiles, wave_sums);
+        if (e < n) {
+            const int toff = c0 + inc - tiles;
+            for (int j = 0; j < tiles; ++j) {
+                tile_expert[toff + j] = e;
+                tile_row0[toff + j] = off + j * TM;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 1023) carry = c0 + inc;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) num_tiles[0] = carry;
+}
+
+int launch_build_tiles(const int32_t *offsets, int n, int tile_rows, int32_t *tile_expert,
+                       int32_t *tile_row0, int32_t *num_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_kernel, dim3(1), dim3(1024), 0, st, offsets, n, tile_rows,
+                       tile_expert, tile_row0, num_tiles);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
 int launch_route(RouteArgs a, hipStream_t st) {
     int nbits = 0;
     while ((1 << nbits) < a.n) ++nbits;

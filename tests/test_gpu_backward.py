@@ -1,0 +1,130 @@
+"""GPU parity of the backward pass (flat layer, bf16 experts) against the oracle's gradients, which
+are themselves pinned by finite differences on the CPU."""
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import moe_workloads as W
+from oracle import moe_oracle as O
+from tests import gpu_harness as G
+
+pytestmark = pytest.mark.gpu
+TOL_BF16 = 2e-2
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def api():
+    assert torch.cuda.is_available()
+    from paper_1701_06538_amd import api as _api
+    return _api
+
+
+def fro_rel(got, ref):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def run_backward(api, shape, with_bias, dy, w_override=None):
+    if w_override is not None:
+        shape = W.scaled_config(shape, w_importance=w_override[0], w_load=w_override[1])
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias)
+    W1, W2 = G.device_weights(shape)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+    run.fused()
+    f32 = dict(dtype=torch.float32, device="cuda")
+    T, d, h, n = shape.T, shape.d, shape.h, shape.n
+    out = dict(dx=torch.full((T, d), float("nan"), **f32), dW_g=torch.full((d, n), float("nan"), **f32),
+               dW_noise=torch.full((d, n), float("nan"), **f32), dW1=torch.full((n, d, h), float("nan"), **f32),
+               dW2=torch.full((n, h, d), float("nan"), **f32))
+    bws = torch.empty(api.moe_backward_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+    dyd = G.dev(dy)
+
+    def call():
+        api.moe_layer_backward(run.cfg, run.x, run.W_g, run.W_noise, run.eps, run.W1, run.W2, dyd,
+                               run.topk_idx, run.topk_gate, run.workspace, out["dx"], out["dW_g"],
+                               out["dW_noise"], out["dW1"], out["dW2"], bws)
+        torch.cuda.synchronize()
+    call()
+    return shape, (x, W_g, W_noise, eps, bias), run, out, call
+
+
+def oracle_backward(shape, inputs, dy, experts_for_dW=None):
+    x, W_g, W_noise, eps, bias = inputs
+    fw = G.oracle_flat(shape, x, W_g, W_noise, eps, bias)
+    # bf16 workloads: the experts' input activations are bf16(x) (the ReLU mask is decided on them)
+    gr = O.flat_backward(x, W_g, W_noise, fw, shape.k, G.oracle_weight_fn(shape), dy, shape.w_importance,
+                         shape.w_load, experts_for_dW=experts_for_dW, expert_input=O.round_to_bf16(x))
+    return fw, gr
+
+
+CASES = [
+    ("small", dict(T=512, n=32), False),
+    ("ragged_bias", dict(T=777, n=64, k=3), True),
+    ("k1", dict(T=300, n=32, k=1), False),
+]
+
+
+@pytest.mark.parametrize("name,ov,with_bias", CASES, ids=[c[0] for c in CASES])
+def test_backward_parity(api, name, ov, with_bias):
+    shape = W.scaled_config(W.CONFIGS[4], **ov)
+    if with_bias:
+        shape = W.scaled_config(shape, zipf_beta=0.5)
+    say("case backward", name, shape)
+    dy = W.upstream_grad(shape)
+    shape, inputs, run, out, call = run_backward(api, shape, with_bias, dy)
+    fw, gr = oracle_backward(shape, inputs, dy)
+    assert np.array_equal(run.topk_idx.cpu().numpy(), fw.idx)
+    errs = dict(dx=G.rel_errors(out["dx"].cpu().numpy(), gr.dx)[0],
+                dW_g=fro_rel(out["dW_g"].cpu().numpy(), gr.dW_g),
+                dW_noise=fro_rel(out["dW_noise"].cpu().numpy(), gr.dW_noise))
+    dW1 = out["dW1"].cpu().numpy()
+    dW2 = out["dW2"].cpu().numpy()
+    worst1 = worst2 = 0.0
+    for e in range(shape.n):
+        if e in gr.dW1:
+            worst1 = max(worst1, fro_rel(dW1[e], gr.dW1[e]))
+            worst2 = max(worst2, fro_rel(dW2[e], gr.dW2[e]))
+        else:
+            assert not dW1[e].any() and not dW2[e].any(), "expert without tokens must get zero gradients"
+    errs["dW1"], errs["dW2"] = worst1, worst2
+    say("  relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= TOL_BF16, (k, v)
+    # bit-reproducible
+    keep = {k: v.clone() for k, v in out.items()}
+    call()
+    for k in keep:
+        assert torch.equal(keep[k], out[k]), k
+
+
+def test_gate_gradients_alone_are_fp32_accurate(api):
+    """dy = 0 leaves J = L_importance + L_load: every gradient then comes from the fp32 gate path."""
+    shape = W.scaled_config(W.CONFIGS[4], T=1024, n=64)
+    say("case backward losses-only", shape)
+    dy = np.zeros((shape.T, shape.d), np.float32)
+    shape, inputs, run, out, call = run_backward(api, shape, False, dy)
+    fw, gr = oracle_backward(shape, inputs, dy)
+    e = dict(dx=fro_rel(out["dx"].cpu().numpy(), gr.dx), dW_g=fro_rel(out["dW_g"].cpu().numpy(), gr.dW_g),
+             dW_noise=fro_rel(out["dW_noise"].cpu().numpy(), gr.dW_noise))
+    say("  relative errors:", {k: "%.2e" % v for k, v in e.items()})
+    for k, v in e.items():
+        assert v <= 1e-4, (k, v)
+    assert not out["dW1"].any() and not out["dW2"].any()
+
+
+def test_backward_without_losses(api):
+    shape = W.scaled_config(W.CONFIGS[4], T=512, n=32)
+    dy = W.upstream_grad(shape)
+    shape, inputs, run, out, call = run_backward(api, shape, False, dy, w_override=(0.0, 0.0))
+    fw, gr = oracle_backward(shape, inputs, dy)
+    for name, ref in (("dx", gr.dx), ("dW_g", gr.dW_g), ("dW_noise", gr.dW_noise)):
+        assert fro_rel(out[name].cpu().numpy(), ref) <= TOL_BF16, name

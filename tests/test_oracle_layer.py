@@ -221,3 +221,12 @@ def test_paper_counts_fixture():
     assert d * h + h * d == vals["params_per_expert"]
     assert k * (d * h + h * d) == vals["macs_per_token_k4"]
     assert 4 * 8192 // 256 == vals["mean_rows_per_expert_n256_b8192"]
+
+
+def test_bf16_rounding_helper_matches_torch():
+    import torch
+    rng = np.random.default_rng(3)
+    a = np.concatenate([rng.standard_normal(100000).astype(np.float32) * 3,
+                        np.array([1.0, 1.00390625, 1.001953125, 1.005859375, -2.5, 0.0], np.float32)])
+    want = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(O.round_to_bf16(a), want)
