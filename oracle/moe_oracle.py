@@ -417,7 +417,7 @@ def flat_backward(x, W_g, W_noise, fwd: FlatForward, k, weight_fn, dy,
         dout = g[r, s][:, None] * dy[r]
         dh = dout @ W2.T
         dz = dh * (z > 0.0)
-        np.add.at(dx, r, dz @ W1.T)
+        dx[r] += dz @ W1.T          # a token reaches an expert at most once, so r has no repeats
         if keep is None or int(e) in keep:
             dW2[int(e)] = hid.T @ dout
             dW1[int(e)] = xe.T @ dz

@@ -27,6 +27,19 @@ def api():
     return _api
 
 
+def row_stats(got, ref):
+    """(Frobenius relative error, fraction of rows whose relative L2 error exceeds the tolerance,
+    worst row).  A hidden unit whose pre-activation is zero to within fp32 accumulation error may
+    fall on either side of the ReLU kink; such a unit moves one row of dx by a few percent, so
+    rows are judged as a population and the worst one is reported."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    num = np.linalg.norm(got - ref, axis=1)
+    den = np.maximum(np.linalg.norm(ref, axis=1), 1e-300)
+    rel = num / den
+    return fro_rel(got, ref), float((rel > TOL_BF16).mean()), float(rel.max())
+
+
 def fro_rel(got, ref):
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
@@ -128,3 +141,43 @@ def test_backward_without_losses(api):
     fw, gr = oracle_backward(shape, inputs, dy)
     for name, ref in (("dx", gr.dx), ("dW_g", gr.dW_g), ("dW_noise", gr.dW_noise)):
         assert fro_rel(out[name].cpu().numpy(), ref) <= TOL_BF16, name
+
+
+def test_cfg4_full_training_step(api):
+    """Config 4 at full size: T=65536, n=512, Zipf-skewed loads, forward + backward."""
+    shape = W.CONFIGS[4]
+    say("full config", shape)
+    dy = W.upstream_grad(shape)
+    shape, inputs, run, out, call = run_backward(api, shape, True, dy)
+    t0 = time.perf_counter()
+    sample = [0, 1, 17, 255, 300, 511]
+    counts = np.bincount(run.topk_idx.cpu().numpy().reshape(-1), minlength=shape.n)
+    sample += [int(np.argmax(counts)), int(np.argmin(counts))]
+    fw, gr = oracle_backward(shape, inputs, dy, experts_for_dW=sample)
+    say("  oracle forward+backward %.1f s; load max/mean %.1f" % (time.perf_counter() - t0, counts.max() / counts.mean()))
+    assert np.array_equal(run.topk_idx.cpu().numpy(), fw.idx)
+    dx_fro, dx_bad, dx_worst = row_stats(out["dx"].cpu().numpy(), gr.dx)
+    say("  dx: Frobenius rel %.2e, rows over tolerance %.2e, worst row %.2e" % (dx_fro, dx_bad, dx_worst))
+    assert dx_bad <= 1e-3 and dx_worst <= 0.25
+    errs = dict(dx=dx_fro,
+                dW_g=fro_rel(out["dW_g"].cpu().numpy(), gr.dW_g),
+                dW_noise=fro_rel(out["dW_noise"].cpu().numpy(), gr.dW_noise))
+    for e in sorted(set(sample)):
+        errs["dW1[%d]" % e] = fro_rel(out["dW1"][e].cpu().numpy(), gr.dW1[e])
+        errs["dW2[%d]" % e] = fro_rel(out["dW2"][e].cpu().numpy(), gr.dW2[e])
+    say("  relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+    for k, v in errs.items():
+        assert v <= TOL_BF16, (k, v)
+    assert torch.isfinite(out["dW1"]).all() and torch.isfinite(out["dW2"]).all()
+
+    def step():
+        run.api.moe_layer_forward(run.cfg, run.x, run.W_g, run.W_noise, run.bias, run.eps, run.W1, run.W2,
+                                  run.y, run.topk_idx, run.topk_gate, run.importance, run.load, run.losses,
+                                  run.workspace)
+        call()
+    step()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        step()
+    ms = (time.perf_counter() - t0) / 3 * 1e3
+    say("  forward+backward step %.3f ms -> %.2f M tokens/s" % (ms, shape.T / ms / 1e3))
