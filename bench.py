@@ -39,6 +39,12 @@ class HipEvents:
         assert err == 0, "hipEventCreate failed: %d" % err
         return ev.value
 
+    def record(self, ev):
+        import torch
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        err = self.hip.hipEventRecord(ev, torch.cuda.current_stream().cuda_stream)
+        assert err == 0, "hipEventRecord failed: %d" % err
+
     def elapsed_ms(self, a, b):
         out = ctypes.c_float()
         err = self.hip.hipEventElapsedTime(ctypes.byref(out), a, b)
@@ -99,7 +105,7 @@ def cpu_baseline(shape, sample_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default 1)")
     ap.add_argument("--cpu-sample", type=int, default=2048)
@@ -108,6 +114,8 @@ def main():
                     help="also run one plain 1 GiB device-to-device copy kernel, so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
     args = ap.parse_args()
+    if args.steps is None:
+        args.steps = 200 if args.config <= 1 else 20
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the MoE layer on ONE GPU (one GPU's share of the batch at its "
                  "real shape); --gpus %d is not available. Sharding is described in DESIGN.md." % args.gpus)
@@ -122,17 +130,42 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
     shape = W.CONFIGS[args.config]
-    assert not shape.hierarchical and not shape.backward, "bench covers the flat forward workloads"
-    x, W_g, W_noise, eps, bias = G.flat_inputs(shape)
-    W1, W2 = G.device_weights(shape)
-    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
-    ws = torch.empty(api.moe_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
     hip = HipEvents()
+    if shape.hierarchical:
+        inputs = W.hier_gate_inputs(shape)
+        W1, W2 = G.device_weights(shape, chunk=256)
+        run = G.HierRun(api, shape, inputs, W1, W2)
+        ws = run.workspace
 
-    def step(events=None):
-        api.moe_layer_forward_profiled(run.cfg, run.x, run.W_g, run.W_noise, run.bias, run.eps, run.W1,
-                                       run.W2, run.y, run.topk_idx, run.topk_gate, run.importance,
-                                       run.load, run.losses, ws, events)
+        def step(events=None):
+            if events is not None and events[4]:
+                hip.record(events[4])
+            api.moe_layer_forward_hier(run.cfg, run.x, run.Wg_p, run.Wn_p, run.eps_p, run.Wg_s, run.Wn_s,
+                                       run.eps_s, run.W1, run.W2, run.y, run.topk_idx, run.topk_gate,
+                                       run.importance, run.load, run.losses, ws)
+            if events is not None and events[5]:
+                hip.record(events[5])
+    else:
+        x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias=shape.zipf_beta > 0)
+        W1, W2 = G.device_weights(shape)
+        run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+        ws = torch.empty(api.moe_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+        if shape.backward:
+            dy = G.dev(W.upstream_grad(shape))
+            f32 = dict(dtype=torch.float32, device="cuda")
+            grads = [torch.empty((shape.T, shape.d), **f32), torch.empty((shape.d, shape.n), **f32),
+                     torch.empty((shape.d, shape.n), **f32), torch.empty((shape.n, shape.d, shape.h), **f32),
+                     torch.empty((shape.n, shape.h, shape.d), **f32)]
+            bws = torch.empty(api.moe_backward_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+
+        def step(events=None):
+            api.moe_layer_forward_profiled(run.cfg, run.x, run.W_g, run.W_noise, run.bias, run.eps, run.W1,
+                                           run.W2, run.y, run.topk_idx, run.topk_gate, run.importance,
+                                           run.load, run.losses, ws, events)
+            if shape.backward:
+                api.moe_layer_backward(run.cfg, run.x, run.W_g, run.W_noise, run.eps, run.W1, run.W2, dy,
+                                       run.topk_idx, run.topk_gate, ws, grads[0], grads[1], grads[2],
+                                       grads[3], grads[4], bws)
 
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
@@ -142,6 +175,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.config > 1:
+        args.warmup = min(args.warmup, 3)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -152,21 +187,22 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(K):
-        step([0, 0, 0, 0, ffn_ev[i][0], ffn_ev[i][1], 0, 0, 0, 0])
+        step([0, 0, 0, 0, ffn_ev[i][0], ffn_ev[i][1], 0, 0, 0, 0])   # hierarchical: brackets the whole call
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ffn_ms = float(np.mean([hip.elapsed_ms(a, b) for a, b in ffn_ev]))
 
     # second, untimed pass with every stage bracketed (diagnostics only)
-    all_ev = [[hip.create() for _ in range(10)] for _ in range(min(K, 50))]
-    for evs in all_ev:
-        step(evs)
-    torch.cuda.synchronize()
-    stage_ms = {name: float(np.mean([hip.elapsed_ms(evs[2 * i], evs[2 * i + 1]) for evs in all_ev]))
-                for i, name in enumerate(STAGES)}
+    stage_ms = None
+    if not shape.hierarchical:
+        all_ev = [[hip.create() for _ in range(10)] for _ in range(min(K, 50))]
+        for evs in all_ev:
+            step(evs)
+        torch.cuda.synchronize()
+        stage_ms = {name: float(np.mean([hip.elapsed_ms(evs[2 * i], evs[2 * i + 1]) for evs in all_ev]))
+                    for i, name in enumerate(STAGES)}
 
-    counts = run.api.moe_get_workspace_layout(run.cfg)
-    lay = counts
+    lay = run.api.moe_get_workspace_layout(run.cfg)
     cnt = ws[lay.counts:lay.counts + 4 * shape.n].view(torch.int32).cpu().numpy()
     used = int((cnt > 0).sum())
     A = shape.T * shape.k
@@ -179,7 +215,7 @@ def main():
     ms_per_step = elapsed / K * 1e3
 
     out = {
-        "metric": "MoE-layer tokens/sec (fwd) at d=512,h=1024",
+        "metric": "MoE-layer tokens/sec (%s) at d=512,h=1024" % ("fwd+bwd" if shape.backward else "fwd"),
         "value": shape.T / (elapsed / K),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -196,7 +232,9 @@ def main():
                      "mfma_tflops": ffn_flops / (ffn_ms * 1e-3) / 1e12},
         "stage_ms": stage_ms,
     }
-    if not args.no_cpu_baseline:
+    if shape.hierarchical:
+        out["roofline"].update({"kernel": "moe_layer_forward_hier (whole call)", "note": "event pair brackets the whole layer"})
+    if not args.no_cpu_baseline and not shape.hierarchical and not shape.backward:
         out["cpu_baseline"] = cpu_baseline(shape, min(args.cpu_sample, shape.T))
     print(json.dumps(out))
 

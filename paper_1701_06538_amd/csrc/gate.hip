@@ -218,9 +218,13 @@ __device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
     return v1 > v2 || (v1 == v2 && i1 < i2);
 }
 
-template <int L>
+// L >= k+1 candidate slots per lane; NCH >= ceil(n/64) register chunks: a lane holds the whole of
+// its share of a row (clean, softplus, H) in registers, so the row is read from memory once, all
+// loads are in flight together, and both passes (top-k, then P(x,i)) run from registers.  The
+// per-expert sums of G(x) and P(x,.) also stay in registers across the rows a wave walks.
+template <int L, int NCH>
 __global__ __launch_bounds__(256) void gate_topk_kernel(TopkArgs p) {
-    extern __shared__ float lds_acc[];  // [4][2][n]
+    extern __shared__ float lds_acc[];  // [2][n]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = p.n, k = p.k;
     const int RPB = p.rows_per_block;
@@ -239,18 +243,31 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(TopkArgs p) {
         rb = (int64_t)blockIdx.x * RPB;
         re = min(rb + RPB, p.R);
     }
-
-    for (int i = tid; i < 8 * n; i += 256) lds_acc[i] = 0.f;
-    __syncthreads();
-    float *acc_imp = lds_acc + (size_t)wave * 2 * n;
-    float *acc_load = acc_imp + n;
     const int kp1 = (k < n) ? k + 1 : k;
+    float acc_imp[NCH], acc_load[NCH];
+#pragma unroll
+    for (int q = 0; q < NCH; ++q) {
+        acc_imp[q] = 0.f;
+        acc_load[q] = 0.f;
+    }
 
     for (int64_t r = rb + wave; r < re; r += 4) {
         const float *c_row = p.cleanb + r * n;
         const float *s_row = p.sp + r * n;
         const int64_t orow = p.row_map ? p.row_map[r] : r;
         const float *e_row = p.eps ? p.eps + orow * n : nullptr;
+
+        float cv[NCH], sv[NCH], hv[NCH];
+#pragma unroll
+        for (int q = 0; q < NCH; ++q) {
+            const int i = lane + 64 * q;
+            const bool in = i < n;
+            cv[q] = in ? c_row[i] : 0.f;
+            sv[q] = in ? s_row[i] : 1.f;
+            hv[q] = (in && e_row) ? e_row[i] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < NCH; ++q) hv[q] = e_row ? __fmaf_rn(hv[q], sv[q], cv[q]) : cv[q];
 
         float lv[L];
         int li[L];
@@ -259,19 +276,22 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(TopkArgs p) {
             lv[j] = -INFINITY;
             li[j] = 0x7fffffff;
         }
-        for (int i = lane; i < n; i += 64) {
-            const float c = c_row[i];
-            float v = e_row ? __fmaf_rn(e_row[i], s_row[i], c) : c;
-            int id = i;
 #pragma unroll
-            for (int j = 0; j < L; ++j) {
-                if (better(v, id, lv[j], li[j])) {
-                    const float tv = lv[j];
-                    const int ti = li[j];
-                    lv[j] = v;
-                    li[j] = id;
-                    v = tv;
-                    id = ti;
+        for (int q = 0; q < NCH; ++q) {
+            const int i = lane + 64 * q;
+            if (i < n) {
+                float v = hv[q];
+                int id = i;
+#pragma unroll
+                for (int j = 0; j < L; ++j) {
+                    if (better(v, id, lv[j], li[j])) {
+                        const float tv = lv[j];
+                        const int ti = li[j];
+                        lv[j] = v;
+                        li[j] = id;
+                        v = tv;
+                        id = ti;
+                    }
                 }
             }
         }
@@ -337,28 +357,44 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(TopkArgs p) {
             if (j == k - 1) thr_out = tv[j];
         }
         if (lane == 0 && p.next_idx) p.next_idx[orow] = nxt;
-        for (int i = lane; i < n; i += 64) {
-            float gi = 0.f;
-            bool kept = false;
 #pragma unroll
-            for (int j = 0; j < L; ++j)
-                if (j < k && ti[j] == i) {
-                    kept = true;
-                    gi = g[j];
+        for (int q = 0; q < NCH; ++q) {
+            const int i = lane + 64 * q;
+            if (i < n) {
+                float gi = 0.f;
+                bool kept = false;
+#pragma unroll
+                for (int j = 0; j < L; ++j)
+                    if (j < k && ti[j] == i) {
+                        kept = true;
+                        gi = g[j];
+                    }
+                float P = 1.0f;
+                if (k < n) {
+                    const float u = (cv[q] - (kept ? thr_in : thr_out)) / sv[q];
+                    P = 0.5f * erfcf(-0.70710678118654752f * u);
                 }
-            float P = 1.0f;
-            if (k < n) {
-                const float u = (c_row[i] - (kept ? thr_in : thr_out)) / s_row[i];
-                P = 0.5f * erfcf(-0.70710678118654752f * u);
+                acc_load[q] += P;
+                acc_imp[q] += gi;
             }
-            acc_load[i] += P;
-            acc_imp[i] += gi;
         }
     }
-    __syncthreads();
+    // the four waves' sums, added in wave order through one [2][n] LDS buffer
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) {
+                const int i = lane + 64 * q;
+                if (i < n) {
+                    lds_acc[i] = (w ? lds_acc[i] : 0.f) + acc_imp[q];
+                    lds_acc[n + i] = (w ? lds_acc[n + i] : 0.f) + acc_load[q];
+                }
+            }
+        }
+        __syncthreads();
+    }
     float *out = p.partials + (size_t)blockIdx.x * 2 * n;
-    for (int i = tid; i < 2 * n; i += 256)
-        out[i] = (lds_acc[i] + lds_acc[2 * n + i]) + (lds_acc[4 * n + i] + lds_acc[6 * n + i]);
+    for (int i = tid; i < 2 * n; i += 256) out[i] = lds_acc[i];
 }
 
 // Eq.(12): global expert id and gate product for every (token, primary slot, secondary slot)
@@ -410,16 +446,20 @@ int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
     return MOE_OK;
 }
 
+template <int L>
+static void launch_topk_nch(const TopkArgs &a, unsigned blocks, size_t lds, hipStream_t st) {
+    if (a.n <= 256) hipLaunchKernelGGL((gate_topk_kernel<L, 4>), dim3(blocks), dim3(256), lds, st, a);
+    else if (a.n <= 512) hipLaunchKernelGGL((gate_topk_kernel<L, 8>), dim3(blocks), dim3(256), lds, st, a);
+    else if (a.n <= 1024) hipLaunchKernelGGL((gate_topk_kernel<L, 16>), dim3(blocks), dim3(256), lds, st, a);
+    else hipLaunchKernelGGL((gate_topk_kernel<L, 32>), dim3(blocks), dim3(256), lds, st, a);
+}
+
 int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st) {
     if (blocks <= 0) return MOE_OK;
-    const size_t lds = (size_t)8 * a.n * sizeof(float);
-    if (a.k + 1 <= 3) {
-        hipLaunchKernelGGL(gate_topk_kernel<3>, dim3((unsigned)blocks), dim3(256), lds, st, a);
-    } else if (a.k + 1 <= 5) {
-        hipLaunchKernelGGL(gate_topk_kernel<5>, dim3((unsigned)blocks), dim3(256), lds, st, a);
-    } else {
-        hipLaunchKernelGGL(gate_topk_kernel<9>, dim3((unsigned)blocks), dim3(256), lds, st, a);
-    }
+    const size_t lds = (size_t)2 * a.n * sizeof(float);
+    if (a.k + 1 <= 3) launch_topk_nch<3>(a, (unsigned)blocks, lds, st);
+    else if (a.k + 1 <= 5) launch_topk_nch<5>(a, (unsigned)blocks, lds, st);
+    else launch_topk_nch<9>(a, (unsigned)blocks, lds, st);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
 }

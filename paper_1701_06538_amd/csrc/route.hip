@@ -43,17 +43,36 @@ __global__ __launch_bounds__(256) void route_hist_kernel(RouteArgs p) {
     for (int e = threadIdx.x; e < n; e += 256) out[e] = lds_hist[e];
 }
 
+// Per expert, the exclusive scan of the chunk histograms over the chunks (in place) and the
+// total.  A workgroup covers 32 experts x 8 chunk groups: every thread first sums its group of
+// chunks (independent loads), the eight group sums are scanned in LDS, then every thread rewrites
+// its chunks with the running prefix.
 __global__ __launch_bounds__(256) void route_colscan_kernel(RouteArgs p) {
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= p.n) return;
+    __shared__ int grp[8][33];
+    const int ex = threadIdx.x & 31, cg = threadIdx.x >> 5;
+    const int e = blockIdx.x * 32 + ex;
+    const int per = (p.num_chunks + 7) / 8;
+    const int c0 = cg * per, c1 = min(p.num_chunks, c0 + per);
+    int sum = 0;
+    if (e < p.n)
+        for (int c = c0; c < c1; ++c) sum += p.hist[(size_t)c * p.n + e];
+    grp[cg][ex] = sum;
+    __syncthreads();
     int run = 0;
-    for (int c = 0; c < p.num_chunks; ++c) {
-        int32_t *cell = p.hist + (size_t)c * p.n + e;
-        const int v = *cell;
-        *cell = run;
-        run += v;
+    for (int q = 0; q < cg; ++q) run += grp[q][ex];
+    if (e < p.n) {
+        for (int c = c0; c < c1; ++c) {
+            int32_t *cell = p.hist + (size_t)c * p.n + e;
+            const int v = *cell;
+            *cell = run;
+            run += v;
+        }
+        if (cg == 7) {
+            int total = 0;
+            for (int q = 0; q < 8; ++q) total += grp[q][ex];
+            p.counts[e] = total;
+        }
     }
-    p.counts[e] = run;
 }
 
 // Block-wide inclusive scan of one int per thread (1024 threads = 16 waves).
@@ -345,7 +364,7 @@ int launch_route(RouteArgs a, hipStream_t st) {
         hipLaunchKernelGGL(route_hist_kernel, dim3(a.num_chunks), dim3(256), lds, st, a);
         MOE_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(route_colscan_kernel, dim3((unsigned)ceil_div(a.n, 256)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(route_colscan_kernel, dim3((unsigned)ceil_div(a.n, 32)), dim3(256), 0, st, a);
     MOE_LAUNCH_CHECK();
     hipLaunchKernelGGL(route_offsets_kernel, dim3(1), dim3(1024), 0, st, a);
     MOE_LAUNCH_CHECK();
