@@ -210,7 +210,7 @@ int moe_layer_forward_hier(const moe_config *cfg, const float *x, const float *W
  * workspace exactly as moe_layer_forward left it (logits, permutation, expert outputs, loss sums).
  * Outputs (overwritten): dx [T,d], dW_g, dW_noise [d,n], dW1 [n,d,h], dW2 [n,h,d], all f32
  * (fp32 master gradients; experts that received no token get zeros).
- * bf16 experts only, d and h multiples of 128, n a multiple of 32; expert math in bf16 MFMA with
+ * bf16 experts only, d and h multiples of 256, n a multiple of 32; expert math in bf16 MFMA with
  * fp32 accumulation, gate math in fp32.  workspace: moe_backward_workspace_bytes().
  */
 size_t moe_backward_workspace_bytes(const moe_config *cfg);

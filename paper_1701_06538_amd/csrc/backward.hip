@@ -221,58 +221,80 @@ struct GGWgrad {
     const int32_t *offsets;
 };
 
-// C_e[M, N] = sum over the rows r of expert e of A[r, :]^T B[r, :]
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// 8 rows x 8 columns of a row-major bf16 matrix held by one lane: rows r..r+7, columns c..c+7
+struct Blk8 {
+    uint32_t r[8][4];
+};
+__device__ __forceinline__ void load_blk8(Blk8 &f, const uint16_t *src, int64_t ld, int row, int row_end) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint4 v = (row + i) < row_end ? *reinterpret_cast<const uint4 *>(src + (int64_t)(row + i) * ld)
+                                            : make_uint4(0u, 0u, 0u, 0u);
+        f.r[i][0] = v.x; f.r[i][1] = v.y; f.r[i][2] = v.z; f.r[i][3] = v.w;
+    }
+}
+// column j of the block: 8 consecutive rows -> one MFMA operand (register transpose by byte permutes)
+__device__ __forceinline__ v8bf blk8_column(const Blk8 &f, int j) {
+    const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+    uint4 o;
+    o.x = __builtin_amdgcn_perm(f.r[1][j >> 1], f.r[0][j >> 1], sel);
+    o.y = __builtin_amdgcn_perm(f.r[3][j >> 1], f.r[2][j >> 1], sel);
+    o.z = __builtin_amdgcn_perm(f.r[5][j >> 1], f.r[4][j >> 1], sel);
+    o.w = __builtin_amdgcn_perm(f.r[7][j >> 1], f.r[6][j >> 1], sel);
+    return __builtin_bit_cast(v8bf, o);
+}
+
+// C_e[M, N] = sum over the rows r of expert e of A[r, :]^T B[r, :]   (both operands row-major in
+// the rows being contracted).  No LDS: lane (c = lane%16, g = lane/16) loads rows r0+8g..+7,
+// columns 8c..8c+7 of A and of B with 16-byte loads and transposes the 8x8 blocks in registers,
+// which yields v_mfma_f32_16x16x32_bf16 operands for 128 columns of A and 128 of B; one wave
+// accumulates a 128 x 128 block of C (64 MFMAs per 32 contracted rows), four waves a 256 x 256 one.
 __global__ __launch_bounds__(256) void gg_wgrad_kernel(GGWgrad p) {
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][GBM][GLD];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][GBN][GLD];
     const int e = blockIdx.z;
     const int r0 = p.offsets[e], r1 = p.offsets[e + 1];
-    const int m0 = blockIdx.x * GBM, n0 = blockIdx.y * GBN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-    v16f acc[2][2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int m0 = blockIdx.x * 256 + (wave >> 1) * 128, n0 = blockIdx.y * 256 + (wave & 1) * 128;
+    v4f acc[8][8];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    Tile16 ta, tb;
-    const uint16_t *Ab = p.A + (size_t)r0 * p.M;
-    const uint16_t *Bb = p.B + (size_t)r0 * p.N;
-    const int K = r1 - r0;
-    auto load = [&](int k0) {
-        load_kstrided(ta, Ab, p.M, m0, k0, K, tid);
-        load_kstrided(tb, Bb, p.N, n0, k0, K, tid);
-    };
-    auto store = [&](int buf) {
-        store_kstrided(ta, As[buf], tid);
-        store_kstrided(tb, Bs[buf], tid);
-    };
-    if (K > 0) {
-        load(0);
-        store(0);
+        for (int j = 0; j < 8; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+    const uint16_t *Ab = p.A + m0 + 8 * c;
+    const uint16_t *Bb = p.B + n0 + 8 * c;
+    Blk8 fa, fb;
+    if (r0 < r1) {
+        load_blk8(fa, Ab, p.M, r0 + 8 * g, r1);
+        load_blk8(fb, Bb, p.N, r0 + 8 * g, r1);
     }
-    __syncthreads();
-    for (int k0 = 0; k0 < K; k0 += GKC) {
-        const int buf = (k0 / GKC) & 1;
-        const bool more = k0 + GKC < K;
-        if (more) load(k0 + GKC);
-        mma_slab(acc, As[buf], Bs[buf], wm, wn, lane);
-        if (more) store(buf ^ 1);
-        __syncthreads();
+    for (int r = r0; r < r1; r += 32) {
+        v8bf a[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a[j] = blk8_column(fa, j);
+        v8bf b[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) b[j] = blk8_column(fb, j);
+        if (r + 32 < r1) {   // next 32 rows while the matrix cores work on these
+            load_blk8(fa, Ab, p.M, r + 32 + 8 * g, r1);
+            load_blk8(fb, Bb, p.N, r + 32 + 8 * g, r1);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    const int l32 = lane & 31, half = lane >> 5;
     float *Ce = p.C + (size_t)e * p.M * p.N;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * 64 + 32 * i + 8 * (r / 4) + 4 * half + (r % 4);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int col = n0 + wn * 64 + 32 * j + l32;
-                Ce[(size_t)row * p.N + col] = acc[i][j][r];
-            }
+        for (int q = 0; q < 4; ++q) {
+            const int row = m0 + 8 * (4 * g + q) + i;
+            float *dst = Ce + (size_t)row * p.N + n0 + 8 * c;
+            *reinterpret_cast<float4 *>(dst) = make_float4(acc[i][0][q], acc[i][1][q], acc[i][2][q], acc[i][3][q]);
+            *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[i][4][q], acc[i][5][q], acc[i][6][q], acc[i][7][q]);
         }
 }
 
@@ -645,7 +667,7 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     if (st != MOE_OK) return st;
     if (cfg->a != 0) return MOE_EUNSUPPORTED;           // flat layer only
     if (cfg->expert_dtype != MOE_DTYPE_BF16) return MOE_EUNSUPPORTED;
-    if (cfg->d % 128 != 0 || cfg->h % 128 != 0 || cfg->n % 32 != 0) return MOE_EUNSUPPORTED;
+    if (cfg->d % 256 != 0 || cfg->h % 256 != 0 || cfg->n % 32 != 0) return MOE_EUNSUPPORTED;
     if (!x || !W_g || !W_noise || !W1 || !W2 || !dy || !topk_idx || !topk_gate || !fwd_workspace ||
         !dx || !dW_g || !dW_noise || !dW1 || !dW2 || !workspace)
         return MOE_EINVAL;
@@ -691,10 +713,10 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     hipLaunchKernelGGL((gg_rows_kernel<false, EPI_MASK_BF16>), dim3(max_tiles, h / GBN), dim3(256), 0, s, g2);
     MOE_LAUNCH_CHECK();
     GGWgrad w2{hid, dout, dW2, h, d, offsets};
-    hipLaunchKernelGGL(gg_wgrad_kernel, dim3(h / GBM, d / GBN, n), dim3(256), 0, s, w2);
+    hipLaunchKernelGGL(gg_wgrad_kernel, dim3(h / 256, d / 256, n), dim3(256), 0, s, w2);
     MOE_LAUNCH_CHECK();
     GGWgrad w1{xs, dz, dW1, d, h, offsets};
-    hipLaunchKernelGGL(gg_wgrad_kernel, dim3(d / GBM, h / GBN, n), dim3(256), 0, s, w1);
+    hipLaunchKernelGGL(gg_wgrad_kernel, dim3(d / 256, h / 256, n), dim3(256), 0, s, w1);
     MOE_LAUNCH_CHECK();
     GGRows g5{dz, (const uint16_t *)W1, dxs, nullptr, h, d, offsets, tile_expert, tile_row0, num_tiles};
     hipLaunchKernelGGL((gg_rows_kernel<false, EPI_F32>), dim3(max_tiles, d / GBN), dim3(256), 0, s, g5);
