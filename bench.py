@@ -148,7 +148,8 @@ def main():
     else:
         x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias=shape.zipf_beta > 0)
         W1, W2 = G.device_weights(shape)
-        run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+        run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2,
+                        flags=api.MOE_FLAG_SAVE_HIDDEN if shape.backward else 0)
         ws = torch.empty(api.moe_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
         if shape.backward:
             dy = G.dev(W.upstream_grad(shape))

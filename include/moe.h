@@ -58,7 +58,14 @@ typedef struct moe_config {
     int32_t expert_dtype;  /* MOE_DTYPE_F32 or MOE_DTYPE_BF16: storage type of W1, W2 */
     float w_importance;    /* Eq.(7) */
     float w_load;          /* Eq.(11) */
+    int32_t flags;         /* MOE_FLAG_* */
 } moe_config;
+
+/* moe_layer_forward also keeps the experts' hidden activations (bf16 [T*k, h], routed-row order)
+ * in its workspace, and moe_layer_backward reads them instead of recomputing them.  The paper
+ * recomputes (Appendix D) to fit 12 GB devices; with 288 GB of HBM the 2*h bytes per routed row
+ * are the cheaper side of the trade.  Without the flag the backward pass recomputes. */
+enum { MOE_FLAG_SAVE_HIDDEN = 1 };
 
 int moe_version(void);
 const char *moe_strerror(int status);
@@ -86,7 +93,8 @@ size_t moe_workspace_bytes(const moe_config *cfg);
  * caller can inspect them or hand them to moe_layer_backward. */
 typedef struct moe_workspace_layout {
     size_t cleanb, sp, next_idx, partials, counts, offsets, perm, inv_perm, tile_expert,
-        tile_row0, num_tiles, route_ws, out_sorted, ffn_ws, aux_ws, total;
+        tile_row0, num_tiles, route_ws, out_sorted, ffn_ws, aux_ws, hidden /* (size_t)-1 if absent */,
+        total;
     /* hierarchical only */
     size_t p_cleanb, p_sp, p_next_idx, p_partials, p_idx, p_gate, p_counts, p_offsets, p_perm,
         p_inv_perm, p_tile_group, p_tile_row0, p_num_tiles, p_tile_offsets, p_route_ws, p_aux_ws,

@@ -10,6 +10,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 
 MOE_OK, MOE_EINVAL, MOE_EUNSUPPORTED, MOE_EWORKSPACE, MOE_EHIP = 0, -1, -2, -3, -4
 MOE_DTYPE_F32, MOE_DTYPE_BF16 = 0, 1
+MOE_FLAG_SAVE_HIDDEN = 1
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -23,12 +24,12 @@ class MoeConfig(ctypes.Structure):
                 ("n", ctypes.c_int32), ("k", ctypes.c_int32), ("a", ctypes.c_int32),
                 ("b", ctypes.c_int32), ("k_primary", ctypes.c_int32),
                 ("k_secondary", ctypes.c_int32), ("expert_dtype", ctypes.c_int32),
-                ("w_importance", ctypes.c_float), ("w_load", ctypes.c_float)]
+                ("w_importance", ctypes.c_float), ("w_load", ctypes.c_float), ("flags", ctypes.c_int32)]
 
 
 _LAYOUT_FIELDS = ["cleanb", "sp", "next_idx", "partials", "counts", "offsets", "perm", "inv_perm",
                   "tile_expert", "tile_row0", "num_tiles", "route_ws", "out_sorted", "ffn_ws",
-                  "aux_ws", "total", "p_cleanb", "p_sp", "p_next_idx", "p_partials", "p_idx",
+                  "aux_ws", "hidden", "total", "p_cleanb", "p_sp", "p_next_idx", "p_partials", "p_idx",
                   "p_gate", "p_counts", "p_offsets", "p_perm", "p_inv_perm", "p_tile_group",
                   "p_tile_row0", "p_num_tiles", "p_tile_offsets", "p_route_ws", "p_aux_ws",
                   "s_idx", "s_gate"]
@@ -103,7 +104,7 @@ def _check(status):
 def make_config(shape=None, **kw) -> MoeConfig:
     """MoeConfig from a moe_workloads.MoEShape-like object and/or keyword overrides."""
     vals = dict(T=0, d=0, h=0, n=0, k=0, a=0, b=0, k_primary=0, k_secondary=0,
-                expert_dtype=MOE_DTYPE_BF16, w_importance=0.1, w_load=0.1)
+                expert_dtype=MOE_DTYPE_BF16, w_importance=0.1, w_load=0.1, flags=0)
     if shape is not None:
         for f in ("T", "d", "h", "n", "k", "a", "b", "k_primary", "k_secondary", "w_importance", "w_load"):
             vals[f] = getattr(shape, f)

@@ -682,7 +682,7 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     const int64_t T = cfg->T, A = T * cfg->k;
     const int d = cfg->d, h = cfg->h, n = cfg->n, k = cfg->k;
     if (T == 0) return MOE_OK;
-    const char *fw = (const char *)fwd_workspace;
+    char *fw = (char *)fwd_workspace;   // read-only here
     char *ws = (char *)workspace;
     const float *cleanb = (const float *)(fw + F.cleanb), *sp = (const float *)(fw + F.sp);
     const int32_t *next_idx = (const int32_t *)(fw + F.next_idx);
@@ -691,7 +691,9 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     const float *out_sorted = (const float *)(fw + F.out_sorted);
     const double *sums64 = (const double *)(fw + F.aux_ws);
     uint16_t *xs = (uint16_t *)(ws + L.xs), *dout = (uint16_t *)(ws + L.dout);
-    uint16_t *hid = (uint16_t *)(ws + L.hid), *dz = (uint16_t *)(ws + L.dz);
+    const bool saved_hidden = F.hidden != (size_t)-1;
+    uint16_t *hid = saved_hidden ? (uint16_t *)(fw + F.hidden) : (uint16_t *)(ws + L.hid);
+    uint16_t *dz = (uint16_t *)(ws + L.dz);
     float *dxs = (float *)(ws + L.dxs), *dgate = (float *)(ws + L.dgate);
     float *dclean = (float *)(ws + L.dclean), *draw = (float *)(ws + L.draw);
     float *gI = (float *)(ws + L.gI), *gL = (float *)(ws + L.gL), *wpart = (float *)(ws + L.wpart);
@@ -706,9 +708,11 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     const unsigned max_tiles = (unsigned)(ceil_div(A, GBM) + n);
 
     // experts (hidden layer recomputed)
-    GGRows g1{xs, (const uint16_t *)W1, hid, nullptr, d, h, offsets, tile_expert, tile_row0, num_tiles};
-    hipLaunchKernelGGL((gg_rows_kernel<true, EPI_RELU_BF16>), dim3(max_tiles, h / GBN), dim3(256), 0, s, g1);
-    MOE_LAUNCH_CHECK();
+    if (!saved_hidden) {   // Appendix D: recompute the hidden activations
+        GGRows g1{xs, (const uint16_t *)W1, hid, nullptr, d, h, offsets, tile_expert, tile_row0, num_tiles};
+        hipLaunchKernelGGL((gg_rows_kernel<true, EPI_RELU_BF16>), dim3(max_tiles, h / GBN), dim3(256), 0, s, g1);
+        MOE_LAUNCH_CHECK();
+    }
     GGRows g2{dout, (const uint16_t *)W2, dz, hid, d, h, offsets, tile_expert, tile_row0, num_tiles};
     hipLaunchKernelGGL((gg_rows_kernel<false, EPI_MASK_BF16>), dim3(max_tiles, h / GBN), dim3(256), 0, s, g2);
     MOE_LAUNCH_CHECK();

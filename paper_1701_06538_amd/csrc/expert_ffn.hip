@@ -229,6 +229,15 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
         __syncthreads();
         FFN_STAMP(3);
     }
+    if (p.hid_out) {   // training: keep the hidden activations for the backward pass
+        constexpr int U4 = H / 8;   // 16-byte pieces per row
+        for (int i = tid; i < TM * U4; i += 512) {
+            const int r = i / U4, cc = i % U4;
+            if (r < rows)
+                *reinterpret_cast<uint4 *>(p.hid_out + (size_t)(row0 + r) * H + 8 * cc) =
+                    *reinterpret_cast<const uint4 *>(lds + (size_t)r * HS + 8 * cc);
+        }
+    }
 
     // out = hidden W2: wave (cg, kh) owns output columns [128cg, +128) and hidden units
     // [512kh, +512); the two k halves are added through LDS.
@@ -398,12 +407,14 @@ extern "C" size_t moe_ffn_workspace_bytes(const moe_config *cfg) {
     return (size_t)cfg->T * cfg->k * cfg->h * sizeof(float);
 }
 
-extern "C" int moe_expert_ffn(const moe_config *cfg, const float *x, const int32_t *perm,
-                              const int32_t *offsets, const int32_t *tile_expert,
-                              const int32_t *tile_row0, const int32_t *num_tiles, const void *W1,
-                              const void *W2, float *out_sorted, void *workspace, void *stream) {
-    int st = check_config(cfg);
-    if (st != MOE_OK) return st;
+namespace moe {
+int expert_ffn_with_hidden(const moe_config *cfg, const float *x, const int32_t *perm,
+                           const int32_t *offsets, const int32_t *tile_expert,
+                           const int32_t *tile_row0, const int32_t *num_tiles, const void *W1,
+                           const void *W2, float *out_sorted, void *workspace, uint16_t *hid_out,
+                           hipStream_t st) {
+    int rc = check_config(cfg);
+    if (rc != MOE_OK) return rc;
     if (!x || !perm || !offsets || !tile_expert || !tile_row0 || !num_tiles || !W1 || !W2 ||
         !out_sorted)
         return MOE_EINVAL;
@@ -415,7 +426,17 @@ extern "C" int moe_expert_ffn(const moe_config *cfg, const float *x, const int32
     a.x = x; a.perm = perm; a.offsets = offsets;
     a.tile_expert = tile_expert; a.tile_row0 = tile_row0; a.num_tiles = num_tiles;
     a.W1 = W1; a.W2 = W2; a.out = out_sorted; a.hidden = (float *)workspace;
+    a.hid_out = hid_out;
     a.d = cfg->d; a.h = cfg->h; a.k = cfg->k;
     a.k_shift = (cfg->k & (cfg->k - 1)) == 0 ? __builtin_ctz(cfg->k) : -1;
-    return launch_expert_ffn(cfg, a, moe_max_tiles(cfg), (hipStream_t)stream);
+    return launch_expert_ffn(cfg, a, moe_max_tiles(cfg), st);
+}
+}  // namespace moe
+
+extern "C" int moe_expert_ffn(const moe_config *cfg, const float *x, const int32_t *perm,
+                              const int32_t *offsets, const int32_t *tile_expert,
+                              const int32_t *tile_row0, const int32_t *num_tiles, const void *W1,
+                              const void *W2, float *out_sorted, void *workspace, void *stream) {
+    return expert_ffn_with_hidden(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2,
+                                  out_sorted, workspace, nullptr, (hipStream_t)stream);
 }

@@ -55,6 +55,7 @@ struct FfnArgs {
     const void *W1, *W2;
     float *out;               // [A,d]
     float *hidden;            // fp32 path workspace [A,h]
+    uint16_t *hid_out;        // bf16 path: optional copy of the hidden activations [A,h], or null
     int d, h, k;
     int k_shift;              // log2(k) when k is a power of two, else -1
 };
@@ -65,6 +66,11 @@ int gate_rows_per_block(int64_t rows, int n);
 size_t route_ws_bytes(int64_t A, int n);
 int launch_route(RouteArgs a, hipStream_t st);
 int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles, hipStream_t st);
+int expert_ffn_with_hidden(const moe_config *cfg, const float *x, const int32_t *perm,
+                           const int32_t *offsets, const int32_t *tile_expert,
+                           const int32_t *tile_row0, const int32_t *num_tiles, const void *W1,
+                           const void *W2, float *out_sorted, void *workspace, uint16_t *hid_out,
+                           hipStream_t st);
 int launch_combine(const float *out_sorted, const float *gate, const int32_t *inv_perm, float *y,
                    int64_t T, int d, int k, hipStream_t st);
 int launch_aux_losses(const float *partials, int64_t rows, int n, float w_imp, float w_load,

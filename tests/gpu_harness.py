@@ -17,10 +17,10 @@ def dev(a, dtype=None):
 class FlatRun:
     """One forward pass of the flat layer on the GPU, stage by stage or fused."""
 
-    def __init__(self, api, shape, x, W_g, W_noise, eps, bias, W1, W2):
+    def __init__(self, api, shape, x, W_g, W_noise, eps, bias, W1, W2, flags=0):
         self.api = api
         self.shape = shape
-        self.cfg = api.make_config(shape)
+        self.cfg = api.make_config(shape, flags=flags)
         c = self.cfg
         self.x, self.W_g, self.W_noise = dev(x), dev(W_g), dev(W_noise)
         self.eps = None if eps is None else dev(eps)

@@ -46,12 +46,12 @@ def fro_rel(got, ref):
     return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-def run_backward(api, shape, with_bias, dy, w_override=None):
+def run_backward(api, shape, with_bias, dy, w_override=None, flags=0):
     if w_override is not None:
         shape = W.scaled_config(shape, w_importance=w_override[0], w_load=w_override[1])
     x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias)
     W1, W2 = G.device_weights(shape)
-    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2, flags=flags)
     run.fused()
     f32 = dict(dtype=torch.float32, device="cuda")
     T, d, h, n = shape.T, shape.d, shape.h, shape.n
@@ -80,20 +80,21 @@ def oracle_backward(shape, inputs, dy, experts_for_dW=None):
 
 
 CASES = [
-    ("small", dict(T=512, n=32), False),
-    ("ragged_bias", dict(T=777, n=64, k=3), True),
-    ("k1", dict(T=300, n=32, k=1), False),
+    ("small", dict(T=512, n=32), False, 0),
+    ("ragged_bias", dict(T=777, n=64, k=3), True, 0),
+    ("k1", dict(T=300, n=32, k=1), False, 0),
+    ("saved_hidden", dict(T=777, n=64, k=3), True, 1),      # MOE_FLAG_SAVE_HIDDEN: no recomputation
 ]
 
 
-@pytest.mark.parametrize("name,ov,with_bias", CASES, ids=[c[0] for c in CASES])
-def test_backward_parity(api, name, ov, with_bias):
+@pytest.mark.parametrize("name,ov,with_bias,flags", CASES, ids=[c[0] for c in CASES])
+def test_backward_parity(api, name, ov, with_bias, flags):
     shape = W.scaled_config(W.CONFIGS[4], **ov)
     if with_bias:
         shape = W.scaled_config(shape, zipf_beta=0.5)
     say("case backward", name, shape)
     dy = W.upstream_grad(shape)
-    shape, inputs, run, out, call = run_backward(api, shape, with_bias, dy)
+    shape, inputs, run, out, call = run_backward(api, shape, with_bias, dy, flags=flags)
     fw, gr = oracle_backward(shape, inputs, dy)
     assert np.array_equal(run.topk_idx.cpu().numpy(), fw.idx)
     errs = dict(dx=G.rel_errors(out["dx"].cpu().numpy(), gr.dx)[0],
@@ -148,7 +149,7 @@ def test_cfg4_full_training_step(api):
     shape = W.CONFIGS[4]
     say("full config", shape)
     dy = W.upstream_grad(shape)
-    shape, inputs, run, out, call = run_backward(api, shape, True, dy)
+    shape, inputs, run, out, call = run_backward(api, shape, True, dy, flags=api.MOE_FLAG_SAVE_HIDDEN)
     t0 = time.perf_counter()
     sample = [0, 1, 17, 255, 300, 511]
     counts = np.bincount(run.topk_idx.cpu().numpy().reshape(-1), minlength=shape.n)
