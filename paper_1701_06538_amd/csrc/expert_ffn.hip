@@ -294,6 +294,169 @@ extern "C" int moe_debug_read_ffn_timing(long long *host_out) {
 #endif
 
 // ---------------------------------------------------------------------------------------
+// Four-wave variant: one wave per SIMD with the whole 512-register budget.  Each wave owns 256
+// hidden columns in the first GEMM (accumulators in AGPRs) and 128 output columns over the full
+// hidden dimension in the second, so there is no split-k exchange, half as many waves meet at the
+// barriers, and the registers left over hold three (first GEMM) and six (second GEMM) k-steps of
+// weights in flight.
+// ---------------------------------------------------------------------------------------
+template <int K, int LD, int STAGES, int NG>   // NG groups of 128 columns per wave
+struct WeightStream4 {
+    static constexpr int NSTEPS = K / 32;
+    BFrag f[STAGES][NG];
+    const char *base;
+    uint32_t lane_off;
+
+    __device__ __forceinline__ void start(const uint16_t *W, int col, int g) {
+        base = reinterpret_cast<const char *>(W);
+        lane_off = (uint32_t)((8 * g) * LD + col) * 2u;
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s)
+#pragma unroll
+            for (int q = 0; q < NG; ++q) load_bfrag<LD * 2>(f[s][q], base + 256 * q, lane_off, 32 * s);
+    }
+
+    __device__ __forceinline__ void run(v4f (&acc)[NG][4][8], const uint16_t *A_lds, int lda, int c, int g) {
+        const uint16_t *ap = A_lds + (size_t)c * lda + 8 * g;
+#pragma unroll
+        for (int step = 0; step < NSTEPS; ++step) {
+            const int s = step % STAGES, kk = 32 * step;
+            const bool reload = step + STAGES < NSTEPS;
+            v8bf a[4];
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt)
+                a[rt] = __builtin_bit_cast(v8bf, *reinterpret_cast<const uint4 *>(ap + (size_t)(16 * rt) * lda + kk));
+#pragma unroll
+            for (int q = 0; q < NG; ++q) {
+                v8bf b[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) b[j] = bfrag_column(f[s][q], j);
+                __builtin_amdgcn_sched_barrier(0);
+                if (reload) load_bfrag<LD * 2>(f[s][q], base + 256 * q, lane_off, kk + 32 * STAGES);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+#pragma unroll
+                    for (int rt = 0; rt < 4; ++rt)
+                        acc[q][rt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rt], b[j], acc[q][rt][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+};
+
+#ifndef FFN4_STAGES1
+#define FFN4_STAGES1 2
+#define FFN4_STAGES2 6
+#endif
+
+template <int D, int H>
+__global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
+    constexpr int TM = kFfnTM;
+    constexpr int XS = D + 8, HS = H + 8;
+    static_assert(H == 4 * 256 && D == 4 * 128, "four waves: 256 hidden / 128 output columns each");
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+
+    const int tile = xcd_tile(blockIdx.x, *p.num_tiles);
+    if (tile < 0) return;
+    const int e = p.tile_expert[tile];
+    const int row0 = p.tile_row0[tile];
+    const int rows = min(TM, p.offsets[e + 1] - row0);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const uint16_t *W1 = (const uint16_t *)p.W1 + (size_t)e * D * H;
+    const uint16_t *W2 = (const uint16_t *)p.W2 + (size_t)e * H * D;
+
+    WeightStream4<D, H, FFN4_STAGES1, 2> s1;
+    const int col1 = 256 * wave + 8 * c;
+    {
+        constexpr int F4 = D / 4, RPP = 256 / F4, HALF = TM / RPP / 2;
+        const int c4 = tid % F4, rr = tid / F4;
+        int tok[2 * HALF];
+#pragma unroll
+        for (int i = 0; i < 2 * HALF; ++i) tok[i] = p.perm[row0 + min(rr + i * RPP, rows - 1)];
+        s1.start(W1, col1, g);
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb) {
+            float4 v[HALF];
+#pragma unroll
+            for (int i = 0; i < HALF; ++i) {
+                const int a = tok[hb * HALF + i];
+                const int t = p.k_shift >= 0 ? (a >> p.k_shift) : (a / p.k);
+                v[i] = *reinterpret_cast<const float4 *>(p.x + (size_t)t * D + 4 * c4);
+            }
+#pragma unroll
+            for (int i = 0; i < HALF; ++i) {
+                const int r = rr + (hb * HALF + i) * RPP;
+                const bool live = r < rows;
+                *reinterpret_cast<uint2 *>(lds + (size_t)r * XS + 4 * c4) =
+                    make_uint2(live ? pack_bf16x2(v[i].x, v[i].y) : 0u, live ? pack_bf16x2(v[i].z, v[i].w) : 0u);
+            }
+        }
+    }
+    __syncthreads();
+
+    WeightStream4<H, D, FFN4_STAGES2, 1> s2;
+    const int col2 = 128 * wave + 8 * c;
+    {
+        v4f acc[2][4][8];
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[q][rt][j] = v4f{0.f, 0.f, 0.f, 0.f};
+        s1.run(acc, lds, XS, c, g);
+        s2.start(W2, col2, g);
+        __syncthreads();  // the hidden tile overwrites the x tile
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = 16 * rt + 4 * g + r;
+                    uint4 w;
+                    w.x = pack_bf16x2(fmaxf(acc[q][rt][0][r], 0.f), fmaxf(acc[q][rt][1][r], 0.f));
+                    w.y = pack_bf16x2(fmaxf(acc[q][rt][2][r], 0.f), fmaxf(acc[q][rt][3][r], 0.f));
+                    w.z = pack_bf16x2(fmaxf(acc[q][rt][4][r], 0.f), fmaxf(acc[q][rt][5][r], 0.f));
+                    w.w = pack_bf16x2(fmaxf(acc[q][rt][6][r], 0.f), fmaxf(acc[q][rt][7][r], 0.f));
+                    *reinterpret_cast<uint4 *>(lds + (size_t)row * HS + col1 + 128 * q) = w;
+                }
+        __syncthreads();
+    }
+    if (p.hid_out) {
+        constexpr int U4 = H / 8;
+        for (int i = tid; i < TM * U4; i += 256) {
+            const int r = i / U4, cc = i % U4;
+            if (r < rows)
+                *reinterpret_cast<uint4 *>(p.hid_out + (size_t)(row0 + r) * H + 8 * cc) =
+                    *reinterpret_cast<const uint4 *>(lds + (size_t)r * HS + 8 * cc);
+        }
+    }
+    {
+        v4f acc[1][4][8];
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[0][rt][j] = v4f{0.f, 0.f, 0.f, 0.f};
+        s2.run(acc, lds, HS, c, g);
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = 16 * rt + 4 * g + r;
+                if (row >= rows) continue;
+                float *dst = p.out + (size_t)(row0 + row) * D + col2;
+                *reinterpret_cast<float4 *>(dst) =
+                    make_float4(acc[0][rt][0][r], acc[0][rt][1][r], acc[0][rt][2][r], acc[0][rt][3][r]);
+                *reinterpret_cast<float4 *>(dst + 4) =
+                    make_float4(acc[0][rt][4][r], acc[0][rt][5][r], acc[0][rt][6][r], acc[0][rt][7][r]);
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // fp32 experts: C[rows, N] = act(A[rows, K] W_e[K, N]) per row tile; A rows either gathered
 // from x through perm or read from the sorted hidden buffer.
 // ---------------------------------------------------------------------------------------
@@ -373,7 +536,18 @@ int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles
             attr_set = true;
         }
         const unsigned grid = (unsigned)(ceil_div(max_tiles, 8) * 8);
-        hipLaunchKernelGGL((ffn_bf16_kernel<512, 1024>), dim3(grid), dim3(512), lds, st, a);
+        // One tile per expert (<= 64 rows on average): every tile streams its weights from HBM, and
+        // the four-wave kernel's deeper load pipeline pays.  Several tiles per expert: the tiles
+        // share weights through L2 and the eight-wave kernel is marginally faster.
+        const bool four_waves = (int64_t)cfg->T * cfg->k <= (int64_t)cfg->n * kFfnTM;
+        static bool attr4_set = false;
+        if (four_waves && !attr4_set) {
+            MOE_HIP_TRY(hipFuncSetAttribute((const void *)ffn_bf16_w4_kernel<512, 1024>,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            attr4_set = true;
+        }
+        if (four_waves) hipLaunchKernelGGL((ffn_bf16_w4_kernel<512, 1024>), dim3(grid), dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((ffn_bf16_kernel<512, 1024>), dim3(grid), dim3(512), lds, st, a);
         MOE_LAUNCH_CHECK();
         return MOE_OK;
     }
