@@ -165,6 +165,8 @@ int moe_aux_losses(const moe_config *cfg, const float *partials, float *importan
                    float *losses, void *workspace, void *stream);
 
 /* ---- the whole forward pass of the flat layer: a1..a5 on one stream ------------------- */
+/* T = 0 is accepted (pointers to [T,...] tensors may then be NULL): counts, offsets and the tile
+ * table in the workspace are zeroed, importance = load = 0 and the losses are reported as 0. */
 int moe_layer_forward(const moe_config *cfg, const float *x, const float *W_g,
                       const float *W_noise, const float *gate_bias, const float *eps,
                       const void *W1, const void *W2, float *y, int32_t *topk_idx,

@@ -103,6 +103,33 @@ extern "C" size_t moe_workspace_bytes(const moe_config *cfg) {
     return L.total;
 }
 
+__global__ void fill_zero_kernel(float *p, int64_t count) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) p[i] = 0.f;
+}
+
+// T = 0: nothing to gate or route.  Counts, offsets and the tile table are zeroed (so the
+// workspace is consistent), Importance = Load = 0 and the losses are reported as 0.
+static int forward_empty(const moe_config *cfg, const moe_workspace_layout &L, char *ws,
+                         float *importance, float *load, float *losses, void *stream) {
+    RouteArgs ra{};
+    ra.A = 0; ra.n = cfg->n; ra.tile_rows = moe_tile_rows(cfg);
+    ra.counts = (int32_t *)(ws + L.counts); ra.offsets = (int32_t *)(ws + L.offsets);
+    ra.perm = (int32_t *)(ws + L.perm); ra.inv_perm = (int32_t *)(ws + L.inv_perm);
+    ra.tile_expert = (int32_t *)(ws + L.tile_expert); ra.tile_row0 = (int32_t *)(ws + L.tile_row0);
+    ra.num_tiles = (int32_t *)(ws + L.num_tiles);
+    ra.hist = (int32_t *)(ws + L.route_ws);
+    int st = launch_route(ra, (hipStream_t)stream);
+    if (st != MOE_OK) return st;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)ceil_div(cfg->n, 256)), dim3(256), 0,
+                       (hipStream_t)stream, importance, (int64_t)cfg->n);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)ceil_div(cfg->n, 256)), dim3(256), 0,
+                       (hipStream_t)stream, load, (int64_t)cfg->n);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, losses, (int64_t)4);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
 static int record(void *const *ev, int i, void *stream) {
     if (!ev || !ev[i]) return MOE_OK;
     MOE_HIP_TRY(hipEventRecord((hipEvent_t)ev[i], (hipStream_t)stream));
@@ -120,13 +147,12 @@ extern "C" int moe_layer_forward_profiled(const moe_config *cfg, const float *x,
     int st = workspace_layout(cfg, &L);
     if (st != MOE_OK) return st;
     if (cfg->a != 0) return MOE_EINVAL;
-    if (!x || !W_g || !W_noise || !W1 || !W2 || !y || !topk_idx || !topk_gate || !importance ||
-        !load || !losses || !workspace)
-        return MOE_EINVAL;
-    if (!aligned16(workspace) || !aligned16(x) || !aligned16(y) || !aligned16(W1) || !aligned16(W2))
-        return MOE_EINVAL;
+    if (!importance || !load || !losses || !workspace || !aligned16(workspace)) return MOE_EINVAL;
     if (workspace_bytes < L.total) return MOE_EWORKSPACE;
     char *ws = (char *)workspace;
+    if (cfg->T == 0) return forward_empty(cfg, L, ws, importance, load, losses, stream);
+    if (!x || !W_g || !W_noise || !W1 || !W2 || !y || !topk_idx || !topk_gate) return MOE_EINVAL;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(W1) || !aligned16(W2)) return MOE_EINVAL;
     float *cleanb = (float *)(ws + L.cleanb), *sp = (float *)(ws + L.sp);
     int32_t *next_idx = (int32_t *)(ws + L.next_idx);
     float *partials = (float *)(ws + L.partials);

@@ -75,6 +75,28 @@ def test_null_pointers_are_rejected_before_any_launch(api):
         assert st == api.MOE_EINVAL
     st = api._moe_layer_forward(ctypes.byref(cfg), *([None] * 14), 0, None)
     assert st == api.MOE_EINVAL
+    st = api._moe_layer_backward(ctypes.byref(cfg), *([None] * 16), 0, None)
+    assert st in (api.MOE_EINVAL, api.MOE_EUNSUPPORTED)
+    hier = api.make_config(T=64, d=512, h=1024, n=64, k=4, a=8, b=8, k_primary=2, k_secondary=2)
+    assert api._moe_gate_hier(ctypes.byref(hier), *([None] * 10), 0, None) == api.MOE_EINVAL
+    assert api._moe_layer_forward_hier(ctypes.byref(hier), *([None] * 16), 0, None) == api.MOE_EINVAL
+    assert api._moe_aux_losses_hier(ctypes.byref(hier), *([None] * 4), 0, *([None] * 4)) == api.MOE_EINVAL
+    # flat entry points refuse a hierarchical shape and vice versa
+    assert api._moe_gate_hier(ctypes.byref(cfg), *([None] * 10), 0, None) == api.MOE_EINVAL
+
+
+def test_backward_workspace_and_flags(api):
+    cfg = api.make_config(T=65536, d=512, h=1024, n=512, k=4)
+    assert api.moe_backward_workspace_bytes(cfg) > 2 * 262144 * 1024 * 2
+    L0 = api.moe_get_workspace_layout(cfg)
+    assert L0.hidden == 2 ** 64 - 1                      # absent without the flag
+    cfg1 = api.make_config(T=65536, d=512, h=1024, n=512, k=4, flags=api.MOE_FLAG_SAVE_HIDDEN)
+    L1 = api.moe_get_workspace_layout(cfg1)
+    assert L1.hidden != 2 ** 64 - 1 and L1.total - L0.total >= 262144 * 1024 * 2
+    f32 = api.make_config(T=64, d=512, h=1024, n=32, k=4, expert_dtype=api.MOE_DTYPE_F32)
+    assert api.moe_backward_workspace_bytes(f32) > 0
+    hier = api.make_config(T=64, d=512, h=1024, n=64, k=4, a=8, b=8, k_primary=2, k_secondary=2)
+    assert api.moe_backward_workspace_bytes(hier) == 0   # flat layer only
 
 
 def test_workspace_layout_is_ordered_aligned_and_sized(api):

@@ -209,3 +209,40 @@ def test_error_paths(api):
     bad = api.make_config(W.CONFIGS[0], k=17)
     with pytest.raises(api.MoeError):
         api.moe_combine(bad, t, t, t, t)
+
+
+def test_degenerate_shapes(api):
+    """n = 1, k = 1 (the layer is one MLP) and every token on the same experts (one expert with
+    many row tiles, all others empty)."""
+    _ffn_case(api, _shape(1, T=200, n=1, k=1), TOL_BF16, "bf16 single expert")
+    shape = _shape(1, T=700, n=16, k=2)
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape)
+    W_g = np.zeros_like(W_g)
+    W_g[:, 3] = 0.0
+    big = np.zeros(shape.n, np.float32)
+    big[3], big[11] = 50.0, 40.0                       # bias makes experts 3 and 11 win everywhere
+    fw = G.oracle_flat(shape, x, W_g, W_noise, eps, big)
+    assert set(np.unique(fw.idx)) == {3, 11}
+    W1, W2 = G.device_weights(shape)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, big, W1, W2)
+    run.fused()
+    assert np.array_equal(run.topk_idx.cpu().numpy(), fw.idx)
+    y_ref = O.moe_output(x, fw.idx, fw.gates, G.oracle_weight_fn(shape), shape.n)
+    row, mx = G.rel_errors(run.y.cpu().numpy(), y_ref)
+    assert row <= TOL_BF16 and mx <= TOL_BF16
+    check_losses(run, fw)
+
+
+def test_empty_batch(api):
+    """T = 0: every entry point accepts it and launches nothing that could fault."""
+    shape = _shape(1, T=0, n=8, k=2)
+    x = np.zeros((0, shape.d), np.float32)
+    Wg = np.zeros((shape.d, shape.n), np.float32)
+    eps = np.zeros((0, shape.n), np.float32)
+    W1, W2 = G.device_weights(shape)
+    run = G.FlatRun(api, shape, x, Wg, Wg, eps, None, W1, W2)
+    run.fused()
+    L = api.moe_get_workspace_layout(run.cfg)
+    counts = run.workspace[L.counts:L.counts + 4 * shape.n].view(torch.int32).cpu().numpy()
+    assert not counts.any()
+    assert not run.losses.cpu().numpy().any() and not run.importance.cpu().numpy().any()
