@@ -214,6 +214,27 @@ __global__ __launch_bounds__(256, 2) void gate_logits_kernel(LogitsArgs p) {
 // top-k, softmax, P(x,i) and partial sums
 // ---------------------------------------------------------------------------------------
 
+// Phi(u), the standard normal CDF of Eq.(9), in fp32: erfc(x) = t exp(-x^2 + P(t)), t = 1/(1 + x/2),
+// with P a degree-10 fit derived by gen_phi_coeffs.py (relative error below 1e-6 wherever Phi
+// matters; the sums of P(x,.) over a batch need far less).
+__device__ __forceinline__ float normal_cdf(float u) {
+    const float x = fabsf(u) * 0.70710678118654752f;
+    const float t = __frcp_rn(fmaf(0.5f, x, 1.0f));
+    float p = 8.192740381e-03f;
+    p = fmaf(p, t, 1.299090832e-01f);
+    p = fmaf(p, t, -7.351043820e-01f);
+    p = fmaf(p, t, 1.386106610e+00f);
+    p = fmaf(p, t, -1.062397480e+00f);
+    p = fmaf(p, t, 2.468332201e-01f);
+    p = fmaf(p, t, -1.777072996e-01f);
+    p = fmaf(p, t, 9.546407312e-02f);
+    p = fmaf(p, t, 3.741950989e-01f);
+    p = fmaf(p, t, 1.000020504e+00f);
+    p = fmaf(p, t, -1.265512228e+00f);
+    const float half_erfc = 0.5f * t * __expf(fmaf(-x, x, p));   // = Phi(-|u|)
+    return u < 0.f ? half_erfc : 1.0f - half_erfc;
+}
+
 __device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
     return v1 > v2 || (v1 == v2 && i1 < i2);
 }
@@ -223,7 +244,7 @@ __device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
 // loads are in flight together, and both passes (top-k, then P(x,i)) run from registers.  The
 // per-expert sums of G(x) and P(x,.) also stay in registers across the rows a wave walks.
 template <int L, int NCH>
-__global__ __launch_bounds__(256) void gate_topk_kernel(TopkArgs p) {
+__global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
     extern __shared__ float lds_acc[];  // [2][n]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = p.n, k = p.k;
@@ -371,8 +392,8 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(TopkArgs p) {
                     }
                 float P = 1.0f;
                 if (k < n) {
-                    const float u = (cv[q] - (kept ? thr_in : thr_out)) / sv[q];
-                    P = 0.5f * erfcf(-0.70710678118654752f * u);
+                    const float u = (cv[q] - (kept ? thr_in : thr_out)) * __frcp_rn(sv[q]);
+                    P = normal_cdf(u);
                 }
                 acc_load[q] += P;
                 acc_imp[q] += gi;
