@@ -15,6 +15,8 @@
 namespace moe {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------------------
 // Softplus in binary64, rounded once to fp32.  Fixed operation sequence:
@@ -78,14 +80,35 @@ __device__ __forceinline__ float softplus_spec(float zf) {
 // ---------------------------------------------------------------------------------------
 
 constexpr int BM = kGateBM;  // 128 rows: 4 waves x 32
-constexpr int KC = 32;       // k-slab staged in LDS
-constexpr int ASTR = KC + 4; // floats per LDS row of the x tile: [parity][KC/2] + pad
 
-template <int RN>  // the block tile is BM x (32*RN) columns of ONE of the two matrices
-__global__ __launch_bounds__(256, 2) void gate_logits_kernel(LogitsArgs p) {
+#ifdef MOE_GATE_TIMING
+__device__ long long g_gate_timing[4096 * 40];
+#define GATE_STAMP(i) do { const unsigned b_ = blockIdx.y * gridDim.x + blockIdx.x; if (threadIdx.x == 0 && b_ < 4096) g_gate_timing[b_ * 40 + (i)] = wall_clock64(); } while (0)
+#else
+#define GATE_STAMP(i) do { } while (0)
+#endif
+
+// RN: the block tile is BM x (32*RN) columns of ONE of the two matrices.  VEC: n is a multiple of
+// four, so weight rows can be read 16 bytes at a time.
+// Every global load of the main loop is unconditional: rows past the end of the tile and columns
+// past n re-read a valid element instead (their products only reach outputs that are never
+// stored).  A conditional load would put a join, and with it a wait for the load, between the
+// load and the matrix work that is supposed to hide it.
+// KC: depth of the k-slab staged in LDS.
+template <int RN, bool VEC, int KC>
+__global__ __launch_bounds__(256) void gate_logits_kernel(LogitsArgs p) {
     constexpr int BN = 32 * RN;
-    __shared__ __attribute__((aligned(16))) float As[2][BM][ASTR];
-    __shared__ __attribute__((aligned(16))) float Bs[2][KC][BN];
+    constexpr int ASTR = KC + 4;  // floats per LDS row of the x tile: [parity][KC/2] + pad
+    constexpr int APT = KC / 4;   // threads per x row (one float4 each)
+    constexpr int ARP = 256 / APT, APASS = BM / ARP;   // x rows per pass, passes
+    constexpr int A_BYTES = 2 * BM * ASTR * 4, B_BYTES = 2 * KC * BN * 4;
+    // the epilogue stages EC of the RN column tiles at a time in the (then dead) operand buffers
+    constexpr int EC = BM * (BN + 4) * 4 <= A_BYTES + B_BYTES ? RN : RN / 2;
+    constexpr int CS = 32 * EC + 4;   // floats per LDS row of the staged output tile
+    static_assert(EC >= 1 && BM * CS * 4 <= A_BYTES + B_BYTES, "the output tile reuses the operand buffers");
+    __shared__ __attribute__((aligned(16))) char smem[A_BYTES + B_BYTES];
+    float (*As)[BM][ASTR] = reinterpret_cast<float (*)[BM][ASTR]>(smem);
+    float (*Bs)[KC][BN] = reinterpret_cast<float (*)[KC][BN]>(smem + A_BYTES);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
@@ -101,6 +124,7 @@ __global__ __launch_bounds__(256, 2) void gate_logits_kernel(LogitsArgs p) {
     } else {
         rows = (int)min((int64_t)BM, p.R - row0);
     }
+    if (rows <= 0) return;
     const int NT = (p.n + BN - 1) / BN;
     const int which = blockIdx.y / NT;
     const int col0 = (blockIdx.y % NT) * BN;
@@ -108,57 +132,51 @@ __global__ __launch_bounds__(256, 2) void gate_logits_kernel(LogitsArgs p) {
     const float *W = (which ? p.Wn : p.Wg) + (size_t)group * d * n;
 
     // global -> register staging
-    const int a_r = tid >> 3, a_k = (tid & 7) * 4;       // + 32*i rows
-    const float *a_src[4];
+    const int a_r = tid / APT, a_k = (tid % APT) * 4;       // + ARP*i rows
+    const float *a_src[APASS];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = a_r + 32 * i;
-        if (r < rows) {
-            const int64_t tok = p.row_src ? (int64_t)(p.row_src[row0 + r] / p.row_div) : row0 + r;
-            a_src[i] = p.x + tok * d + a_k;
-        } else {
-            a_src[i] = nullptr;
-        }
+    for (int i = 0; i < APASS; ++i) {
+        const int r = min(a_r + ARP * i, rows - 1);
+        const int64_t tok = p.row_src ? (int64_t)(p.row_src[row0 + r] / p.row_div) : row0 + r;
+        a_src[i] = p.x + tok * d + a_k;
     }
     constexpr int BQ = BN / 4;                  // float4 per B row
     constexpr int BROWS = 256 / BQ;             // B rows covered per pass
     constexpr int BPASS = KC / BROWS;
     const int b_k = tid / BQ, b_c = (tid % BQ) * 4;
-    const bool vec_ok = (n % 4) == 0;
+    const float *b_src[4];   // VEC: [0] only
+    if (VEC) {
+        b_src[0] = W + (size_t)b_k * n + min(col0 + b_c, n - 4);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b_src[j] = W + (size_t)b_k * n + min(col0 + b_c + j, n - 1);
+    }
 
-    float4 a_reg[4], b_reg[BPASS];
+    static_assert(BPASS >= 1, "slab too shallow for this tile width");
+    v4f a_reg[APASS], b_reg[BPASS];
     auto load_global = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            a_reg[i] = a_src[i] ? *reinterpret_cast<const float4 *>(a_src[i] + k0)
-                                : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = 0; i < APASS; ++i) a_reg[i] = *reinterpret_cast<const v4f *>(a_src[i] + k0);
 #pragma unroll
         for (int i = 0; i < BPASS; ++i) {
-            const float *src = W + (size_t)(k0 + b_k + BROWS * i) * n + col0 + b_c;
-            const int col = col0 + b_c;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (vec_ok && col + 3 < n) {
-                v = *reinterpret_cast<const float4 *>(src);
-            } else {
-                if (col + 0 < n) v.x = src[0];
-                if (col + 1 < n) v.y = src[1];
-                if (col + 2 < n) v.z = src[2];
-                if (col + 3 < n) v.w = src[3];
-            }
-            b_reg[i] = v;
+            const size_t off = (size_t)(k0 + BROWS * i) * n;
+            if (VEC)
+                b_reg[i] = *reinterpret_cast<const v4f *>(b_src[0] + off);
+            else
+                b_reg[i] = v4f{b_src[0][off], b_src[1][off], b_src[2][off], b_src[3][off]};
         }
     };
     auto store_lds = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float *row = &As[buf][a_r + 32 * i][0];
+        for (int i = 0; i < APASS; ++i) {
+            float *row = &As[buf][a_r + ARP * i][0];
             // k parity 0 -> first half of the row, parity 1 -> second half
-            *reinterpret_cast<float2 *>(row + a_k / 2) = make_float2(a_reg[i].x, a_reg[i].z);
-            *reinterpret_cast<float2 *>(row + KC / 2 + a_k / 2) = make_float2(a_reg[i].y, a_reg[i].w);
+            *reinterpret_cast<v2f *>(row + a_k / 2) = v2f{a_reg[i].x, a_reg[i].z};
+            *reinterpret_cast<v2f *>(row + KC / 2 + a_k / 2) = v2f{a_reg[i].y, a_reg[i].w};
         }
 #pragma unroll
         for (int i = 0; i < BPASS; ++i)
-            *reinterpret_cast<float4 *>(&Bs[buf][b_k + BROWS * i][b_c]) = b_reg[i];
+            *reinterpret_cast<v4f *>(&Bs[buf][b_k + BROWS * i][b_c]) = b_reg[i];
     };
 
     v16f acc[RN];
@@ -167,48 +185,134 @@ __global__ __launch_bounds__(256, 2) void gate_logits_kernel(LogitsArgs p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
 
+    // Main loop, software-pipelined at three levels.  (1) Global -> registers: the loads of slab
+    // s+2 are issued as soon as the registers holding slab s+1 have been stored to LDS, in the
+    // middle of slab s, so they have a whole slab of matrix work to arrive.  (2) Registers -> LDS:
+    // that store also sits in the middle of slab s, far ahead of the barrier that publishes it.
+    // (3) LDS -> operand registers: operands are read one group (four k-steps) ahead, and the
+    // barrier comes BEFORE the slab's last group, whose operands are already in registers: the
+    // first reads of the next slab are in flight while that group runs, so no wave waits on LDS
+    // with the matrix pipe empty.
+    constexpr int NG = KC / 8;          // operand groups per slab
+    constexpr int PG = NG / 2 - 1;      // group after which slab s+1 is stored and s+2 fetched
+    v4f a_grp[2];
+    float b_grp[2][4][RN];
+    auto read_group = [&](int slot, int buf, int kk4) {
+        const float *a_row = &As[buf][wave * 32 + l32][half * (KC / 2)];
+        const float *b_col = &Bs[buf][half][l32];
+        a_grp[slot] = *reinterpret_cast<const v4f *>(a_row + kk4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int c = 0; c < RN; ++c) b_grp[slot][u][c] = b_col[2 * (kk4 + u) * BN + 32 * c];
+    };
+    GATE_STAMP(0);
     load_global(0);
     store_lds(0);
+    load_global(min(KC, d - KC));
     __syncthreads();
+    read_group(0, 0, 0);
+    GATE_STAMP(1);
     for (int k0 = 0; k0 < d; k0 += KC) {
         const int buf = (k0 / KC) & 1;
-        const bool more = k0 + KC < d;
-        if (more) load_global(k0 + KC);
-        const float *a_row = &As[buf][wave * 32 + l32][half * (KC / 2)];
 #pragma unroll
-        for (int kk4 = 0; kk4 < KC / 2; kk4 += 4) {
-            const float4 a4 = *reinterpret_cast<const float4 *>(a_row + kk4);
-            const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+        for (int g = 0; g < NG; ++g) {
+            if (g == NG - 1) {
+                GATE_STAMP(2 + 2 * (k0 / KC));
+                __syncthreads();
+                GATE_STAMP(3 + 2 * (k0 / KC));
+                read_group((g + 1) & 1, buf ^ 1, 0);   // after the last slab: unused
+            } else {
+                read_group((g + 1) & 1, buf, 4 * (g + 1));
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int k = 2 * (kk4 + u) + half;
+            for (int u = 0; u < 4; ++u)
 #pragma unroll
                 for (int c = 0; c < RN; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], Bs[buf][k][32 * c + l32],
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_grp[g & 1][u], b_grp[g & 1][u][c],
                                                                   acc[c], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (g == PG) {
+                // unconditional (a conditional load or store would put a wait at the join);
+                // past the last slab they re-read a valid slab and fill a buffer nobody reads
+                store_lds(buf ^ 1);
+                load_global(min(k0 + 2 * KC, d - KC));
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if (more) store_lds(buf ^ 1);
-        __syncthreads();
     }
 
+    // Epilogue.  The accumulators go through LDS (the operand buffers are dead after the last
+    // barrier of the loop) so that every lane then owns four adjacent columns of a row: rows leave
+    // as 16-byte stores, and the softplus chains of a lane's values are independent straight-line
+    // code that the scheduler can interleave.
+    float *Ct = reinterpret_cast<float *>(smem);
     float *out = which ? p.sp : p.cleanb;
+    constexpr int EQ = 8 * EC;              // float4 per staged row
+    constexpr int RPP = 256 / EQ;           // rows per pass
+    const int cq = tid % EQ, rr = tid / EQ;
+    const bool add_bias = !which && p.bias;
 #pragma unroll
-    for (int c = 0; c < RN; ++c) {
-        const int col = col0 + 32 * c + l32;
-        if (col >= n) continue;
-        const float bias = (!which && p.bias) ? p.bias[col] : 0.f;
+    for (int c0 = 0; c0 < RN; c0 += EC) {
+        if (c0) __syncthreads();
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int i = wave * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            if (i >= rows) continue;
-            float v = acc[c][r];
-            if (which) v = softplus_spec(v);
-            else if (p.bias) v = __fadd_rn(v, bias);
-            out[(row0 + i) * (int64_t)n + col] = v;
+        for (int c = 0; c < EC; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = wave * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                Ct[i * CS + 32 * c + l32] = acc[c0 + c][r];
+            }
+        __syncthreads();
+        GATE_STAMP(34);
+        const int col = col0 + 32 * c0 + 4 * cq;
+        float bias[4] = {0.f, 0.f, 0.f, 0.f};
+        if (add_bias) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bias[j] = p.bias[min(col + j, n - 1)];
+        }
+        // four passes at a time: all LDS reads first, then the arithmetic, then the stores
+        constexpr int PB = 4;
+        static_assert((BM / RPP) % PB == 0, "passes come in batches");
+        for (int pass0 = 0; pass0 < BM / RPP; pass0 += PB) {
+            v4f t[PB];
+#pragma unroll
+            for (int u = 0; u < PB; ++u)
+                t[u] = *reinterpret_cast<const v4f *>(Ct + (rr + (pass0 + u) * RPP) * CS + 4 * cq);
+            if (which) {
+#pragma unroll
+                for (int u = 0; u < PB; ++u)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) t[u][j] = softplus_spec(t[u][j]);
+            } else if (add_bias) {
+#pragma unroll
+                for (int u = 0; u < PB; ++u)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) t[u][j] = __fadd_rn(t[u][j], bias[j]);
+            }
+#pragma unroll
+            for (int u = 0; u < PB; ++u) {
+                const int i = rr + (pass0 + u) * RPP;
+                if (i < rows) {
+                    float *dst = out + (row0 + i) * (int64_t)n + col;
+                    if (VEC) {
+                        if (col < n) *reinterpret_cast<v4f *>(dst) = t[u];
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (col + j < n) dst[j] = t[u][j];
+                    }
+                }
+            }
         }
     }
+    GATE_STAMP(36);
 }
+#ifdef MOE_GATE_TIMING
+extern "C" int moe_debug_read_gate_timing(long long *host_out) {
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_gate_timing), sizeof(long long) * 4096 * 40);
+}
+#endif
 
 // ---------------------------------------------------------------------------------------
 // top-k, softmax, P(x,i) and partial sums
@@ -447,22 +551,21 @@ int launch_hier_compose(const int32_t *p_idx, const float *p_gate, const int32_t
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
+template <int RN>
+static void launch_logits_rn(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
+    constexpr int KC = 32;
+    dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 32 * RN));
+    if (a.n % 4 == 0) hipLaunchKernelGGL((gate_logits_kernel<RN, true, KC>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((gate_logits_kernel<RN, false, KC>), grid, dim3(256), 0, st, a);
+}
+
 int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
     if (row_tiles <= 0) return MOE_OK;
-    if (a.n <= 32) {
-        dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 32));
-        hipLaunchKernelGGL(gate_logits_kernel<1>, grid, dim3(256), 0, st, a);
-    } else if (a.n <= 64) {
-        dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 64));
-        hipLaunchKernelGGL(gate_logits_kernel<2>, grid, dim3(256), 0, st, a);
-    } else if (row_tiles * 2 * ceil_div(a.n, 128) < 1024) {
-        // few tiles: narrower column tiles so that every CU holds at least two workgroups
-        dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 64));
-        hipLaunchKernelGGL(gate_logits_kernel<2>, grid, dim3(256), 0, st, a);
-    } else {
-        dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 128));
-        hipLaunchKernelGGL(gate_logits_kernel<4>, grid, dim3(256), 0, st, a);
-    }
+    if (a.n <= 32) launch_logits_rn<1>(a, row_tiles, st);
+    else if (a.n <= 64) launch_logits_rn<2>(a, row_tiles, st);
+    // few tiles: narrower column tiles so that every CU holds at least two workgroups
+    else if (row_tiles * 2 * ceil_div(a.n, 128) < 1024) launch_logits_rn<2>(a, row_tiles, st);
+    else launch_logits_rn<4>(a, row_tiles, st);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
 }
