@@ -170,14 +170,38 @@ extern "C" int moe_layer_forward_profiled(const moe_config *cfg, const float *x,
 
     MOE_STAGE(0, moe_gate(cfg, x, W_g, W_noise, gate_bias, eps, topk_idx, topk_gate, cleanb, sp,
                           next_idx, partials, stream))
-    MOE_STAGE(1, moe_route(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0,
-                           num_tiles, ws + L.route_ws, stream))
+    // Few experts and a short assignment list: the stages between the big kernels are launch
+    // bound, so the loss sums share a launch with routing and their last step shares one with
+    // the combine (stage 4 is then empty).
+    const bool fuse = route_is_small((int64_t)cfg->T * cfg->k, cfg->n) && aligned16(out_sorted);
+    const int64_t prow = moe_gate_partial_rows(cfg);
+    if (fuse) {
+        RouteArgs ra{};
+        ra.idx = topk_idx; ra.A = (int64_t)cfg->T * cfg->k; ra.n = cfg->n;
+        ra.tile_rows = moe_tile_rows(cfg);
+        ra.counts = counts; ra.offsets = offsets; ra.perm = perm; ra.inv_perm = inv_perm;
+        ra.tile_expert = tile_expert; ra.tile_row0 = tile_row0; ra.num_tiles = num_tiles;
+        ra.tile_offsets = nullptr;
+        ra.hist = (int32_t *)(ws + L.route_ws);
+        MOE_STAGE(1, launch_route_small_sums(ra, partials, prow, (double *)(ws + L.aux_ws),
+                                             (hipStream_t)stream))
+    } else {
+        MOE_STAGE(1, moe_route(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0,
+                               num_tiles, ws + L.route_ws, stream))
+    }
     MOE_STAGE(2, expert_ffn_with_hidden(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2,
                                         out_sorted, ws + L.ffn_ws,
                                         L.hidden == (size_t)-1 ? nullptr : (uint16_t *)(ws + L.hidden),
                                         (hipStream_t)stream))
-    MOE_STAGE(3, moe_combine(cfg, out_sorted, topk_gate, inv_perm, y, stream))
-    MOE_STAGE(4, moe_aux_losses(cfg, partials, importance, load, losses, ws + L.aux_ws, stream))
+    if (fuse) {
+        MOE_STAGE(3, launch_combine_losses(out_sorted, topk_gate, inv_perm, y, cfg->T, cfg->d, cfg->k,
+                                           prow, cfg->n, (double *)(ws + L.aux_ws), cfg->w_importance,
+                                           cfg->w_load, importance, load, losses, (hipStream_t)stream))
+        MOE_STAGE(4, MOE_OK)
+    } else {
+        MOE_STAGE(3, moe_combine(cfg, out_sorted, topk_gate, inv_perm, y, stream))
+        MOE_STAGE(4, moe_aux_losses(cfg, partials, importance, load, losses, ws + L.aux_ws, stream))
+    }
 #undef MOE_STAGE
     return MOE_OK;
 }

@@ -9,6 +9,7 @@
 //                        assignment among equal experts inside a 64-wide step comes from
 //                        ballots over the bits of the expert id, so no atomics decide positions
 #include "stages.h"
+#include "device_bodies.h"
 
 namespace moe {
 
@@ -162,152 +163,9 @@ __global__ __launch_bounds__(64) void route_scatter_kernel(RouteArgs p, int nbit
     }
 }
 
-// Small problems (n <= 512, A <= 65536) in ONE launch: every workgroup rebuilds the two
-// histograms it needs by reading the whole (L2-resident) assignment list -- totals, and counts
-// of everything ahead of its own 1024-assignment chunk -- so no cross-workgroup scan is needed;
-// it then scatters its chunk with the same ordered, ballot-ranked walk, one 256-assignment
-// sub-chunk per wave.
-constexpr int kSmallChunk = 1024;
-constexpr int kSmallMaxN = 512;
-
 __global__ __launch_bounds__(256) void route_small_kernel(RouteArgs p, int nbits) {
-    extern __shared__ int lds_s[];  // total[n] | before[n] | wavehist[4][n]
-    __shared__ int wave_sums[4];
-    const int n = p.n, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int *total = lds_s, *before = lds_s + n, *wh = lds_s + 2 * n;
-    for (int i = tid; i < 6 * n; i += 256) lds_s[i] = 0;
-    __syncthreads();
-    const int64_t c0 = (int64_t)blockIdx.x * kSmallChunk;
-    const int64_t c1 = min(c0 + kSmallChunk, p.A);
-    for (int64_t base = 0; base < p.A; base += 256 * 8) {
-        int ev8[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {   // eight independent loads in flight
-            const int64_t a = base + 256 * u + tid;
-            ev8[u] = a < p.A ? p.idx[a] : -1;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t a = base + 256 * u + tid;
-            const int e = ev8[u];
-            if (e >= 0 && e < n) {
-                atomicAdd(&total[e], 1);
-                if (a < c0) atomicAdd(&before[e], 1);
-                else if (a < c1) atomicAdd(&wh[((a - c0) >> 8) * n + e], 1);
-            }
-        }
-    }
-    __syncthreads();
-    // exclusive scan of the totals over experts: two adjacent experts per thread
-    const int TM = p.tile_rows;
-    {
-        const int e0 = 2 * tid, e1 = 2 * tid + 1;
-        const int v0 = e0 < n ? total[e0] : 0, v1 = e1 < n ? total[e1] : 0;
-        const int t0 = (v0 + TM - 1) / TM, t1 = (v1 + TM - 1) / TM;
-        int rows_inc = v0 + v1, tiles_inc = t0 + t1;
-        // block scan over 256 threads (4 waves)
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int o = __shfl_up(rows_inc, off);
-            const int o2 = __shfl_up(tiles_inc, off);
-            if (lane >= off) {
-                rows_inc += o;
-                tiles_inc += o2;
-            }
-        }
-        if (lane == 63) wave_sums[wave] = rows_inc;
-        __syncthreads();
-        int add = 0;
-        for (int w = 0; w < wave; ++w) add += wave_sums[w];
-        __syncthreads();
-        if (lane == 63) wave_sums[wave] = tiles_inc;
-        __syncthreads();
-        int tadd = 0;
-        for (int w = 0; w < wave; ++w) tadd += wave_sums[w];
-        rows_inc += add;
-        tiles_inc += tadd;
-        const int off0 = rows_inc - v0 - v1, off1 = off0 + v0;
-        const int toff0 = tiles_inc - t0 - t1, toff1 = toff0 + t0;
-        // cursors: offsets + assignments ahead of this chunk + earlier waves of this chunk
-        if (e0 < n) {
-            int run = off0 + before[e0];
-            for (int w = 0; w < 4; ++w) {
-                const int v = wh[w * n + e0];
-                wh[w * n + e0] = run;
-                run += v;
-            }
-        }
-        if (e1 < n) {
-            int run = off1 + before[e1];
-            for (int w = 0; w < 4; ++w) {
-                const int v = wh[w * n + e1];
-                wh[w * n + e1] = run;
-                run += v;
-            }
-        }
-        if (blockIdx.x == 0) {
-            if (e0 < n) {
-                p.counts[e0] = v0;
-                p.offsets[e0] = off0;
-                if (p.tile_offsets) p.tile_offsets[e0] = toff0;
-                for (int j = 0; j < t0; ++j) {
-                    p.tile_expert[toff0 + j] = e0;
-                    p.tile_row0[toff0 + j] = off0 + j * TM;
-                }
-            }
-            if (e1 < n) {
-                p.counts[e1] = v1;
-                p.offsets[e1] = off1;
-                if (p.tile_offsets) p.tile_offsets[e1] = toff1;
-                for (int j = 0; j < t1; ++j) {
-                    p.tile_expert[toff1 + j] = e1;
-                    p.tile_row0[toff1 + j] = off1 + j * TM;
-                }
-            }
-            if (tid == 255) {
-                p.offsets[n] = rows_inc;
-                if (p.tile_offsets) p.tile_offsets[n] = tiles_inc;
-                p.num_tiles[0] = tiles_inc;
-            }
-        }
-    }
-    __syncthreads();
-    // ordered scatter of this wave's 256 assignments
-    int *my = wh + wave * n;
-    const int64_t a0 = c0 + 256 * wave;
-    int ev[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int64_t a = a0 + 64 * s + lane;
-        int e = -1;
-        if (a < c1) {
-            e = p.idx[a];
-            if (e < 0 || e >= n) e = -1;
-        }
-        ev[s] = e;
-    }
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int64_t a = a0 + 64 * s + lane;
-        const int ex = ev[s];
-        const bool active = ex >= 0;
-        unsigned long long same = __ballot(active);
-        for (int b = 0; b < nbits; ++b) {
-            const bool bit = (ex >> b) & 1;
-            const unsigned long long bal = __ballot(active && bit);
-            same &= bit ? bal : ~bal;
-        }
-        if (active) {
-            const int rank = __popcll(same & lt_mask);
-            const int c = __popcll(same);
-            const int before_me = my[ex];
-            const int pos = before_me + rank;
-            p.perm[pos] = (int32_t)a;
-            p.inv_perm[a] = pos;
-            if (rank == c - 1) my[ex] = before_me + c;  // issued after every lane's read
-        }
-    }
+    extern __shared__ int lds_s[];
+    route_small_body(p, nbits, blockIdx.x, lds_s);
 }
 
 // Row-tile table for another tile height, from an existing offsets array (one workgroup).
@@ -348,10 +206,12 @@ int launch_build_tiles(const int32_t *offsets, int n, int tile_rows, int32_t *ti
     return MOE_OK;
 }
 
+bool route_is_small(int64_t A, int n) { return n <= kSmallMaxN && A <= 65536; }
+
 int launch_route(RouteArgs a, hipStream_t st) {
     int nbits = 0;
     while ((1 << nbits) < a.n) ++nbits;
-    if (a.n <= kSmallMaxN && a.A <= 65536) {
+    if (route_is_small(a.A, a.n)) {
         const unsigned blocks = (unsigned)(a.A > 0 ? ceil_div(a.A, kSmallChunk) : 1);
         hipLaunchKernelGGL(route_small_kernel, dim3(blocks), dim3(256), (size_t)6 * a.n * sizeof(int),
                            st, a, nbits);

@@ -65,6 +65,13 @@ int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st);
 int gate_rows_per_block(int64_t rows, int n);
 size_t route_ws_bytes(int64_t A, int n);
 int launch_route(RouteArgs a, hipStream_t st);
+bool route_is_small(int64_t A, int n);   // one-launch path (few experts, short assignment list)
+// fused launches of the layer forward (small path only; aux_ws as in aux_ws_bytes)
+int launch_route_small_sums(RouteArgs a, const float *partials, int64_t prow, double *aux_ws,
+                            hipStream_t st);
+int launch_combine_losses(const float *out_sorted, const float *gate, const int32_t *inv_perm, float *y,
+                          int64_t T, int d, int k, int64_t prow, int n, double *aux_ws, float w_imp,
+                          float w_load, float *importance, float *load, float *losses, hipStream_t st);
 int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles, hipStream_t st);
 int expert_ffn_with_hidden(const moe_config *cfg, const float *x, const int32_t *perm,
                            const int32_t *offsets, const int32_t *tile_expert,
