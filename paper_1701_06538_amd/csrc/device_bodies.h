@@ -23,24 +23,52 @@ __device__ __forceinline__ void route_small_body(const RouteArgs &p, int nbits, 
     __syncthreads();
     const int64_t c0 = (int64_t)block * kSmallChunk;
     const int64_t c1 = min(c0 + kSmallChunk, p.A);
-    for (int64_t base = 0; base < p.A; base += 256 * 8) {
-        int ev8[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {   // eight independent loads in flight
-            const int64_t a = base + 256 * u + tid;
-            ev8[u] = a < p.A ? p.idx[a] : -1;
+    // One LDS atomic per assignment: it falls before the chunk, into one of the chunk's four
+    // 256-assignment quarters, or after the chunk (that last bin temporarily lives in total[]).
+    auto count_one = [&](int64_t a, int e) {
+        if (e >= 0 && e < n) {
+            int *bin = a < c0 ? &before[e] : a < c1 ? &wh[((a - c0) >> 8) * n + e] : &total[e];
+            atomicAdd(bin, 1);   // integer counts: order-independent
         }
+    };
+    if ((reinterpret_cast<uintptr_t>(p.idx) & 15) == 0) {
+        // 16-byte loads, eight in flight per thread: the whole list takes A / 8192 round trips
+        const int64_t n4 = p.A >> 2;
+        const int4 *idx4 = reinterpret_cast<const int4 *>(p.idx);
+        for (int64_t base = 0; base < n4; base += 256 * 8) {
+            int4 ev8[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t a = base + 256 * u + tid;
-            const int e = ev8[u];
-            if (e >= 0 && e < n) {
-                atomicAdd(&total[e], 1);
-                if (a < c0) atomicAdd(&before[e], 1);
-                else if (a < c1) atomicAdd(&wh[((a - c0) >> 8) * n + e], 1);
+            for (int u = 0; u < 8; ++u) {
+                const int64_t g = base + 256 * u + tid;
+                ev8[u] = g < n4 ? idx4[g] : make_int4(-1, -1, -1, -1);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t a = 4 * (base + 256 * u + tid);
+                count_one(a, ev8[u].x);
+                count_one(a + 1, ev8[u].y);
+                count_one(a + 2, ev8[u].z);
+                count_one(a + 3, ev8[u].w);
             }
         }
+        const int64_t a = 4 * n4 + tid;
+        if (a < p.A) count_one(a, p.idx[a]);
+    } else {
+        for (int64_t base = 0; base < p.A; base += 256 * 8) {
+            int ev8[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {   // eight independent loads in flight
+                const int64_t a = base + 256 * u + tid;
+                ev8[u] = a < p.A ? p.idx[a] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) count_one(base + 256 * u + tid, ev8[u]);
+        }
     }
+    __syncthreads();
+    // totals = before + the chunk's quarters + after
+    for (int e = tid; e < n; e += 256)
+        total[e] += before[e] + wh[e] + wh[n + e] + wh[2 * n + e] + wh[3 * n + e];
     __syncthreads();
     // exclusive scan of the totals over experts: two adjacent experts per thread
     const int TM = p.tile_rows;
