@@ -81,7 +81,7 @@ __device__ __forceinline__ float softplus_spec(float zf) {
 
 constexpr int BM = kGateBM;  // 128 rows: 4 waves x 32
 
-#ifdef MOE_GATE_TIMING
+#if defined(MOE_GATE_TIMING) || defined(MOE_TOPK_TIMING)
 __device__ long long g_gate_timing[4096 * 40];
 #define GATE_STAMP(i) do { const unsigned b_ = blockIdx.y * gridDim.x + blockIdx.x; if (threadIdx.x == 0 && b_ < 4096) g_gate_timing[b_ * 40 + (i)] = wall_clock64(); } while (0)
 #else
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(LogitsArgs p) {
     }
     GATE_STAMP(36);
 }
-#ifdef MOE_GATE_TIMING
+#if defined(MOE_GATE_TIMING) || defined(MOE_TOPK_TIMING)
 extern "C" int moe_debug_read_gate_timing(long long *host_out) {
     return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_gate_timing), sizeof(long long) * 4096 * 40);
 }
@@ -339,8 +339,29 @@ __device__ __forceinline__ float normal_cdf(float u) {
     return u < 0.f ? half_erfc : 1.0f - half_erfc;
 }
 
-__device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
-    return v1 > v2 || (v1 == v2 && i1 < i2);
+// Selection key: one unsigned 64-bit integer per (logit, expert) whose order is the order the
+// top-k must follow: larger logit first, equal logits -> lower expert index first, +0 = -0.
+// High word: the logit's bits mapped monotonically to unsigned; low word: 0x7fffffff - index.
+// Key 0 is below every real key (logits are finite) and marks an empty slot.
+__device__ __forceinline__ uint64_t sel_key(float h, int i) {
+    uint32_t u = __float_as_uint(h + 0.0f);   // -0 -> +0
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((uint64_t)u << 32) | (uint32_t)(0x7fffffff - i);
+}
+__device__ __forceinline__ float key_logit(uint64_t key) {
+    uint32_t u = (uint32_t)(key >> 32);
+    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+    return __uint_as_float(u);
+}
+__device__ __forceinline__ int key_index(uint64_t key) { return 0x7fffffff - (int)(uint32_t)key; }
+
+// The same pointer in scalar registers (all lanes hold the same value): loads through it can use
+// scalar-base addressing with one 32-bit lane offset.
+__device__ __forceinline__ const float *uniform_ptr(const float *ptr) {
+    const uint64_t v = reinterpret_cast<uint64_t>(ptr);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const float *>(((uint64_t)hi << 32) | lo);
 }
 
 // L >= k+1 candidate slots per lane; NCH >= ceil(n/64) register chunks: a lane holds the whole of
@@ -349,8 +370,9 @@ __device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
 // per-expert sums of G(x) and P(x,.) also stay in registers across the rows a wave walks.
 template <int L, int NCH>
 __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
-    extern __shared__ float lds_acc[];  // [2][n]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    extern __shared__ float lds_acc[];  // Importance per wave [4][n] | Load of the block [n]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: row pointers stay uniform
     const int n = p.n, k = p.k;
     const int RPB = p.rows_per_block;
     const int SUB = kGateBM / RPB;
@@ -369,57 +391,76 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
         re = min(rb + RPB, p.R);
     }
     const int kp1 = (k < n) ? k + 1 : k;
-    float acc_imp[NCH], acc_load[NCH];
+#ifdef MOE_TOPK_TIMING
+    int stamp_i = 0;
+#define TOPK_STAMP() do { if ((threadIdx.x & 63) == 0 && blockIdx.x < 1024 && stamp_i < 10) g_gate_timing[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 10 + stamp_i++] = wall_clock64(); } while (0)
+#else
+#define TOPK_STAMP() do { } while (0)
+#endif
+    TOPK_STAMP();
+    // Load: every expert of every row contributes, so the sums stay in registers.  Importance:
+    // only the k kept experts of a row contribute, so k lanes add their gate values to the
+    // wave's own LDS array (distinct addresses inside one instruction, rows in order: the sum
+    // of each entry is a fixed sequence of fp32 additions).
+    float acc_load[NCH];
 #pragma unroll
-    for (int q = 0; q < NCH; ++q) {
-        acc_imp[q] = 0.f;
-        acc_load[q] = 0.f;
-    }
+    for (int q = 0; q < NCH; ++q) acc_load[q] = 0.f;
+    float *imp_w = lds_acc + wave * n;
+    for (int i = tid; i < 4 * n; i += 256) lds_acc[i] = 0.f;
+    __syncthreads();
 
+#pragma unroll 1
     for (int64_t r = rb + wave; r < re; r += 4) {
-        const float *c_row = p.cleanb + r * n;
-        const float *s_row = p.sp + r * n;
+        const float *c_row = uniform_ptr(p.cleanb + r * n);
+        const float *s_row = uniform_ptr(p.sp + r * n);
         const int64_t orow = p.row_map ? p.row_map[r] : r;
-        const float *e_row = p.eps ? p.eps + orow * n : nullptr;
+        const float *e_row = p.eps ? uniform_ptr(p.eps + orow * n) : nullptr;
 
+        // Unconditional loads from a wave-uniform row pointer plus a clamped lane offset: lanes past
+        // the end of the row re-read its last element (they are masked out of the selection and of
+        // the sums below), so no load sits behind a branch.
         float cv[NCH], sv[NCH], hv[NCH];
 #pragma unroll
         for (int q = 0; q < NCH; ++q) {
-            const int i = lane + 64 * q;
-            const bool in = i < n;
-            cv[q] = in ? c_row[i] : 0.f;
-            sv[q] = in ? s_row[i] : 1.f;
-            hv[q] = (in && e_row) ? e_row[i] : 0.f;
+            const unsigned i = min((unsigned)(lane + 64 * q), (unsigned)(n - 1));
+            cv[q] = c_row[i];
+            sv[q] = s_row[i];
         }
+        if (e_row) {
 #pragma unroll
-        for (int q = 0; q < NCH; ++q) hv[q] = e_row ? __fmaf_rn(hv[q], sv[q], cv[q]) : cv[q];
+            for (int q = 0; q < NCH; ++q)
+                hv[q] = e_row[min((unsigned)(lane + 64 * q), (unsigned)(n - 1))];
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) hv[q] = __fmaf_rn(hv[q], sv[q], cv[q]);
+        } else {
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) hv[q] = cv[q];
+        }
+#ifdef MOE_TOPK_TIMING
+        if (hv[0] == 12345.678f) stamp_i = 100;   // forces the loads to have completed
+#endif
+        TOPK_STAMP();
 
-        float lv[L];
-        int li[L];
+        // per-lane sorted candidate list: branch-free compare-exchange insertion
+        uint64_t lk[L];
 #pragma unroll
-        for (int j = 0; j < L; ++j) {
-            lv[j] = -INFINITY;
-            li[j] = 0x7fffffff;
-        }
+        for (int j = 0; j < L; ++j) lk[j] = 0;
 #pragma unroll
         for (int q = 0; q < NCH; ++q) {
             const int i = lane + 64 * q;
-            if (i < n) {
-                float v = hv[q];
-                int id = i;
+            uint64_t key = i < n ? sel_key(hv[q], i) : 0;
 #pragma unroll
-                for (int j = 0; j < L; ++j) {
-                    if (better(v, id, lv[j], li[j])) {
-                        const float tv = lv[j];
-                        const int ti = li[j];
-                        lv[j] = v;
-                        li[j] = id;
-                        v = tv;
-                        id = ti;
-                    }
-                }
+            for (int j = 0; j < L; ++j) {
+                const bool up = key > lk[j];
+                const uint64_t lo = up ? lk[j] : key;
+                lk[j] = up ? key : lk[j];
+                key = lo;
             }
+            // long rows: one element at a time, or the keys of the whole row are built up front
+            // and spill
+            if (NCH >= 16) __builtin_amdgcn_sched_barrier(0);
         }
+        // k+1 rounds: wave-wide maximum of the list heads (keys are unique), the owner pops
         float tv[L];
         int ti[L];
 #pragma unroll
@@ -427,28 +468,18 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
             tv[j] = -INFINITY;
             ti[j] = 0x7fffffff;
             if (j < kp1) {
-                float v = lv[0];
-                int id = li[0];
+                uint64_t v = lk[0];
 #pragma unroll
                 for (int off = 32; off > 0; off >>= 1) {
-                    const float ov = __shfl_xor(v, off);
-                    const int oi = __shfl_xor(id, off);
-                    if (better(ov, oi, v, id)) {
-                        v = ov;
-                        id = oi;
-                    }
+                    const uint64_t o = __shfl_xor(v, off);
+                    v = o > v ? o : v;
                 }
-                tv[j] = v;
-                ti[j] = id;
-                if (li[0] == id) {
+                tv[j] = key_logit(v);
+                ti[j] = key_index(v);
+                const bool pop = lk[0] == v;
 #pragma unroll
-                    for (int q = 0; q + 1 < L; ++q) {
-                        lv[q] = lv[q + 1];
-                        li[q] = li[q + 1];
-                    }
-                    lv[L - 1] = -INFINITY;
-                    li[L - 1] = 0x7fffffff;
-                }
+                for (int q = 0; q + 1 < L; ++q) lk[q] = pop ? lk[q + 1] : lk[q];
+                lk[L - 1] = pop ? 0 : lk[L - 1];
             }
         }
         // Eq.(3): softmax over the kept logits
@@ -462,15 +493,25 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
         const float inv = 1.0f / sum;
 #pragma unroll
         for (int j = 0; j < L; ++j) g[j] *= inv;
-        if (lane == 0) {
+        {
+            // lane j < k owns slot j: it writes the slot's outputs and adds its gate value
+            int my_i = ti[0];
+            float my_g = g[0];
 #pragma unroll
-            for (int j = 0; j < L; ++j)
-                if (j < k) {
-                    p.idx[orow * k + j] = ti[j];
-                    p.gate[orow * k + j] = g[j];
+            for (int j = 1; j < L; ++j)
+                if (j < k && lane == j) {
+                    my_i = ti[j];
+                    my_g = g[j];
                 }
+            if (lane < k) {
+                p.idx[orow * k + lane] = my_i;
+                p.gate[orow * k + lane] = my_g;
+                unsafeAtomicAdd(&imp_w[my_i], my_g);
+            }
         }
-        // Eq.(9): P(x,i) for every expert; threshold = (k+1)-th H for kept experts, k-th otherwise
+        // Eq.(9): P(x,i) for every expert; threshold = (k+1)-th H for kept experts, k-th otherwise.
+        // "kept" is H_i >= the k-th kept logit: where that misjudges a tie, the (k+1)-th logit
+        // equals the k-th and both thresholds coincide.
         float thr_in = 0.f, thr_out = 0.f;
         int nxt = -1;
 #pragma unroll
@@ -482,44 +523,41 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
             if (j == k - 1) thr_out = tv[j];
         }
         if (lane == 0 && p.next_idx) p.next_idx[orow] = nxt;
+        if (k < n) {
 #pragma unroll
-        for (int q = 0; q < NCH; ++q) {
-            const int i = lane + 64 * q;
-            if (i < n) {
-                float gi = 0.f;
-                bool kept = false;
-#pragma unroll
-                for (int j = 0; j < L; ++j)
-                    if (j < k && ti[j] == i) {
-                        kept = true;
-                        gi = g[j];
-                    }
-                float P = 1.0f;
-                if (k < n) {
-                    const float u = (cv[q] - (kept ? thr_in : thr_out)) * __frcp_rn(sv[q]);
-                    P = normal_cdf(u);
-                }
-                acc_load[q] += P;
-                acc_imp[q] += gi;
+            for (int q = 0; q < NCH; ++q) {
+                const int i = lane + 64 * q;
+                const float u = (cv[q] - (hv[q] >= thr_out ? thr_in : thr_out)) * __frcp_rn(sv[q]);
+                const float P = normal_cdf(u);
+                acc_load[q] += i < n ? P : 0.f;
+                if (NCH >= 16 && (q & 3) == 3) __builtin_amdgcn_sched_barrier(0);
             }
+        } else {
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) acc_load[q] += (lane + 64 * q) < n ? 1.0f : 0.f;
         }
+        TOPK_STAMP();
     }
-    // the four waves' sums, added in wave order through one [2][n] LDS buffer
+    TOPK_STAMP();
+    // the four waves' sums, added in wave order
+    float *load_s = lds_acc + 4 * n;
     for (int w = 0; w < 4; ++w) {
         if (wave == w) {
 #pragma unroll
             for (int q = 0; q < NCH; ++q) {
                 const int i = lane + 64 * q;
-                if (i < n) {
-                    lds_acc[i] = (w ? lds_acc[i] : 0.f) + acc_imp[q];
-                    lds_acc[n + i] = (w ? lds_acc[n + i] : 0.f) + acc_load[q];
-                }
+                if (i < n) load_s[i] = (w ? load_s[i] : 0.f) + acc_load[q];
             }
         }
         __syncthreads();
     }
+    TOPK_STAMP();
     float *out = p.partials + (size_t)blockIdx.x * 2 * n;
-    for (int i = tid; i < 2 * n; i += 256) out[i] = lds_acc[i];
+    for (int i = tid; i < n; i += 256) {
+        out[i] = (((0.f + lds_acc[i]) + lds_acc[n + i]) + lds_acc[2 * n + i]) + lds_acc[3 * n + i];
+        out[n + i] = load_s[i];
+    }
+    TOPK_STAMP();
 }
 
 // Eq.(12): global expert id and gate product for every (token, primary slot, secondary slot)
@@ -580,7 +618,7 @@ static void launch_topk_nch(const TopkArgs &a, unsigned blocks, size_t lds, hipS
 
 int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st) {
     if (blocks <= 0) return MOE_OK;
-    const size_t lds = (size_t)2 * a.n * sizeof(float);
+    const size_t lds = (size_t)5 * a.n * sizeof(float);
     if (a.k + 1 <= 3) launch_topk_nch<3>(a, (unsigned)blocks, lds, st);
     else if (a.k + 1 <= 5) launch_topk_nch<5>(a, (unsigned)blocks, lds, st);
     else launch_topk_nch<9>(a, (unsigned)blocks, lds, st);
