@@ -133,17 +133,6 @@ __device__ __forceinline__ void mma_slab(v16f (&acc)[2][2], uint16_t (*As)[GLD],
     }
 }
 
-enum { EPI_RELU_BF16 = 0, EPI_MASK_BF16 = 1, EPI_F32 = 2 };
-
-struct GGRows {
-    const uint16_t *A;     // [A_rows, K] sorted rows, k contiguous
-    const uint16_t *B;     // per expert: B_KN ? [K, N] : [N, K]
-    void *C;               // [A_rows, N] bf16 or fp32
-    const uint16_t *mask;  // [A_rows, N] (EPI_MASK_BF16)
-    int K, N;
-    const int32_t *offsets, *tile_expert, *tile_row0, *num_tiles;
-};
-
 // C[rows of expert e, N] = A[rows, K] * B_e   over the row tiles of a 128-row tile table
 template <bool B_KN, int EPI>
 __global__ __launch_bounds__(256) void gg_rows_kernel(GGRows p) {
@@ -713,9 +702,11 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
         hipLaunchKernelGGL((gg_rows_kernel<true, EPI_RELU_BF16>), dim3(max_tiles, h / GBN), dim3(256), 0, s, g1);
         MOE_LAUNCH_CHECK();
     }
+    // the two compute-bound GEMMs of the expert backward run on 256-row tiles
+    if ((st = launch_build_tiles(offsets, n, 256, tile_expert, tile_row0, num_tiles, s)) != MOE_OK) return st;
+    const int64_t max_tiles256 = ceil_div(A, 256) + n;
     GGRows g2{dout, (const uint16_t *)W2, dz, hid, d, h, offsets, tile_expert, tile_row0, num_tiles};
-    hipLaunchKernelGGL((gg_rows_kernel<false, EPI_MASK_BF16>), dim3(max_tiles, h / GBN), dim3(256), 0, s, g2);
-    MOE_LAUNCH_CHECK();
+    if ((st = launch_gg_rows256(g2, EPI_MASK_BF16, max_tiles256, s)) != MOE_OK) return st;
     GGWgrad w2{hid, dout, dW2, h, d, offsets};
     hipLaunchKernelGGL(gg_wgrad_kernel, dim3(h / 256, d / 256, n), dim3(256), 0, s, w2);
     MOE_LAUNCH_CHECK();
@@ -723,8 +714,7 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     hipLaunchKernelGGL(gg_wgrad_kernel, dim3(d / 256, h / 256, n), dim3(256), 0, s, w1);
     MOE_LAUNCH_CHECK();
     GGRows g5{dz, (const uint16_t *)W1, dxs, nullptr, h, d, offsets, tile_expert, tile_row0, num_tiles};
-    hipLaunchKernelGGL((gg_rows_kernel<false, EPI_F32>), dim3(max_tiles, d / GBN), dim3(256), 0, s, g5);
-    MOE_LAUNCH_CHECK();
+    if ((st = launch_gg_rows256(g5, EPI_F32, max_tiles256, s)) != MOE_OK) return st;
 
     // gate
     hipLaunchKernelGGL(loss_grad_kernel, dim3(1), dim3(256), 0, s, sums64, n, cfg->w_importance,

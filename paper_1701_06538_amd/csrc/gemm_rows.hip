@@ -1,0 +1,219 @@
+// Compute-bound grouped GEMM of the expert backward pass (Section 2.1: plain back-propagation
+// through the experts): C[rows of expert e, N] = A[rows, K] * B_e^T with B_e stored [N, K]
+// (k contiguous), i.e. dz = (dout W2^T) * relu'  and  dxs = dz W1^T.
+//
+// One workgroup = a 256 x 256 tile of C: 256 rows of ONE expert (a row tile of a 256-row tile
+// table) by 256 columns.  Four waves, one per SIMD, each a 128 x 128 quarter held as 4 x 4
+// v_mfma_f32_32x32x16_bf16 accumulators (256 AGPRs): with this wave tile the LDS read traffic is
+// half a KB per matrix instruction, which the LDS can sustain beside the slab stores.  Operand
+// slabs of 32 k go global -> registers -> LDS (k contiguous for both operands, rows padded to 80
+// bytes so 16-byte reads are conflict free); the three-level software pipeline is the one of the
+// gate's logits kernel: slab s+1 is stored and slab s+2 fetched in the middle of slab s, operand
+// registers are read one k-step ahead, and the barrier sits before the slab's last k-step.
+// Work items are ordered column-tile-fastest and handed out XCD by XCD, so the column tiles of
+// one row tile (same A rows) and the row tiles of one expert (same weights) share an L2.
+#include "stages.h"
+
+namespace moe {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+constexpr int RT = 256;            // tile rows and columns
+#ifndef GG_RKC
+#define GG_RKC 64
+#endif
+constexpr int RKC = GG_RKC;        // slab depth
+constexpr int RLD = RKC + 8;       // bf16 elements per LDS row (+16 bytes: 16-byte reads of 8 rows hit 32 banks)
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+#ifdef MOE_GG_TIMING
+__device__ long long g_gg_timing[8192 * 4];
+#define GG_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_gg_timing[blockIdx.x * 4 + (i)] = wall_clock64(); } while (0)
+extern "C" int moe_debug_read_gg_timing(long long *host_out) {
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_gg_timing), sizeof(long long) * 8192 * 4);
+}
+#else
+#define GG_STAMP(i) do { } while (0)
+#endif
+
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void gg_rows256_kernel(GGRows p, int col_tiles) {
+    constexpr int SLAB = RT * RLD * 2;                       // bytes of one operand slab
+    __shared__ __attribute__((aligned(16))) char smem[4 * SLAB];
+    uint16_t (*As)[RT][RLD] = reinterpret_cast<uint16_t (*)[RT][RLD]>(smem);
+    uint16_t (*Bs)[RT][RLD] = reinterpret_cast<uint16_t (*)[RT][RLD]>(smem + 2 * SLAB);
+
+    // work item = row tile * col_tiles + column tile, handed out XCD by XCD
+    const int num_items = *p.num_tiles * col_tiles;
+    const int per = (num_items + 7) >> 3;
+    const int item = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= per || item >= num_items) return;
+    const int tile = item / col_tiles;
+    const int col0 = (item % col_tiles) * RT;
+    const int e = p.tile_expert[tile];
+    const int row0 = p.tile_row0[tile];
+    const int rows = min(RT, p.offsets[e + 1] - row0);
+    const int K = p.K, N = p.N;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, kg = lane >> 5;
+    const uint16_t *Bw = p.B + (size_t)e * K * N;
+
+    // staging: a slab row is CPR 16-byte chunks handled by CPR adjacent threads (with 64-deep
+    // slabs that is one whole 128-byte line per row); SP passes of SR rows cover the tile.  Rows
+    // past the end of the tile re-read its last row (never stored).
+    constexpr int CPR = RKC / 8, SR = 256 / CPR, SP = RT / SR;
+    const int s_row = tid / CPR, s_kq = (tid % CPR) * 8;
+    const uint16_t *a_src[SP], *b_src[SP];
+#pragma unroll
+    for (int i = 0; i < SP; ++i) {
+        a_src[i] = p.A + (size_t)(row0 + min(s_row + SR * i, rows - 1)) * K + s_kq;
+        b_src[i] = Bw + (size_t)(col0 + s_row + SR * i) * K + s_kq;
+    }
+    v4u a_reg[SP], b_reg[SP];
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < SP; ++i) a_reg[i] = *reinterpret_cast<const v4u *>(a_src[i] + k0);
+#pragma unroll
+        for (int i = 0; i < SP; ++i) b_reg[i] = *reinterpret_cast<const v4u *>(b_src[i] + k0);
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < SP; ++i) *reinterpret_cast<v4u *>(&As[buf][s_row + SR * i][s_kq]) = a_reg[i];
+#pragma unroll
+        for (int i = 0; i < SP; ++i) *reinterpret_cast<v4u *>(&Bs[buf][s_row + SR * i][s_kq]) = b_reg[i];
+    };
+
+    v16f acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // operands of one k-step of 16: four row fragments, four column fragments
+    v4u a_op[2][4], b_op[2][4];
+    auto read_ops = [&](int slot, int buf, int ks) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            a_op[slot][i] = *reinterpret_cast<const v4u *>(&As[buf][128 * wm + 32 * i + l32][16 * ks + 8 * kg]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            b_op[slot][j] = *reinterpret_cast<const v4u *>(&Bs[buf][128 * wn + 32 * j + l32][16 * ks + 8 * kg]);
+    };
+
+    constexpr int NS = RKC / 16;   // k-steps per slab
+    GG_STAMP(0);
+    load_global(0);
+    store_lds(0);
+    load_global(min(RKC, K - RKC));
+    __syncthreads();
+    read_ops(0, 0, 0);
+    GG_STAMP(1);
+    for (int k0 = 0; k0 < K; k0 += RKC) {
+        const int buf = (k0 / RKC) & 1;
+#pragma unroll
+        for (int ks = 0; ks < NS; ++ks) {
+            if (ks == NS - 1) {
+                __syncthreads();
+                read_ops((ks + 1) & 1, buf ^ 1, 0);   // after the last slab: unused
+            } else {
+                read_ops((ks + 1) & 1, buf, ks + 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(   // the transposed product
+                        __builtin_bit_cast(v8bf, b_op[ks & 1][j]), __builtin_bit_cast(v8bf, a_op[ks & 1][i]),
+                        acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks == NS / 2 - 1) {
+                // unconditional: past the last slab they re-read a valid slab into a dead buffer
+                store_lds(buf ^ 1);
+                load_global(min(k0 + 2 * RKC, K - RKC));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    // Epilogue straight from the accumulators.  The matrix instructions computed the transposed
+    // product (weights as the first operand), so a lane holds, for ONE row of C, groups of four
+    // adjacent columns: 16-byte fp32 stores or 8-byte bf16 stores (and 8-byte mask loads), no LDS
+    // round trip and no barrier.
+    GG_STAMP(2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = 128 * wm + 32 * i + l32;
+        const bool live = row < rows;
+        const size_t at0 = (size_t)(row0 + min(row, rows - 1)) * N + col0 + 128 * wn + 4 * kg;
+        if (EPI == EPI_F32) {
+            float *dst = reinterpret_cast<float *>(p.C) + at0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (live)
+                        *reinterpret_cast<v4f *>(dst + 32 * j + 8 * q) =
+                            v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        } else {
+            uint16_t *dst = reinterpret_cast<uint16_t *>(p.C) + at0;
+            uint2 m[4][4];
+            if (EPI == EPI_MASK_BF16) {   // all sixteen loads of the strip in flight together
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        m[j][q] = *reinterpret_cast<const uint2 *>(p.mask + at0 + 32 * j + 8 * q);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    if (EPI == EPI_MASK_BF16) {
+                        // relu'(z) with relu'(0) = 0: the stored hidden value is positive iff z > 0
+                        const uint32_t mw[2] = {m[j][q].x, m[j][q].y};
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const uint32_t hbits = (mw[t >> 1] >> (16 * (t & 1))) & 0xffffu;
+                            const bool on = (hbits & 0x7fffu) != 0 && (hbits & 0x8000u) == 0;
+                            v[t] = on ? v[t] : 0.f;
+                        }
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) v[t] = fmaxf(v[t], 0.f);
+                    }
+                    uint2 o;
+                    o.x = bf16_rne_bits(v[0]) | (bf16_rne_bits(v[1]) << 16);
+                    o.y = bf16_rne_bits(v[2]) | (bf16_rne_bits(v[3]) << 16);
+                    if (live) *reinterpret_cast<uint2 *>(dst + 32 * j + 8 * q) = o;
+                }
+        }
+    }
+    GG_STAMP(3);
+}
+
+// p's tile table must hold 256-row tiles; max_tiles bounds *p.num_tiles.
+int launch_gg_rows256(const GGRows &p, int epi, int64_t max_tiles, hipStream_t st) {
+    if (p.N % RT || p.K % RKC || p.K < RKC) return MOE_EUNSUPPORTED;
+    const int col_tiles = p.N / RT;
+    const unsigned grid = (unsigned)(ceil_div(max_tiles * col_tiles, 8) * 8);
+    if (grid == 0) return MOE_OK;
+    if (epi == EPI_MASK_BF16) hipLaunchKernelGGL((gg_rows256_kernel<EPI_MASK_BF16>), dim3(grid), dim3(256), 0, st, p, col_tiles);
+    else if (epi == EPI_F32) hipLaunchKernelGGL((gg_rows256_kernel<EPI_F32>), dim3(grid), dim3(256), 0, st, p, col_tiles);
+    else hipLaunchKernelGGL((gg_rows256_kernel<EPI_RELU_BF16>), dim3(grid), dim3(256), 0, st, p, col_tiles);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+}  // namespace moe

@@ -64,6 +64,20 @@ int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st);
 int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st);
 int gate_rows_per_block(int64_t rows, int n);
 size_t route_ws_bytes(int64_t A, int n);
+// grouped row GEMMs of the expert backward pass
+enum { EPI_RELU_BF16 = 0, EPI_MASK_BF16 = 1, EPI_F32 = 2 };
+
+struct GGRows {
+    const uint16_t *A;     // [A_rows, K] sorted rows, k contiguous
+    const uint16_t *B;     // per expert: B_KN ? [K, N] : [N, K]
+    void *C;               // [A_rows, N] bf16 or fp32
+    const uint16_t *mask;  // [A_rows, N] (EPI_MASK_BF16)
+    int K, N;
+    const int32_t *offsets, *tile_expert, *tile_row0, *num_tiles;
+};
+
+int launch_gg_rows256(const GGRows &p, int epi, int64_t max_tiles, hipStream_t st);
+
 int launch_route(RouteArgs a, hipStream_t st);
 bool route_is_small(int64_t A, int n);   // one-launch path (few experts, short assignment list)
 // fused launches of the layer forward (small path only; aux_ws as in aux_ws_bytes)
