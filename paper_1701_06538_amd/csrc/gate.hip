@@ -560,6 +560,185 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
     TOPK_STAMP();
 }
 
+// Long rows (n > 1024): the four wavefronts of a workgroup share one row, a quarter each, so a lane
+// holds at most NCH = n/256 logits (the one-wave-per-row kernel would need 32 and spills).  Each
+// wave finds the k+1 best of its quarter, the 4(k+1) candidates meet in LDS, every wave merges
+// them (identically) into the row's k+1 best, and then evaluates P(x,i) on its own quarter.  A
+// wave keeps the same columns for every row of the workgroup, so the Load sums need no exchange
+// at all; Importance is added by the first wave alone, row after row.
+template <int L, int NCH>
+__global__ __launch_bounds__(256, 2) void gate_topk_wide_kernel(TopkArgs p) {
+    extern __shared__ float lds_imp[];            // Importance of the block [n]
+    __shared__ uint64_t cand[2][4][L];            // per row parity, per wave
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = p.n, k = p.k;
+    const int RPB = p.rows_per_block;
+    const int SUB = kGateBM / RPB;
+
+    int64_t rb, re;
+    if (p.tile_row0) {
+        const int tile = blockIdx.x / SUB;
+        if (tile >= *p.num_tiles) return;
+        const int g = p.tile_group[tile];
+        const int64_t t0 = p.tile_row0[tile];
+        const int64_t tend = min(t0 + kGateBM, (int64_t)p.group_offsets[g + 1]);
+        rb = min(t0 + (int64_t)(blockIdx.x % SUB) * RPB, tend);
+        re = min(rb + RPB, tend);
+    } else {
+        rb = (int64_t)blockIdx.x * RPB;
+        re = min(rb + RPB, p.R);
+    }
+    const int kp1 = (k < n) ? k + 1 : k;
+    const int col_base = wave * 64 * NCH;         // this wave's quarter of the row
+    float acc_load[NCH];
+#pragma unroll
+    for (int q = 0; q < NCH; ++q) acc_load[q] = 0.f;
+    for (int i = tid; i < n; i += 256) lds_imp[i] = 0.f;
+    __syncthreads();
+
+#pragma unroll 1
+    for (int64_t r = rb; r < re; ++r) {
+        const int par = (int)(r - rb) & 1;
+        const float *c_row = uniform_ptr(p.cleanb + r * n);
+        const float *s_row = uniform_ptr(p.sp + r * n);
+        const int64_t orow = p.row_map ? p.row_map[r] : r;
+        const float *e_row = p.eps ? uniform_ptr(p.eps + orow * n) : nullptr;
+
+        float cv[NCH], sv[NCH], hv[NCH];
+#pragma unroll
+        for (int q = 0; q < NCH; ++q) {
+            const unsigned i = min((unsigned)(col_base + lane + 64 * q), (unsigned)(n - 1));
+            cv[q] = c_row[i];
+            sv[q] = s_row[i];
+        }
+        if (e_row) {
+#pragma unroll
+            for (int q = 0; q < NCH; ++q)
+                hv[q] = e_row[min((unsigned)(col_base + lane + 64 * q), (unsigned)(n - 1))];
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) hv[q] = __fmaf_rn(hv[q], sv[q], cv[q]);
+        } else {
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) hv[q] = cv[q];
+        }
+
+        // the quarter's k+1 best: per-lane sorted lists, then wave-wide maxima
+        uint64_t lk[L];
+#pragma unroll
+        for (int j = 0; j < L; ++j) lk[j] = 0;
+#pragma unroll
+        for (int q = 0; q < NCH; ++q) {
+            const int i = col_base + lane + 64 * q;
+            uint64_t key = i < n ? sel_key(hv[q], i) : 0;
+#pragma unroll
+            for (int j = 0; j < L; ++j) {
+                const bool up = key > lk[j];
+                const uint64_t lo = up ? lk[j] : key;
+                lk[j] = up ? key : lk[j];
+                key = lo;
+            }
+        }
+        uint64_t mine = 0;   // lane j keeps the quarter's j-th best
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            if (j < kp1) {
+                uint64_t v = lk[0];
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const uint64_t o = __shfl_xor(v, off);
+                    v = o > v ? o : v;
+                }
+                mine = lane == j ? v : mine;
+                const bool pop = lk[0] == v;
+#pragma unroll
+                for (int q = 0; q + 1 < L; ++q) lk[q] = pop ? lk[q + 1] : lk[q];
+                lk[L - 1] = pop ? 0 : lk[L - 1];
+            }
+        }
+        if (lane < L) cand[par][wave][lane] = lane < kp1 ? mine : 0;
+        __syncthreads();
+        // every wave merges the 4L candidates the same way
+        uint64_t ck = lane < 4 * L ? cand[par][lane / L][lane % L] : 0;
+        float tv[L];
+        int ti[L];
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            tv[j] = -INFINITY;
+            ti[j] = 0x7fffffff;
+            if (j < kp1) {
+                uint64_t v = ck;
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const uint64_t o = __shfl_xor(v, off);
+                    v = o > v ? o : v;
+                }
+                tv[j] = key_logit(v);
+                ti[j] = key_index(v);
+                ck = ck == v ? 0 : ck;
+            }
+        }
+        // Eq.(3): softmax over the kept logits
+        float g[L];
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            g[j] = (j < k) ? expf(tv[j] - tv[0]) : 0.f;
+            sum += g[j];
+        }
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (int j = 0; j < L; ++j) g[j] *= inv;
+        float thr_in = 0.f, thr_out = 0.f;
+        int nxt = -1;
+#pragma unroll
+        for (int j = 0; j < L; ++j) {
+            if (j == k && k < n) {
+                thr_in = tv[j];
+                nxt = ti[j];
+            }
+            if (j == k - 1) thr_out = tv[j];
+        }
+        if (wave == 0) {
+            int my_i = ti[0];
+            float my_g = g[0];
+#pragma unroll
+            for (int j = 1; j < L; ++j)
+                if (j < k && lane == j) {
+                    my_i = ti[j];
+                    my_g = g[j];
+                }
+            if (lane < k) {
+                p.idx[orow * k + lane] = my_i;
+                p.gate[orow * k + lane] = my_g;
+                unsafeAtomicAdd(&lds_imp[my_i], my_g);
+            }
+            if (lane == 0 && p.next_idx) p.next_idx[orow] = nxt;
+        }
+        // Eq.(9) on this wave's quarter
+        if (k < n) {
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) {
+                const int i = col_base + lane + 64 * q;
+                const float u = (cv[q] - (hv[q] >= thr_out ? thr_in : thr_out)) * __frcp_rn(sv[q]);
+                const float P = normal_cdf(u);
+                acc_load[q] += i < n ? P : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < NCH; ++q) acc_load[q] += (col_base + lane + 64 * q) < n ? 1.0f : 0.f;
+        }
+    }
+    __syncthreads();
+    float *out = p.partials + (size_t)blockIdx.x * 2 * n;
+    for (int i = tid; i < n; i += 256) out[i] = lds_imp[i];
+#pragma unroll
+    for (int q = 0; q < NCH; ++q) {
+        const int i = col_base + lane + 64 * q;
+        if (i < n) out[n + i] = acc_load[q];
+    }
+}
+
 // Eq.(12): global expert id and gate product for every (token, primary slot, secondary slot)
 __global__ __launch_bounds__(256) void hier_compose_kernel(const int32_t *__restrict__ p_idx,
                                                            const float *__restrict__ p_gate,
@@ -613,7 +792,7 @@ static void launch_topk_nch(const TopkArgs &a, unsigned blocks, size_t lds, hipS
     if (a.n <= 256) hipLaunchKernelGGL((gate_topk_kernel<L, 4>), dim3(blocks), dim3(256), lds, st, a);
     else if (a.n <= 512) hipLaunchKernelGGL((gate_topk_kernel<L, 8>), dim3(blocks), dim3(256), lds, st, a);
     else if (a.n <= 1024) hipLaunchKernelGGL((gate_topk_kernel<L, 16>), dim3(blocks), dim3(256), lds, st, a);
-    else hipLaunchKernelGGL((gate_topk_kernel<L, 32>), dim3(blocks), dim3(256), lds, st, a);
+    else hipLaunchKernelGGL((gate_topk_wide_kernel<L, 8>), dim3(blocks), dim3(256), (size_t)a.n * sizeof(float), st, a);
 }
 
 int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st) {
