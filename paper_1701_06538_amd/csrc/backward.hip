@@ -424,12 +424,32 @@ struct SGArgs {
 
 constexpr int SBM = 128, SBN = 128, SKC = 32, SAS = SKC + 4;
 
+typedef float v4f32 __attribute__((ext_vector_type(4)));
+typedef float v2f32 __attribute__((ext_vector_type(2)));
+
 // A_MK: A(m,k) = A[k*lda + m] (m contiguous; used for x^T), else A(m,k) = A[m*lda + k].
 // B_NK: B(k,n) = B[n*ldb + k] (k contiguous; used for W^T), else B(k,n) = B[k*ldb + n].
+// M, N, lda, ldb, ldc are multiples of 4; without A_MK, K is a multiple of 32.
+//
+// 128 x 128 tile, four waves x (32 rows x four 32x32 tiles of v_mfma_f32_32x32x2f32).  An operand
+// whose rows are contiguous in k is staged in LDS as [row][k parity][k/2] (a lane's 16-byte read
+// feeds four consecutive k-steps); one that is contiguous in the other index is staged as
+// [k][row] and read one element per k-step -- either way the global 16-byte loads go to LDS
+// without a scattering transpose.  All loads are unconditional (clamped addresses, values past
+// the end of k replaced by zero with a select), slab s+1 is stored and slab s+2 fetched in the
+// middle of slab s, operands are read one group of four k-steps ahead and the barrier sits before
+// the slab's last group.  The epilogue goes through LDS so rows leave as 16-byte stores.
 template <bool A_MK, bool B_NK>
-__global__ __launch_bounds__(256, 2) void sg_kernel(SGArgs p) {
-    __shared__ __attribute__((aligned(16))) float As[2][SBM][SAS];  // [row][k parity][k/2]
-    __shared__ __attribute__((aligned(16))) float Bs[2][SKC][SBN];
+__global__ __launch_bounds__(256) void sg_kernel(SGArgs p) {
+    constexpr int OPB = SBM * SAS * 4;   // bytes of one operand buffer (the larger layout)
+    constexpr int CS = SBN + 4;
+    static_assert(SBM * CS * 4 <= 4 * OPB, "the output tile reuses the operand buffers");
+    __shared__ __attribute__((aligned(16))) char smem[4 * OPB];
+    float (*A_mk)[SBM][SAS] = reinterpret_cast<float (*)[SBM][SAS]>(smem);
+    float (*A_km)[SKC][SBM] = reinterpret_cast<float (*)[SKC][SBM]>(smem);
+    float (*B_nk)[SBN][SAS] = reinterpret_cast<float (*)[SBN][SAS]>(smem + 2 * OPB);
+    float (*B_kn)[SKC][SBN] = reinterpret_cast<float (*)[SKC][SBN]>(smem + 2 * OPB);
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
     const int m0 = blockIdx.x * SBM, n0 = blockIdx.y * SBN;
@@ -440,6 +460,8 @@ __global__ __launch_bounds__(256, 2) void sg_kernel(SGArgs p) {
     }
     const int kper = A_MK ? ((p.K + p.ksplit - 1) / p.ksplit + SKC - 1) / SKC * SKC : p.K;
     const int kbeg = split * kper, kend = min(p.K, kbeg + kper);
+    const int per_seg = kend > kbeg ? (kend - kbeg + SKC - 1) / SKC : 0;
+    const int nslab = per_seg * (A_MK ? 1 : p.nseg);
 
     v16f acc[4];
 #pragma unroll
@@ -447,111 +469,131 @@ __global__ __launch_bounds__(256, 2) void sg_kernel(SGArgs p) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
 
-    float4 a_reg[4], b_reg[4];
-    auto load = [&](const float *A, const float *B, int k0) {
-        if (A_MK) {   // 32 k x 128 m, float4 along m
+    // staging coordinates
+    const int rk = tid >> 5, r4 = (tid & 31) * 4;    // [k][row] operands: k = rk + 8 i, rows r4..r4+3
+    const int rr = tid >> 3, kq = (tid & 7) * 4;     // [row][k] operands: row = rr + 32 i, k = kq..kq+3
+    v4f32 a_reg[4], b_reg[4];
+    auto load_global = [&](int slab) {
+        const int sgm = A_MK ? 0 : slab / per_seg;
+        const int k0 = kbeg + (slab - sgm * per_seg) * SKC;
+        const float *A = p.A[A_MK ? 0 : sgm];
+        const float *B = p.B[A_MK ? which : sgm];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int k = (tid >> 5) + 8 * i, m4 = (tid & 31) * 4;
-                a_reg[i] = (k0 + k) < kend ? *reinterpret_cast<const float4 *>(A + (size_t)(k0 + k) * p.lda + m0 + m4)
-                                           : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = 0; i < 4; ++i) {
+            if (A_MK) {
+                const int k = k0 + rk + 8 * i;
+                const v4f32 v = *reinterpret_cast<const v4f32 *>(A + (size_t)min(k, kend - 1) * p.lda + min(m0 + r4, p.M - 4));
+                a_reg[i] = k < kend ? v : v4f32{0.f, 0.f, 0.f, 0.f};
+            } else {
+                const int k = k0 + kq;
+                const v4f32 v = *reinterpret_cast<const v4f32 *>(A + (size_t)min(m0 + rr + 32 * i, p.M - 1) * p.lda + min(k, kend - 4));
+                a_reg[i] = k < kend ? v : v4f32{0.f, 0.f, 0.f, 0.f};
             }
-        } else {      // 128 m x 32 k, float4 along k
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = (tid >> 3) + 32 * i, kq = (tid & 7) * 4;
-                a_reg[i] = (m0 + r) < p.M ? *reinterpret_cast<const float4 *>(A + (size_t)(m0 + r) * p.lda + k0 + kq)
-                                          : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        }
-        if (B_NK) {   // 128 n x 32 k, float4 along k
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int c = (tid >> 3) + 32 * i, kq = (tid & 7) * 4;
-                b_reg[i] = (n0 + c) < p.N ? *reinterpret_cast<const float4 *>(B + (size_t)(n0 + c) * p.ldb + k0 + kq)
-                                          : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        } else {      // 32 k x 128 n, float4 along n
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int k = (tid >> 5) + 8 * i, c4 = (tid & 31) * 4;
-                b_reg[i] = ((k0 + k) < kend && (n0 + c4) < p.N) ? *reinterpret_cast<const float4 *>(B + (size_t)(k0 + k) * p.ldb + n0 + c4)
-                                           : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (B_NK) {
+                const int k = k0 + kq;
+                const v4f32 v = *reinterpret_cast<const v4f32 *>(B + (size_t)min(n0 + rr + 32 * i, p.N - 1) * p.ldb + min(k, kend - 4));
+                b_reg[i] = k < kend ? v : v4f32{0.f, 0.f, 0.f, 0.f};
+            } else {
+                const int k = k0 + rk + 8 * i;
+                const v4f32 v = *reinterpret_cast<const v4f32 *>(B + (size_t)min(k, kend - 1) * p.ldb + min(n0 + r4, p.N - 4));
+                b_reg[i] = k < kend ? v : v4f32{0.f, 0.f, 0.f, 0.f};
             }
         }
     };
-    auto store = [&](int buf) {
-        if (A_MK) {
+    auto store_lds = [&](int buf) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int k = (tid >> 5) + 8 * i, m4 = (tid & 31) * 4;
-                const int pos = (k & 1) * (SKC / 2) + (k >> 1);
-                As[buf][m4 + 0][pos] = a_reg[i].x; As[buf][m4 + 1][pos] = a_reg[i].y;
-                As[buf][m4 + 2][pos] = a_reg[i].z; As[buf][m4 + 3][pos] = a_reg[i].w;
+        for (int i = 0; i < 4; ++i) {
+            if (A_MK) {
+                *reinterpret_cast<v4f32 *>(&A_km[buf][rk + 8 * i][r4]) = a_reg[i];
+            } else {
+                float *row = &A_mk[buf][rr + 32 * i][0];
+                *reinterpret_cast<v2f32 *>(row + kq / 2) = v2f32{a_reg[i].x, a_reg[i].z};
+                *reinterpret_cast<v2f32 *>(row + SKC / 2 + kq / 2) = v2f32{a_reg[i].y, a_reg[i].w};
             }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = (tid >> 3) + 32 * i, kq = (tid & 7) * 4;
-                float *row = &As[buf][r][0];
-                *reinterpret_cast<float2 *>(row + kq / 2) = make_float2(a_reg[i].x, a_reg[i].z);
-                *reinterpret_cast<float2 *>(row + SKC / 2 + kq / 2) = make_float2(a_reg[i].y, a_reg[i].w);
+            if (B_NK) {
+                float *row = &B_nk[buf][rr + 32 * i][0];
+                *reinterpret_cast<v2f32 *>(row + kq / 2) = v2f32{b_reg[i].x, b_reg[i].z};
+                *reinterpret_cast<v2f32 *>(row + SKC / 2 + kq / 2) = v2f32{b_reg[i].y, b_reg[i].w};
+            } else {
+                *reinterpret_cast<v4f32 *>(&B_kn[buf][rk + 8 * i][r4]) = b_reg[i];
             }
         }
-        if (B_NK) {
+    };
+    float a_grp[2][4], b_grp[2][4][4];
+    auto read_group = [&](int slot, int buf, int kk4) {
+        if (A_MK) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int c = (tid >> 3) + 32 * i, kq = (tid & 7) * 4;
-                Bs[buf][kq + 0][c] = b_reg[i].x; Bs[buf][kq + 1][c] = b_reg[i].y;
-                Bs[buf][kq + 2][c] = b_reg[i].z; Bs[buf][kq + 3][c] = b_reg[i].w;
-            }
+            for (int u = 0; u < 4; ++u) a_grp[slot][u] = A_km[buf][2 * (kk4 + u) + half][wave * 32 + l32];
         } else {
+            const v4f32 a4 = *reinterpret_cast<const v4f32 *>(&A_mk[buf][wave * 32 + l32][half * (SKC / 2) + kk4]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int k = (tid >> 5) + 8 * i, c4 = (tid & 31) * 4;
-                *reinterpret_cast<float4 *>(&Bs[buf][k][c4]) = b_reg[i];
+            for (int u = 0; u < 4; ++u) a_grp[slot][u] = a4[u];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (B_NK) {
+                const v4f32 b4 = *reinterpret_cast<const v4f32 *>(&B_nk[buf][32 * c + l32][half * (SKC / 2) + kk4]);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) b_grp[slot][u][c] = b4[u];
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) b_grp[slot][u][c] = B_kn[buf][2 * (kk4 + u) + half][32 * c + l32];
             }
         }
     };
 
-    const int nseg = A_MK ? 1 : p.nseg;
-    int buf = 0;
-    bool first = true;
-    for (int sgm = 0; sgm < nseg; ++sgm) {
-        const float *A = p.A[A_MK ? 0 : sgm];
-        const float *B = p.B[A_MK ? which : sgm];
-        for (int k0 = kbeg; k0 < kend; k0 += SKC) {
-            // single-buffered in time (two LDS buffers avoid one barrier): load, store, barrier, multiply
-            load(A, B, k0);
-            store(buf);
-            __syncthreads();
-            const float *a_row = &As[buf][wave * 32 + l32][half * (SKC / 2)];
+    if (nslab > 0) {
+        constexpr int NG = SKC / 8;
+        load_global(0);
+        store_lds(0);
+        load_global(min(1, nslab - 1));
+        __syncthreads();
+        read_group(0, 0, 0);
+        for (int sl = 0; sl < nslab; ++sl) {
+            const int buf = sl & 1;
 #pragma unroll
-            for (int kk4 = 0; kk4 < SKC / 2; kk4 += 4) {
-                const float4 a4 = *reinterpret_cast<const float4 *>(a_row + kk4);
-                const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+            for (int g = 0; g < NG; ++g) {
+                if (g == NG - 1) {
+                    __syncthreads();
+                    read_group((g + 1) & 1, buf ^ 1, 0);   // after the last slab: unused
+                } else {
+                    read_group((g + 1) & 1, buf, 4 * (g + 1));
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int k = 2 * (kk4 + u) + half;
+                for (int u = 0; u < 4; ++u)
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
-                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], Bs[buf][k][32 * c + l32], acc[c], 0, 0, 0);
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_grp[g & 1][u], b_grp[g & 1][u][c], acc[c], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (g == NG / 2 - 1) {
+                    store_lds(buf ^ 1);
+                    load_global(min(sl + 2, nslab - 1));
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            buf ^= 1;
-            first = false;
         }
     }
-    (void)first;
+    __syncthreads();   // every wave is done with the operand buffers (also the unused last reads)
+
+    float *Ct = reinterpret_cast<float *>(smem);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            Ct[(wave * 32 + 8 * (r / 4) + 4 * half + (r % 4)) * CS + 32 * c + l32] = acc[c][r];
+    __syncthreads();
     float *C = p.C + (A_MK ? which * p.c_which_stride + split * p.c_split_stride : 0);
+    const int cq = tid & 31, r0 = tid >> 5;     // 32 float4 per row, 8 rows per pass
+    const int col = n0 + 4 * cq;
+    for (int pass0 = 0; pass0 < SBM / 8; pass0 += 4) {
+        v4f32 t[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const int col = n0 + 32 * c + l32;
-        if (col >= p.N) continue;
+        for (int u = 0; u < 4; ++u) t[u] = *reinterpret_cast<const v4f32 *>(Ct + (r0 + 8 * (pass0 + u)) * CS + 4 * cq);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wave * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            if (row < p.M) C[(size_t)row * p.ldc + col] = acc[c][r];
+        for (int u = 0; u < 4; ++u) {
+            const int row = m0 + r0 + 8 * (pass0 + u);
+            if (row < p.M && col < p.N) *reinterpret_cast<v4f32 *>(C + (size_t)row * p.ldc + col) = t[u];
         }
     }
 }
