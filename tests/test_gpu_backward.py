@@ -84,6 +84,8 @@ CASES = [
     ("ragged_bias", dict(T=777, n=64, k=3), True, 0),
     ("k1", dict(T=300, n=32, k=1), False, 0),
     ("saved_hidden", dict(T=777, n=64, k=3), True, 1),      # MOE_FLAG_SAVE_HIDDEN: no recomputation
+    ("cfg1_shape", dict(T=2048, n=256), False, 0),           # the other flat workloads' expert counts
+    ("cfg2_shape", dict(T=3000, n=2048), False, 1),          # (few rows per expert, many empty experts)
 ]
 
 
