@@ -118,7 +118,7 @@ def main():
         args.steps = 200 if args.config <= 1 else 20
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the MoE layer on ONE GPU (one GPU's share of the batch at its "
-                 "real shape); --gpus %d is not available. Sharding is described in DESIGN.md." % args.gpus)
+                 "real shape); --gpus %d is not available: nothing here spans GPUs." % args.gpus)
 
     import numpy as np
     import torch

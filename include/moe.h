@@ -44,9 +44,12 @@ enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
 
 /* Shape of one layer call.  Flat MoE: a = b = k_primary = k_secondary = 0.
  * Hierarchical MoE (Appendix B): a groups of b experts, n = a*b, k = k_primary*k_secondary.
- * Supported: d % 64 == 0, h % 128 == 0 for the bf16 experts; 1 <= k <= min(n, 8)
- * (per level when hierarchical); n <= 16384, at most 2048 experts per gating level;
- * T*k < 2^31. */
+ * Supported: d % 32 == 0; bf16 experts: d and h multiples of 128 (the paper's 512 x 1024 expert
+ * runs on a fused kernel that keeps the hidden layer on chip, other shapes on a plain two-GEMM
+ * path with the hidden layer in the workspace); fp32 experts: d and h multiples of 4;
+ * 1 <= k <= min(n, 8) (per level when hierarchical); n <= 16384, at most 2048 experts per
+ * gating level; T*k < 2^31.  moe_layer_backward: bf16 experts, d and h multiples of 256,
+ * n a multiple of 32. */
 typedef struct moe_config {
     int32_t T;             /* tokens in the batch */
     int32_t d;             /* model width: expert input and output size */
@@ -61,8 +64,9 @@ typedef struct moe_config {
     int32_t flags;         /* MOE_FLAG_* */
 } moe_config;
 
-/* moe_layer_forward also keeps the experts' hidden activations (bf16 [T*k, h], routed-row order)
- * in its workspace, and moe_layer_backward reads them instead of recomputing them.  The paper
+/* With MOE_FLAG_SAVE_HIDDEN moe_layer_forward also keeps the experts' hidden activations
+ * (bf16 [T*k, h], routed-row order) in its workspace, and moe_layer_backward reads them instead
+ * of recomputing them.  The paper
  * recomputes (Appendix D) to fit 12 GB devices; with 288 GB of HBM the 2*h bytes per routed row
  * are the cheaper side of the trade.  Without the flag the backward pass recomputes. */
 enum { MOE_FLAG_SAVE_HIDDEN = 1 };
@@ -82,7 +86,8 @@ size_t moe_route_workspace_bytes(const moe_config *cfg);
  * tile_expert and tile_row0 must hold moe_max_tiles() int32 each. */
 int32_t moe_tile_rows(const moe_config *cfg);
 int64_t moe_max_tiles(const moe_config *cfg);
-/* Bytes of scratch moe_expert_ffn needs (fp32 experts keep the hidden layer there; 0 for bf16). */
+/* Bytes of scratch moe_expert_ffn needs: the hidden layer of fp32 experts; the bf16 rows of x and
+ * the hidden layer of bf16 experts off the fused kernel's shape; 0 for 512 x 1024 bf16 experts. */
 size_t moe_ffn_workspace_bytes(const moe_config *cfg);
 /* Bytes of scratch moe_aux_losses needs. */
 size_t moe_aux_workspace_bytes(const moe_config *cfg);

@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void gg_rows_kernel(GGRows p) {
     if (tile >= *p.num_tiles) return;
     const int e = p.tile_expert[tile];
     const int row0 = p.tile_row0[tile];
-    const int rows = min(GBM, p.offsets[e + 1] - row0);
+    const int rows = min(p.tile_rows > 0 ? min(GBM, p.tile_rows) : GBM, p.offsets[e + 1] - row0);
     const int col0 = blockIdx.y * GBN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
     const uint16_t *Bw = p.B + (size_t)e * p.K * p.N;
@@ -631,6 +631,17 @@ __global__ __launch_bounds__(256) void dx_gather_add_kernel(float4 *__restrict__
     }
 }
 
+int launch_gg_rows128(const GGRows &p, bool b_kn, int epi, int64_t max_tiles, hipStream_t st) {
+    if (p.K % GKC || p.N % GBN) return MOE_EUNSUPPORTED;
+    if (max_tiles <= 0) return MOE_OK;
+    const dim3 grid((unsigned)max_tiles, (unsigned)(p.N / GBN));
+    if (b_kn && epi == EPI_RELU_BF16) hipLaunchKernelGGL((gg_rows_kernel<true, EPI_RELU_BF16>), grid, dim3(256), 0, st, p);
+    else if (b_kn && epi == EPI_F32) hipLaunchKernelGGL((gg_rows_kernel<true, EPI_F32>), grid, dim3(256), 0, st, p);
+    else return MOE_EUNSUPPORTED;
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
 static size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct BwdLayout {
@@ -741,8 +752,7 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     // experts (hidden layer recomputed)
     if (!saved_hidden) {   // Appendix D: recompute the hidden activations
         GGRows g1{xs, (const uint16_t *)W1, hid, nullptr, d, h, offsets, tile_expert, tile_row0, num_tiles};
-        hipLaunchKernelGGL((gg_rows_kernel<true, EPI_RELU_BF16>), dim3(max_tiles, h / GBN), dim3(256), 0, s, g1);
-        MOE_LAUNCH_CHECK();
+        if ((st = launch_gg_rows128(g1, true, EPI_RELU_BF16, max_tiles, s)) != MOE_OK) return st;
     }
     // the two compute-bound GEMMs of the expert backward run on 256-row tiles
     if ((st = launch_build_tiles(offsets, n, 256, tile_expert, tile_row0, num_tiles, s)) != MOE_OK) return st;

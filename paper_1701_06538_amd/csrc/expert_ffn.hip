@@ -524,10 +524,49 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(FfnArgs p, const float *A,
     }
 }
 
+// routed rows of x, rounded to bf16: xs[r] = bf16(x[perm[r] / k]); one wavefront per row
+__global__ __launch_bounds__(256) void gather_bf16_kernel(const float *__restrict__ x,
+                                                          const int32_t *__restrict__ perm, int64_t A,
+                                                          int d, int k, uint16_t *__restrict__ xs) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= A) return;
+    const int64_t t = perm[r] / k;
+    for (int c = lane * 4; c < d; c += 256) {
+        const float4 v = *reinterpret_cast<const float4 *>(x + t * d + c);
+        *reinterpret_cast<uint2 *>(xs + r * d + c) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
+    }
+}
+
+static size_t ffn_up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// bf16 experts of any shape with d and h multiples of 128: gather, then two grouped GEMMs with
+// the hidden layer (bf16) in the workspace -- the plain path beside the fused kernel, which is
+// built for the paper's 512 x 1024 experts.
+static int launch_expert_ffn_general(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles,
+                                     hipStream_t st) {
+    if (cfg->d % 128 || cfg->h % 128) return MOE_EUNSUPPORTED;
+    const int64_t A = (int64_t)cfg->T * cfg->k;
+    uint16_t *xs = reinterpret_cast<uint16_t *>(a.hidden);
+    uint16_t *hid = a.hid_out ? a.hid_out
+                              : reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(a.hidden) +
+                                                             ffn_up256((size_t)A * cfg->d * 2));
+    hipLaunchKernelGGL(gather_bf16_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, st, a.x, a.perm, A,
+                       cfg->d, cfg->k, xs);
+    MOE_LAUNCH_CHECK();
+    GGRows g1{xs, (const uint16_t *)a.W1, hid, nullptr, cfg->d, cfg->h, a.offsets, a.tile_expert,
+              a.tile_row0, a.num_tiles, kFfnTM};
+    int rc = launch_gg_rows128(g1, true, EPI_RELU_BF16, max_tiles, st);
+    if (rc != MOE_OK) return rc;
+    GGRows g2{hid, (const uint16_t *)a.W2, a.out, nullptr, cfg->h, cfg->d, a.offsets, a.tile_expert,
+              a.tile_row0, a.num_tiles, kFfnTM};
+    return launch_gg_rows128(g2, true, EPI_F32, max_tiles, st);
+}
+
 int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles, hipStream_t st) {
     if (max_tiles <= 0) return MOE_OK;
     if (cfg->expert_dtype == MOE_DTYPE_BF16) {
-        if (cfg->d != 512 || cfg->h != 1024) return MOE_EUNSUPPORTED;
+        if (cfg->d != 512 || cfg->h != 1024) return launch_expert_ffn_general(cfg, a, max_tiles, st);
         constexpr size_t lds = (size_t)kFfnTM * (1024 + 8) * sizeof(uint16_t);
         static bool attr_set = false;
         if (!attr_set) {
@@ -577,8 +616,12 @@ extern "C" int64_t moe_max_tiles(const moe_config *cfg) {
 
 extern "C" size_t moe_ffn_workspace_bytes(const moe_config *cfg) {
     if (check_config(cfg) != MOE_OK) return 0;
-    if (cfg->expert_dtype == MOE_DTYPE_BF16) return 0;
-    return (size_t)cfg->T * cfg->k * cfg->h * sizeof(float);
+    const size_t A = (size_t)cfg->T * cfg->k;
+    if (cfg->expert_dtype == MOE_DTYPE_BF16) {
+        if (cfg->d == 512 && cfg->h == 1024) return 0;                       // fused kernel
+        return ffn_up256(A * cfg->d * 2) + ffn_up256(A * cfg->h * 2);        // bf16 rows of x, hidden layer
+    }
+    return A * cfg->h * sizeof(float);
 }
 
 namespace moe {
@@ -594,8 +637,7 @@ int expert_ffn_with_hidden(const moe_config *cfg, const float *x, const int32_t 
         return MOE_EINVAL;
     if (!aligned16(x) || !aligned16(W1) || !aligned16(W2) || !aligned16(out_sorted))
         return MOE_EINVAL;
-    if (cfg->expert_dtype == MOE_DTYPE_F32 && (!workspace || !aligned16(workspace)))
-        return MOE_EINVAL;
+    if (moe_ffn_workspace_bytes(cfg) > 0 && (!workspace || !aligned16(workspace))) return MOE_EINVAL;
     FfnArgs a{};
     a.x = x; a.perm = perm; a.offsets = offsets;
     a.tile_expert = tile_expert; a.tile_row0 = tile_row0; a.num_tiles = num_tiles;

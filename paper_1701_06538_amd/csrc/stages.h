@@ -74,8 +74,11 @@ struct GGRows {
     const uint16_t *mask;  // [A_rows, N] (EPI_MASK_BF16)
     int K, N;
     const int32_t *offsets, *tile_expert, *tile_row0, *num_tiles;
+    int tile_rows;         // rows per tile of the table if smaller than the kernel's own tile (0: not)
 };
 
+// 128-row-tile kernel (K % 32 == 0, N % 128 == 0; B stored [K,N] if b_kn, else [N,K])
+int launch_gg_rows128(const GGRows &p, bool b_kn, int epi, int64_t max_tiles, hipStream_t st);
 int launch_gg_rows256(const GGRows &p, int epi, int64_t max_tiles, hipStream_t st);
 
 int launch_route(RouteArgs a, hipStream_t st);

@@ -187,6 +187,12 @@ def test_layer_bf16_small(api):
     _ffn_case(api, _shape(1, T=300, n=8, k=2), TOL_BF16, "bf16 T=300 n=8")
 
 
+def test_layer_bf16_other_expert_shapes(api):
+    """bf16 experts that are not 512 x 1024 take the plain path (gather, two grouped GEMMs)."""
+    _ffn_case(api, _shape(1, T=400, d=256, h=512, n=12, k=2), TOL_BF16, "bf16 d=256 h=512")
+    _ffn_case(api, _shape(1, T=300, d=512, h=2048, n=6, k=3), TOL_BF16, "bf16 d=512 h=2048")
+
+
 def test_layer_bf16_one_token_per_expert_tail(api):
     _ffn_case(api, _shape(1, T=65, n=70, k=1), TOL_BF16, "bf16 tiny tiles")
 
