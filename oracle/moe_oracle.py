@@ -17,6 +17,8 @@ Citations are to the paper's sections/equations:
   Eq.(6,7) Importance, L_importance = w CV(Importance)^2            Section 4
   Eq.(8-11) P(x,i), Load, L_load                                    Appendix A
   Eq.(12-14) hierarchical output, Importance_H, Load_H              Appendix B
+  Eq.(15-20) strictly balanced gating: softmax gate, batchwise mask,
+             threshold mask, L_batchwise                            Appendix F
 Readings of points the paper leaves open are listed next to the code that takes them.
 """
 import ctypes
@@ -48,6 +50,8 @@ def _lib():
         lib.oracle_noisy_logits_f32.argtypes = [f32p, f32p, f32p, f32p, ctypes.c_int64,
                                                 ctypes.c_int64, f32p, f32p, f32p]
         lib.oracle_noisy_logits_f32.restype = None
+        lib.oracle_softmax_rows_f32.argtypes = [f32p, ctypes.c_int64, ctypes.c_int64, f32p]
+        lib.oracle_softmax_rows_f32.restype = None
         _LIB = lib
     return _LIB
 
@@ -470,3 +474,72 @@ def flat_objective(x, W_g, W_noise, eps, bias, k, weight_fn, dy, w_importance, w
     ld, _ = load(lg, k, idx)
     return float((np.asarray(dy, np.float64) * y).sum()
                  + w_importance * cv_squared(imp) + w_load * cv_squared(ld))
+
+
+# --------------------------------------------------------------------------------------
+# Appendix F: strictly balanced gating
+# --------------------------------------------------------------------------------------
+
+def softmax_gate_f32(x, W_g, bias=None):
+    """Eq.(15): G_sigma(x) = Softmax(x W_g) over all n experts, in the pinned fp32 arithmetic
+    (logits by R1, softmax by R18 of gate_arith.c).  Returns (logits, G_sigma), both fp32."""
+    clean = dot_chain_f32(x, W_g)
+    if bias is not None:
+        clean = (clean + np.asarray(bias, np.float32)[None, :]).astype(np.float32)
+    clean, cp = _f32(clean)
+    out = np.empty_like(clean)
+    _lib().oracle_softmax_rows_f32(cp, clean.shape[0], clean.shape[1],
+                                   out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    return clean, out
+
+
+def batchwise_mask(X, m):
+    """Eq.(18): M_batchwise(X, m)[j, i] = 1 iff X[j, i] is among the m largest values of column i.
+    Reading: equal values -> the lower token index first.  Returns (mask [T,n] bool, tokens [n,m]
+    int32: the kept tokens of every expert in ascending order)."""
+    X = np.asarray(X)
+    T, n = X.shape
+    assert 0 <= m <= T
+    order = np.argsort(-X.astype(np.float64), axis=0, kind="stable")   # per column, ties: lower j first
+    kept = np.sort(order[:m, :], axis=0)                               # [m, n]
+    mask = np.zeros((T, n), dtype=bool)
+    mask[kept, np.arange(n)[None, :]] = True
+    return mask, np.ascontiguousarray(kept.T.astype(np.int32))
+
+
+def balanced_gates(X, mask):
+    """Eq.(16): G(x)_i = G_sigma(x)_i M_i / sum_j G_sigma(x)_j M_j.  Reading: a token that no
+    expert keeps has G(x) = 0 (the quotient would be 0/0).  Returns (G [T,n] float64, denom [T])."""
+    Xm = np.where(mask, np.asarray(X, np.float64), 0.0)
+    denom = Xm.sum(axis=1)
+    G = np.divide(Xm, denom[:, None], out=np.zeros_like(Xm), where=denom[:, None] > 0)
+    return G, denom
+
+
+def threshold_mask(X, thresholds):
+    """Eq.(19): M_threshold(x, T)_i = 1 iff x_i > T_i."""
+    return np.asarray(X, np.float64) > np.asarray(thresholds, np.float64)[None, :]
+
+
+def batchwise_loss(X, mask, thresholds):
+    """Eq.(20): L_batchwise = sum_j sum_i (M_threshold - M_batchwise)(X_ji - T_i)."""
+    X = np.asarray(X, np.float64)
+    Tv = np.asarray(thresholds, np.float64)[None, :]
+    diff = threshold_mask(X, thresholds).astype(np.float64) - mask.astype(np.float64)
+    return float((diff * (X - Tv)).sum())
+
+
+def balanced_output(x, G, weight_fn, token_subset=None):
+    """Eq.(1) with the gates of Eq.(16): y_t = sum_i G(x_t)_i E_i(x_t)."""
+    x64 = np.asarray(x, np.float64)
+    T, n = G.shape
+    toks = np.arange(T) if token_subset is None else np.asarray(token_subset)
+    y = np.zeros((len(toks), x64.shape[1]))
+    sub = G[toks]
+    for e in range(n):
+        rows = np.nonzero(sub[:, e] > 0)[0]
+        if rows.size == 0:
+            continue
+        W1, W2 = weight_fn(e)
+        y[rows] += sub[rows, e][:, None] * expert_ffn(x64[toks[rows]], W1, W2)
+    return y

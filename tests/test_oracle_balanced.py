@@ -1,0 +1,133 @@
+"""Pins for the oracle's strictly balanced gating (Appendix F, Eq.(15)-(20)): every function is
+checked against something other than itself -- a library softmax, brute-force counting on tiny
+inputs, closed forms, and the reductions to the dense softmax mixture the paper states."""
+import itertools
+
+import numpy as np
+import pytest
+from scipy.special import softmax
+
+from oracle import moe_oracle as O
+
+
+def _inputs(T, d, n, seed, scale=0.3):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    W = (scale * rng.standard_normal((d, n))).astype(np.float32)
+    return x, W
+
+
+def test_softmax_gate_matches_library_softmax():
+    x, W = _inputs(300, 64, 40, 1)
+    clean, X = O.softmax_gate_f32(x, W)
+    ref = softmax(x.astype(np.float64) @ W.astype(np.float64), axis=1)
+    # fp32 logits (error ~1e-6 relative on exp) and one rounding of the result
+    assert np.abs(X.astype(np.float64) - ref).max() <= 2e-6
+    assert np.abs(X.astype(np.float64).sum(axis=1) - 1.0).max() <= 5e-7
+    # the pinned arithmetic against the same formula in plain binary64 on the SAME fp32 logits
+    l = clean.astype(np.float64)
+    ref2 = np.exp(l - l.max(axis=1, keepdims=True))
+    ref2 /= ref2.sum(axis=1, keepdims=True)
+    ulp = np.spacing(ref2.astype(np.float32)).astype(np.float64)
+    assert (np.abs(X.astype(np.float64) - ref2) <= 1.0 * ulp).all()
+    assert (X == ref2.astype(np.float32)).mean() > 0.99
+
+
+def test_softmax_gate_large_spread_and_single_expert():
+    x = np.array([[100.0, 0.0], [-100.0, 0.0]], np.float32)
+    W = np.array([[1.0, 0.0, -1.0], [0.0, 0.0, 0.0]], np.float32)
+    _, X = O.softmax_gate_f32(x, W)
+    assert X[0, 0] == 1.0 and X[1, 2] == 1.0 and (X > 0).all()       # clipped tail stays positive
+    x1, W1 = _inputs(5, 8, 1, 2)
+    _, X1 = O.softmax_gate_f32(x1, W1)
+    assert (X1 == 1.0).all()
+
+
+def _brute_mask(X, m):
+    T, n = X.shape
+    mask = np.zeros((T, n), bool)
+    for i in range(n):
+        for j in range(T):
+            ahead = sum(1 for jj in range(T) if X[jj, i] > X[j, i] or (X[jj, i] == X[j, i] and jj < j))
+            mask[j, i] = ahead < m
+    return mask
+
+
+@pytest.mark.parametrize("T,n,m", [(6, 3, 2), (5, 2, 5), (7, 4, 0), (8, 3, 3)])
+def test_batchwise_mask_brute_force(T, n, m):
+    rng = np.random.default_rng(T * 100 + n)
+    X = rng.random((T, n)).astype(np.float32)
+    X[rng.integers(0, T, 3), rng.integers(0, n, 3)] = X[0, 0]          # ties, also across rows of a column
+    X[1, :] = X[0, :]
+    mask, toks = O.batchwise_mask(X, m)
+    assert np.array_equal(mask, _brute_mask(X, m))
+    assert (mask.sum(axis=0) == m).all()                               # every expert gets exactly m
+    assert toks.shape == (n, m)
+    for i in range(n):
+        assert np.array_equal(toks[i], np.nonzero(mask[:, i])[0])       # ascending token order
+
+
+def test_all_equal_column_keeps_lowest_tokens():
+    X = np.full((9, 2), 0.5, np.float32)
+    mask, toks = O.batchwise_mask(X, 4)
+    assert np.array_equal(toks, np.array([[0, 1, 2, 3], [0, 1, 2, 3]], np.int32))
+
+
+def test_gates_normalised_and_unkept_tokens_zero():
+    x, W = _inputs(64, 16, 8, 3)
+    _, X = O.softmax_gate_f32(x, W)
+    mask, _ = O.batchwise_mask(X, 8)          # m = k T / n with k = 1: some tokens get no expert
+    G, denom = O.balanced_gates(X, mask)
+    kept_any = mask.any(axis=1)
+    assert (~kept_any).any() and kept_any.any()
+    assert np.allclose(G[kept_any].sum(axis=1), 1.0, atol=1e-15)
+    assert (G[~kept_any] == 0).all() and (denom[~kept_any] == 0).all()
+    assert ((G > 0) == mask).all()
+    # Eq.(16) written out for one kept entry
+    j, i = np.argwhere(mask)[5]
+    assert G[j, i] == pytest.approx(float(X[j, i]) / float(X[j][mask[j]].astype(np.float64).sum()), rel=1e-15)
+
+
+def test_full_mask_is_the_dense_softmax_mixture():
+    """m = |X| (k = n): every entry is kept, G = G_sigma (Eq.(16) normalises a row that already
+    sums to one) and the layer is the dense mixture of Eq.(2), which the flat oracle also reaches
+    with k = n and no noise."""
+    T, d, n = 24, 16, 4
+    x, W = _inputs(T, d, n, 4)
+    clean, X = O.softmax_gate_f32(x, W)
+    mask, toks = O.batchwise_mask(X, T)
+    assert mask.all()
+    G, _ = O.balanced_gates(X, mask)
+    assert np.abs(G - X.astype(np.float64)).max() <= 2e-7
+    lg = O.noisy_logits_f32(x, W, np.zeros_like(W), None, None)
+    fw = O.gate_and_losses(lg, n, 0.0, 0.0)
+    dense = O.dense_gates(fw.idx, fw.gates, n)
+    assert np.abs(G - dense).max() <= 2e-7
+    rng = np.random.default_rng(5)
+    Ws = [(rng.standard_normal((d, 8)), rng.standard_normal((8, d))) for _ in range(n)]
+    y = O.balanced_output(x, G, lambda e: Ws[e])
+    y_flat = O.moe_output(x, fw.idx, fw.gates, lambda e: Ws[e], n)
+    assert np.abs(y - y_flat).max() <= 1e-5 * np.abs(y_flat).max()
+
+
+def test_threshold_mask_and_batchwise_loss_closed_forms():
+    X = np.array([[0.9, 0.2], [0.6, 0.7], [0.3, 0.5], [0.1, 0.4]], np.float32)
+    mask, _ = O.batchwise_mask(X, 2)           # column 0 keeps tokens 0,1; column 1 keeps 1,2
+    assert np.array_equal(mask, np.array([[1, 0], [1, 1], [0, 1], [0, 0]], bool))
+    # thresholds strictly between the m-th and (m+1)-th value of each column: masks agree, loss 0
+    Tsep = np.array([0.45, 0.45])
+    assert np.array_equal(O.threshold_mask(X, Tsep), mask)
+    assert O.batchwise_loss(X, mask, Tsep) == 0.0
+    # a too-low threshold lets extra entries through: each contributes (X - T) > 0
+    Tlow = np.array([0.25, 0.45])
+    extra = (float(X[2, 0]) - 0.25)
+    assert O.batchwise_loss(X, mask, Tlow) == pytest.approx(extra, rel=1e-12)
+    # a too-high threshold drops kept entries: each contributes (T - X) > 0
+    Thigh = np.array([0.45, 0.65])
+    assert O.batchwise_loss(X, mask, Thigh) == pytest.approx(0.65 - float(X[2, 1]), rel=1e-12)
+    # the loss is never negative
+    rng = np.random.default_rng(6)
+    Xr = rng.random((50, 6)).astype(np.float32)
+    mr, _ = O.batchwise_mask(Xr, 10)
+    for _ in range(20):
+        assert O.batchwise_loss(Xr, mr, rng.random(6)) >= 0.0
