@@ -236,6 +236,45 @@ int moe_layer_backward(const moe_config *cfg, const float *x, const float *W_g,
                        float *dW1, float *dW2, void *workspace, size_t workspace_bytes,
                        void *stream);
 
+/* ---- strictly balanced gating (Appendix F, Eq.(15)-(20)) ---------------------------------- */
+/*
+ * The gate that replaces noisy top-k where every expert must receive the same number of rows:
+ *   G_sigma = Softmax(x W_g [+ gate_bias])                                   Eq.(15)
+ *   M_batchwise keeps, for every expert, the m = k*T/n largest values of its column of G_sigma
+ *   (equal values: the lower token index first)                             Eq.(17),(18)
+ *   G(x)_i = G_sigma_i M_i / sum_j G_sigma_j M_j                             Eq.(16)
+ * and, given per-expert thresholds, the loss that fits the inference-time mask
+ * M_threshold = [G_sigma > T_i] to the batchwise one                        Eq.(19),(20)
+ *   L_batchwise = sum_{t,i} (M_threshold - M_batchwise)(G_sigma - T_i).
+ * cfg: flat (a == 0); k*T must be a multiple of n (else MOE_EINVAL); n <= 2048.
+ * The softmax is computed in a pinned arithmetic (fp32 logits by the sequential fma chain of
+ * moe_gate; exponentials, the sum and the division in binary64 by a fixed operation sequence;
+ * one rounding to fp32), since the mask compares its values across tokens.
+ * Device inputs: x [T,d], W_g [d,n], gate_bias [n] or NULL, thresholds [n] or NULL.
+ * Device outputs (overwritten):
+ *   gsigma [T,n] f32; tokens [n,m] i32, expert e's kept tokens in ascending order (its rows of the
+ *   dispatch, which needs no further sort); kept [T, ceil(n/32)] u32, bit (e & 31) of word e >> 5
+ *   set iff M_batchwise(t,e) = 1; denom [T] f32, the denominator of Eq.(16) (0 for a token no
+ *   expert kept: its output row is zero); loss_batchwise [1] f32, written only if thresholds != NULL.
+ * workspace: moe_balanced_workspace_bytes(), 16-byte aligned.  Asynchronous on `stream`.
+ */
+int64_t moe_balanced_rows_per_expert(const moe_config *cfg);   /* m, or -1 if cfg is not valid */
+size_t moe_balanced_workspace_bytes(const moe_config *cfg);
+int moe_gate_balanced(const moe_config *cfg, const float *x, const float *W_g,
+                      const float *gate_bias, const float *thresholds, float *gsigma,
+                      int32_t *tokens, uint32_t *kept, float *denom, float *loss_batchwise,
+                      void *workspace, size_t workspace_bytes, void *stream);
+/*
+ * The whole layer with that gate: moe_gate_balanced, the experts of Section 3.2 / Appendix C on
+ * their m rows each (W1 [n,d,h], W2 [n,h,d] as in moe_expert_ffn), and Eq.(1) with the gates of
+ * Eq.(16) -> y [T,d] f32, each token adding its kept experts in ascending expert order.
+ */
+int moe_layer_forward_balanced(const moe_config *cfg, const float *x, const float *W_g,
+                               const float *gate_bias, const float *thresholds, const void *W1,
+                               const void *W2, float *y, float *gsigma, int32_t *tokens,
+                               uint32_t *kept, float *denom, float *loss_batchwise,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
 /* Same as moe_layer_forward, with optional timing hooks: stage_events is a HOST array of 10
  * hipEvent_t (as void*), or NULL; entry 2i is recorded on `stream` just before stage i and entry
  * 2i+1 just after it, for i = 0 gate, 1 route, 2 experts, 3 combine, 4 losses.  NULL entries

@@ -86,6 +86,12 @@ _moe_backward_workspace_bytes = _proto("moe_backward_workspace_bytes", ctypes.c_
 _moe_layer_backward = _proto("moe_layer_backward", ctypes.c_int,
                              [_cfgp] + [_vp] * 16 + [ctypes.c_size_t, _vp])
 
+_moe_balanced_rows_per_expert = _proto("moe_balanced_rows_per_expert", ctypes.c_int64, [_cfgp])
+_moe_balanced_workspace_bytes = _proto("moe_balanced_workspace_bytes", ctypes.c_size_t, [_cfgp])
+_moe_gate_balanced = _proto("moe_gate_balanced", ctypes.c_int, [_cfgp] + [_vp] * 10 + [ctypes.c_size_t, _vp])
+_moe_layer_forward_balanced = _proto("moe_layer_forward_balanced", ctypes.c_int,
+                                     [_cfgp] + [_vp] * 13 + [ctypes.c_size_t, _vp])
+
 
 class MoeError(RuntimeError):
     def __init__(self, status):
@@ -264,3 +270,26 @@ def moe_layer_backward(cfg, x, W_g, W_noise, eps, W1, W2, dy, topk_idx, topk_gat
                                _ptr(W2), _ptr(dy), _ptr(topk_idx), _ptr(topk_gate), _ptr(fwd_workspace),
                                _ptr(dx), _ptr(dW_g), _ptr(dW_noise), _ptr(dW1), _ptr(dW2), _ptr(workspace),
                                _nbytes(workspace), _stream(stream)))
+
+
+def moe_balanced_rows_per_expert(cfg):
+    return _moe_balanced_rows_per_expert(ctypes.byref(cfg))
+
+
+def moe_balanced_workspace_bytes(cfg):
+    return _moe_balanced_workspace_bytes(ctypes.byref(cfg))
+
+
+def moe_gate_balanced(cfg, x, W_g, gate_bias, thresholds, gsigma, tokens, kept, denom, loss_batchwise,
+                      workspace, stream=None):
+    _check(_moe_gate_balanced(ctypes.byref(cfg), _ptr(x), _ptr(W_g), _ptr(gate_bias), _ptr(thresholds),
+                              _ptr(gsigma), _ptr(tokens), _ptr(kept), _ptr(denom), _ptr(loss_batchwise),
+                              _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def moe_layer_forward_balanced(cfg, x, W_g, gate_bias, thresholds, W1, W2, y, gsigma, tokens, kept, denom,
+                               loss_batchwise, workspace, stream=None):
+    _check(_moe_layer_forward_balanced(ctypes.byref(cfg), _ptr(x), _ptr(W_g), _ptr(gate_bias),
+                                       _ptr(thresholds), _ptr(W1), _ptr(W2), _ptr(y), _ptr(gsigma),
+                                       _ptr(tokens), _ptr(kept), _ptr(denom), _ptr(loss_batchwise),
+                                       _ptr(workspace), _nbytes(workspace), _stream(stream)))

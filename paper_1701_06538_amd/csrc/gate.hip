@@ -771,7 +771,8 @@ int launch_hier_compose(const int32_t *p_idx, const float *p_gate, const int32_t
 template <int RN>
 static void launch_logits_rn(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
     constexpr int KC = 32;
-    dim3 grid((unsigned)row_tiles, 2 * (unsigned)ceil_div(a.n, 32 * RN));
+    // without a noise matrix only the clean half of the grid exists
+    dim3 grid((unsigned)row_tiles, (a.Wn ? 2u : 1u) * (unsigned)ceil_div(a.n, 32 * RN));
     if (a.n % 4 == 0) hipLaunchKernelGGL((gate_logits_kernel<RN, true, KC>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((gate_logits_kernel<RN, false, KC>), grid, dim3(256), 0, st, a);
 }

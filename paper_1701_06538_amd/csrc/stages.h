@@ -7,7 +7,7 @@ namespace moe {
 
 struct LogitsArgs {
     const float *x;            // [*, d]
-    const float *Wg, *Wn;      // [groups][d][n]
+    const float *Wg, *Wn;      // [groups][d][n]; Wn null: clean logits only (sp is not written)
     const float *bias;         // [n] or null
     float *cleanb, *sp;        // [R][n]
     int64_t R;                 // rows

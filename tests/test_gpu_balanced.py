@@ -1,0 +1,207 @@
+"""GPU parity of strictly balanced gating (Appendix F, Eq.(15)-(20)) against the oracle: the softmax
+gate, the batchwise mask and the per-expert token lists bit for bit, the denominators and
+L_batchwise within 1e-5, the layer output within the bf16 tolerance."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import moe_workloads as W
+from oracle import moe_oracle as O
+from tests import gpu_harness as G
+
+pytestmark = pytest.mark.gpu
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-2
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def api():
+    assert torch.cuda.is_available()
+    from paper_1701_06538_amd import api as _api
+    return _api
+
+
+class BalancedRun:
+    def __init__(self, api, shape, x, W_g, bias, thresholds, W1=None, W2=None):
+        self.api = api
+        self.cfg = c = api.make_config(shape)
+        T, n, d = c.T, c.n, c.d
+        self.m = api.moe_balanced_rows_per_expert(c)
+        assert self.m == T * c.k // n
+        self.x, self.W_g = G.dev(x), G.dev(W_g)
+        self.bias = None if bias is None else G.dev(bias)
+        self.thr = None if thresholds is None else G.dev(thresholds)
+        self.W1, self.W2 = W1, W2
+        f32 = dict(dtype=torch.float32, device="cuda")
+        self.gsigma = torch.full((max(T, 1), n), float("nan"), **f32)
+        self.tokens = torch.full((n, max(self.m, 1)), -7, dtype=torch.int32, device="cuda")
+        self.kw = (n + 31) // 32
+        self.kept = torch.full((max(T, 1), self.kw), 0x5a5a5a5a, dtype=torch.int32, device="cuda")
+        self.denom = torch.full((max(T, 1),), float("nan"), **f32)
+        self.loss = torch.full((4,), float("nan"), **f32)
+        self.y = torch.full((max(T, 1), d), float("nan"), **f32)
+        self.ws = torch.empty(max(256, api.moe_balanced_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
+
+    def gate(self):
+        self.api.moe_gate_balanced(self.cfg, self.x, self.W_g, self.bias, self.thr, self.gsigma, self.tokens,
+                                   self.kept, self.denom, self.loss, self.ws)
+        torch.cuda.synchronize()
+
+    def layer(self):
+        self.api.moe_layer_forward_balanced(self.cfg, self.x, self.W_g, self.bias, self.thr, self.W1, self.W2,
+                                            self.y, self.gsigma, self.tokens, self.kept, self.denom,
+                                            self.loss, self.ws)
+        torch.cuda.synchronize()
+
+    def kept_mask(self):
+        words = self.kept.cpu().numpy().view(np.uint32)
+        T, n = self.cfg.T, self.cfg.n
+        bits = (words[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1
+        return bits.reshape(words.shape[0], -1)[:T, :n].astype(bool)
+
+
+def make_thresholds(X, m, seed):
+    """Per-expert thresholds near the m-th largest value of the column, so that the two masks of
+    Eq.(20) differ on a few percent of the entries."""
+    T = X.shape[0]
+    rng = np.random.default_rng(seed)
+    q = np.sort(X.astype(np.float64), axis=0)[max(T - m, 0) if m > 0 else T - 1]
+    return (q * (1.0 + 0.05 * rng.standard_normal(q.shape))).astype(np.float32)
+
+
+def check_gate(run, x, W_g, bias, thresholds):
+    c = run.cfg
+    T, n = c.T, c.n
+    _, X = O.softmax_gate_f32(x, W_g, bias)
+    got = run.gsigma.cpu().numpy()[:T]
+    assert np.array_equal(got.view(np.uint32), X.view(np.uint32)), \
+        "G_sigma differs in %d of %d values" % ((got != X).sum(), X.size)
+    mask, toks = O.batchwise_mask(X, run.m)
+    assert np.array_equal(run.tokens.cpu().numpy()[:, :run.m], toks)
+    assert np.array_equal(run.kept_mask(), mask)
+    assert (mask.sum(axis=0) == run.m).all()
+    Gm, denom = O.balanced_gates(X, mask)
+    d_got = run.denom.cpu().numpy()[:T].astype(np.float64)
+    assert np.abs(d_got - denom).max() <= TOL_F32 * max(denom.max(), 1e-30)
+    assert ((denom == 0) == (d_got == 0)).all()
+    if thresholds is not None:
+        ref = O.batchwise_loss(X, mask, thresholds)
+        gl = float(run.loss.cpu().numpy()[0])
+        assert abs(gl - ref) <= TOL_F32 * abs(ref) + 1e-9, (gl, ref)
+    return X, mask, Gm
+
+
+GATE_CASES = {
+    # name: (T, n, k, d, with_bias, gate_std)
+    "small": (256, 8, 2, 512, False, 0.02),
+    "ragged_n40": (1000, 40, 4, 512, True, 0.05),
+    "one_expert": (130, 1, 1, 512, False, 0.02),
+    "m_equals_T": (96, 4, 4, 512, False, 0.02),
+    "n320_d256": (640, 320, 4, 256, False, 0.05),
+    "cfg1_shape": (8192, 256, 4, 512, True, 0.02),
+    "n2048": (4096, 2048, 4, 512, False, 0.05),
+}
+
+
+@pytest.mark.parametrize("name", list(GATE_CASES))
+def test_gate_balanced(api, name):
+    T, n, k, d, with_bias, std = GATE_CASES[name]
+    say("gate_balanced", name)
+    shape = W.scaled_config(W.CONFIGS[1], T=T, n=n, k=k, d=d)
+    x, W_g, _, _, bias = G.flat_inputs(shape, with_bias=with_bias, gate_std=std)
+    _, X = O.softmax_gate_f32(x, W_g, bias)
+    thr = make_thresholds(X, T * k // n, 5)
+    run = BalancedRun(api, shape, x, W_g, bias, thr)
+    run.gate()
+    check_gate(run, x, W_g, bias, thr)
+
+
+def test_gate_balanced_ties(api):
+    """Duplicated tokens give equal values within every column: the lower token index is kept."""
+    say("gate_balanced ties")
+    shape = W.scaled_config(W.CONFIGS[1], T=512, n=16, k=2)
+    x, W_g, _, _, _ = G.flat_inputs(shape)
+    x[100:120] = x[5]
+    x[256:] = x[:256]                       # token t and t+256 are the same row
+    run = BalancedRun(api, shape, x, W_g, None, None)
+    run.gate()
+    X, mask, _ = check_gate(run, x, W_g, None, None)
+    assert (X[256:] == X[:256]).all()
+    assert not (mask[256:] & ~mask[:256]).any()      # the later copy is never kept without the earlier
+
+
+def test_gate_balanced_no_thresholds_leaves_loss(api):
+    say("gate_balanced no thresholds")
+    shape = W.scaled_config(W.CONFIGS[1], T=128, n=8, k=2)
+    x, W_g, _, _, _ = G.flat_inputs(shape)
+    run = BalancedRun(api, shape, x, W_g, None, None)
+    run.gate()
+    assert np.isnan(run.loss.cpu().numpy()[0])
+    check_gate(run, x, W_g, None, None)
+
+
+def test_balanced_rejects_unbalanced_batch(api):
+    shape = W.scaled_config(W.CONFIGS[1], T=100, n=8, k=3)      # 300 rows over 8 experts
+    cfg = api.make_config(shape)
+    assert api.moe_balanced_rows_per_expert(cfg) == -1
+    assert api.moe_balanced_workspace_bytes(cfg) == 0
+    t = torch.zeros(16, device="cuda")
+    with pytest.raises(api.MoeError) as e:
+        api.moe_gate_balanced(cfg, t, t, None, None, t, t, t, t, t, torch.zeros(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == api.MOE_EINVAL
+
+
+def test_balanced_empty_batch(api):
+    shape = W.scaled_config(W.CONFIGS[1], T=0, n=8, k=2)
+    x = np.zeros((0, shape.d), np.float32)
+    W_g = np.zeros((shape.d, shape.n), np.float32)
+    run = BalancedRun(api, shape, x, W_g, None, None)
+    run.gate()
+    assert run.m == 0
+
+
+LAYER_CASES = {
+    # name: (T, n, k, d, h, dtype, sampled tokens or None)
+    "small_bf16": (256, 8, 2, 512, 1024, "bf16", None),
+    "ragged_bf16": (1000, 40, 4, 512, 1024, "bf16", None),
+    "small_f32": (192, 8, 2, 512, 1024, "f32", None),
+    "d256_h512": (640, 16, 2, 256, 512, "bf16", None),
+    "cfg1_shape": (8192, 256, 4, 512, 1024, "bf16", 192),
+}
+
+
+@pytest.mark.parametrize("name", list(LAYER_CASES))
+def test_layer_balanced(api, name):
+    T, n, k, d, h, dtype, sample = LAYER_CASES[name]
+    say("layer_balanced", name)
+    shape = W.scaled_config(W.CONFIGS[1], T=T, n=n, k=k, d=d, h=h, expert_dtype=dtype)
+    x, W_g, _, _, bias = G.flat_inputs(shape, with_bias=True, gate_std=0.05)
+    W1, W2 = G.device_weights(shape)
+    if dtype == "bf16":
+        W1, W2 = W1.to(torch.bfloat16), W2.to(torch.bfloat16)
+    _, X = O.softmax_gate_f32(x, W_g, bias)
+    thr = make_thresholds(X, T * k // n, 9)
+    run = BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
+    run.layer()
+    _, mask, Gm = check_gate(run, x, W_g, bias, thr)
+    toks = None
+    if sample:
+        rng = np.random.default_rng(3)
+        unkept = np.nonzero(~mask.any(axis=1))[0][:8]
+        toks = np.unique(np.concatenate([rng.choice(T, sample, replace=False), unkept, [0, T - 1]]))
+    y_ref = O.balanced_output(x, Gm, G.oracle_weight_fn(shape), toks)
+    y = run.y.cpu().numpy()[:T]
+    y = y if toks is None else y[toks]
+    row, mx = G.rel_errors(y, y_ref)
+    say("  y row-rel %.2e max-rel %.2e, tokens without an expert: %d" % (row, mx, (~mask.any(axis=1)).sum()))
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    assert row <= tol and mx <= tol
+    zero_rows = ~(Gm > 0).any(axis=1) if toks is None else ~(Gm[toks] > 0).any(axis=1)
+    assert (y[zero_rows] == 0).all()
