@@ -102,12 +102,49 @@ def cpu_baseline(shape, sample_tokens):
                       "(gate, routing, experts in fp64, combine, losses), %.1f s" % (sample_tokens, shape.T, dt)}
 
 
+def cpu_baseline_balanced(shape, sample_tokens):
+    """The oracle's strictly balanced layer (Appendix F) on the first `sample_tokens` tokens taken as
+    a batch of their own (every expert keeps sample_tokens*k/n of them)."""
+    import numpy as np
+    import torch
+
+    import moe_workloads as W
+    from oracle import moe_oracle as O
+
+    x, W_g, _, _ = W.gate_inputs(shape)
+    x = x[:sample_tokens]
+    w1 = W.expert_weights_all(shape, 0, range(shape.n))
+    w2 = W.expert_weights_all(shape, 1, range(shape.n))
+
+    def wf(e):
+        return w1[e].to(torch.float64).numpy(), w2[e].to(torch.float64).numpy()
+
+    t0 = time.perf_counter()
+    _, X = O.softmax_gate_f32(x, W_g)
+    mask, _ = O.batchwise_mask(X, sample_tokens * shape.k // shape.n)
+    Gm, _ = O.balanced_gates(X, mask)
+    y = O.balanced_output(x, Gm, wf)
+    dt = time.perf_counter() - t0
+    assert np.isfinite(y).all()
+    try:
+        import threadpoolctl
+        threads = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "first %d of %d tokens of the same seeded workload as one balanced batch, full forward "
+                      "(softmax gate, batchwise mask, experts in fp64, combine), %.1f s" % (sample_tokens, shape.T, dt)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="index into the five workloads (default 1)")
+    ap.add_argument("--gating", choices=["noisy_topk", "balanced"], default="noisy_topk",
+                    help="balanced: the strictly balanced gate of Appendix F on the same workload "
+                         "(flat forward configs only)")
     ap.add_argument("--cpu-sample", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -131,7 +168,22 @@ def main():
     torch.cuda.set_device(0)
     shape = W.CONFIGS[args.config]
     hip = HipEvents()
-    if shape.hierarchical:
+    balanced = args.gating == "balanced"
+    if balanced:
+        if shape.hierarchical or shape.backward:
+            sys.exit("bench.py: --gating balanced runs the flat forward configs only")
+        x, W_g, _, _, bias = G.flat_inputs(shape, with_bias=shape.zipf_beta > 0)
+        W1, W2 = G.device_weights(shape, chunk=256)
+        thr = np.full((shape.n,), 1.0 / shape.n, np.float32)
+        run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
+        ws = run.ws
+
+        def step(events=None):
+            ev = None if events is None else [0, 0, events[4], events[5], 0]
+            api.moe_layer_forward_balanced_profiled(run.cfg, run.x, run.W_g, run.bias, run.thr, run.W1, run.W2,
+                                                    run.y, run.gsigma, run.tokens, run.kept, run.denom,
+                                                    run.loss, ws, ev)
+    elif shape.hierarchical:
         inputs = W.hier_gate_inputs(shape)
         W1, W2 = G.device_weights(shape, chunk=256)
         run = G.HierRun(api, shape, inputs, W1, W2)
@@ -195,7 +247,7 @@ def main():
 
     # second, untimed pass with every stage bracketed (diagnostics only)
     stage_ms = None
-    if not shape.hierarchical:
+    if not shape.hierarchical and not balanced:
         all_ev = [[hip.create() for _ in range(10)] for _ in range(min(K, 50))]
         for evs in all_ev:
             step(evs)
@@ -203,9 +255,21 @@ def main():
         stage_ms = {name: float(np.mean([hip.elapsed_ms(evs[2 * i], evs[2 * i + 1]) for evs in all_ev]))
                     for i, name in enumerate(STAGES)}
 
-    lay = run.api.moe_get_workspace_layout(run.cfg)
-    cnt = ws[lay.counts:lay.counts + 4 * shape.n].view(torch.int32).cpu().numpy()
-    used = int((cnt > 0).sum())
+    if balanced:
+        used = shape.n
+        bal_ev = [[hip.create() for _ in range(5)] for _ in range(min(K, 50))]
+        for evs in bal_ev:
+            api.moe_layer_forward_balanced_profiled(run.cfg, run.x, run.W_g, run.bias, run.thr, run.W1, run.W2,
+                                                    run.y, run.gsigma, run.tokens, run.kept, run.denom,
+                                                    run.loss, ws, evs)
+        torch.cuda.synchronize()
+        pairs = {"gate": (0, 1), "tiles": (1, 2), "experts": (2, 3), "combine": (3, 4)}
+        stage_ms = {name: float(np.mean([hip.elapsed_ms(evs[a], evs[b]) for evs in bal_ev]))
+                    for name, (a, b) in pairs.items()}
+    else:
+        lay = run.api.moe_get_workspace_layout(run.cfg)
+        cnt = ws[lay.counts:lay.counts + 4 * shape.n].view(torch.int32).cpu().numpy()
+        used = int((cnt > 0).sum())
     A = shape.T * shape.k
     wbytes = 2 if shape.expert_dtype == "bf16" else 4
     # algorithmic bytes of one expert-kernel launch: every used expert's two matrices once, the
@@ -224,7 +288,8 @@ def main():
         "dtype": "bf16" if shape.expert_dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": shape.name, "T": shape.T, "d": shape.d, "h": shape.h, "n": shape.n,
-                   "k": shape.k, "experts_used": used, "gating": "fp32 noisy top-k",
+                   "k": shape.k, "experts_used": used,
+                   "gating": "strictly balanced (softmax, batchwise mask)" if balanced else "fp32 noisy top-k",
                    "expert_math": "bf16 MFMA, fp32 accumulate" if wbytes == 2 else "fp32"},
         "roofline": {"kernel": "ffn_bf16_kernel" if wbytes == 2 else "ffn_f32_kernel",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -235,7 +300,11 @@ def main():
     }
     if shape.hierarchical:
         out["roofline"].update({"kernel": "moe_layer_forward_hier (whole call)", "note": "event pair brackets the whole layer"})
-    if not args.no_cpu_baseline and not shape.hierarchical and not shape.backward:
+    if balanced:
+        out["roofline"]["traffic"] = read_traffic("ffn_bf16_%s_balanced_pmc.txt" % shape.name.split("_")[0])
+    if not args.no_cpu_baseline and balanced:
+        out["cpu_baseline"] = cpu_baseline_balanced(shape, min(args.cpu_sample, shape.T))
+    elif not args.no_cpu_baseline and not shape.hierarchical and not shape.backward:
         out["cpu_baseline"] = cpu_baseline(shape, min(args.cpu_sample, shape.T))
     print(json.dumps(out))
 

@@ -274,6 +274,17 @@ int moe_layer_forward_balanced(const moe_config *cfg, const float *x, const floa
                                const void *W2, float *y, float *gsigma, int32_t *tokens,
                                uint32_t *kept, float *denom, float *loss_batchwise,
                                void *workspace, size_t workspace_bytes, void *stream);
+/* The same call with optional timing hooks: stage_events is a HOST array of 5 hipEvent_t (as
+ * void*), or NULL, recorded on `stream` before the gate [0], after it [1], before the expert
+ * kernels [2], after them [3] and after the combine [4].  NULL entries are skipped; the events
+ * belong to the caller. */
+int moe_layer_forward_balanced_profiled(const moe_config *cfg, const float *x, const float *W_g,
+                                        const float *gate_bias, const float *thresholds,
+                                        const void *W1, const void *W2, float *y, float *gsigma,
+                                        int32_t *tokens, uint32_t *kept, float *denom,
+                                        float *loss_batchwise, void *workspace,
+                                        size_t workspace_bytes, void *const *stage_events,
+                                        void *stream);
 
 /* Same as moe_layer_forward, with optional timing hooks: stage_events is a HOST array of 10
  * hipEvent_t (as void*), or NULL; entry 2i is recorded on `stream` just before stage i and entry

@@ -91,6 +91,8 @@ _moe_balanced_workspace_bytes = _proto("moe_balanced_workspace_bytes", ctypes.c_
 _moe_gate_balanced = _proto("moe_gate_balanced", ctypes.c_int, [_cfgp] + [_vp] * 10 + [ctypes.c_size_t, _vp])
 _moe_layer_forward_balanced = _proto("moe_layer_forward_balanced", ctypes.c_int,
                                      [_cfgp] + [_vp] * 13 + [ctypes.c_size_t, _vp])
+_moe_layer_forward_balanced_profiled = _proto("moe_layer_forward_balanced_profiled", ctypes.c_int,
+                                              [_cfgp] + [_vp] * 13 + [ctypes.c_size_t, ctypes.POINTER(_vp), _vp])
 
 
 class MoeError(RuntimeError):
@@ -293,3 +295,15 @@ def moe_layer_forward_balanced(cfg, x, W_g, gate_bias, thresholds, W1, W2, y, gs
                                        _ptr(thresholds), _ptr(W1), _ptr(W2), _ptr(y), _ptr(gsigma),
                                        _ptr(tokens), _ptr(kept), _ptr(denom), _ptr(loss_batchwise),
                                        _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def moe_layer_forward_balanced_profiled(cfg, x, W_g, gate_bias, thresholds, W1, W2, y, gsigma, tokens, kept,
+                                        denom, loss_batchwise, workspace, stage_events, stream=None):
+    """stage_events: None or a sequence of 5 hipEvent_t handles (ints, 0/None to skip)."""
+    ev = None
+    if stage_events is not None:
+        ev = (_vp * 5)(*[(e or None) for e in stage_events])
+    _check(_moe_layer_forward_balanced_profiled(ctypes.byref(cfg), _ptr(x), _ptr(W_g), _ptr(gate_bias),
+                                                _ptr(thresholds), _ptr(W1), _ptr(W2), _ptr(y), _ptr(gsigma),
+                                                _ptr(tokens), _ptr(kept), _ptr(denom), _ptr(loss_batchwise),
+                                                _ptr(workspace), _nbytes(workspace), ev, _stream(stream)))

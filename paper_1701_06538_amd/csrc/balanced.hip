@@ -47,10 +47,12 @@ __device__ __forceinline__ double exp_neg_spec(double a) {
 // added by the tree p_l += p_{l+off}, off = 32 .. 1, and lane 0's total divides every element.
 template <int NCH>
 __global__ __launch_bounds__(256) void softmax_rows_kernel(const float *__restrict__ logits, int64_t T,
-                                                           int n, float *__restrict__ out) {
+                                                           int n, float *__restrict__ out,
+                                                           uint32_t *__restrict__ kept, int kept_words) {
     const int lane = threadIdx.x & 63;
     const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
+    if (lane < kept_words) kept[t * kept_words + lane] = 0u;   // the selection ORs its bits into zeros
     const float *row = logits + t * n;
     float l[NCH];
     float mx = -INFINITY;
@@ -93,81 +95,161 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict_
         if (c0 + i < C && r0 + tx < R) out[(int64_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
 }
 
-__global__ void fill_u32_kernel(uint32_t *p, int64_t count, uint32_t v) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < count) p[i] = v;
-}
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 // Eq.(18) for one expert: column = Gt[e][0..T), all values positive, so the fp32 bit patterns
-// order like the values.  tokens[e][0..m) ascending; kept bit (t, e) set.
-__global__ __launch_bounds__(256) void select_columns_kernel(const float *__restrict__ Gt, int64_t T,
-                                                             int n, int m, int32_t *__restrict__ tokens,
-                                                             uint32_t *__restrict__ kept, int kept_words) {
+// order like the values.  Writes tokens[e][0..m) ascending, pos[t][e] = the token's place in that
+// list, and sets the kept bit (t, e); also the expert's share of the dispatch tables (m rows at
+// offset e*m, ceil(m/TM) row tiles).
+// A thread owns KPT consecutive tokens of a span of 256*KPT; a column that fits one span stays in
+// registers for all passes.
+template <int KPT, bool VEC>
+__global__ __launch_bounds__(256) void select_columns_kernel(
+    const float *__restrict__ Gt, int64_t T, int n, int m, int TM, int32_t *__restrict__ tokens,
+    uint32_t *__restrict__ kept, int kept_words, int32_t *__restrict__ pos, int32_t *__restrict__ counts,
+    int32_t *__restrict__ offsets, int32_t *__restrict__ tile_expert, int32_t *__restrict__ tile_row0,
+    int32_t *__restrict__ num_tiles) {
     __shared__ int hist[256];
+    __shared__ int wave_a[4], wave_b[4];
     __shared__ uint32_t sh_prefix;
-    __shared__ int sh_remaining;
-    __shared__ int wave_eq[4], wave_take[4], carry_eq, carry_take;
+    __shared__ int sh_remaining, carry_eq, carry_take;
     const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t *col = reinterpret_cast<const uint32_t *>(Gt) + (int64_t)e * T;
-    if (m <= 0) return;
+    const int tpe = (m + TM - 1) / TM;
     if (tid == 0) {
+        offsets[e] = e * m;
+        counts[e] = m;
+        if (e == n - 1) {
+            offsets[n] = n * m;
+            num_tiles[0] = n * tpe;
+        }
         sh_prefix = 0u;
         sh_remaining = m;
+        carry_eq = 0;
+        carry_take = 0;
     }
+    for (int j = tid; j < tpe; j += 256) {
+        tile_expert[e * tpe + j] = e;
+        tile_row0[e * tpe + j] = e * m + j * TM;
+    }
+    if (m <= 0) return;
+    const uint32_t *col = reinterpret_cast<const uint32_t *>(Gt) + (int64_t)e * T;
+    constexpr int64_t SPAN = 256 * KPT;
+    const bool single = T <= SPAN;
+    uint32_t kk[KPT];
+    auto load = [&](int64_t base) {
+        const int64_t t0 = base + (int64_t)tid * KPT;
+        if (VEC) {
+#pragma unroll
+            for (int q = 0; q < KPT / 4; ++q) {
+                const int64_t at = min(t0 + 4 * q, T - 4);    // clamped: tokens past T are masked below
+                const v4u v = *reinterpret_cast<const v4u *>(col + at);
+                kk[4 * q] = v.x; kk[4 * q + 1] = v.y; kk[4 * q + 2] = v.z; kk[4 * q + 3] = v.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < KPT; ++j) kk[j] = col[min(t0 + j, T - 1)];
+        }
+    };
+
     // the m-th largest key, one byte per pass from the top
     for (int pass = 3; pass >= 0; --pass) {
         hist[tid] = 0;
         __syncthreads();
         const uint32_t prefix = sh_prefix;
+        const int remaining = sh_remaining;
         const uint32_t hi_mask = pass == 3 ? 0u : (0xffffffffu << (8 * (pass + 1)));
-        for (int64_t t = tid; t < T; t += 256) {
-            const uint32_t key = col[t];
-            if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> (8 * pass)) & 255u], 1);
+        for (int64_t base = 0; base < T; base += SPAN) {
+            if (!single || pass == 3) load(base);
+            const int64_t t0 = base + (int64_t)tid * KPT;
+            int run_bin = -1, run = 0;                       // equal neighbours share one LDS atomic
+#pragma unroll
+            for (int j = 0; j < KPT; ++j) {
+                const bool in = t0 + j < T && (kk[j] & hi_mask) == prefix;
+                const int bin = (int)((kk[j] >> (8 * pass)) & 255u);
+                if (in) {
+                    if (bin == run_bin) {
+                        ++run;
+                    } else {
+                        if (run) atomicAdd(&hist[run_bin], run);
+                        run_bin = bin;
+                        run = 1;
+                    }
+                }
+            }
+            if (run) atomicAdd(&hist[run_bin], run);
         }
         __syncthreads();
-        if (tid == 0) {
-            int remaining = sh_remaining, b = 255;
-            while (b > 0 && hist[b] < remaining) {
-                remaining -= hist[b];
-                --b;
-            }
-            sh_prefix = prefix | ((uint32_t)b << (8 * pass));
-            sh_remaining = remaining;
+        // bin b with  #(bins above b) < remaining <= #(bins above b) + hist[b]
+        const int hcount = hist[tid];
+        int sfx = hcount;                                    // sum over lanes >= lane of this wave
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int v = __shfl_down(sfx, off);
+            if (lane + off < 64) sfx += v;
+        }
+        if (lane == 0) wave_a[wave] = sfx;
+        __syncthreads();
+        int above = sfx - hcount;
+        for (int w = wave + 1; w < 4; ++w) above += wave_a[w];
+        if (hcount > 0 && above < remaining && remaining <= above + hcount) {
+            sh_prefix = prefix | ((uint32_t)tid << (8 * pass));
+            sh_remaining = remaining - above;
         }
         __syncthreads();
     }
     const uint32_t vstar = sh_prefix;   // the m-th largest key
     const int ties = sh_remaining;      // how many tokens with that key are kept (lowest first)
-    if (tid == 0) {
-        carry_eq = 0;
-        carry_take = 0;
-    }
-    __syncthreads();
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    for (int64_t base = 0; base < T; base += 256) {
-        const int64_t t = base + tid;
-        const uint32_t key = t < T ? col[t] : 0u;
-        const bool gt = t < T && key > vstar;
-        const bool eq = t < T && key == vstar;
-        const unsigned long long beq = __ballot(eq);
-        if (lane == 0) wave_eq[wave] = __popcll(beq);
+
+    for (int64_t base = 0; base < T; base += SPAN) {
+        if (!single) load(base);
+        const int64_t t0 = base + (int64_t)tid * KPT;
+        int gt_cnt = 0, eq_cnt = 0;
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const bool valid = t0 + j < T;
+            gt_cnt += valid && kk[j] > vstar;
+            eq_cnt += valid && kk[j] == vstar;
+        }
+        // exclusive block scan of the equal counts, then of the kept counts they imply
+        int inc = eq_cnt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int v = __shfl_up(inc, off);
+            if (lane >= off) inc += v;
+        }
+        if (lane == 63) wave_a[wave] = inc;
         __syncthreads();
-        int eq_before = carry_eq + __popcll(beq & lt_mask);
-        for (int w = 0; w < wave; ++w) eq_before += wave_eq[w];
-        const bool take = gt || (eq && eq_before < ties);
-        const unsigned long long btk = __ballot(take);
-        if (lane == 0) wave_take[wave] = __popcll(btk);
+        int eq_before = carry_eq + inc - eq_cnt;
+        for (int w = 0; w < wave; ++w) eq_before += wave_a[w];
+        const int take_cnt = gt_cnt + min(eq_cnt, max(ties - eq_before, 0));
+        int inc2 = take_cnt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int v = __shfl_up(inc2, off);
+            if (lane >= off) inc2 += v;
+        }
+        if (lane == 63) wave_b[wave] = inc2;
         __syncthreads();
-        int pos = carry_take + __popcll(btk & lt_mask);
-        for (int w = 0; w < wave; ++w) pos += wave_take[w];
-        if (take) {
-            tokens[(int64_t)e * m + pos] = (int32_t)t;
-            atomicOr(&kept[t * kept_words + (e >> 5)], 1u << (e & 31));   // bitwise: order-independent
+        int at = carry_take + inc2 - take_cnt;
+        for (int w = 0; w < wave; ++w) at += wave_b[w];
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const int64_t t = t0 + j;
+            const bool valid = t < T;
+            const bool eq = valid && kk[j] == vstar;
+            const bool take = (valid && kk[j] > vstar) || (eq && eq_before < ties);
+            eq_before += eq;
+            if (take) {
+                tokens[(int64_t)e * m + at] = (int32_t)t;
+                pos[t * n + e] = at;
+                atomicOr(&kept[t * kept_words + (e >> 5)], 1u << (e & 31));   // bitwise: order-independent
+                ++at;
+            }
         }
         __syncthreads();
         if (tid == 0) {
-            carry_eq += wave_eq[0] + wave_eq[1] + wave_eq[2] + wave_eq[3];
-            carry_take += wave_take[0] + wave_take[1] + wave_take[2] + wave_take[3];
+            carry_eq += wave_a[0] + wave_a[1] + wave_a[2] + wave_a[3];
+            carry_take += wave_b[0] + wave_b[1] + wave_b[2] + wave_b[3];
         }
         __syncthreads();
     }
@@ -227,70 +309,82 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const double *__restr
     }
 }
 
-// offsets, counts and the row-tile table of n experts with exactly m rows each
-__global__ __launch_bounds__(256) void balanced_tiles_kernel(int n, int m, int TM, int32_t *counts,
-                                                             int32_t *offsets, int32_t *tile_expert,
-                                                             int32_t *tile_row0, int32_t *num_tiles) {
-    const int tpe = (m + TM - 1) / TM;
-    for (int e = blockIdx.x * 256 + threadIdx.x; e <= n; e += gridDim.x * 256) {
-        offsets[e] = e * m;
-        if (e < n) {
-            counts[e] = m;
-            for (int j = 0; j < tpe; ++j) {
-                tile_expert[e * tpe + j] = e;
-                tile_row0[e * tpe + j] = e * m + j * TM;
-            }
-        }
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0) num_tiles[0] = n * tpe;
-}
-
-// Eq.(1) with Eq.(16): one wavefront per token, kept experts in ascending order; the token's row
-// in expert e's list (sorted by token) by binary search.
+// Eq.(1) with Eq.(16): one wavefront per token.  The lanes first list the token's kept experts in
+// ascending order (row in the dispatch and gate value, 64 at a time in LDS), then every lane adds
+// the listed rows for its columns, so the row loads are independent of each other.
+// NC: float4 columns per lane (d/4 <= 64*NC).
+template <int NC>
 __global__ __launch_bounds__(256) void combine_balanced_kernel(const float4 *__restrict__ out_rows,
                                                                const float *__restrict__ G,
                                                                const uint32_t *__restrict__ kept,
+                                                               const int32_t *__restrict__ pos,
                                                                const float *__restrict__ denom,
-                                                               const int32_t *__restrict__ tokens,
                                                                int64_t T, int n, int m, int kept_words,
                                                                int d4, float4 *__restrict__ y) {
-    const int lane = threadIdx.x & 63;
-    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    __shared__ int l_row[4][64];
+    __shared__ float l_g[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t t = (int64_t)blockIdx.x * 4 + wave;
     if (t >= T) return;
     const float dn = denom[t];
-    for (int c0 = 0; c0 < d4; c0 += 64) {
-        const int c = c0 + lane;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int w = 0; w < kept_words; ++w) {
-            uint32_t bits = kept[t * kept_words + w];
-            while (bits) {
-                const int e = 32 * w + __ffs(bits) - 1;
-                bits &= bits - 1;
-                const int32_t *list = tokens + (int64_t)e * m;
-                int lo = 0, hi = m;                       // first position with list[pos] >= t
-                while (lo < hi) {
-                    const int mid = (lo + hi) >> 1;
-                    if (list[mid] < (int32_t)t) lo = mid + 1;
-                    else hi = mid;
-                }
-                const float g = G[t * n + e] / dn;
-                if (c < d4) {
-                    const float4 v = out_rows[((int64_t)e * m + lo) * d4 + c];
-                    acc.x = fmaf(g, v.x, acc.x);
-                    acc.y = fmaf(g, v.y, acc.y);
-                    acc.z = fmaf(g, v.z, acc.z);
-                    acc.w = fmaf(g, v.w, acc.w);
+    const uint32_t bits = lane < kept_words ? kept[t * kept_words + lane] : 0u;   // kept_words <= 64
+    const int cnt = __popc(bits);
+    int inc = cnt;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int v = __shfl_up(inc, off);
+        if (lane >= off) inc += v;
+    }
+    const int total = __shfl(inc, 63);
+    const int before = inc - cnt;
+    float4 acc[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) acc[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int r0 = 0; r0 < total; r0 += 64) {
+        int idx = before;
+        uint32_t b = bits;
+        while (b) {
+            const int e = 32 * lane + __ffs(b) - 1;
+            b &= b - 1;
+            if (idx >= r0 && idx < r0 + 64) {
+                l_row[wave][idx - r0] = e * m + pos[t * n + e];
+                l_g[wave][idx - r0] = G[t * n + e] / dn;
+            }
+            ++idx;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int here = min(64, total - r0);
+#pragma unroll 4
+        for (int j = 0; j < here; ++j) {
+            const int64_t row = l_row[wave][j];
+            const float g = l_g[wave][j];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const int col = lane + 64 * c;
+                if (col < d4) {
+                    const float4 v = out_rows[row * d4 + col];
+                    acc[c].x = fmaf(g, v.x, acc[c].x);
+                    acc[c].y = fmaf(g, v.y, acc[c].y);
+                    acc[c].z = fmaf(g, v.z, acc[c].z);
+                    acc[c].w = fmaf(g, v.w, acc[c].w);
                 }
             }
         }
-        if (c < d4) y[t * d4 + c] = acc;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+        if (lane + 64 * c < d4) y[t * d4 + lane + 64 * c] = acc[c];
 }
 
 static size_t b_up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct BalancedLayout {
-    size_t clean, Gt, loss_part, counts, offsets, tile_expert, tile_row0, num_tiles, out_rows, ffn_ws, total;
+    size_t clean, Gt, pos, loss_part, counts, offsets, tile_expert, tile_row0, num_tiles, out_rows, ffn_ws, total;
 };
 
 static int balanced_layout(const moe_config *cfg, BalancedLayout *L) {
@@ -303,6 +397,7 @@ static int balanced_layout(const moe_config *cfg, BalancedLayout *L) {
     };
     L->clean = take(T * n * 4);
     L->Gt = take(T * n * 4);
+    L->pos = take(T * n * 4);
     L->loss_part = take(((T + 3) / 4) * 8);
     L->counts = take(n * 4);
     L->offsets = take((n + 1) * 4);
@@ -325,6 +420,7 @@ static int balanced_check(const moe_config *cfg) {
     if (cfg->a != 0) return MOE_EINVAL;
     if (cfg->n > kMaxGateExperts) return MOE_EUNSUPPORTED;
     if (((int64_t)cfg->T * cfg->k) % cfg->n != 0) return MOE_EINVAL;   // m = k|X|/n must be whole
+    if (cfg->d > 2048) return MOE_EUNSUPPORTED;                        // combine: 8 float4 per lane
     return MOE_OK;
 }
 
@@ -369,16 +465,27 @@ extern "C" int moe_gate_balanced(const moe_config *cfg, const float *x, const fl
     la.R = T; la.d = cfg->d; la.n = n;
     if ((st = launch_gate_logits(la, ceil_div(T, kGateBM), s)) != MOE_OK) return st;
     const unsigned rb = (unsigned)ceil_div(T, 4);
-    if (n <= 256) hipLaunchKernelGGL(softmax_rows_kernel<4>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma);
-    else if (n <= 512) hipLaunchKernelGGL(softmax_rows_kernel<8>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma);
-    else if (n <= 1024) hipLaunchKernelGGL(softmax_rows_kernel<16>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma);
-    else hipLaunchKernelGGL(softmax_rows_kernel<32>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma);
+    if (n <= 256) hipLaunchKernelGGL(softmax_rows_kernel<4>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
+    else if (n <= 512) hipLaunchKernelGGL(softmax_rows_kernel<8>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
+    else if (n <= 1024) hipLaunchKernelGGL(softmax_rows_kernel<16>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
+    else hipLaunchKernelGGL(softmax_rows_kernel<32>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
     MOE_LAUNCH_CHECK();
     hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)ceil_div(T, 64), (unsigned)ceil_div(n, 64)), dim3(256), 0,
                        s, gsigma, T, n, Gt);
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)ceil_div(T * kw, 256)), dim3(256), 0, s, kept, T * kw, 0u);
     MOE_LAUNCH_CHECK();
-    hipLaunchKernelGGL(select_columns_kernel, dim3(n), dim3(256), 0, s, Gt, T, n, m, tokens, kept, kw);
+    {
+        int32_t *pos = (int32_t *)(ws + L.pos), *counts = (int32_t *)(ws + L.counts);
+        int32_t *offsets = (int32_t *)(ws + L.offsets), *tile_expert = (int32_t *)(ws + L.tile_expert);
+        int32_t *tile_row0 = (int32_t *)(ws + L.tile_row0), *num_tiles = (int32_t *)(ws + L.num_tiles);
+        const int TM = moe_tile_rows(cfg);
+#define MOE_SELECT(KPT, VEC)                                                                              \
+    hipLaunchKernelGGL((select_columns_kernel<KPT, VEC>), dim3(n), dim3(256), 0, s, Gt, T, n, m, TM, tokens, \
+                       kept, kw, pos, counts, offsets, tile_expert, tile_row0, num_tiles)
+        const bool vec = T % 4 == 0;
+        if (T <= 256 * 8) { if (vec) MOE_SELECT(8, true); else MOE_SELECT(8, false); }
+        else { if (vec) MOE_SELECT(32, true); else MOE_SELECT(32, false); }
+#undef MOE_SELECT
+    }
     MOE_LAUNCH_CHECK();
     double *lp = thresholds ? (double *)(ws + L.loss_part) : nullptr;
     hipLaunchKernelGGL(balanced_rows_kernel, dim3(rb), dim3(256), 0, s, gsigma, kept, thresholds, T, n, kw, denom, lp);
@@ -390,39 +497,70 @@ extern "C" int moe_gate_balanced(const moe_config *cfg, const float *x, const fl
     return MOE_OK;
 }
 
+static int record_event(void *const *ev, int i, hipStream_t s) {
+    if (!ev || !ev[i]) return MOE_OK;
+    MOE_HIP_TRY(hipEventRecord((hipEvent_t)ev[i], s));
+    return MOE_OK;
+}
+
+extern "C" int moe_layer_forward_balanced_profiled(const moe_config *cfg, const float *x, const float *W_g,
+                                                   const float *gate_bias, const float *thresholds,
+                                                   const void *W1, const void *W2, float *y, float *gsigma,
+                                                   int32_t *tokens, uint32_t *kept, float *denom,
+                                                   float *loss_batchwise, void *workspace,
+                                                   size_t workspace_bytes, void *const *ev, void *stream) {
+    hipStream_t s = (hipStream_t)stream;
+    int st = balanced_check(cfg);
+    if (st != MOE_OK) return st;
+    if (cfg->T > 0 && (!W1 || !W2 || !y || !aligned16(y) || !aligned16(W1) || !aligned16(W2))) return MOE_EINVAL;
+    if ((st = record_event(ev, 0, s)) != MOE_OK) return st;
+    st = moe_gate_balanced(cfg, x, W_g, gate_bias, thresholds, gsigma, tokens, kept, denom,
+                           loss_batchwise, workspace, workspace_bytes, stream);
+    if (st != MOE_OK) return st;
+    if ((st = record_event(ev, 1, s)) != MOE_OK) return st;
+    if (cfg->T == 0) return MOE_OK;
+    BalancedLayout L;
+    balanced_layout(cfg, &L);
+    char *ws = (char *)workspace;
+    const int64_t T = cfg->T;
+    const int n = cfg->n, m = (int)(T * cfg->k / n), kw = (n + 31) / 32;
+    int32_t *offsets = (int32_t *)(ws + L.offsets);
+    int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
+    int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
+    float *out_rows = (float *)(ws + L.out_rows);
+    // the experts see n*m rows, each row one token: the routed-row list IS the per-expert token list
+    moe_config f = *cfg;
+    f.T = (int32_t)((int64_t)n * m);
+    f.k = 1;
+    if ((st = record_event(ev, 2, s)) != MOE_OK) return st;
+    st = expert_ffn_with_hidden(&f, x, tokens, offsets, tile_expert, tile_row0, num_tiles, W1, W2, out_rows,
+                                ws + L.ffn_ws, nullptr, s);
+    if (st != MOE_OK) return st;
+    if ((st = record_event(ev, 3, s)) != MOE_OK) return st;
+    {
+        const int32_t *pos = (const int32_t *)(ws + L.pos);
+        const int d4 = cfg->d / 4;
+        const dim3 grid((unsigned)ceil_div(T, 4));
+#define MOE_COMBINE(NC)                                                                                    \
+    hipLaunchKernelGGL(combine_balanced_kernel<NC>, grid, dim3(256), 0, s, (const float4 *)out_rows, gsigma, \
+                       kept, pos, denom, T, n, m, kw, d4, (float4 *)y)
+        if (d4 <= 64) MOE_COMBINE(1);
+        else if (d4 <= 128) MOE_COMBINE(2);
+        else if (d4 <= 256) MOE_COMBINE(4);
+        else MOE_COMBINE(8);
+#undef MOE_COMBINE
+    }
+    MOE_LAUNCH_CHECK();
+    return record_event(ev, 4, s);
+}
+
 extern "C" int moe_layer_forward_balanced(const moe_config *cfg, const float *x, const float *W_g,
                                           const float *gate_bias, const float *thresholds,
                                           const void *W1, const void *W2, float *y, float *gsigma,
                                           int32_t *tokens, uint32_t *kept, float *denom,
                                           float *loss_batchwise, void *workspace,
                                           size_t workspace_bytes, void *stream) {
-    int st = moe_gate_balanced(cfg, x, W_g, gate_bias, thresholds, gsigma, tokens, kept, denom,
-                               loss_batchwise, workspace, workspace_bytes, stream);
-    if (st != MOE_OK) return st;
-    if (cfg->T == 0) return MOE_OK;
-    if (!W1 || !W2 || !y || !aligned16(y) || !aligned16(W1) || !aligned16(W2)) return MOE_EINVAL;
-    BalancedLayout L;
-    balanced_layout(cfg, &L);
-    hipStream_t s = (hipStream_t)stream;
-    char *ws = (char *)workspace;
-    const int64_t T = cfg->T;
-    const int n = cfg->n, m = (int)(T * cfg->k / n), kw = (n + 31) / 32;
-    int32_t *counts = (int32_t *)(ws + L.counts), *offsets = (int32_t *)(ws + L.offsets);
-    int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
-    int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
-    float *out_rows = (float *)(ws + L.out_rows);
-    hipLaunchKernelGGL(balanced_tiles_kernel, dim3((unsigned)ceil_div(n + 1, 256)), dim3(256), 0, s, n, m,
-                       moe_tile_rows(cfg), counts, offsets, tile_expert, tile_row0, num_tiles);
-    MOE_LAUNCH_CHECK();
-    // the experts see n*m rows, each row one token: the routed-row list IS the per-expert token list
-    moe_config f = *cfg;
-    f.T = (int32_t)((int64_t)n * m);
-    f.k = 1;
-    st = expert_ffn_with_hidden(&f, x, tokens, offsets, tile_expert, tile_row0, num_tiles, W1, W2, out_rows,
-                                ws + L.ffn_ws, nullptr, s);
-    if (st != MOE_OK) return st;
-    hipLaunchKernelGGL(combine_balanced_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s,
-                       (const float4 *)out_rows, gsigma, kept, denom, tokens, T, n, m, kw, cfg->d / 4, (float4 *)y);
-    MOE_LAUNCH_CHECK();
-    return MOE_OK;
+    return moe_layer_forward_balanced_profiled(cfg, x, W_g, gate_bias, thresholds, W1, W2, y, gsigma, tokens,
+                                               kept, denom, loss_batchwise, workspace, workspace_bytes,
+                                               nullptr, stream);
 }

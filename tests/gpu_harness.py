@@ -125,6 +125,47 @@ def rel_errors(got, ref):
     return row, mx
 
 
+class BalancedRun:
+    """One forward pass with strictly balanced gating (Appendix F) on the GPU."""
+
+    def __init__(self, api, shape, x, W_g, bias, thresholds, W1=None, W2=None):
+        self.api = api
+        self.cfg = c = api.make_config(shape)
+        T, n, d = c.T, c.n, c.d
+        self.m = api.moe_balanced_rows_per_expert(c)
+        assert self.m == T * c.k // n
+        self.x, self.W_g = dev(x), dev(W_g)
+        self.bias = None if bias is None else dev(bias)
+        self.thr = None if thresholds is None else dev(thresholds)
+        self.W1, self.W2 = W1, W2
+        f32 = dict(dtype=torch.float32, device="cuda")
+        self.gsigma = torch.full((max(T, 1), n), float("nan"), **f32)
+        self.tokens = torch.full((n, max(self.m, 1)), -7, dtype=torch.int32, device="cuda")
+        self.kw = (n + 31) // 32
+        self.kept = torch.full((max(T, 1), self.kw), 0x5a5a5a5a, dtype=torch.int32, device="cuda")
+        self.denom = torch.full((max(T, 1),), float("nan"), **f32)
+        self.loss = torch.full((4,), float("nan"), **f32)
+        self.y = torch.full((max(T, 1), d), float("nan"), **f32)
+        self.ws = torch.empty(max(256, api.moe_balanced_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
+
+    def gate(self):
+        self.api.moe_gate_balanced(self.cfg, self.x, self.W_g, self.bias, self.thr, self.gsigma, self.tokens,
+                                   self.kept, self.denom, self.loss, self.ws)
+        torch.cuda.synchronize()
+
+    def layer(self):
+        self.api.moe_layer_forward_balanced(self.cfg, self.x, self.W_g, self.bias, self.thr, self.W1, self.W2,
+                                            self.y, self.gsigma, self.tokens, self.kept, self.denom,
+                                            self.loss, self.ws)
+        torch.cuda.synchronize()
+
+    def kept_mask(self):
+        words = self.kept.cpu().numpy().view(np.uint32)
+        T, n = self.cfg.T, self.cfg.n
+        bits = (words[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1
+        return bits.reshape(words.shape[0], -1)[:T, :n].astype(bool)
+
+
 class HierRun:
     """One forward pass of the hierarchical layer on the GPU through the C ABI."""
 

@@ -28,45 +28,6 @@ def api():
     return _api
 
 
-class BalancedRun:
-    def __init__(self, api, shape, x, W_g, bias, thresholds, W1=None, W2=None):
-        self.api = api
-        self.cfg = c = api.make_config(shape)
-        T, n, d = c.T, c.n, c.d
-        self.m = api.moe_balanced_rows_per_expert(c)
-        assert self.m == T * c.k // n
-        self.x, self.W_g = G.dev(x), G.dev(W_g)
-        self.bias = None if bias is None else G.dev(bias)
-        self.thr = None if thresholds is None else G.dev(thresholds)
-        self.W1, self.W2 = W1, W2
-        f32 = dict(dtype=torch.float32, device="cuda")
-        self.gsigma = torch.full((max(T, 1), n), float("nan"), **f32)
-        self.tokens = torch.full((n, max(self.m, 1)), -7, dtype=torch.int32, device="cuda")
-        self.kw = (n + 31) // 32
-        self.kept = torch.full((max(T, 1), self.kw), 0x5a5a5a5a, dtype=torch.int32, device="cuda")
-        self.denom = torch.full((max(T, 1),), float("nan"), **f32)
-        self.loss = torch.full((4,), float("nan"), **f32)
-        self.y = torch.full((max(T, 1), d), float("nan"), **f32)
-        self.ws = torch.empty(max(256, api.moe_balanced_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
-
-    def gate(self):
-        self.api.moe_gate_balanced(self.cfg, self.x, self.W_g, self.bias, self.thr, self.gsigma, self.tokens,
-                                   self.kept, self.denom, self.loss, self.ws)
-        torch.cuda.synchronize()
-
-    def layer(self):
-        self.api.moe_layer_forward_balanced(self.cfg, self.x, self.W_g, self.bias, self.thr, self.W1, self.W2,
-                                            self.y, self.gsigma, self.tokens, self.kept, self.denom,
-                                            self.loss, self.ws)
-        torch.cuda.synchronize()
-
-    def kept_mask(self):
-        words = self.kept.cpu().numpy().view(np.uint32)
-        T, n = self.cfg.T, self.cfg.n
-        bits = (words[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1
-        return bits.reshape(words.shape[0], -1)[:T, :n].astype(bool)
-
-
 def make_thresholds(X, m, seed):
     """Per-expert thresholds near the m-th largest value of the column, so that the two masks of
     Eq.(20) differ on a few percent of the entries."""
@@ -118,7 +79,7 @@ def test_gate_balanced(api, name):
     x, W_g, _, _, bias = G.flat_inputs(shape, with_bias=with_bias, gate_std=std)
     _, X = O.softmax_gate_f32(x, W_g, bias)
     thr = make_thresholds(X, T * k // n, 5)
-    run = BalancedRun(api, shape, x, W_g, bias, thr)
+    run = G.BalancedRun(api, shape, x, W_g, bias, thr)
     run.gate()
     check_gate(run, x, W_g, bias, thr)
 
@@ -130,7 +91,7 @@ def test_gate_balanced_ties(api):
     x, W_g, _, _, _ = G.flat_inputs(shape)
     x[100:120] = x[5]
     x[256:] = x[:256]                       # token t and t+256 are the same row
-    run = BalancedRun(api, shape, x, W_g, None, None)
+    run = G.BalancedRun(api, shape, x, W_g, None, None)
     run.gate()
     X, mask, _ = check_gate(run, x, W_g, None, None)
     assert (X[256:] == X[:256]).all()
@@ -141,7 +102,7 @@ def test_gate_balanced_no_thresholds_leaves_loss(api):
     say("gate_balanced no thresholds")
     shape = W.scaled_config(W.CONFIGS[1], T=128, n=8, k=2)
     x, W_g, _, _, _ = G.flat_inputs(shape)
-    run = BalancedRun(api, shape, x, W_g, None, None)
+    run = G.BalancedRun(api, shape, x, W_g, None, None)
     run.gate()
     assert np.isnan(run.loss.cpu().numpy()[0])
     check_gate(run, x, W_g, None, None)
@@ -162,7 +123,7 @@ def test_balanced_empty_batch(api):
     shape = W.scaled_config(W.CONFIGS[1], T=0, n=8, k=2)
     x = np.zeros((0, shape.d), np.float32)
     W_g = np.zeros((shape.d, shape.n), np.float32)
-    run = BalancedRun(api, shape, x, W_g, None, None)
+    run = G.BalancedRun(api, shape, x, W_g, None, None)
     run.gate()
     assert run.m == 0
 
@@ -188,7 +149,7 @@ def test_layer_balanced(api, name):
         W1, W2 = W1.to(torch.bfloat16), W2.to(torch.bfloat16)
     _, X = O.softmax_gate_f32(x, W_g, bias)
     thr = make_thresholds(X, T * k // n, 9)
-    run = BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
+    run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
     run.layer()
     _, mask, Gm = check_gate(run, x, W_g, bias, thr)
     toks = None
