@@ -286,6 +286,29 @@ int moe_layer_forward_balanced_profiled(const moe_config *cfg, const float *x, c
                                         size_t workspace_bytes, void *const *stage_events,
                                         void *stream);
 
+/*
+ * Inference with the threshold mask (Appendix F, Eq.(19)): the layer with
+ * G(x)_i = G_sigma_i M_i / sum_j G_sigma_j M_j,  M_i = [G_sigma(x)_i > T_i],
+ * in place of the batchwise mask, so a token's experts no longer depend on the rest of the batch.
+ * The number of rows per expert is then data dependent: the caller sizes the dispatch with
+ * row_capacity (rows of expert input the workspace and `tokens` can hold, < 2^31; T*n < 2^31).
+ * cfg as for moe_gate_balanced, except that k only has to be valid (it sizes nothing).
+ * Device inputs as for moe_layer_forward_balanced; thresholds [n] f32 is required.
+ * Device outputs (overwritten): y [T,d]; gsigma [T,n]; counts [n] i32 = rows per expert;
+ * tokens [row_capacity] i32 = expert e's tokens in ascending order from the exclusive prefix sum of
+ * counts on; kept [T, ceil(n/32)] u32 = the mask as bits; denom [T] f32; rows_total [1] i32 = sum of
+ * counts.  If rows_total > row_capacity no expert runs and y is all zeros: the caller reads
+ * rows_total after the stream has finished and calls again with a larger capacity.
+ * workspace: moe_threshold_workspace_bytes(cfg, row_capacity).
+ */
+size_t moe_threshold_workspace_bytes(const moe_config *cfg, int64_t row_capacity);
+int moe_layer_forward_threshold(const moe_config *cfg, const float *x, const float *W_g,
+                                const float *gate_bias, const float *thresholds, const void *W1,
+                                const void *W2, int64_t row_capacity, float *y, float *gsigma,
+                                int32_t *counts, int32_t *tokens, uint32_t *kept, float *denom,
+                                int32_t *rows_total, void *workspace, size_t workspace_bytes,
+                                void *stream);
+
 /* Same as moe_layer_forward, with optional timing hooks: stage_events is a HOST array of 10
  * hipEvent_t (as void*), or NULL; entry 2i is recorded on `stream` just before stage i and entry
  * 2i+1 just after it, for i = 0 gate, 1 route, 2 experts, 3 combine, 4 losses.  NULL entries

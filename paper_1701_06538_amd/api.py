@@ -93,6 +93,9 @@ _moe_layer_forward_balanced = _proto("moe_layer_forward_balanced", ctypes.c_int,
                                      [_cfgp] + [_vp] * 13 + [ctypes.c_size_t, _vp])
 _moe_layer_forward_balanced_profiled = _proto("moe_layer_forward_balanced_profiled", ctypes.c_int,
                                               [_cfgp] + [_vp] * 13 + [ctypes.c_size_t, ctypes.POINTER(_vp), _vp])
+_moe_threshold_workspace_bytes = _proto("moe_threshold_workspace_bytes", ctypes.c_size_t, [_cfgp, ctypes.c_int64])
+_moe_layer_forward_threshold = _proto("moe_layer_forward_threshold", ctypes.c_int,
+                                      [_cfgp] + [_vp] * 6 + [ctypes.c_int64] + [_vp] * 8 + [ctypes.c_size_t, _vp])
 
 
 class MoeError(RuntimeError):
@@ -307,3 +310,15 @@ def moe_layer_forward_balanced_profiled(cfg, x, W_g, gate_bias, thresholds, W1, 
                                                 _ptr(thresholds), _ptr(W1), _ptr(W2), _ptr(y), _ptr(gsigma),
                                                 _ptr(tokens), _ptr(kept), _ptr(denom), _ptr(loss_batchwise),
                                                 _ptr(workspace), _nbytes(workspace), ev, _stream(stream)))
+
+
+def moe_threshold_workspace_bytes(cfg, row_capacity):
+    return _moe_threshold_workspace_bytes(ctypes.byref(cfg), row_capacity)
+
+
+def moe_layer_forward_threshold(cfg, x, W_g, gate_bias, thresholds, W1, W2, row_capacity, y, gsigma, counts,
+                                tokens, kept, denom, rows_total, workspace, stream=None):
+    _check(_moe_layer_forward_threshold(ctypes.byref(cfg), _ptr(x), _ptr(W_g), _ptr(gate_bias),
+                                        _ptr(thresholds), _ptr(W1), _ptr(W2), row_capacity, _ptr(y),
+                                        _ptr(gsigma), _ptr(counts), _ptr(tokens), _ptr(kept), _ptr(denom),
+                                        _ptr(rows_total), _ptr(workspace), _nbytes(workspace), _stream(stream)))

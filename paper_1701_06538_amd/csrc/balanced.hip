@@ -103,35 +103,48 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 // offset e*m, ceil(m/TM) row tiles).
 // A thread owns KPT consecutive tokens of a span of 256*KPT; a column that fits one span stays in
 // registers for all passes.
-template <int KPT, bool VEC>
+// MODE: SEL_BATCHWISE as above.  The threshold mask of Eq.(19) runs the same column walk twice:
+// SEL_THR_COUNT writes counts[e] = #{t : G_sigma(t,e) > T_e}; after the offsets are known,
+// SEL_THR_COMPACT writes the list at offsets[e] (rows at or past `capacity` are dropped; the caller
+// is told through the total row count).
+enum { SEL_BATCHWISE = 0, SEL_THR_COUNT = 1, SEL_THR_COMPACT = 2 };
+
+// key of a threshold: values are positive, so every threshold <= 0 keeps all of them
+__device__ __forceinline__ uint32_t threshold_key(float th) { return th > 0.f ? __float_as_uint(th) : 0u; }
+
+template <int KPT, bool VEC, int MODE>
 __global__ __launch_bounds__(256) void select_columns_kernel(
     const float *__restrict__ Gt, int64_t T, int n, int m, int TM, int32_t *__restrict__ tokens,
     uint32_t *__restrict__ kept, int kept_words, int32_t *__restrict__ pos, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ tile_expert, int32_t *__restrict__ tile_row0,
-    int32_t *__restrict__ num_tiles) {
+    int32_t *__restrict__ num_tiles, const float *__restrict__ thresholds, int64_t capacity) {
     __shared__ int hist[256];
     __shared__ int wave_a[4], wave_b[4];
     __shared__ uint32_t sh_prefix;
     __shared__ int sh_remaining, carry_eq, carry_take;
     const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tpe = (m + TM - 1) / TM;
     if (tid == 0) {
-        offsets[e] = e * m;
-        counts[e] = m;
-        if (e == n - 1) {
-            offsets[n] = n * m;
-            num_tiles[0] = n * tpe;
-        }
         sh_prefix = 0u;
         sh_remaining = m;
         carry_eq = 0;
         carry_take = 0;
     }
-    for (int j = tid; j < tpe; j += 256) {
-        tile_expert[e * tpe + j] = e;
-        tile_row0[e * tpe + j] = e * m + j * TM;
+    if (MODE == SEL_BATCHWISE) {
+        const int tpe = (m + TM - 1) / TM;
+        if (tid == 0) {
+            offsets[e] = e * m;
+            counts[e] = m;
+            if (e == n - 1) {
+                offsets[n] = n * m;
+                num_tiles[0] = n * tpe;
+            }
+        }
+        for (int j = tid; j < tpe; j += 256) {
+            tile_expert[e * tpe + j] = e;
+            tile_row0[e * tpe + j] = e * m + j * TM;
+        }
+        if (m <= 0) return;
     }
-    if (m <= 0) return;
     const uint32_t *col = reinterpret_cast<const uint32_t *>(Gt) + (int64_t)e * T;
     constexpr int64_t SPAN = 256 * KPT;
     const bool single = T <= SPAN;
@@ -151,8 +164,25 @@ __global__ __launch_bounds__(256) void select_columns_kernel(
         }
     };
 
+    if (MODE == SEL_THR_COUNT) {
+        const uint32_t tk = threshold_key(thresholds[e]);
+        int c = 0;
+        for (int64_t base = 0; base < T; base += SPAN) {
+            load(base);
+            const int64_t t0 = base + (int64_t)tid * KPT;
+#pragma unroll
+            for (int j = 0; j < KPT; ++j) c += t0 + j < T && kk[j] > tk;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) c += __shfl_xor(c, off);
+        if (lane == 0) wave_a[wave] = c;
+        __syncthreads();
+        if (tid == 0) counts[e] = wave_a[0] + wave_a[1] + wave_a[2] + wave_a[3];
+        return;
+    }
+
     // the m-th largest key, one byte per pass from the top
-    for (int pass = 3; pass >= 0; --pass) {
+    for (int pass = 3; MODE == SEL_BATCHWISE && pass >= 0; --pass) {
         hist[tid] = 0;
         __syncthreads();
         const uint32_t prefix = sh_prefix;
@@ -197,11 +227,14 @@ __global__ __launch_bounds__(256) void select_columns_kernel(
         }
         __syncthreads();
     }
-    const uint32_t vstar = sh_prefix;   // the m-th largest key
-    const int ties = sh_remaining;      // how many tokens with that key are kept (lowest first)
+    if (MODE == SEL_THR_COMPACT) __syncthreads();    // the carries written above
+    // batchwise: the m-th largest key and how many tokens with that key are kept (lowest first)
+    const uint32_t vstar = MODE == SEL_BATCHWISE ? sh_prefix : threshold_key(thresholds[e]);
+    const int ties = MODE == SEL_BATCHWISE ? sh_remaining : 0;
+    const int64_t row_base = MODE == SEL_BATCHWISE ? (int64_t)e * m : (int64_t)offsets[e];
 
     for (int64_t base = 0; base < T; base += SPAN) {
-        if (!single) load(base);
+        if (!single || MODE == SEL_THR_COMPACT) load(base);
         const int64_t t0 = base + (int64_t)tid * KPT;
         int gt_cnt = 0, eq_cnt = 0;
 #pragma unroll
@@ -240,7 +273,7 @@ __global__ __launch_bounds__(256) void select_columns_kernel(
             const bool take = (valid && kk[j] > vstar) || (eq && eq_before < ties);
             eq_before += eq;
             if (take) {
-                tokens[(int64_t)e * m + at] = (int32_t)t;
+                if (MODE == SEL_BATCHWISE || row_base + at < capacity) tokens[row_base + at] = (int32_t)t;
                 pos[t * n + e] = at;
                 atomicOr(&kept[t * kept_words + (e >> 5)], 1u << (e & 31));   // bitwise: order-independent
                 ++at;
@@ -252,6 +285,66 @@ __global__ __launch_bounds__(256) void select_columns_kernel(
             carry_take += wave_b[0] + wave_b[1] + wave_b[2] + wave_b[3];
         }
         __syncthreads();
+    }
+}
+
+// threshold path: offsets = exclusive scan of counts, the row-tile table, the total row count.
+// One workgroup; n <= 2048, eight experts per thread.  More rows than `capacity`: no tiles.
+__global__ __launch_bounds__(256) void threshold_offsets_kernel(const int32_t *__restrict__ counts, int n, int TM,
+                                                                int64_t capacity, int32_t *__restrict__ offsets,
+                                                                int32_t *__restrict__ tile_expert,
+                                                                int32_t *__restrict__ tile_row0,
+                                                                int32_t *__restrict__ num_tiles,
+                                                                int32_t *__restrict__ rows_total) {
+    __shared__ int wave_r[4], wave_t[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int c[8], rows = 0, tiles = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int e = tid * 8 + j;
+        c[j] = e < n ? counts[e] : 0;
+        rows += c[j];
+        tiles += (c[j] + TM - 1) / TM;
+    }
+    int ir = rows, it = tiles;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int vr = __shfl_up(ir, off), vt = __shfl_up(it, off);
+        if (lane >= off) {
+            ir += vr;
+            it += vt;
+        }
+    }
+    if (lane == 63) {
+        wave_r[wave] = ir;
+        wave_t[wave] = it;
+    }
+    __syncthreads();
+    int r = ir - rows, tl = it - tiles;
+    for (int w = 0; w < wave; ++w) {
+        r += wave_r[w];
+        tl += wave_t[w];
+    }
+    const int64_t total = (int64_t)wave_r[0] + wave_r[1] + wave_r[2] + wave_r[3];
+    const bool fits = total <= capacity;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int e = tid * 8 + j;
+        if (e < n) {
+            offsets[e] = r;
+            if (fits)
+                for (int q = 0; q * TM < c[j]; ++q) {
+                    tile_expert[tl] = e;
+                    tile_row0[tl] = r + q * TM;
+                    ++tl;
+                }
+            r += c[j];
+        }
+    }
+    if (tid == 0) {
+        offsets[n] = (int32_t)total;
+        rows_total[0] = (int32_t)total;
+        num_tiles[0] = fits ? wave_t[0] + wave_t[1] + wave_t[2] + wave_t[3] : 0;
     }
 }
 
@@ -319,13 +412,21 @@ __global__ __launch_bounds__(256) void combine_balanced_kernel(const float4 *__r
                                                                const uint32_t *__restrict__ kept,
                                                                const int32_t *__restrict__ pos,
                                                                const float *__restrict__ denom,
-                                                               int64_t T, int n, int m, int kept_words,
-                                                               int d4, float4 *__restrict__ y) {
+                                                               const int32_t *__restrict__ offsets,
+                                                               const int32_t *__restrict__ rows_total,
+                                                               int64_t capacity, int64_t T, int n,
+                                                               int kept_words, int d4, float4 *__restrict__ y) {
     __shared__ int l_row[4][64];
     __shared__ float l_g[4][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t t = (int64_t)blockIdx.x * 4 + wave;
     if (t >= T) return;
+    if (rows_total && rows_total[0] > capacity) {      // the dispatch did not fit: no rows were computed
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            if (lane + 64 * c < d4) y[t * d4 + lane + 64 * c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        return;
+    }
     const float dn = denom[t];
     const uint32_t bits = lane < kept_words ? kept[t * kept_words + lane] : 0u;   // kept_words <= 64
     const int cnt = __popc(bits);
@@ -347,7 +448,7 @@ __global__ __launch_bounds__(256) void combine_balanced_kernel(const float4 *__r
             const int e = 32 * lane + __ffs(b) - 1;
             b &= b - 1;
             if (idx >= r0 && idx < r0 + 64) {
-                l_row[wave][idx - r0] = e * m + pos[t * n + e];
+                l_row[wave][idx - r0] = offsets[e] + pos[t * n + e];
                 l_g[wave][idx - r0] = G[t * n + e] / dn;
             }
             ++idx;
@@ -387,8 +488,18 @@ struct BalancedLayout {
     size_t clean, Gt, pos, loss_part, counts, offsets, tile_expert, tile_row0, num_tiles, out_rows, ffn_ws, total;
 };
 
-static int balanced_layout(const moe_config *cfg, BalancedLayout *L) {
-    const size_t T = cfg->T, n = cfg->n, A = T * (size_t)cfg->k;
+// the experts see `rows` dispatched rows, each one token: a flat layer of `rows` tokens with k = 1
+static moe_config expert_view(const moe_config *cfg, int64_t rows) {
+    moe_config f = *cfg;
+    f.T = (int32_t)rows;
+    f.k = 1;
+    return f;
+}
+
+// rows: dispatched rows the buffers hold (k*T for the batchwise mask, the caller's capacity for
+// the threshold mask)
+static void balanced_layout(const moe_config *cfg, int64_t rows, BalancedLayout *L) {
+    const size_t T = cfg->T, n = cfg->n;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -401,26 +512,110 @@ static int balanced_layout(const moe_config *cfg, BalancedLayout *L) {
     L->loss_part = take(((T + 3) / 4) * 8);
     L->counts = take(n * 4);
     L->offsets = take((n + 1) * 4);
-    const size_t mt = (size_t)moe_max_tiles(cfg) + 8;
+    const moe_config f = expert_view(cfg, rows);
+    const size_t mt = (size_t)moe_max_tiles(&f) + 8;
     L->tile_expert = take(mt * 4);
     L->tile_row0 = take(mt * 4);
     L->num_tiles = take(16);
-    L->out_rows = take(A * cfg->d * 4);
-    moe_config f = *cfg;
-    f.T = (int32_t)A;
-    f.k = 1;
+    L->out_rows = take((size_t)rows * cfg->d * 4);
     L->ffn_ws = take(moe_ffn_workspace_bytes(&f));
     L->total = off;
-    return MOE_OK;
 }
 
-static int balanced_check(const moe_config *cfg) {
+static int softmax_gate_check(const moe_config *cfg) {
     int st = check_config(cfg);
     if (st != MOE_OK) return st;
     if (cfg->a != 0) return MOE_EINVAL;
     if (cfg->n > kMaxGateExperts) return MOE_EUNSUPPORTED;
-    if (((int64_t)cfg->T * cfg->k) % cfg->n != 0) return MOE_EINVAL;   // m = k|X|/n must be whole
     if (cfg->d > 2048) return MOE_EUNSUPPORTED;                        // combine: 8 float4 per lane
+    return MOE_OK;
+}
+
+static int balanced_check(const moe_config *cfg) {
+    int st = softmax_gate_check(cfg);
+    if (st != MOE_OK) return st;
+    if (((int64_t)cfg->T * cfg->k) % cfg->n != 0) return MOE_EINVAL;   // m = k|X|/n must be whole
+    return MOE_OK;
+}
+
+static int threshold_check(const moe_config *cfg, int64_t row_capacity) {
+    int st = softmax_gate_check(cfg);
+    if (st != MOE_OK) return st;
+    if (row_capacity < 0 || row_capacity >= ((int64_t)1 << 31)) return MOE_EINVAL;
+    if ((int64_t)cfg->T * cfg->n >= ((int64_t)1 << 31)) return MOE_EUNSUPPORTED;   // the row count is an int32
+    return MOE_OK;
+}
+
+// Eq.(15) and its transposed copy; clears the kept bits
+static int launch_softmax_gate(const moe_config *cfg, const float *x, const float *W_g, const float *gate_bias,
+                               float *clean, float *gsigma, float *Gt, uint32_t *kept, hipStream_t s) {
+    const int64_t T = cfg->T;
+    const int n = cfg->n, kw = (n + 31) / 32;
+    LogitsArgs la{};
+    la.x = x; la.Wg = W_g; la.Wn = nullptr; la.bias = gate_bias; la.cleanb = clean; la.sp = nullptr;
+    la.R = T; la.d = cfg->d; la.n = n;
+    int st = launch_gate_logits(la, ceil_div(T, kGateBM), s);
+    if (st != MOE_OK) return st;
+    const unsigned rb = (unsigned)ceil_div(T, 4);
+    if (n <= 256) hipLaunchKernelGGL(softmax_rows_kernel<4>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
+    else if (n <= 512) hipLaunchKernelGGL(softmax_rows_kernel<8>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
+    else if (n <= 1024) hipLaunchKernelGGL(softmax_rows_kernel<16>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
+    else hipLaunchKernelGGL(softmax_rows_kernel<32>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)ceil_div(T, 64), (unsigned)ceil_div(n, 64)), dim3(256), 0,
+                       s, gsigma, T, n, Gt);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+struct SelectArgs {
+    const float *Gt;
+    int64_t T;
+    int n, m, TM;
+    int32_t *tokens;
+    uint32_t *kept;
+    int32_t *pos, *counts, *offsets, *tile_expert, *tile_row0, *num_tiles;
+    const float *thresholds;
+    int64_t capacity;
+};
+
+template <int MODE>
+static int launch_select(const SelectArgs &a, hipStream_t s) {
+    const int kw = (a.n + 31) / 32;
+#define MOE_SELECT(KPT, VEC)                                                                                  \
+    hipLaunchKernelGGL((select_columns_kernel<KPT, VEC, MODE>), dim3(a.n), dim3(256), 0, s, a.Gt, a.T, a.n, a.m, \
+                       a.TM, a.tokens, a.kept, kw, a.pos, a.counts, a.offsets, a.tile_expert, a.tile_row0,     \
+                       a.num_tiles, a.thresholds, a.capacity)
+    const bool vec = a.T % 4 == 0;
+    if (a.T <= 256 * 8) { if (vec) MOE_SELECT(8, true); else MOE_SELECT(8, false); }
+    else { if (vec) MOE_SELECT(32, true); else MOE_SELECT(32, false); }
+#undef MOE_SELECT
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+static int launch_combine_balanced(const moe_config *cfg, const float *out_rows, const float *gsigma,
+                                   const uint32_t *kept, const int32_t *pos, const float *denom,
+                                   const int32_t *offsets, const int32_t *rows_total, int64_t capacity, float *y,
+                                   hipStream_t s) {
+    const int64_t T = cfg->T;
+    const int n = cfg->n, kw = (n + 31) / 32, d4 = cfg->d / 4;
+    const dim3 grid((unsigned)ceil_div(T, 4));
+#define MOE_COMBINE(NC)                                                                                    \
+    hipLaunchKernelGGL(combine_balanced_kernel<NC>, grid, dim3(256), 0, s, (const float4 *)out_rows, gsigma, \
+                       kept, pos, denom, offsets, rows_total, capacity, T, n, kw, d4, (float4 *)y)
+    if (d4 <= 64) MOE_COMBINE(1);
+    else if (d4 <= 128) MOE_COMBINE(2);
+    else if (d4 <= 256) MOE_COMBINE(4);
+    else MOE_COMBINE(8);
+#undef MOE_COMBINE
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+static int record_event(void *const *ev, int i, hipStream_t s) {
+    if (!ev || !ev[i]) return MOE_OK;
+    MOE_HIP_TRY(hipEventRecord((hipEvent_t)ev[i], s));
     return MOE_OK;
 }
 
@@ -436,7 +631,14 @@ extern "C" int64_t moe_balanced_rows_per_expert(const moe_config *cfg) {
 extern "C" size_t moe_balanced_workspace_bytes(const moe_config *cfg) {
     if (balanced_check(cfg) != MOE_OK) return 0;
     BalancedLayout L;
-    balanced_layout(cfg, &L);
+    balanced_layout(cfg, (int64_t)cfg->T * cfg->k, &L);
+    return L.total;
+}
+
+extern "C" size_t moe_threshold_workspace_bytes(const moe_config *cfg, int64_t row_capacity) {
+    if (threshold_check(cfg, row_capacity) != MOE_OK) return 0;
+    BalancedLayout L;
+    balanced_layout(cfg, row_capacity, &L);
     return L.total;
 }
 
@@ -449,7 +651,7 @@ extern "C" int moe_gate_balanced(const moe_config *cfg, const float *x, const fl
     if (!gsigma || !tokens || !kept || !denom || !workspace) return MOE_EINVAL;
     if (thresholds && !loss_batchwise) return MOE_EINVAL;
     BalancedLayout L;
-    balanced_layout(cfg, &L);
+    balanced_layout(cfg, (int64_t)cfg->T * cfg->k, &L);
     if (workspace_bytes < L.total) return MOE_EWORKSPACE;
     if (cfg->T == 0) return MOE_OK;
     if (!x || !W_g) return MOE_EINVAL;
@@ -457,36 +659,17 @@ extern "C" int moe_gate_balanced(const moe_config *cfg, const float *x, const fl
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
     const int64_t T = cfg->T;
-    const int n = cfg->n, m = (int)(T * cfg->k / n), kw = (n + 31) / 32;
-    float *clean = (float *)(ws + L.clean), *Gt = (float *)(ws + L.Gt);
-
-    LogitsArgs la{};
-    la.x = x; la.Wg = W_g; la.Wn = nullptr; la.bias = gate_bias; la.cleanb = clean; la.sp = nullptr;
-    la.R = T; la.d = cfg->d; la.n = n;
-    if ((st = launch_gate_logits(la, ceil_div(T, kGateBM), s)) != MOE_OK) return st;
+    const int n = cfg->n, kw = (n + 31) / 32;
+    float *Gt = (float *)(ws + L.Gt);
+    if ((st = launch_softmax_gate(cfg, x, W_g, gate_bias, (float *)(ws + L.clean), gsigma, Gt, kept, s)) != MOE_OK)
+        return st;
+    SelectArgs sa{};
+    sa.Gt = Gt; sa.T = T; sa.n = n; sa.m = (int)(T * cfg->k / n); sa.TM = moe_tile_rows(cfg);
+    sa.tokens = tokens; sa.kept = kept; sa.pos = (int32_t *)(ws + L.pos); sa.counts = (int32_t *)(ws + L.counts);
+    sa.offsets = (int32_t *)(ws + L.offsets); sa.tile_expert = (int32_t *)(ws + L.tile_expert);
+    sa.tile_row0 = (int32_t *)(ws + L.tile_row0); sa.num_tiles = (int32_t *)(ws + L.num_tiles);
+    if ((st = launch_select<SEL_BATCHWISE>(sa, s)) != MOE_OK) return st;
     const unsigned rb = (unsigned)ceil_div(T, 4);
-    if (n <= 256) hipLaunchKernelGGL(softmax_rows_kernel<4>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
-    else if (n <= 512) hipLaunchKernelGGL(softmax_rows_kernel<8>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
-    else if (n <= 1024) hipLaunchKernelGGL(softmax_rows_kernel<16>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
-    else hipLaunchKernelGGL(softmax_rows_kernel<32>, dim3(rb), dim3(256), 0, s, clean, T, n, gsigma, kept, kw);
-    MOE_LAUNCH_CHECK();
-    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)ceil_div(T, 64), (unsigned)ceil_div(n, 64)), dim3(256), 0,
-                       s, gsigma, T, n, Gt);
-    MOE_LAUNCH_CHECK();
-    {
-        int32_t *pos = (int32_t *)(ws + L.pos), *counts = (int32_t *)(ws + L.counts);
-        int32_t *offsets = (int32_t *)(ws + L.offsets), *tile_expert = (int32_t *)(ws + L.tile_expert);
-        int32_t *tile_row0 = (int32_t *)(ws + L.tile_row0), *num_tiles = (int32_t *)(ws + L.num_tiles);
-        const int TM = moe_tile_rows(cfg);
-#define MOE_SELECT(KPT, VEC)                                                                              \
-    hipLaunchKernelGGL((select_columns_kernel<KPT, VEC>), dim3(n), dim3(256), 0, s, Gt, T, n, m, TM, tokens, \
-                       kept, kw, pos, counts, offsets, tile_expert, tile_row0, num_tiles)
-        const bool vec = T % 4 == 0;
-        if (T <= 256 * 8) { if (vec) MOE_SELECT(8, true); else MOE_SELECT(8, false); }
-        else { if (vec) MOE_SELECT(32, true); else MOE_SELECT(32, false); }
-#undef MOE_SELECT
-    }
-    MOE_LAUNCH_CHECK();
     double *lp = thresholds ? (double *)(ws + L.loss_part) : nullptr;
     hipLaunchKernelGGL(balanced_rows_kernel, dim3(rb), dim3(256), 0, s, gsigma, kept, thresholds, T, n, kw, denom, lp);
     MOE_LAUNCH_CHECK();
@@ -494,12 +677,6 @@ extern "C" int moe_gate_balanced(const moe_config *cfg, const float *x, const fl
         hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, s, lp, (int64_t)rb, loss_batchwise);
         MOE_LAUNCH_CHECK();
     }
-    return MOE_OK;
-}
-
-static int record_event(void *const *ev, int i, hipStream_t s) {
-    if (!ev || !ev[i]) return MOE_OK;
-    MOE_HIP_TRY(hipEventRecord((hipEvent_t)ev[i], s));
     return MOE_OK;
 }
 
@@ -519,38 +696,23 @@ extern "C" int moe_layer_forward_balanced_profiled(const moe_config *cfg, const 
     if (st != MOE_OK) return st;
     if ((st = record_event(ev, 1, s)) != MOE_OK) return st;
     if (cfg->T == 0) return MOE_OK;
+    const int64_t rows = (int64_t)cfg->T * cfg->k;
     BalancedLayout L;
-    balanced_layout(cfg, &L);
+    balanced_layout(cfg, rows, &L);
     char *ws = (char *)workspace;
-    const int64_t T = cfg->T;
-    const int n = cfg->n, m = (int)(T * cfg->k / n), kw = (n + 31) / 32;
-    int32_t *offsets = (int32_t *)(ws + L.offsets);
-    int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
-    int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
+    const int32_t *offsets = (const int32_t *)(ws + L.offsets);
     float *out_rows = (float *)(ws + L.out_rows);
-    // the experts see n*m rows, each row one token: the routed-row list IS the per-expert token list
-    moe_config f = *cfg;
-    f.T = (int32_t)((int64_t)n * m);
-    f.k = 1;
+    // the routed-row list IS the per-expert token list
+    const moe_config f = expert_view(cfg, rows);
     if ((st = record_event(ev, 2, s)) != MOE_OK) return st;
-    st = expert_ffn_with_hidden(&f, x, tokens, offsets, tile_expert, tile_row0, num_tiles, W1, W2, out_rows,
-                                ws + L.ffn_ws, nullptr, s);
+    st = expert_ffn_with_hidden(&f, x, tokens, offsets, (const int32_t *)(ws + L.tile_expert),
+                                (const int32_t *)(ws + L.tile_row0), (const int32_t *)(ws + L.num_tiles), W1, W2,
+                                out_rows, ws + L.ffn_ws, nullptr, s);
     if (st != MOE_OK) return st;
     if ((st = record_event(ev, 3, s)) != MOE_OK) return st;
-    {
-        const int32_t *pos = (const int32_t *)(ws + L.pos);
-        const int d4 = cfg->d / 4;
-        const dim3 grid((unsigned)ceil_div(T, 4));
-#define MOE_COMBINE(NC)                                                                                    \
-    hipLaunchKernelGGL(combine_balanced_kernel<NC>, grid, dim3(256), 0, s, (const float4 *)out_rows, gsigma, \
-                       kept, pos, denom, T, n, m, kw, d4, (float4 *)y)
-        if (d4 <= 64) MOE_COMBINE(1);
-        else if (d4 <= 128) MOE_COMBINE(2);
-        else if (d4 <= 256) MOE_COMBINE(4);
-        else MOE_COMBINE(8);
-#undef MOE_COMBINE
-    }
-    MOE_LAUNCH_CHECK();
+    st = launch_combine_balanced(cfg, out_rows, gsigma, kept, (const int32_t *)(ws + L.pos), denom, offsets,
+                                 nullptr, rows, y, s);
+    if (st != MOE_OK) return st;
     return record_event(ev, 4, s);
 }
 
@@ -563,4 +725,54 @@ extern "C" int moe_layer_forward_balanced(const moe_config *cfg, const float *x,
     return moe_layer_forward_balanced_profiled(cfg, x, W_g, gate_bias, thresholds, W1, W2, y, gsigma, tokens,
                                                kept, denom, loss_batchwise, workspace, workspace_bytes,
                                                nullptr, stream);
+}
+
+extern "C" int moe_layer_forward_threshold(const moe_config *cfg, const float *x, const float *W_g,
+                                           const float *gate_bias, const float *thresholds, const void *W1,
+                                           const void *W2, int64_t row_capacity, float *y, float *gsigma,
+                                           int32_t *counts, int32_t *tokens, uint32_t *kept, float *denom,
+                                           int32_t *rows_total, void *workspace, size_t workspace_bytes,
+                                           void *stream) {
+    int st = threshold_check(cfg, row_capacity);
+    if (st != MOE_OK) return st;
+    if (!thresholds || !gsigma || !counts || !tokens || !kept || !denom || !rows_total || !workspace)
+        return MOE_EINVAL;
+    BalancedLayout L;
+    balanced_layout(cfg, row_capacity, &L);
+    if (workspace_bytes < L.total) return MOE_EWORKSPACE;
+    if (cfg->T == 0) return MOE_OK;
+    if (!x || !W_g || !W1 || !W2 || !y) return MOE_EINVAL;
+    if (!aligned16(x) || !aligned16(W_g) || !aligned16(gsigma) || !aligned16(workspace) || !aligned16(y) ||
+        !aligned16(W1) || !aligned16(W2))
+        return MOE_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const int64_t T = cfg->T;
+    const int n = cfg->n, kw = (n + 31) / 32;
+    float *Gt = (float *)(ws + L.Gt);
+    if ((st = launch_softmax_gate(cfg, x, W_g, gate_bias, (float *)(ws + L.clean), gsigma, Gt, kept, s)) != MOE_OK)
+        return st;
+    SelectArgs sa{};
+    sa.Gt = Gt; sa.T = T; sa.n = n; sa.m = 0; sa.TM = moe_tile_rows(cfg);
+    sa.tokens = tokens; sa.kept = kept; sa.pos = (int32_t *)(ws + L.pos); sa.counts = counts;
+    sa.offsets = (int32_t *)(ws + L.offsets); sa.tile_expert = (int32_t *)(ws + L.tile_expert);
+    sa.tile_row0 = (int32_t *)(ws + L.tile_row0); sa.num_tiles = (int32_t *)(ws + L.num_tiles);
+    sa.thresholds = thresholds; sa.capacity = row_capacity;
+    if ((st = launch_select<SEL_THR_COUNT>(sa, s)) != MOE_OK) return st;
+    hipLaunchKernelGGL(threshold_offsets_kernel, dim3(1), dim3(256), 0, s, counts, n, sa.TM, row_capacity, sa.offsets,
+                       sa.tile_expert, sa.tile_row0, sa.num_tiles, rows_total);
+    MOE_LAUNCH_CHECK();
+    if ((st = launch_select<SEL_THR_COMPACT>(sa, s)) != MOE_OK) return st;
+    hipLaunchKernelGGL(balanced_rows_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s, gsigma, kept,
+                       (const float *)nullptr, T, n, kw, denom, (double *)nullptr);
+    MOE_LAUNCH_CHECK();
+    float *out_rows = (float *)(ws + L.out_rows);
+    const moe_config f = expert_view(cfg, row_capacity);
+    if (row_capacity > 0) {
+        st = expert_ffn_with_hidden(&f, x, tokens, sa.offsets, sa.tile_expert, sa.tile_row0, sa.num_tiles, W1, W2,
+                                    out_rows, ws + L.ffn_ws, nullptr, s);
+        if (st != MOE_OK) return st;
+    }
+    return launch_combine_balanced(cfg, out_rows, gsigma, kept, sa.pos, denom, sa.offsets, rows_total, row_capacity,
+                                   y, s);
 }

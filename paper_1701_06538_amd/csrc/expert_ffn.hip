@@ -524,13 +524,15 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(FfnArgs p, const float *A,
     }
 }
 
-// routed rows of x, rounded to bf16: xs[r] = bf16(x[perm[r] / k]); one wavefront per row
+// routed rows of x, rounded to bf16: xs[r] = bf16(x[perm[r] / k]); one wavefront per row.
+// rows_used[0]: rows the dispatch really holds (offsets[n]); perm is defined only below it.
 __global__ __launch_bounds__(256) void gather_bf16_kernel(const float *__restrict__ x,
                                                           const int32_t *__restrict__ perm, int64_t A,
-                                                          int d, int k, uint16_t *__restrict__ xs) {
+                                                          const int32_t *__restrict__ rows_used, int d, int k,
+                                                          uint16_t *__restrict__ xs) {
     const int lane = threadIdx.x & 63;
     const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= A) return;
+    if (r >= A || r >= rows_used[0]) return;
     const int64_t t = perm[r] / k;
     for (int c = lane * 4; c < d; c += 256) {
         const float4 v = *reinterpret_cast<const float4 *>(x + t * d + c);
@@ -552,7 +554,7 @@ static int launch_expert_ffn_general(const moe_config *cfg, const FfnArgs &a, in
                               : reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(a.hidden) +
                                                              ffn_up256((size_t)A * cfg->d * 2));
     hipLaunchKernelGGL(gather_bf16_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, st, a.x, a.perm, A,
-                       cfg->d, cfg->k, xs);
+                       a.offsets + cfg->n, cfg->d, cfg->k, xs);
     MOE_LAUNCH_CHECK();
     GGRows g1{xs, (const uint16_t *)a.W1, hid, nullptr, cfg->d, cfg->h, a.offsets, a.tile_expert,
               a.tile_row0, a.num_tiles, kFfnTM};

@@ -166,3 +166,90 @@ def test_layer_balanced(api, name):
     assert row <= tol and mx <= tol
     zero_rows = ~(Gm > 0).any(axis=1) if toks is None else ~(Gm[toks] > 0).any(axis=1)
     assert (y[zero_rows] == 0).all()
+
+
+THRESHOLD_CASES = {
+    # name: (T, n, k, d, h, dtype, capacity factor, sampled tokens or None)
+    "small_bf16": (256, 8, 2, 512, 1024, "bf16", 2.0, None),
+    "ragged_bf16": (1001, 40, 4, 512, 1024, "bf16", 2.0, None),
+    "small_f32": (192, 8, 2, 512, 1024, "f32", 2.0, None),
+    "d256_h512": (640, 16, 2, 256, 512, "bf16", 1.5, None),
+    "n320": (900, 320, 4, 512, 1024, "bf16", 2.0, 128),
+    "cfg1_shape": (8192, 256, 4, 512, 1024, "bf16", 1.25, 192),
+}
+
+
+def run_threshold(api, shape, x, W_g, bias, thr, W1, W2, capacity):
+    cfg = api.make_config(shape)
+    T, n, d = cfg.T, cfg.n, cfg.d
+    f32 = dict(dtype=torch.float32, device="cuda")
+    i32 = dict(dtype=torch.int32, device="cuda")
+    out = dict(y=torch.full((T, d), float("nan"), **f32), gsigma=torch.full((T, n), float("nan"), **f32),
+               counts=torch.full((n,), -7, **i32), tokens=torch.full((max(capacity, 1),), -7, **i32),
+               kept=torch.full((T, (n + 31) // 32), 0x5a5a5a5a, **i32), denom=torch.full((T,), float("nan"), **f32),
+               rows_total=torch.full((4,), -7, **i32))
+    ws = torch.empty(max(256, api.moe_threshold_workspace_bytes(cfg, capacity)), dtype=torch.uint8, device="cuda")
+    api.moe_layer_forward_threshold(cfg, G.dev(x), G.dev(W_g), None if bias is None else G.dev(bias), G.dev(thr),
+                                    W1, W2, capacity, out["y"], out["gsigma"], out["counts"], out["tokens"],
+                                    out["kept"], out["denom"], out["rows_total"], ws)
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in out.items()}
+
+
+def unpack_kept(words, n):
+    words = words.view(np.uint32)
+    bits = (words[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1
+    return bits.reshape(words.shape[0], -1)[:, :n].astype(bool)
+
+
+@pytest.mark.parametrize("name", list(THRESHOLD_CASES))
+def test_layer_threshold(api, name):
+    T, n, k, d, h, dtype, cap, sample = THRESHOLD_CASES[name]
+    say("layer_threshold", name)
+    shape = W.scaled_config(W.CONFIGS[1], T=T, n=n, k=k, d=d, h=h, expert_dtype=dtype)
+    x, W_g, _, _, bias = G.flat_inputs(shape, with_bias=True, gate_std=0.05)
+    W1, W2 = G.device_weights(shape)
+    _, X = O.softmax_gate_f32(x, W_g, bias)
+    thr = make_thresholds(X, max(1, T * k // n), 11)
+    thr[0] = 0.0 if n > 1 else thr[0]          # an expert that keeps every token
+    if n > 2:
+        thr[2] = 2.0                            # and one that keeps none
+    mask = O.threshold_mask(X, thr)
+    capacity = int(cap * mask.sum()) + 7
+    got = run_threshold(api, shape, x, W_g, bias, thr, W1, W2, capacity)
+    assert np.array_equal(got["gsigma"].view(np.uint32), X.view(np.uint32))
+    assert np.array_equal(unpack_kept(got["kept"], n), mask)
+    assert np.array_equal(got["counts"], mask.sum(axis=0))
+    assert got["rows_total"][0] == mask.sum()
+    ref_list = np.concatenate([np.nonzero(mask[:, e])[0] for e in range(n)]).astype(np.int32)
+    assert np.array_equal(got["tokens"][:ref_list.size], ref_list)
+    Gm, denom = O.balanced_gates(X, mask)
+    assert np.abs(got["denom"].astype(np.float64) - denom).max() <= TOL_F32 * max(denom.max(), 1e-30)
+    toks = None
+    if sample:
+        rng = np.random.default_rng(4)
+        unkept = np.nonzero(~mask.any(axis=1))[0][:8]
+        toks = np.unique(np.concatenate([rng.choice(T, sample, replace=False), unkept, [0, T - 1]]))
+    y_ref = O.balanced_output(x, Gm, G.oracle_weight_fn(shape), toks)
+    y = got["y"] if toks is None else got["y"][toks]
+    row, mx = G.rel_errors(y, y_ref)
+    say("  rows %d (capacity %d), y row-rel %.2e max-rel %.2e" % (mask.sum(), capacity, row, mx))
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    assert row <= tol and mx <= tol
+
+
+def test_layer_threshold_capacity_exceeded(api):
+    """More kept rows than the caller made room for: the total is reported, no expert runs, y = 0."""
+    say("layer_threshold capacity exceeded")
+    shape = W.scaled_config(W.CONFIGS[1], T=512, n=16, k=2)
+    x, W_g, _, _, _ = G.flat_inputs(shape, gate_std=0.05)
+    W1, W2 = G.device_weights(shape)
+    _, X = O.softmax_gate_f32(x, W_g)
+    thr = make_thresholds(X, 64, 12)
+    mask = O.threshold_mask(X, thr)
+    capacity = int(mask.sum()) // 2
+    got = run_threshold(api, shape, x, W_g, None, thr, W1, W2, capacity)
+    assert got["rows_total"][0] == mask.sum() > capacity
+    assert np.array_equal(got["counts"], mask.sum(axis=0))
+    assert np.array_equal(unpack_kept(got["kept"], shape.n), mask)
+    assert not got["y"].any()
