@@ -8,7 +8,7 @@
 //   gg_rows_kernel       grouped bf16 MFMA GEMM over the ragged rows of each expert:
 //                          hid = relu(xs W1)            dz = (dout W2^T) * [hid > 0]
 //                          dxs = dz W1^T
-//   gg_wgrad_kernel      per expert, contraction over its rows: dW2 = hid^T dout, dW1 = xs^T dz
+//   gg_wgrad_kernel      (gemm_wgrad.hip) per expert, contraction over its rows: dW2 = hid^T dout, dW1 = xs^T dz
 //   gate_bwd_rows_kernel per token: softmax-over-k backward, d/dclean and d/draw of Eq.(9) incl.
 //                        the threshold element, H = clean + eps * sp
 //   sg_kernel            fp32 MFMA GEMMs of the gate: dW_g = x^T dclean, dW_noise = x^T draw
@@ -199,91 +199,6 @@ __global__ __launch_bounds__(256) void gg_rows_kernel(GGRows p) {
                     reinterpret_cast<float *>(p.C)[at] = v;
                 }
             }
-        }
-}
-
-struct GGWgrad {
-    const uint16_t *A;   // [A_rows, M] sorted rows
-    const uint16_t *B;   // [A_rows, N] sorted rows
-    float *C;            // [n, M, N]
-    int M, N;
-    const int32_t *offsets;
-};
-
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-// 8 rows x 8 columns of a row-major bf16 matrix held by one lane: rows r..r+7, columns c..c+7
-struct Blk8 {
-    uint32_t r[8][4];
-};
-__device__ __forceinline__ void load_blk8(Blk8 &f, const uint16_t *src, int64_t ld, int row, int row_end) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint4 v = (row + i) < row_end ? *reinterpret_cast<const uint4 *>(src + (int64_t)(row + i) * ld)
-                                            : make_uint4(0u, 0u, 0u, 0u);
-        f.r[i][0] = v.x; f.r[i][1] = v.y; f.r[i][2] = v.z; f.r[i][3] = v.w;
-    }
-}
-// column j of the block: 8 consecutive rows -> one MFMA operand (register transpose by byte permutes)
-__device__ __forceinline__ v8bf blk8_column(const Blk8 &f, int j) {
-    const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-    uint4 o;
-    o.x = __builtin_amdgcn_perm(f.r[1][j >> 1], f.r[0][j >> 1], sel);
-    o.y = __builtin_amdgcn_perm(f.r[3][j >> 1], f.r[2][j >> 1], sel);
-    o.z = __builtin_amdgcn_perm(f.r[5][j >> 1], f.r[4][j >> 1], sel);
-    o.w = __builtin_amdgcn_perm(f.r[7][j >> 1], f.r[6][j >> 1], sel);
-    return __builtin_bit_cast(v8bf, o);
-}
-
-// C_e[M, N] = sum over the rows r of expert e of A[r, :]^T B[r, :]   (both operands row-major in
-// the rows being contracted).  No LDS: lane (c = lane%16, g = lane/16) loads rows r0+8g..+7,
-// columns 8c..8c+7 of A and of B with 16-byte loads and transposes the 8x8 blocks in registers,
-// which yields v_mfma_f32_16x16x32_bf16 operands for 128 columns of A and 128 of B; one wave
-// accumulates a 128 x 128 block of C (64 MFMAs per 32 contracted rows), four waves a 256 x 256 one.
-__global__ __launch_bounds__(256) void gg_wgrad_kernel(GGWgrad p) {
-    const int e = blockIdx.z;
-    const int r0 = p.offsets[e], r1 = p.offsets[e + 1];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 15, g = lane >> 4;
-    const int m0 = blockIdx.x * 256 + (wave >> 1) * 128, n0 = blockIdx.y * 256 + (wave & 1) * 128;
-    v4f acc[8][8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
-    const uint16_t *Ab = p.A + m0 + 8 * c;
-    const uint16_t *Bb = p.B + n0 + 8 * c;
-    Blk8 fa, fb;
-    if (r0 < r1) {
-        load_blk8(fa, Ab, p.M, r0 + 8 * g, r1);
-        load_blk8(fb, Bb, p.N, r0 + 8 * g, r1);
-    }
-    for (int r = r0; r < r1; r += 32) {
-        v8bf a[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) a[j] = blk8_column(fa, j);
-        v8bf b[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) b[j] = blk8_column(fb, j);
-        if (r + 32 < r1) {   // next 32 rows while the matrix cores work on these
-            load_blk8(fa, Ab, p.M, r + 32 + 8 * g, r1);
-            load_blk8(fb, Bb, p.N, r + 32 + 8 * g, r1);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    float *Ce = p.C + (size_t)e * p.M * p.N;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int row = m0 + 8 * (4 * g + q) + i;
-            float *dst = Ce + (size_t)row * p.N + n0 + 8 * c;
-            *reinterpret_cast<float4 *>(dst) = make_float4(acc[i][0][q], acc[i][1][q], acc[i][2][q], acc[i][3][q]);
-            *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[i][4][q], acc[i][5][q], acc[i][6][q], acc[i][7][q]);
         }
 }
 
@@ -646,7 +561,7 @@ static size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct BwdLayout {
     size_t xs, dout, hid, dz, dxs, dgate, dclean, draw, gI, gL, wpart, tile_expert, tile_row0,
-        num_tiles, total;
+        num_tiles, order, total;
     int ksplit;
 };
 
@@ -680,6 +595,7 @@ static int bwd_layout(const moe_config *cfg, BwdLayout *L) {
     L->tile_expert = take(MT * 4);
     L->tile_row0 = take(MT * 4);
     L->num_tiles = take(16);
+    L->order = take(n * 4);
     L->total = off;
     return MOE_OK;
 }
@@ -759,12 +675,12 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     const int64_t max_tiles256 = ceil_div(A, 256) + n;
     GGRows g2{dout, (const uint16_t *)W2, dz, hid, d, h, offsets, tile_expert, tile_row0, num_tiles};
     if ((st = launch_gg_rows256(g2, EPI_MASK_BF16, max_tiles256, s)) != MOE_OK) return st;
-    GGWgrad w2{hid, dout, dW2, h, d, offsets};
-    hipLaunchKernelGGL(gg_wgrad_kernel, dim3(h / 256, d / 256, n), dim3(256), 0, s, w2);
-    MOE_LAUNCH_CHECK();
-    GGWgrad w1{xs, dz, dW1, d, h, offsets};
-    hipLaunchKernelGGL(gg_wgrad_kernel, dim3(d / 256, h / 256, n), dim3(256), 0, s, w1);
-    MOE_LAUNCH_CHECK();
+    int32_t *order = (int32_t *)(ws + L.order);
+    if ((st = launch_expert_order(offsets, n, order, s)) != MOE_OK) return st;
+    GGWgrad w2{hid, dout, dW2, h, d, offsets, order};
+    if ((st = launch_gg_wgrad(w2, n, s)) != MOE_OK) return st;
+    GGWgrad w1{xs, dz, dW1, d, h, offsets, order};
+    if ((st = launch_gg_wgrad(w1, n, s)) != MOE_OK) return st;
     GGRows g5{dz, (const uint16_t *)W1, dxs, nullptr, h, d, offsets, tile_expert, tile_row0, num_tiles};
     if ((st = launch_gg_rows256(g5, EPI_F32, max_tiles256, s)) != MOE_OK) return st;
 

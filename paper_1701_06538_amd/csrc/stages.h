@@ -81,6 +81,19 @@ struct GGRows {
 int launch_gg_rows128(const GGRows &p, bool b_kn, int epi, int64_t max_tiles, hipStream_t st);
 int launch_gg_rows256(const GGRows &p, int epi, int64_t max_tiles, hipStream_t st);
 
+// per-expert weight gradient C_e[M, N] = sum over the expert's rows of A[r, :]^T B[r, :]  (M, N % 256 == 0)
+struct GGWgrad {
+    const uint16_t *A;   // [A_rows, M] sorted rows
+    const uint16_t *B;   // [A_rows, N] sorted rows
+    float *C;            // [n, M, N]
+    int M, N;
+    const int32_t *offsets;
+    const int32_t *order;   // experts by decreasing row count (launch_expert_order)
+};
+int launch_gg_wgrad(const GGWgrad &p, int n, hipStream_t st);
+// order[r] = the expert with the r-th most rows (equal counts: lower index first)
+int launch_expert_order(const int32_t *offsets, int n, int32_t *order, hipStream_t st);
+
 int launch_route(RouteArgs a, hipStream_t st);
 bool route_is_small(int64_t A, int n);   // one-launch path (few experts, short assignment list)
 // fused launches of the layer forward (small path only; aux_ws as in aux_ws_bytes)
