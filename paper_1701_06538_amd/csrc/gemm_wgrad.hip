@@ -2,18 +2,19 @@
 //   C_e[M, N] = sum over the rows r of expert e of A[r, :]^T B[r, :]
 // (dW2 = hid^T dout, dW1 = xs^T dz), both operands row-major in the rows being contracted.
 //
-// One workgroup of four wavefronts owns a 256 x 256 block of C_e, each wavefront 128 x 128 as 8 x 8
-// v_mfma_f32_16x16x32_bf16 tiles (256 accumulators).  The matrix cores want, per lane, eight
+// One workgroup of eight wavefronts owns a 256 x 256 block of C_e, each wavefront 128 x 64 as 8 x 4
+// v_mfma_f32_16x16x32_bf16 tiles (128 accumulators, two wavefronts per SIMD so that one's LDS and
+// vector work runs under the other's matrix work).  The matrix cores want, per lane, eight
 // CONSECUTIVE contracted rows of one column, but memory has the columns consecutive.  So every
-// thread loads an 8 x 8 block (eight 16-byte loads), transposes it in registers with byte permutes
-// and writes eight 16-byte column pieces to LDS; the operand reads are then plain 16-byte LDS
-// reads, and the four wavefronts share one copy of both panels.  Column 8c+j of a 128-column
-// group is stored in slot 16j+c: with 80-byte slots both the writes and the reads are free of bank
-// conflicts, and a lane ends up holding eight consecutive columns of a row of C.
+// thread loads a 4 x 8 block (four 16-byte loads), transposes it in registers with byte permutes
+// and writes eight 8-byte column pieces to LDS; the operand reads are then plain 16-byte LDS
+// reads, and the wavefronts share one copy of both panels.  Column 8c+j of a 128-column group is
+// stored in slot 16j+c (80-byte slots), so that a lane ends up holding four consecutive columns of
+// a row of C and a pair of wavefronts fills whole 32-byte pieces.
 // Pipeline per 32 contracted rows: slab s is multiplied from LDS while slab s+1 is transposed into
-// the other LDS buffer (in the shadow of the matrix instructions) and slab s+2 is in flight from
-// memory; every load and store is
-// unconditional (clamped rows, selected values).
+// the other LDS buffer and slab s+2 is in flight from memory; every load and store is
+// unconditional (clamped rows, selected values).  The kernel is bound by LDS traffic: per slab the
+// wavefronts read 96 KB and write 32 KB, about 1700 cycles, against 1024 cycles of matrix work.
 #include "stages.h"
 
 namespace moe {
@@ -74,9 +75,8 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
     const int slot0 = (is_b ? WG_TILE : 0) + 128 * (cbl >> 4) + (cbl & 15);
     const int st_off = slot0 * WG_SLOT + 8 * sg;        // + 16*j*WG_SLOT for column j
 
-    // multiply role: wave (wm, wn) owns rows 128 wm .. +127 and columns 64 wn .. +63 of the block;
-    // its B columns are slots 16 j + c, j < 4, of the 128-column group wn / 2 when wn is even and
-    // slots 16 (j + 4) + c when it is odd
+    // multiply role: wave (wm, wn) owns rows 128 wm .. +127 of the block and, of the 128-column group
+    // wn / 2, the columns 8 c + 4 (wn % 2) + j, j < 4: slots 16 (4 (wn % 2) + j) + c
     const int c = lane & 15, g = lane >> 4;
     const int wm = wave >> 2, wn = wave & 3;
     const int a_off = (128 * wm + c) * WG_SLOT + 16 * g;                // + 16*i*WG_SLOT for tile i
