@@ -44,8 +44,13 @@ extern "C" int moe_debug_read_gg_timing(long long *host_out) {
 #define GG_STAMP(i) do { } while (0)
 #endif
 
-template <int EPI>
-__global__ __launch_bounds__(256, 1) void gg_rows256_kernel(GGRows p, int col_tiles) {
+// NW wavefronts: four own 128 x 128 each (256 accumulators, one wave per SIMD), eight own 128 x 64
+// (two waves per SIMD: one's LDS reads and stores run under the other's matrix work).
+template <int EPI, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void gg_rows256_kernel(GGRows p, int col_tiles) {
+    constexpr int NT = 64 * NW;          // threads
+    constexpr int NJ = NW == 8 ? 2 : 4;  // 32-column fragments per wave
+    constexpr int WCOLS = 32 * NJ;       // columns per wave
     constexpr int SLAB = RT * RLD * 2;                       // bytes of one operand slab
     __shared__ __attribute__((aligned(16))) char smem[4 * SLAB];
     uint16_t (*As)[RT][RLD] = reinterpret_cast<uint16_t (*)[RT][RLD]>(smem);
@@ -63,13 +68,14 @@ __global__ __launch_bounds__(256, 1) void gg_rows256_kernel(GGRows p, int col_ti
     const int rows = min(RT, p.offsets[e + 1] - row0);
     const int K = p.K, N = p.N;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, kg = lane >> 5;
+    const int wm = NW == 8 ? wave >> 2 : wave >> 1, wn = NW == 8 ? wave & 3 : wave & 1;
+    const int l32 = lane & 31, kg = lane >> 5;
     const uint16_t *Bw = p.B + (size_t)e * K * N;
 
     // staging: a slab row is CPR 16-byte chunks handled by CPR adjacent threads (with 64-deep
     // slabs that is one whole 128-byte line per row); SP passes of SR rows cover the tile.  Rows
     // past the end of the tile re-read its last row (never stored).
-    constexpr int CPR = RKC / 8, SR = 256 / CPR, SP = RT / SR;
+    constexpr int CPR = RKC / 8, SR = NT / CPR, SP = RT / SR;
     const int s_row = tid / CPR, s_kq = (tid % CPR) * 8;
     const uint16_t *a_src[SP], *b_src[SP];
 #pragma unroll
@@ -91,23 +97,23 @@ __global__ __launch_bounds__(256, 1) void gg_rows256_kernel(GGRows p, int col_ti
         for (int i = 0; i < SP; ++i) *reinterpret_cast<v4u *>(&Bs[buf][s_row + SR * i][s_kq]) = b_reg[i];
     };
 
-    v16f acc[4][4];
+    v16f acc[4][NJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     // operands of one k-step of 16: four row fragments, four column fragments
-    v4u a_op[2][4], b_op[2][4];
+    v4u a_op[2][4], b_op[2][NJ];
     auto read_ops = [&](int slot, int buf, int ks) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             a_op[slot][i] = *reinterpret_cast<const v4u *>(&As[buf][128 * wm + 32 * i + l32][16 * ks + 8 * kg]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            b_op[slot][j] = *reinterpret_cast<const v4u *>(&Bs[buf][128 * wn + 32 * j + l32][16 * ks + 8 * kg]);
+        for (int j = 0; j < NJ; ++j)
+            b_op[slot][j] = *reinterpret_cast<const v4u *>(&Bs[buf][WCOLS * wn + 32 * j + l32][16 * ks + 8 * kg]);
     };
 
     constexpr int NS = RKC / 16;   // k-steps per slab
@@ -132,7 +138,7 @@ __global__ __launch_bounds__(256, 1) void gg_rows256_kernel(GGRows p, int col_ti
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < NJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(   // the transposed product
                         __builtin_bit_cast(v8bf, b_op[ks & 1][j]), __builtin_bit_cast(v8bf, a_op[ks & 1][i]),
                         acc[i][j], 0, 0, 0);
@@ -155,11 +161,11 @@ __global__ __launch_bounds__(256, 1) void gg_rows256_kernel(GGRows p, int col_ti
     for (int i = 0; i < 4; ++i) {
         const int row = 128 * wm + 32 * i + l32;
         const bool live = row < rows;
-        const size_t at0 = (size_t)(row0 + min(row, rows - 1)) * N + col0 + 128 * wn + 4 * kg;
+        const size_t at0 = (size_t)(row0 + min(row, rows - 1)) * N + col0 + WCOLS * wn + 4 * kg;
         if (EPI == EPI_F32) {
             float *dst = reinterpret_cast<float *>(p.C) + at0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
                     if (live)
@@ -167,16 +173,16 @@ __global__ __launch_bounds__(256, 1) void gg_rows256_kernel(GGRows p, int col_ti
                             v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
         } else {
             uint16_t *dst = reinterpret_cast<uint16_t *>(p.C) + at0;
-            uint2 m[4][4];
-            if (EPI == EPI_MASK_BF16) {   // all sixteen loads of the strip in flight together
+            uint2 m[NJ][4];
+            if (EPI == EPI_MASK_BF16) {   // all loads of the strip in flight together
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < NJ; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         m[j][q] = *reinterpret_cast<const uint2 *>(p.mask + at0 + 32 * j + 8 * q);
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
@@ -209,9 +215,13 @@ int launch_gg_rows256(const GGRows &p, int epi, int64_t max_tiles, hipStream_t s
     const int col_tiles = p.N / RT;
     const unsigned grid = (unsigned)(ceil_div(max_tiles * col_tiles, 8) * 8);
     if (grid == 0) return MOE_OK;
-    if (epi == EPI_MASK_BF16) hipLaunchKernelGGL((gg_rows256_kernel<EPI_MASK_BF16>), dim3(grid), dim3(256), 0, st, p, col_tiles);
-    else if (epi == EPI_F32) hipLaunchKernelGGL((gg_rows256_kernel<EPI_F32>), dim3(grid), dim3(256), 0, st, p, col_tiles);
-    else hipLaunchKernelGGL((gg_rows256_kernel<EPI_RELU_BF16>), dim3(grid), dim3(256), 0, st, p, col_tiles);
+#ifndef GG_NW
+#define GG_NW 8
+#endif
+    constexpr int NW = GG_NW;
+    if (epi == EPI_MASK_BF16) hipLaunchKernelGGL((gg_rows256_kernel<EPI_MASK_BF16, NW>), dim3(grid), dim3(64 * NW), 0, st, p, col_tiles);
+    else if (epi == EPI_F32) hipLaunchKernelGGL((gg_rows256_kernel<EPI_F32, NW>), dim3(grid), dim3(64 * NW), 0, st, p, col_tiles);
+    else hipLaunchKernelGGL((gg_rows256_kernel<EPI_RELU_BF16, NW>), dim3(grid), dim3(64 * NW), 0, st, p, col_tiles);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
 }

@@ -51,8 +51,8 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
     const int n_experts = gridDim.x / per_e;
     int rank = blockIdx.x / per_e, sub = blockIdx.x % per_e;
     if (n_experts % 8 == 0) {
-        const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-        rank = (slot / per_e) * 8 + xcd;
+        const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, round = slot / per_e;
+        rank = round * 8 + ((round & 1) ? 7 - xcd : xcd);   // serpentine: the XCDs' row totals stay close
         sub = slot % per_e;
     }
     const int e = p.order[rank];
