@@ -543,3 +543,33 @@ def balanced_output(x, G, weight_fn, token_subset=None):
         W1, W2 = weight_fn(e)
         y[rows] += sub[rows, e][:, None] * expert_ffn(x64[toks[rows]], W1, W2)
     return y
+
+
+# --------------------------------------------------------------------------------------
+# Appendix D: Adam with beta1 = 0 and a factored second-moment estimator for the expert matrices
+# --------------------------------------------------------------------------------------
+
+def factored_adam_step(W, G, v_row, v_col, lr, beta2, eps, step):
+    """One update of a parameter matrix W [R, C] with gradient G (Appendix D, "Optimizer").
+
+    No first-moment estimator (beta1 = 0: the update direction is G itself).  Instead of the
+    full matrix V of second-moment estimates only its row-wise and column-wise averages are
+    kept: v_row [R], v_col [C].  V obeys V <- beta2 V + (1 - beta2) G*G elementwise, and
+    averaging is linear, so the two vectors obey the same recursion with the row and column
+    averages of G*G.  At the step the matrix of estimators is taken as
+        Vhat[r, c] = v_row[r] * v_col[c] / mean(v_row)        (mean(v_row) == mean(v_col)).
+    Readings where the paper is silent: Adam's bias correction Vhat / (1 - beta2**step) with
+    step counted from 1, and its epsilon outside the square root,
+        W <- W - lr * G / (sqrt(Vhat / (1 - beta2**step)) + eps);
+    an all-zero gradient history (mean(v_row) == 0) leaves W unchanged.
+    Returns (W_new, v_row_new, v_col_new), all float64."""
+    W = np.asarray(W, np.float64)
+    G = np.asarray(G, np.float64)
+    g2 = G * G
+    v_row = beta2 * np.asarray(v_row, np.float64) + (1.0 - beta2) * g2.mean(axis=1)
+    v_col = beta2 * np.asarray(v_col, np.float64) + (1.0 - beta2) * g2.mean(axis=0)
+    m = v_row.mean()
+    if m == 0.0:
+        return W.copy(), v_row, v_col
+    vhat = np.outer(v_row, v_col) / m / (1.0 - beta2 ** step)
+    return W - lr * G / (np.sqrt(vhat) + eps), v_row, v_col
