@@ -309,6 +309,33 @@ int moe_layer_forward_threshold(const moe_config *cfg, const float *x, const flo
                                 int32_t *rows_total, void *workspace, size_t workspace_bytes,
                                 void *stream);
 
+/* ---- optimiser step for the expert matrices (Appendix D, "Optimizer") --------------------- */
+/*
+ * Adam without a first-moment estimator (beta1 = 0) and with a FACTORED second-moment estimator:
+ * for a parameter matrix [R, C] only the row-wise and column-wise averages v_row [R], v_col [C] of
+ * the second-moment matrix are kept; both follow v <- beta2 v + (1 - beta2) avg(G*G), and the
+ * step uses  Vhat[r,c] = v_row[r] v_col[c] / mean(v_row)  (the two means are equal):
+ *     W <- W - lr * G / (sqrt(Vhat / (1 - beta2^step)) + eps)      (step counts from 1)
+ * -- Adam's bias correction and epsilon placement, which the paper does not restate.  A matrix
+ * whose gradient history is all zero is left unchanged.
+ * Every expert's W1 [d,h] (R = d, C = h) and W2 [h,d] (R = h, C = d) is one such matrix.
+ * Device inputs: dW1 [n,d,h], dW2 [n,h,d] f32 (as moe_layer_backward writes them).
+ * Device in/out: W1_master, W2_master f32 parameters in the weights' layout; v_row1 [n,d],
+ * v_col1 [n,h], v_row2 [n,h], v_col2 [n,d] f32 (zero before the first step).
+ * Device outputs: W1_copy, W2_copy: the bf16 weights the layer reads (nearest-even rounding of the
+ * updated parameters), or both NULL for fp32 experts, whose parameters are the weights themselves.
+ * d and h multiples of 4; workspace: moe_adam_workspace_bytes().  cfg->T and cfg->k are not used.
+ */
+typedef struct moe_adam_params {
+    float lr, beta2, eps;
+    int32_t step;          /* 1 for the first update */
+} moe_adam_params;
+size_t moe_adam_workspace_bytes(const moe_config *cfg);
+int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params *hp, const float *dW1,
+                         const float *dW2, float *W1_master, float *W2_master, void *W1_copy,
+                         void *W2_copy, float *v_row1, float *v_col1, float *v_row2, float *v_col2,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* Same as moe_layer_forward, with optional timing hooks: stage_events is a HOST array of 10
  * hipEvent_t (as void*), or NULL; entry 2i is recorded on `stream` just before stage i and entry
  * 2i+1 just after it, for i = 0 gate, 1 route, 2 experts, 3 combine, 4 losses.  NULL entries

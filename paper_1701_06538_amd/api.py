@@ -98,6 +98,16 @@ _moe_layer_forward_threshold = _proto("moe_layer_forward_threshold", ctypes.c_in
                                       [_cfgp] + [_vp] * 6 + [ctypes.c_int64] + [_vp] * 8 + [ctypes.c_size_t, _vp])
 
 
+class MoeAdamParams(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("step", ctypes.c_int32)]
+
+
+_moe_adam_workspace_bytes = _proto("moe_adam_workspace_bytes", ctypes.c_size_t, [_cfgp])
+_moe_expert_adam_step = _proto("moe_expert_adam_step", ctypes.c_int,
+                               [_cfgp, ctypes.POINTER(MoeAdamParams)] + [_vp] * 11 + [ctypes.c_size_t, _vp])
+
+
 class MoeError(RuntimeError):
     def __init__(self, status):
         self.status = status
@@ -322,3 +332,16 @@ def moe_layer_forward_threshold(cfg, x, W_g, gate_bias, thresholds, W1, W2, row_
                                         _ptr(thresholds), _ptr(W1), _ptr(W2), row_capacity, _ptr(y),
                                         _ptr(gsigma), _ptr(counts), _ptr(tokens), _ptr(kept), _ptr(denom),
                                         _ptr(rows_total), _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def moe_adam_workspace_bytes(cfg):
+    return _moe_adam_workspace_bytes(ctypes.byref(cfg))
+
+
+def moe_expert_adam_step(cfg, lr, beta2, eps, step, dW1, dW2, W1_master, W2_master, W1_copy, W2_copy, v_row1,
+                         v_col1, v_row2, v_col2, workspace, stream=None):
+    hp = MoeAdamParams(lr, beta2, eps, step)
+    _check(_moe_expert_adam_step(ctypes.byref(cfg), ctypes.byref(hp), _ptr(dW1), _ptr(dW2), _ptr(W1_master),
+                                 _ptr(W2_master), _ptr(W1_copy), _ptr(W2_copy), _ptr(v_row1), _ptr(v_col1),
+                                 _ptr(v_row2), _ptr(v_col2), _ptr(workspace), _nbytes(workspace),
+                                 _stream(stream)))
