@@ -145,6 +145,9 @@ def main():
     ap.add_argument("--gating", choices=["noisy_topk", "balanced"], default="noisy_topk",
                     help="balanced: the strictly balanced gate of Appendix F on the same workload "
                          "(flat forward configs only)")
+    ap.add_argument("--optimizer", action="store_true",
+                    help="training configs: also time the factored-second-moment Adam step of the expert "
+                         "matrices (outside the timed region; reported under \"optimizer\")")
     ap.add_argument("--cpu-sample", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -300,6 +303,26 @@ def main():
     }
     if shape.hierarchical:
         out["roofline"].update({"kernel": "moe_layer_forward_hier (whole call)", "note": "event pair brackets the whole layer"})
+    if args.optimizer and shape.backward:
+        masters = [run.W1.to(torch.float32), run.W2.to(torch.float32)]
+        state = [torch.zeros((shape.n, shape.d), **f32), torch.zeros((shape.n, shape.h), **f32),
+                 torch.zeros((shape.n, shape.h), **f32), torch.zeros((shape.n, shape.d), **f32)]
+        ows = torch.empty(api.moe_adam_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+        opt_ev = [(hip.create(), hip.create()) for _ in range(6)]
+        for i, (e0, e1) in enumerate(opt_ev):
+            hip.record(e0)
+            api.moe_expert_adam_step(run.cfg, 1e-3, 0.999, 1e-8, i + 1, grads[3], grads[4], masters[0], masters[1],
+                                     run.W1, run.W2, state[0], state[1], state[2], state[3], ows)
+            hip.record(e1)
+        torch.cuda.synchronize()
+        opt_ms = float(np.mean([hip.elapsed_ms(a, b) for a, b in opt_ev[1:]]))
+        elems = 2 * shape.n * shape.d * shape.h
+        # gradients read twice (moments, update), fp32 parameters read and written, bf16 copy written
+        opt_bytes = elems * (4 + 4 + 4 + 4 + 2)
+        out["optimizer"] = {"kernel": "moe_expert_adam_step (3 kernels per matrix family)", "ms": opt_ms,
+                            "algorithmic_bytes": opt_bytes, "bound": "hbm",
+                            "achieved": opt_bytes / (opt_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": opt_bytes / (opt_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     if balanced:
         out["roofline"]["traffic"] = read_traffic("ffn_bf16_%s_balanced_pmc.txt" % shape.name.split("_")[0])
     if not args.no_cpu_baseline and balanced:

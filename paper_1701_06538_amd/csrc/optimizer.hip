@@ -21,8 +21,57 @@ struct AdamMat {
     double *colpart;    // [count, ceil(R/64), C]
 };
 
-// blockIdx.x = row block, blockIdx.y = matrix index within the family (expert)
+// Rows of up to 256*NJ floats: a wavefront owns whole rows (w, w+4, ... of the block), so a row sum
+// is one wave reduction and goes straight to memory; the four waves' column sums meet in LDS and
+// are added in wave order.  blockIdx.x = row block, blockIdx.y = expert.
+template <int NJ>
 __global__ __launch_bounds__(256) void adam_moments_kernel(AdamMat m) {
+    extern __shared__ double col_part[];            // [4][C]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int R = m.R, C = m.C, C4 = C >> 2;
+    const int rb = blockIdx.x, e = blockIdx.y;
+    const int nrb = (R + kAdamRB - 1) / kAdamRB;
+    const int r0 = rb * kAdamRB, rows = min(kAdamRB, R - r0);
+    const float4 *G = reinterpret_cast<const float4 *>(m.G + ((size_t)e * R + r0) * C);
+    double cs[NJ][4];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) cs[j][0] = cs[j][1] = cs[j][2] = cs[j][3] = 0.0;
+    int c4[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) c4[j] = min(lane + 64 * j, C4 - 1);     // clamped: masked below
+#pragma unroll 2
+    for (int r = wave; r < rows; r += 4) {
+        float4 g[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) g[j] = G[(size_t)r * C4 + c4[j]];
+        double rs = 0.0;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const bool on = lane + 64 * j < C4;
+            const double q0 = on ? (double)g[j].x * g[j].x : 0.0, q1 = on ? (double)g[j].y * g[j].y : 0.0,
+                         q2 = on ? (double)g[j].z * g[j].z : 0.0, q3 = on ? (double)g[j].w * g[j].w : 0.0;
+            cs[j][0] += q0; cs[j][1] += q1; cs[j][2] += q2; cs[j][3] += q3;
+            rs += (q0 + q1) + (q2 + q3);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) rs += __shfl_xor(rs, off);
+        if (lane == 0) m.rowsum[(size_t)e * R + r0 + r] = rs;
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+        if (lane + 64 * j < C4) {
+            double *dst = col_part + (size_t)wave * C + 4 * (lane + 64 * j);
+            dst[0] = cs[j][0]; dst[1] = cs[j][1]; dst[2] = cs[j][2]; dst[3] = cs[j][3];
+        }
+    __syncthreads();
+    double *colpart = m.colpart + ((size_t)e * nrb + rb) * C;
+    for (int c = tid; c < C; c += 256)
+        colpart[c] = ((col_part[c] + col_part[C + c]) + col_part[2 * C + c]) + col_part[3 * C + c];
+}
+
+// Any row length: every wavefront takes a quarter of each row (blockIdx.x = row block,
+// blockIdx.y = expert).
+__global__ __launch_bounds__(256) void adam_moments_wide_kernel(AdamMat m) {
     __shared__ double row_part[kAdamRB][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int R = m.R, C = m.C, C4 = C >> 2;
@@ -215,7 +264,18 @@ extern "C" int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params
         double *rowsum = (double *)(ws + L.rowsum[w]), *colpart = (double *)(ws + L.colpart[w]);
         float *scale = (float *)(ws + L.scale[w]);
         AdamMat am{G[w], R[w], C[w], n, rowsum, colpart};
-        hipLaunchKernelGGL(adam_moments_kernel, dim3((unsigned)ceil_div(R[w], kAdamRB), (unsigned)n), dim3(256), 0, s, am);
+        const dim3 mgrid((unsigned)ceil_div(R[w], kAdamRB), (unsigned)n);
+        const size_t mlds = (size_t)4 * C[w] * sizeof(double);
+        if (C[w] <= 1024) hipLaunchKernelGGL(adam_moments_kernel<4>, mgrid, dim3(256), mlds, s, am);
+        else if (C[w] <= 2048) {
+            static bool attr_set = false;
+            if (!attr_set) {
+                MOE_HIP_TRY(hipFuncSetAttribute((const void *)adam_moments_kernel<8>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 2048 * 8));
+                attr_set = true;
+            }
+            hipLaunchKernelGGL(adam_moments_kernel<8>, mgrid, dim3(256), mlds, s, am);
+        } else hipLaunchKernelGGL(adam_moments_wide_kernel, mgrid, dim3(256), 0, s, am);
         MOE_LAUNCH_CHECK();
         AdamVec av{rowsum, colpart, vr[w], vc[w], scale, R[w], C[w], hp->beta2, bias_corr};
         hipLaunchKernelGGL(adam_vectors_kernel, dim3((unsigned)n), dim3(256), 0, s, av);

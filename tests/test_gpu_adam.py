@@ -31,6 +31,7 @@ CASES = {
     "ragged_f32": (2, 96, 132, "f32", 2),
     "paper_expert_bf16": (4, 512, 1024, "bf16", 3),
     "wide_rows_bf16": (2, 128, 2048, "bf16", 2),
+    "very_wide_rows_f32": (1, 32, 4160, "f32", 2),
 }
 
 
