@@ -376,6 +376,74 @@ class Grads:
     dW2: dict   # expert id -> [h,d]
 
 
+def gate_level_backward(lg: Logits, idx, g, dgate, gL, k):
+    """Backward of one noisy top-k gate (Eq.(3)-(5), (8)-(10)) on its own rows.
+    dgate [R,k]: everything that arrives at the kept softmax values; gL [n]: dJ/dLoad of this
+    gate's Load vector, or None when it carries no Load term.  Returns (dclean, draw) [R,n]:
+    gradients with respect to the clean logits (bias included) and to the raw noise logits."""
+    g = np.asarray(g, np.float64)
+    dgate = np.asarray(dgate, np.float64)
+    cleanb = np.asarray(lg.cleanb, np.float64)
+    sp = np.asarray(lg.sp, np.float64)
+    raw = np.asarray(lg.raw, np.float64)
+    eps = np.asarray(lg.eps, np.float64)
+    T, n = cleanb.shape
+
+    # softmax over the kept entries, Eq.(3)
+    dH = np.zeros((T, n), dtype=np.float64)
+    inner = (g * dgate).sum(axis=1, keepdims=True)
+    dH[np.arange(T)[:, None], idx] = g * (dgate - inner)
+
+    dclean = np.zeros((T, n), dtype=np.float64)
+    dsp = np.zeros((T, n), dtype=np.float64)
+    # L_load, Eq.(8)-(11)
+    if gL is not None and k < n:
+        gL = np.asarray(gL, np.float64)
+        thr, in_top, j_in, j_out = kth_excluding(lg.H, k, idx)
+        thr = np.asarray(thr, np.float64)
+        u = (cleanb - thr) / sp
+        phi = np.exp(-0.5 * u * u) / np.sqrt(2.0 * np.pi)
+        c = gL[None, :] * phi / sp
+        dclean += c
+        dsp += -c * u
+        rows = np.arange(T)
+        np.add.at(dH, (rows, j_in), -(c * in_top).sum(axis=1))
+        np.add.at(dH, (rows, j_out), -(c * ~in_top).sum(axis=1))
+
+    # H = cleanb + eps * sp, Eq.(4)
+    dclean += dH
+    dsp += dH * eps
+    draw = dsp / (1.0 + np.exp(-raw))        # d softplus = sigmoid
+    return dclean, draw
+
+
+def experts_backward(xe_all, idx, g, weight_fn, dy, experts_for_dW=None):
+    """Backward of Eq.(1) and of the experts (Appendix C) for assignments idx [T,k] with gate values
+    g [T,k]: returns (dx through the experts [T,d], dgate [T,k] = <dy_t, E_e(x_t)>, dW1, dW2)."""
+    xe_all = np.asarray(xe_all, np.float64)
+    g = np.asarray(g, np.float64)
+    dx = np.zeros_like(xe_all)
+    dgate = np.zeros_like(g)
+    dW1, dW2 = {}, {}
+    keep = None if experts_for_dW is None else set(int(e) for e in experts_for_dW)
+    for e in np.unique(idx):
+        r, s = np.nonzero(idx == e)
+        W1, W2 = (np.asarray(w, np.float64) for w in weight_fn(int(e)))
+        xe = xe_all[r]
+        z = xe @ W1
+        hid = np.maximum(z, 0.0)
+        out = hid @ W2
+        dgate[r, s] = np.einsum("ij,ij->i", dy[r], out)
+        dout = g[r, s][:, None] * dy[r]
+        dh = dout @ W2.T
+        dz = dh * (z > 0.0)
+        dx[r] += dz @ W1.T          # a token reaches an expert at most once, so r has no repeats
+        if keep is None or int(e) in keep:
+            dW2[int(e)] = hid.T @ dout
+            dW1[int(e)] = xe.T @ dz
+    return dx, dgate, dW1, dW2
+
+
 def flat_backward(x, W_g, W_noise, fwd: FlatForward, k, weight_fn, dy,
                   w_importance=0.1, w_load=0.1, experts_for_dW=None, expert_input=None) -> Grads:
     """Gradients of J = <dy, y> + L_importance + L_load for the flat layer.
@@ -404,57 +472,14 @@ def flat_backward(x, W_g, W_noise, fwd: FlatForward, k, weight_fn, dy,
     eps = np.asarray(lg.eps, np.float64)
     H = np.asarray(lg.H, np.float64)
 
-    dx = np.zeros_like(x)
-    dgate = np.zeros_like(g)
-    dW1, dW2 = {}, {}
-    keep = None if experts_for_dW is None else set(int(e) for e in experts_for_dW)
-
-    # experts and Eq.(1)
-    for e in np.unique(idx):
-        r, s = np.nonzero(idx == e)
-        W1, W2 = (np.asarray(w, np.float64) for w in weight_fn(int(e)))
-        xe = xe_all[r]
-        z = xe @ W1
-        hid = np.maximum(z, 0.0)
-        out = hid @ W2
-        dgate[r, s] = np.einsum("ij,ij->i", dy[r], out)
-        dout = g[r, s][:, None] * dy[r]
-        dh = dout @ W2.T
-        dz = dh * (z > 0.0)
-        dx[r] += dz @ W1.T          # a token reaches an expert at most once, so r has no repeats
-        if keep is None or int(e) in keep:
-            dW2[int(e)] = hid.T @ dout
-            dW1[int(e)] = xe.T @ dz
+    dx, dgate, dW1, dW2 = experts_backward(xe_all, idx, g, weight_fn, dy, experts_for_dW)
 
     # L_importance, Eq.(6)-(7)
     gI = w_importance * dcv_squared(fwd.importance)
     dgate += gI[idx]
 
-    # softmax over the kept entries, Eq.(3)
-    dH = np.zeros((T, n), dtype=np.float64)
-    inner = (g * dgate).sum(axis=1, keepdims=True)
-    dH[np.arange(T)[:, None], idx] = g * (dgate - inner)
-
-    dclean = np.zeros((T, n), dtype=np.float64)
-    dsp = np.zeros((T, n), dtype=np.float64)
-    # L_load, Eq.(8)-(11)
-    if k < n and w_load != 0.0:
-        gL = w_load * dcv_squared(fwd.load)
-        thr, in_top, j_in, j_out = kth_excluding(lg.H, k, idx)
-        thr = np.asarray(thr, np.float64)
-        u = (cleanb - thr) / sp
-        phi = np.exp(-0.5 * u * u) / np.sqrt(2.0 * np.pi)
-        c = gL[None, :] * phi / sp
-        dclean += c
-        dsp += -c * u
-        rows = np.arange(T)
-        np.add.at(dH, (rows, j_in), -(c * in_top).sum(axis=1))
-        np.add.at(dH, (rows, j_out), -(c * ~in_top).sum(axis=1))
-
-    # H = cleanb + eps * sp, Eq.(4)
-    dclean += dH
-    dsp += dH * eps
-    draw = dsp / (1.0 + np.exp(-raw))        # d softplus = sigmoid
+    gL = w_load * dcv_squared(fwd.load) if (k < n and w_load != 0.0) else None
+    dclean, draw = gate_level_backward(lg, idx, g, dgate, gL, k)
     dW_g = x.T @ dclean
     dW_noise = x.T @ draw
     dx += dclean @ W_g.T + draw @ W_noise.T
@@ -474,6 +499,116 @@ def flat_objective(x, W_g, W_noise, eps, bias, k, weight_fn, dy, w_importance, w
     ld, _ = load(lg, k, idx)
     return float((np.asarray(dy, np.float64) * y).sum()
                  + w_importance * cv_squared(imp) + w_load * cv_squared(ld))
+
+
+@dataclass
+class HierGrads:
+    dx: np.ndarray
+    dWg_p: np.ndarray      # [d,a]
+    dWn_p: np.ndarray
+    dWg_s: np.ndarray      # [a,d,b]
+    dWn_s: np.ndarray
+    dW1: dict
+    dW2: dict
+
+
+def _hier_forward_parts(x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, k_p, k_s, logits_fn,
+                        fixed_gidx=None, fixed_sidx=None):
+    """The hierarchical gate with every intermediate the backward pass needs."""
+    a, d, b = Wg_s.shape
+    T = x.shape[0]
+    lp = logits_fn(x, Wg_p, Wn_p, eps_p)
+    gidx = keep_top_k(lp.H, k_p) if fixed_gidx is None else fixed_gidx
+    ggate = topk_softmax(lp.H, gidx)
+    load_p = load(lp, k_p, gidx)[0]
+    sec_idx = np.zeros((T, k_p, k_s), dtype=np.int64)
+    sec_gate = np.zeros((T, k_p, k_s), dtype=np.float64)
+    load_s = np.zeros((a, b), dtype=np.float64)
+    gcount = np.zeros(a, dtype=np.int64)
+    members, sec_logits = {}, {}
+    for i in range(a):
+        tt, pp = np.nonzero(gidx == i)
+        gcount[i] = tt.shape[0]
+        if tt.shape[0] == 0:
+            continue
+        li = logits_fn(x[tt], Wg_s[i], Wn_s[i], eps_s[tt, pp, :])
+        si = keep_top_k(li.H, k_s) if fixed_sidx is None else fixed_sidx[tt, pp, :]
+        sec_idx[tt, pp, :] = si
+        sec_gate[tt, pp, :] = topk_softmax(li.H, si)
+        load_s[i] = load(li, k_s, si)[0]
+        members[i], sec_logits[i] = (tt, pp), li
+    idx = (gidx[:, :, None].astype(np.int64) * b + sec_idx).reshape(T, k_p * k_s)
+    gates = (ggate[:, :, None] * sec_gate).reshape(T, k_p * k_s)
+    imp = importance(idx, gates, a * b)
+    denom = np.where(gcount > 0, gcount, 1).astype(np.float64)
+    load_h = (load_p[:, None] * load_s / denom[:, None]).reshape(-1)
+    return dict(lp=lp, gidx=gidx, ggate=ggate, load_p=load_p, sec_idx=sec_idx, sec_gate=sec_gate,
+                load_s=load_s, gcount=gcount, denom=denom, members=members, sec_logits=sec_logits,
+                idx=idx, gates=gates, imp=imp, load_h=load_h)
+
+
+def hier_backward(x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, k_p, k_s, weight_fn, dy,
+                  w_importance=0.1, w_load=0.1, experts_for_dW=None, expert_input=None,
+                  logits_fn=None) -> HierGrads:
+    """Gradients of J = <dy, y> + w_importance CV^2(Importance_H) + w_load CV^2(Load_H) for the
+    hierarchical layer (Appendix B, Eq.(12)-(14)), by the chain rule through
+        gate(t, i, j) = G_primary(x_t)_i * G_i(x_t)_j,
+        Importance_H(i,j) = sum_t gate(t,i,j),
+        Load_H(i,j) = Load_primary(i) * Load_i(X^(i))_j / |X^(i)|     (|X^(i)| is a count: constant),
+    into both gating levels (each a noisy top-k gate: gate_level_backward) and the experts.
+    logits_fn defaults to the pinned fp32 logits of the forward pass."""
+    if logits_fn is None:
+        logits_fn = noisy_logits_f32
+    x64 = np.asarray(x, np.float64)
+    dy = np.asarray(dy, np.float64)
+    a, d, b = Wg_s.shape
+    T = x64.shape[0]
+    f = _hier_forward_parts(x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, k_p, k_s, logits_fn)
+    xe_all = x64 if expert_input is None else np.asarray(expert_input, np.float64)
+    dx_e, dgate, dW1, dW2 = experts_backward(xe_all, f["idx"], f["gates"], weight_fn, dy, experts_for_dW)
+    dx = dx_e.copy()
+
+    # Eq.(13): the composite gate values also feed Importance_H
+    dgate = dgate + (w_importance * dcv_squared(f["imp"]))[f["idx"]]
+    dg3 = dgate.reshape(T, k_p, k_s)
+    dGp = (dg3 * f["sec_gate"]).sum(axis=2)                    # Eq.(12): product rule
+    dGs = dg3 * f["ggate"][:, :, None]
+
+    # Eq.(14)
+    dLoad_p, dLoad_s = None, None
+    if w_load != 0.0:
+        gLh = (w_load * dcv_squared(f["load_h"])).reshape(a, b)
+        dLoad_p = (gLh * f["load_s"]).sum(axis=1) / f["denom"]
+        dLoad_s = gLh * f["load_p"][:, None] / f["denom"][:, None]
+
+    Wg_p64, Wn_p64 = np.asarray(Wg_p, np.float64), np.asarray(Wn_p, np.float64)
+    dclean, draw = gate_level_backward(f["lp"], f["gidx"], f["ggate"], dGp, dLoad_p, k_p)
+    dWg_p, dWn_p = x64.T @ dclean, x64.T @ draw
+    dx += dclean @ Wg_p64.T + draw @ Wn_p64.T
+
+    dWg_s = np.zeros((a, d, b))
+    dWn_s = np.zeros((a, d, b))
+    for i, (tt, pp) in f["members"].items():
+        dci, dri = gate_level_backward(f["sec_logits"][i], f["sec_idx"][tt, pp, :], f["sec_gate"][tt, pp, :],
+                                       dGs[tt, pp, :], None if dLoad_s is None else dLoad_s[i], k_s)
+        dWg_s[i] = x64[tt].T @ dci
+        dWn_s[i] = x64[tt].T @ dri
+        # a token picks a group at most once, so tt has no repeats
+        dx[tt] += dci @ np.asarray(Wg_s[i], np.float64).T + dri @ np.asarray(Wn_s[i], np.float64).T
+    return HierGrads(dx, dWg_p, dWn_p, dWg_s, dWn_s, dW1, dW2)
+
+
+def hier_objective(x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, k_p, k_s, weight_fn, dy,
+                   w_importance, w_load, fixed_gidx, fixed_sidx):
+    """J of hier_backward evaluated entirely in binary64 with both selections frozen (for
+    finite differences)."""
+    f = _hier_forward_parts(x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, k_p, k_s, noisy_logits_f64,
+                            fixed_gidx, fixed_sidx)
+    a, _, b = Wg_s.shape
+    y = moe_output(x, f["idx"], f["gates"], weight_fn, a * b)
+    return float((np.asarray(dy, np.float64) * y).sum()
+                 + w_importance * cv_squared(f["imp"]) + w_load * cv_squared(f["load_h"]))
+
 
 
 # --------------------------------------------------------------------------------------

@@ -230,3 +230,75 @@ def test_bf16_rounding_helper_matches_torch():
                         np.array([1.0, 1.00390625, 1.001953125, 1.005859375, -2.5, 0.0], np.float32)])
     want = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
     assert np.array_equal(O.round_to_bf16(a), want)
+
+
+def _hier_fd_setup(seed, T=7, d=5, h=6, a=3, b=4):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, d))
+    Wgp, Wnp = 0.7 * rng.standard_normal((d, a)), 0.7 * rng.standard_normal((d, a))
+    Wgs, Wns = 0.7 * rng.standard_normal((a, d, b)), 0.7 * rng.standard_normal((a, d, b))
+    ep = rng.standard_normal((T, a))
+    W1, W2, wf = _weights(rng, a * b, d, h, 0.5)
+    dy = rng.standard_normal((T, d))
+    return x, Wgp, Wnp, ep, Wgs, Wns, W1, W2, wf, dy, rng
+
+
+@pytest.mark.parametrize("w_imp,w_load", [(0.1, 0.1), (0.0, 0.0), (1.0, 0.0), (0.0, 1.0)])
+def test_hierarchical_backward_against_central_finite_differences(w_imp, w_load):
+    """Gradients through Eq.(12)-(14) vs central differences of the binary64 forward with both
+    levels' selections frozen."""
+    k_p, k_s = 2, 2
+    x, Wgp, Wnp, ep, Wgs, Wns, W1, W2, wf, dy, rng = _hier_fd_setup(21)
+    es = rng.standard_normal((x.shape[0], k_p, Wgs.shape[2]))
+    parts = O._hier_forward_parts(x, Wgp, Wnp, ep, Wgs, Wns, es, k_p, k_s, O.noisy_logits_f64)
+    gidx, sidx = parts["gidx"], parts["sec_idx"]
+    assert (parts["gcount"] > 0).all()
+    gr = O.hier_backward(x, Wgp, Wnp, ep, Wgs, Wns, es, k_p, k_s, wf, dy, w_imp, w_load,
+                         logits_fn=O.noisy_logits_f64)
+
+    def J(x_=x, Wgp_=Wgp, Wnp_=Wnp, Wgs_=Wgs, Wns_=Wns, wf_=wf):
+        return O.hier_objective(x_, Wgp_, Wnp_, ep, Wgs_, Wns_, es, k_p, k_s, wf_, dy, w_imp, w_load, gidx, sidx)
+
+    def fd(arr, analytic, make, count=10):
+        r = np.random.default_rng(1)
+        for _ in range(count):
+            pos = tuple(r.integers(0, s) for s in arr.shape)
+            step = 1e-6
+            p = arr.copy(); p[pos] += step
+            m = arr.copy(); m[pos] -= step
+            num = (make(p) - make(m)) / (2 * step)
+            assert abs(num - analytic[pos]) < 3e-6 * max(1.0, abs(num)), (pos, num, analytic[pos])
+
+    fd(x, gr.dx, lambda v: J(x_=v))
+    fd(Wgp, gr.dWg_p, lambda v: J(Wgp_=v))
+    fd(Wnp, gr.dWn_p, lambda v: J(Wnp_=v))
+    fd(Wgs, gr.dWg_s, lambda v: J(Wgs_=v), 16)
+    fd(Wns, gr.dWn_s, lambda v: J(Wns_=v), 16)
+    for e in list(gr.dW1)[:2]:
+        fd(W1[e], gr.dW1[e], lambda v, e=e: J(wf_=lambda q: ((v if q == e else W1[q]), W2[q])), 6)
+        fd(W2[e], gr.dW2[e], lambda v, e=e: J(wf_=lambda q: (W1[q], (v if q == e else W2[q]))), 6)
+
+
+def test_hierarchical_backward_with_one_group_is_the_flat_backward():
+    """a = 1, k_primary = 1: the primary gate is the constant 1, Load_H = Load of the only
+    secondary gate, so every gradient must equal the flat layer's over the b experts."""
+    rng = np.random.default_rng(22)
+    T, d, h, b, k = 9, 6, 5, 5, 2
+    x = rng.standard_normal((T, d))
+    Wg, Wn = 0.6 * rng.standard_normal((d, b)), 0.6 * rng.standard_normal((d, b))
+    eps = rng.standard_normal((T, b))
+    W1, W2, wf = _weights(rng, b, d, h, 0.5)
+    dy = rng.standard_normal((T, d))
+    Wgp, Wnp = rng.standard_normal((d, 1)), rng.standard_normal((d, 1))
+    gr = O.hier_backward(x, Wgp, Wnp, rng.standard_normal((T, 1)), Wg[None], Wn[None], eps[:, None, :], 1, k, wf, dy,
+                         0.3, 0.7, logits_fn=O.noisy_logits_f64)
+    lg = O.noisy_logits_f64(x, Wg, Wn, eps)
+    fwd = O.gate_and_losses(lg, k, 0.3, 0.7)
+    fl = O.flat_backward(x, Wg, Wn, fwd, k, wf, dy, 0.3, 0.7)
+    assert np.allclose(gr.dx, fl.dx, rtol=1e-10, atol=1e-12)
+    assert np.allclose(gr.dWg_s[0], fl.dW_g, rtol=1e-10, atol=1e-12)
+    assert np.allclose(gr.dWn_s[0], fl.dW_noise, rtol=1e-10, atol=1e-12)
+    assert np.abs(gr.dWg_p).max() < 1e-12 and np.abs(gr.dWn_p).max() < 1e-12     # a constant gate learns nothing
+    for e in fl.dW1:
+        assert np.allclose(gr.dW1[e], fl.dW1[e], rtol=1e-10, atol=1e-12)
+        assert np.allclose(gr.dW2[e], fl.dW2[e], rtol=1e-10, atol=1e-12)
