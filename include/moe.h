@@ -336,6 +336,28 @@ int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params *hp, const
                          void *W2_copy, float *v_row1, float *v_col1, float *v_row2, float *v_col2,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- backward pass of the hierarchical layer (Appendix B, Eq.(12)-(14)) ------------------- */
+/*
+ * Gradients of J = <dy, y> + w_importance*CV^2(Importance_H) + w_load*CV^2(Load_H) with respect
+ * to x, both gating levels' matrices and every expert's W1, W2.  The chain rule runs through
+ * gate(t,i,j) = G_primary(x_t)_i * G_i(x_t)_j (Eq.(12)), Importance_H (Eq.(13)) and
+ * Load_H(i,j) = Load_primary(i) * Load_i(X^(i))_j / |X^(i)| (Eq.(14); |X^(i)| is a count, hence
+ * constant), then through each level as through the flat gate (moe_layer_backward).
+ * Inputs: the forward call's inputs, dy [T,d], its outputs topk_idx/topk_gate and its workspace as
+ * moe_layer_forward_hier left it.  Outputs (overwritten): dx [T,d]; dWg_p, dWn_p [d,a];
+ * dWg_s, dWn_s [a,d,b] (zeros for a group no token chose); dW1 [n,d,h], dW2 [n,h,d]; all f32.
+ * bf16 experts, d and h multiples of 256, a and b multiples of 32; the hidden activations are
+ * recomputed (Appendix D).  workspace: moe_backward_hier_workspace_bytes().
+ */
+size_t moe_backward_hier_workspace_bytes(const moe_config *cfg);
+int moe_layer_backward_hier(const moe_config *cfg, const float *x, const float *Wg_p,
+                            const float *Wn_p, const float *eps_p, const float *Wg_s,
+                            const float *Wn_s, const float *eps_s, const void *W1, const void *W2,
+                            const float *dy, const int32_t *topk_idx, const float *topk_gate,
+                            const void *fwd_workspace, float *dx, float *dWg_p, float *dWn_p,
+                            float *dWg_s, float *dWn_s, float *dW1, float *dW2, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
 /* Same as moe_layer_forward, with optional timing hooks: stage_events is a HOST array of 10
  * hipEvent_t (as void*), or NULL; entry 2i is recorded on `stream` just before stage i and entry
  * 2i+1 just after it, for i = 0 gate, 1 route, 2 experts, 3 combine, 4 losses.  NULL entries

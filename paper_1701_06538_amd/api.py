@@ -97,6 +97,10 @@ _moe_threshold_workspace_bytes = _proto("moe_threshold_workspace_bytes", ctypes.
 _moe_layer_forward_threshold = _proto("moe_layer_forward_threshold", ctypes.c_int,
                                       [_cfgp] + [_vp] * 6 + [ctypes.c_int64] + [_vp] * 8 + [ctypes.c_size_t, _vp])
 
+_moe_backward_hier_workspace_bytes = _proto("moe_backward_hier_workspace_bytes", ctypes.c_size_t, [_cfgp])
+_moe_layer_backward_hier = _proto("moe_layer_backward_hier", ctypes.c_int,
+                                  [_cfgp] + [_vp] * 21 + [ctypes.c_size_t, _vp])
+
 
 class MoeAdamParams(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
@@ -345,3 +349,16 @@ def moe_expert_adam_step(cfg, lr, beta2, eps, step, dW1, dW2, W1_master, W2_mast
                                  _ptr(W2_master), _ptr(W1_copy), _ptr(W2_copy), _ptr(v_row1), _ptr(v_col1),
                                  _ptr(v_row2), _ptr(v_col2), _ptr(workspace), _nbytes(workspace),
                                  _stream(stream)))
+
+
+def moe_backward_hier_workspace_bytes(cfg):
+    return _moe_backward_hier_workspace_bytes(ctypes.byref(cfg))
+
+
+def moe_layer_backward_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, W1, W2, dy, topk_idx, topk_gate,
+                            fwd_workspace, dx, dWg_p, dWn_p, dWg_s, dWn_s, dW1, dW2, workspace, stream=None):
+    _check(_moe_layer_backward_hier(ctypes.byref(cfg), _ptr(x), _ptr(Wg_p), _ptr(Wn_p), _ptr(eps_p), _ptr(Wg_s),
+                                    _ptr(Wn_s), _ptr(eps_s), _ptr(W1), _ptr(W2), _ptr(dy), _ptr(topk_idx),
+                                    _ptr(topk_gate), _ptr(fwd_workspace), _ptr(dx), _ptr(dWg_p), _ptr(dWn_p),
+                                    _ptr(dWg_s), _ptr(dWn_s), _ptr(dW1), _ptr(dW2), _ptr(workspace),
+                                    _nbytes(workspace), _stream(stream)))

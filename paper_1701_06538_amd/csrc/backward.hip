@@ -245,6 +245,12 @@ struct GateBwdArgs {
     float *dclean, *draw;             // [T, n]
     int64_t T;
     int n, k;
+    // a secondary gate of the hierarchical layer: row t of cleanb/sp/dclean/draw belongs to row
+    // row_map[t] of eps/idx/gate/dgate/next_idx and to the group g with
+    // group_offsets[g] <= t < group_offsets[g+1], whose Load gradient is gL[g*n ..]; null = flat
+    const int32_t *row_map;
+    const int32_t *group_offsets;
+    int groups;
 };
 
 __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
@@ -253,15 +259,26 @@ __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
     if (t >= p.T) return;
     const int n = p.n, k = p.k;
     const float *c_row = p.cleanb + t * n, *s_row = p.sp + t * n;
-    const float *e_row = p.eps ? p.eps + t * n : nullptr;
+    const int64_t ot = p.row_map ? (int64_t)p.row_map[t] : t;
+    const float *gL_row = p.gL;
+    if (p.group_offsets) {
+        int lo = 0, hi = p.groups;                 // last group whose first row is <= t
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if ((int64_t)p.group_offsets[mid] <= t) lo = mid;
+            else hi = mid;
+        }
+        gL_row = p.gL + (size_t)lo * n;
+    }
+    const float *e_row = p.eps ? p.eps + ot * n : nullptr;
     int ki[kMaxK];
     float g[kMaxK], dH[kMaxK];
     float inner = 0.f;
 #pragma unroll
     for (int s = 0; s < kMaxK; ++s) {
-        ki[s] = s < k ? p.idx[t * k + s] : -1;
-        g[s] = s < k ? p.gate[t * k + s] : 0.f;
-        const float dg = s < k ? p.dgate[t * k + s] + p.gI[ki[s]] : 0.f;
+        ki[s] = s < k ? p.idx[ot * k + s] : -1;
+        g[s] = s < k ? p.gate[ot * k + s] : 0.f;
+        const float dg = s < k ? p.dgate[ot * k + s] + (p.gI ? p.gI[ki[s]] : 0.f) : 0.f;
         dH[s] = dg;
         inner = fmaf(g[s], dg, inner);
     }
@@ -272,7 +289,7 @@ __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
     int j_in = -1, j_out = -1;
     float thr_in = 0.f, thr_out = 0.f;
     if (with_load) {
-        j_in = p.next_idx[t];
+        j_in = p.next_idx[ot];
 #pragma unroll
         for (int s = 0; s < kMaxK; ++s)
             if (s == k - 1) j_out = ki[s];
@@ -288,7 +305,7 @@ __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
             for (int s = 0; s < kMaxK; ++s) kept |= (ki[s] == i);
             const float sp = s_row[i];
             const float u = (c_row[i] - (kept ? thr_in : thr_out)) / sp;
-            const float c = p.gL[i] * 0.3989422804014327f * expf(-0.5f * u * u) / sp;
+            const float c = gL_row[i] * 0.3989422804014327f * expf(-0.5f * u * u) / sp;
             if (kept) S_in += c;
             else S_out += c;
         }
@@ -312,7 +329,7 @@ __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
         float c = 0.f, u = 0.f;
         if (with_load) {
             u = (c_row[i] - (kept ? thr_in : thr_out)) / sp;
-            c = p.gL[i] * 0.3989422804014327f * expf(-0.5f * u * u) / sp;
+            c = gL_row[i] * 0.3989422804014327f * expf(-0.5f * u * u) / sp;
             if (i == j_in) dh -= S_in;     // the threshold of the kept experts
             if (i == j_out) dh -= S_out;   // the threshold of all the others
         }
@@ -335,6 +352,11 @@ struct SGArgs {
     int nseg;
     int ksplit;       // blockIdx.z = which * ksplit + split (A_MK only)
     size_t c_which_stride, c_split_stride;
+    // optional row range on the device (rows lo = range[range_idx] .. range[range_idx+1] of the
+    // row-indexed operands): with A_MK the contraction runs over those rows (K = their number),
+    // otherwise they are the rows of A and C (M = their number; tiles past the end exit)
+    const int32_t *range;
+    int range_idx;
 };
 
 constexpr int SBM = 128, SBN = 128, SKC = 32, SAS = SKC + 4;
@@ -373,8 +395,26 @@ __global__ __launch_bounds__(256) void sg_kernel(SGArgs p) {
         which = blockIdx.z / p.ksplit;
         split = blockIdx.z % p.ksplit;
     }
-    const int kper = A_MK ? ((p.K + p.ksplit - 1) / p.ksplit + SKC - 1) / SKC * SKC : p.K;
-    const int kbeg = split * kper, kend = min(p.K, kbeg + kper);
+    int M_ = p.M, K_ = p.K;
+    const float *A0 = p.A[0], *A1 = p.A[1], *B0 = p.B[0], *B1 = p.B[1];
+    float *C_ = p.C;
+    if (p.range) {
+        const int lo = p.range[p.range_idx], hi = p.range[p.range_idx + 1];
+        if (A_MK) {
+            K_ = hi - lo;
+            A0 += (size_t)lo * p.lda;
+            B0 += (size_t)lo * p.ldb;
+            B1 += (size_t)lo * p.ldb;
+        } else {
+            M_ = hi - lo;
+            if (m0 >= M_) return;
+            A0 += (size_t)lo * p.lda;
+            A1 += (size_t)lo * p.lda;
+            C_ += (size_t)lo * p.ldc;
+        }
+    }
+    const int kper = A_MK ? ((K_ + p.ksplit - 1) / p.ksplit + SKC - 1) / SKC * SKC : K_;
+    const int kbeg = split * kper, kend = min(K_, kbeg + kper);
     const int per_seg = kend > kbeg ? (kend - kbeg + SKC - 1) / SKC : 0;
     const int nslab = per_seg * (A_MK ? 1 : p.nseg);
 
@@ -391,17 +431,17 @@ __global__ __launch_bounds__(256) void sg_kernel(SGArgs p) {
     auto load_global = [&](int slab) {
         const int sgm = A_MK ? 0 : slab / per_seg;
         const int k0 = kbeg + (slab - sgm * per_seg) * SKC;
-        const float *A = p.A[A_MK ? 0 : sgm];
-        const float *B = p.B[A_MK ? which : sgm];
+        const float *A = (A_MK || sgm == 0) ? A0 : A1;
+        const float *B = (A_MK ? which : sgm) == 0 ? B0 : B1;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (A_MK) {
                 const int k = k0 + rk + 8 * i;
-                const v4f32 v = *reinterpret_cast<const v4f32 *>(A + (size_t)min(k, kend - 1) * p.lda + min(m0 + r4, p.M - 4));
+                const v4f32 v = *reinterpret_cast<const v4f32 *>(A + (size_t)min(k, kend - 1) * p.lda + min(m0 + r4, M_ - 4));
                 a_reg[i] = k < kend ? v : v4f32{0.f, 0.f, 0.f, 0.f};
             } else {
                 const int k = k0 + kq;
-                const v4f32 v = *reinterpret_cast<const v4f32 *>(A + (size_t)min(m0 + rr + 32 * i, p.M - 1) * p.lda + min(k, kend - 4));
+                const v4f32 v = *reinterpret_cast<const v4f32 *>(A + (size_t)min(m0 + rr + 32 * i, M_ - 1) * p.lda + min(k, kend - 4));
                 a_reg[i] = k < kend ? v : v4f32{0.f, 0.f, 0.f, 0.f};
             }
             if (B_NK) {
@@ -498,7 +538,7 @@ __global__ __launch_bounds__(256) void sg_kernel(SGArgs p) {
         for (int r = 0; r < 16; ++r)
             Ct[(wave * 32 + 8 * (r / 4) + 4 * half + (r % 4)) * CS + 32 * c + l32] = acc[c][r];
     __syncthreads();
-    float *C = p.C + (A_MK ? which * p.c_which_stride + split * p.c_split_stride : 0);
+    float *C = C_ + (A_MK ? which * p.c_which_stride + split * p.c_split_stride : 0);
     const int cq = tid & 31, r0 = tid >> 5;     // 32 float4 per row, 8 rows per pass
     const int col = n0 + 4 * cq;
     for (int pass0 = 0; pass0 < SBM / 8; pass0 += 4) {
@@ -508,7 +548,7 @@ __global__ __launch_bounds__(256) void sg_kernel(SGArgs p) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int row = m0 + r0 + 8 * (pass0 + u);
-            if (row < p.M && col < p.N) *reinterpret_cast<v4f32 *>(C + (size_t)row * p.ldc + col) = t[u];
+            if (row < M_ && col < p.N) *reinterpret_cast<v4f32 *>(C + (size_t)row * p.ldc + col) = t[u];
         }
     }
 }
@@ -603,6 +643,48 @@ static int bwd_layout(const moe_config *cfg, BwdLayout *L) {
 int launch_build_tiles(const int32_t *offsets, int n, int tile_rows, int32_t *tile_expert,
                        int32_t *tile_row0, int32_t *num_tiles, hipStream_t st);
 
+// The experts' share of a backward pass, for any assignment list (flat or hierarchical gate):
+// Eq.(1) per routed row, the two-layer expert's backward GEMMs and both weight gradients.
+struct ExpertBwd {
+    const float *x, *dy, *out_sorted, *gate;   // gate [T*k] in assignment order
+    const int32_t *perm, *offsets;
+    const void *W1, *W2;
+    const uint16_t *saved_hid;                 // hidden activations kept by the forward pass, or null
+    uint16_t *xs, *dout, *hid, *dz;            // workspace (hid unused when saved_hid is given)
+    float *dxs, *dgate;                        // out: [T*k, d] expert part of dx per routed row; [T*k]
+    int32_t *tile_expert, *tile_row0, *num_tiles, *order;
+    float *dW1, *dW2;
+};
+
+static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStream_t s) {
+    const int64_t A = (int64_t)cfg->T * cfg->k;
+    const int d = cfg->d, h = cfg->h, n = cfg->n, k = cfg->k;
+    int st;
+    hipLaunchKernelGGL(bwd_prepare_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, s, b.x, b.dy,
+                       b.out_sorted, b.gate, b.perm, A, d, k, b.xs, b.dout, b.dgate);
+    MOE_LAUNCH_CHECK();
+    const uint16_t *hid = b.saved_hid;
+    if (!hid) {   // Appendix D: recompute the hidden activations
+        if ((st = launch_build_tiles(b.offsets, n, GBM, b.tile_expert, b.tile_row0, b.num_tiles, s)) != MOE_OK) return st;
+        const unsigned max_tiles = (unsigned)(ceil_div(A, GBM) + n);
+        GGRows g1{b.xs, (const uint16_t *)b.W1, b.hid, nullptr, d, h, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
+        if ((st = launch_gg_rows128(g1, true, EPI_RELU_BF16, max_tiles, s)) != MOE_OK) return st;
+        hid = b.hid;
+    }
+    // the two compute-bound GEMMs of the expert backward run on 256-row tiles
+    if ((st = launch_build_tiles(b.offsets, n, 256, b.tile_expert, b.tile_row0, b.num_tiles, s)) != MOE_OK) return st;
+    const int64_t max_tiles256 = ceil_div(A, 256) + n;
+    GGRows g2{b.dout, (const uint16_t *)b.W2, b.dz, hid, d, h, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
+    if ((st = launch_gg_rows256(g2, EPI_MASK_BF16, max_tiles256, s)) != MOE_OK) return st;
+    if ((st = launch_expert_order(b.offsets, n, b.order, s)) != MOE_OK) return st;
+    GGWgrad w2{hid, b.dout, b.dW2, h, d, b.offsets, b.order};
+    if ((st = launch_gg_wgrad(w2, n, s)) != MOE_OK) return st;
+    GGWgrad w1{b.xs, b.dz, b.dW1, d, h, b.offsets, b.order};
+    if ((st = launch_gg_wgrad(w1, n, s)) != MOE_OK) return st;
+    GGRows g5{b.dz, (const uint16_t *)b.W1, b.dxs, nullptr, h, d, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
+    return launch_gg_rows256(g5, EPI_F32, max_tiles256, s);
+}
+
 }  // namespace moe
 
 using namespace moe;
@@ -658,31 +740,10 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
     int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
 
-    // Eq.(1) backward per routed row
-    hipLaunchKernelGGL(bwd_prepare_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, s, x, dy,
-                       out_sorted, topk_gate, perm, A, d, k, xs, dout, dgate);
-    MOE_LAUNCH_CHECK();
-    if ((st = launch_build_tiles(offsets, n, GBM, tile_expert, tile_row0, num_tiles, s)) != MOE_OK) return st;
-    const unsigned max_tiles = (unsigned)(ceil_div(A, GBM) + n);
-
-    // experts (hidden layer recomputed)
-    if (!saved_hidden) {   // Appendix D: recompute the hidden activations
-        GGRows g1{xs, (const uint16_t *)W1, hid, nullptr, d, h, offsets, tile_expert, tile_row0, num_tiles};
-        if ((st = launch_gg_rows128(g1, true, EPI_RELU_BF16, max_tiles, s)) != MOE_OK) return st;
-    }
-    // the two compute-bound GEMMs of the expert backward run on 256-row tiles
-    if ((st = launch_build_tiles(offsets, n, 256, tile_expert, tile_row0, num_tiles, s)) != MOE_OK) return st;
-    const int64_t max_tiles256 = ceil_div(A, 256) + n;
-    GGRows g2{dout, (const uint16_t *)W2, dz, hid, d, h, offsets, tile_expert, tile_row0, num_tiles};
-    if ((st = launch_gg_rows256(g2, EPI_MASK_BF16, max_tiles256, s)) != MOE_OK) return st;
-    int32_t *order = (int32_t *)(ws + L.order);
-    if ((st = launch_expert_order(offsets, n, order, s)) != MOE_OK) return st;
-    GGWgrad w2{hid, dout, dW2, h, d, offsets, order};
-    if ((st = launch_gg_wgrad(w2, n, s)) != MOE_OK) return st;
-    GGWgrad w1{xs, dz, dW1, d, h, offsets, order};
-    if ((st = launch_gg_wgrad(w1, n, s)) != MOE_OK) return st;
-    GGRows g5{dz, (const uint16_t *)W1, dxs, nullptr, h, d, offsets, tile_expert, tile_row0, num_tiles};
-    if ((st = launch_gg_rows256(g5, EPI_F32, max_tiles256, s)) != MOE_OK) return st;
+    ExpertBwd eb{x, dy, out_sorted, topk_gate, perm, offsets, W1, W2, saved_hidden ? hid : nullptr,
+                 xs, dout, saved_hidden ? nullptr : hid, dz, dxs, dgate, tile_expert, tile_row0, num_tiles,
+                 (int32_t *)(ws + L.order), dW1, dW2};
+    if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
 
     // gate
     hipLaunchKernelGGL(loss_grad_kernel, dim3(1), dim3(256), 0, s, sums64, n, cfg->w_importance,
@@ -718,6 +779,277 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     MOE_LAUNCH_CHECK();
     hipLaunchKernelGGL(dx_gather_add_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s,
                        (float4 *)dx, (const float4 *)dxs, inv_perm, T, d / 4, k);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// hierarchical layer (Appendix B): backward through Eq.(12)-(14)
+// ---------------------------------------------------------------------------------------
+namespace moe {
+
+// Eq.(12),(13): gate(t,p,s) = G_primary(t,p) * G_secondary(t,p,s) feeds Eq.(1) and Importance_H.
+// One thread per (token, primary slot): product rule into both levels.
+__global__ __launch_bounds__(256) void hier_dgate_kernel(const float *__restrict__ dgate,
+                                                         const int32_t *__restrict__ topk_idx,
+                                                         const float *__restrict__ gI,
+                                                         const float *__restrict__ p_gate,
+                                                         const float *__restrict__ s_gate, int64_t Ap,
+                                                         int k_s, float *__restrict__ dGp,
+                                                         float *__restrict__ dGs) {
+    const int64_t ap = (int64_t)blockIdx.x * 256 + threadIdx.x;     // t * k_p + p
+    if (ap >= Ap) return;
+    const float gp = p_gate[ap];
+    float acc = 0.f;
+    for (int s = 0; s < k_s; ++s) {
+        const int64_t at = ap * k_s + s;                            // = t * k + p * k_s + s
+        const float dg = dgate[at] + gI[topk_idx[at]];
+        dGs[at] = dg * gp;
+        acc = fmaf(dg, s_gate[at], acc);
+    }
+    dGp[ap] = acc;
+}
+
+// Eq.(14): Load_H(i,j) = Load_p(i) * Load_i(j) / |X^(i)|.  One workgroup per group i:
+// dLoad_s[i][j] = gL[i][j] * Load_p(i) / |X^(i)|,  dLoad_p[i] = sum_j gL[i][j] * Load_i(j) / |X^(i)|,
+// the secondary loads re-summed from the forward pass's per-block partial rows, in order.
+__global__ __launch_bounds__(256) void hier_load_grads_kernel(const float *__restrict__ gL,
+                                                              const double *__restrict__ p_sums,
+                                                              const float *__restrict__ s_partials,
+                                                              const int32_t *__restrict__ p_counts,
+                                                              const int32_t *__restrict__ p_tile_offsets,
+                                                              int a, int b, int sub,
+                                                              float *__restrict__ dLoad_p,
+                                                              float *__restrict__ dLoad_s) {
+    __shared__ double red[256];
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const int cnt = p_counts[i];
+    const double inv = cnt > 0 ? 1.0 / (double)cnt : 0.0;
+    const double lp = p_sums[a + i];
+    const int blk0 = p_tile_offsets[i] * sub, blk1 = p_tile_offsets[i + 1] * sub;
+    double acc = 0.0;
+    for (int j = tid; j < b; j += 256) {
+        double ls = 0.0;
+        for (int blk = blk0; blk < blk1; ++blk) ls += (double)s_partials[((size_t)blk * 2 + 1) * b + j];
+        const double g = (double)gL[(size_t)i * b + j];
+        dLoad_s[(size_t)i * b + j] = (float)(g * lp * inv);
+        acc += g * ls * inv;
+    }
+    red[tid] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        double t = 0.0;
+        for (int q = 0; q < 256; ++q) t += red[q];
+        dLoad_p[i] = (float)t;
+    }
+}
+
+// xg[r] = x[row_src[r] / div]  (fp32 rows in routed order); one wavefront per row
+__global__ __launch_bounds__(256) void gather_rows_f32_kernel(const float4 *__restrict__ x,
+                                                              const int32_t *__restrict__ row_src, int div,
+                                                              int64_t rows, int d4, float4 *__restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int64_t t = row_src[r] / div;
+    for (int c = lane; c < d4; c += 64) out[r * d4 + c] = x[t * d4 + c];
+}
+
+struct HierBwdLayout {
+    size_t xs, dout, hid, dz, dxs, dgate, gI, gL, tile_expert, tile_row0, num_tiles, order;
+    size_t dGp, dGs, dLoad_p, dLoad_s, dclean_p, draw_p, dclean_s, draw_s, xg, dxg, wpart, total;
+    int ksplit;
+};
+
+static void hier_bwd_layout(const moe_config *cfg, HierBwdLayout *L) {
+    const size_t T = cfg->T, n = cfg->n, A = T * (size_t)cfg->k, d = cfg->d, h = cfg->h;
+    const size_t a = cfg->a, b = cfg->b, Ap = T * (size_t)cfg->k_primary;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = up256(off + (bytes ? bytes : 1));
+        return at;
+    };
+    L->xs = take(A * d * 2);
+    L->dout = take(A * d * 2);
+    L->hid = take(A * h * 2);
+    L->dz = take(A * h * 2);
+    L->dxs = take(A * d * 4);
+    L->dgate = take(A * 4);
+    L->gI = take(n * 4);
+    L->gL = take(n * 4);
+    const size_t MT = (size_t)ceil_div((int64_t)A, GBM) + n + 8;
+    L->tile_expert = take(MT * 4);
+    L->tile_row0 = take(MT * 4);
+    L->num_tiles = take(16);
+    L->order = take(n * 4);
+    L->dGp = take(Ap * 4);
+    L->dGs = take(A * 4);
+    L->dLoad_p = take(a * 4);
+    L->dLoad_s = take(n * 4);
+    L->dclean_p = take(T * a * 4);
+    L->draw_p = take(T * a * 4);
+    L->dclean_s = take(Ap * b * 4);
+    L->draw_s = take(Ap * b * 4);
+    L->xg = take(Ap * d * 4);
+    L->dxg = take(Ap * d * 4);
+    const int64_t tiles = ceil_div(cfg->d, SBM) * ceil_div(cfg->a, SBN) * 2;
+    int ks = (int)ceil_div(1024, tiles);
+    const int maxks = (int)ceil_div(cfg->T > 0 ? cfg->T : 1, 256);
+    if (ks > maxks) ks = maxks;
+    if (ks < 1) ks = 1;
+    L->ksplit = ks;
+    L->wpart = take((size_t)ks * 2 * d * a * 4);
+    L->total = off;
+}
+
+static int hier_bwd_check(const moe_config *cfg) {
+    int st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (cfg->a <= 0) return MOE_EINVAL;
+    if (cfg->expert_dtype != MOE_DTYPE_BF16) return MOE_EUNSUPPORTED;
+    if (cfg->d % 256 != 0 || cfg->h % 256 != 0) return MOE_EUNSUPPORTED;
+    if (cfg->a % 32 != 0 || cfg->b % 32 != 0) return MOE_EUNSUPPORTED;   // k-slabs of the gate GEMMs
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+extern "C" size_t moe_backward_hier_workspace_bytes(const moe_config *cfg) {
+    if (hier_bwd_check(cfg) != MOE_OK) return 0;
+    HierBwdLayout L;
+    hier_bwd_layout(cfg, &L);
+    return L.total;
+}
+
+extern "C" int moe_layer_backward_hier(const moe_config *cfg, const float *x, const float *Wg_p,
+                                       const float *Wn_p, const float *eps_p, const float *Wg_s,
+                                       const float *Wn_s, const float *eps_s, const void *W1,
+                                       const void *W2, const float *dy, const int32_t *topk_idx,
+                                       const float *topk_gate, const void *fwd_workspace, float *dx,
+                                       float *dWg_p, float *dWn_p, float *dWg_s, float *dWn_s,
+                                       float *dW1, float *dW2, void *workspace, size_t workspace_bytes,
+                                       void *stream) {
+    int st = hier_bwd_check(cfg);
+    if (st != MOE_OK) return st;
+    moe_workspace_layout F;
+    if ((st = moe_get_workspace_layout(cfg, &F)) != MOE_OK) return st;
+    if (!x || !Wg_p || !Wn_p || !Wg_s || !Wn_s || !W1 || !W2 || !dy || !topk_idx || !topk_gate ||
+        !fwd_workspace || !dx || !dWg_p || !dWn_p || !dWg_s || !dWn_s || !dW1 || !dW2 || !workspace)
+        return MOE_EINVAL;
+    const void *ptrs[] = {x, Wg_p, Wn_p, Wg_s, Wn_s, W1, W2, dy, fwd_workspace, dx, dWg_p, dWn_p, dWg_s, dWn_s,
+                          dW1, dW2, workspace};
+    for (const void *q : ptrs)
+        if (!aligned16(q)) return MOE_EINVAL;
+    if ((eps_p && !aligned16(eps_p)) || (eps_s && !aligned16(eps_s))) return MOE_EINVAL;
+    HierBwdLayout L;
+    hier_bwd_layout(cfg, &L);
+    if (workspace_bytes < L.total) return MOE_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t T = cfg->T, A = T * cfg->k, Ap = T * cfg->k_primary;
+    const int d = cfg->d, n = cfg->n, a = cfg->a, b = cfg->b, k_p = cfg->k_primary, k_s = cfg->k_secondary;
+    if (T == 0) return MOE_OK;
+    char *fw = (char *)fwd_workspace;   // read-only here
+    char *ws = (char *)workspace;
+
+    // experts (the flat kernels on the k_p * k_s assignments of every token)
+    const bool saved_hidden = F.hidden != (size_t)-1;
+    float *dgate = (float *)(ws + L.dgate), *dxs = (float *)(ws + L.dxs);
+    ExpertBwd eb{x, dy, (const float *)(fw + F.out_sorted), topk_gate, (const int32_t *)(fw + F.perm),
+                 (const int32_t *)(fw + F.offsets), W1, W2,
+                 saved_hidden ? (const uint16_t *)(fw + F.hidden) : nullptr, (uint16_t *)(ws + L.xs),
+                 (uint16_t *)(ws + L.dout), (uint16_t *)(ws + L.hid), (uint16_t *)(ws + L.dz), dxs, dgate,
+                 (int32_t *)(ws + L.tile_expert), (int32_t *)(ws + L.tile_row0), (int32_t *)(ws + L.num_tiles),
+                 (int32_t *)(ws + L.order), dW1, dW2};
+    if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
+
+    // Eq.(13),(14): gradients of both CV^2 with respect to Importance_H and Load_H, then into the levels
+    float *gI = (float *)(ws + L.gI), *gL = (float *)(ws + L.gL);
+    hipLaunchKernelGGL(loss_grad_kernel, dim3(1), dim3(256), 0, s, (const double *)(fw + F.aux_ws), n,
+                       cfg->w_importance, cfg->w_load, gI, gL);
+    MOE_LAUNCH_CHECK();
+    const float *p_gate = (const float *)(fw + F.p_gate), *s_gate = (const float *)(fw + F.s_gate);
+    const int32_t *p_idx = (const int32_t *)(fw + F.p_idx), *s_idx = (const int32_t *)(fw + F.s_idx);
+    const int32_t *p_offsets = (const int32_t *)(fw + F.p_offsets), *p_perm = (const int32_t *)(fw + F.p_perm);
+    const int32_t *p_inv_perm = (const int32_t *)(fw + F.p_inv_perm);
+    float *dGp = (float *)(ws + L.dGp), *dGs = (float *)(ws + L.dGs);
+    float *dLoad_p = (float *)(ws + L.dLoad_p), *dLoad_s = (float *)(ws + L.dLoad_s);
+    hipLaunchKernelGGL(hier_dgate_kernel, dim3((unsigned)ceil_div(Ap, 256)), dim3(256), 0, s, dgate, topk_idx, gI,
+                       p_gate, s_gate, Ap, k_s, dGp, dGs);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(hier_load_grads_kernel, dim3((unsigned)a), dim3(256), 0, s, gL,
+                       (const double *)(fw + F.p_aux_ws), (const float *)(fw + F.partials),
+                       (const int32_t *)(fw + F.p_counts), (const int32_t *)(fw + F.p_tile_offsets), a, b,
+                       kGateBM / gate_rows_per_block(Ap, b), dLoad_p, dLoad_s);
+    MOE_LAUNCH_CHECK();
+
+    // primary gate: rows = tokens
+    float *dclean_p = (float *)(ws + L.dclean_p), *draw_p = (float *)(ws + L.draw_p);
+    GateBwdArgs gp{(const float *)(fw + F.p_cleanb), (const float *)(fw + F.p_sp), eps_p, p_idx, p_gate, dGp,
+                   (const int32_t *)(fw + F.p_next_idx), nullptr, dLoad_p, dclean_p, draw_p, T, a, k_p};
+    hipLaunchKernelGGL(gate_bwd_rows_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s, gp);
+    MOE_LAUNCH_CHECK();
+    float *wpart = (float *)(ws + L.wpart);
+    SGArgs wa{};
+    wa.A[0] = x; wa.B[0] = dclean_p; wa.B[1] = draw_p; wa.C = wpart;
+    wa.M = d; wa.N = a; wa.K = (int)T; wa.lda = d; wa.ldb = a; wa.ldc = a; wa.nseg = 1;
+    wa.ksplit = L.ksplit;
+    wa.c_split_stride = (size_t)2 * d * a;
+    wa.c_which_stride = (size_t)d * a;
+    hipLaunchKernelGGL((sg_kernel<true, false>), dim3(ceil_div(d, SBM), ceil_div(a, SBN), 2 * L.ksplit), dim3(256),
+                       0, s, wa);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)ceil_div((int64_t)d * a, 256)), dim3(256), 0, s, wpart,
+                       L.ksplit, (size_t)2 * d * a, (size_t)d * a, dWg_p);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)ceil_div((int64_t)d * a, 256)), dim3(256), 0, s,
+                       wpart + (size_t)d * a, L.ksplit, (size_t)2 * d * a, (size_t)d * a, dWn_p);
+    MOE_LAUNCH_CHECK();
+    SGArgs xa{};
+    xa.A[0] = dclean_p; xa.A[1] = draw_p; xa.B[0] = Wg_p; xa.B[1] = Wn_p; xa.C = dx;
+    xa.M = (int)T; xa.N = d; xa.K = a; xa.lda = a; xa.ldb = a; xa.ldc = d; xa.nseg = 2; xa.ksplit = 1;
+    hipLaunchKernelGGL((sg_kernel<false, true>), dim3((unsigned)ceil_div(T, SBM), ceil_div(d, SBN), 1), dim3(256), 0,
+                       s, xa);
+    MOE_LAUNCH_CHECK();
+
+    // secondary gates: rows = (token, primary slot) pairs in the forward pass's group order
+    float *dclean_s = (float *)(ws + L.dclean_s), *draw_s = (float *)(ws + L.draw_s);
+    GateBwdArgs gs{(const float *)(fw + F.cleanb), (const float *)(fw + F.sp), eps_s, s_idx, s_gate, dGs,
+                   (const int32_t *)(fw + F.next_idx), nullptr, dLoad_s, dclean_s, draw_s, Ap, b, k_s,
+                   p_perm, p_offsets, a};
+    hipLaunchKernelGGL(gate_bwd_rows_kernel, dim3((unsigned)ceil_div(Ap, 4)), dim3(256), 0, s, gs);
+    MOE_LAUNCH_CHECK();
+    float *xg = (float *)(ws + L.xg), *dxg = (float *)(ws + L.dxg);
+    hipLaunchKernelGGL(gather_rows_f32_kernel, dim3((unsigned)ceil_div(Ap, 4)), dim3(256), 0, s, (const float4 *)x,
+                       p_perm, k_p, Ap, d / 4, (float4 *)xg);
+    MOE_LAUNCH_CHECK();
+    // per group: its two weight gradients over its own rows, and its rows of dx.  A token picks a
+    // group at most once, so no group has more than T rows.
+    for (int g = 0; g < a; ++g) {
+        for (int which = 0; which < 2; ++which) {
+            SGArgs wg{};
+            wg.A[0] = xg; wg.B[0] = which ? draw_s : dclean_s;
+            wg.C = (which ? dWn_s : dWg_s) + (size_t)g * d * b;
+            wg.M = d; wg.N = b; wg.K = 0; wg.lda = d; wg.ldb = b; wg.ldc = b; wg.nseg = 1; wg.ksplit = 1;
+            wg.range = p_offsets; wg.range_idx = g;
+            hipLaunchKernelGGL((sg_kernel<true, false>), dim3(ceil_div(d, SBM), ceil_div(b, SBN), 1), dim3(256), 0, s, wg);
+            MOE_LAUNCH_CHECK();
+        }
+        SGArgs xg_{};
+        xg_.A[0] = dclean_s; xg_.A[1] = draw_s;
+        xg_.B[0] = Wg_s + (size_t)g * d * b; xg_.B[1] = Wn_s + (size_t)g * d * b; xg_.C = dxg;
+        xg_.M = 0; xg_.N = d; xg_.K = b; xg_.lda = b; xg_.ldb = b; xg_.ldc = d; xg_.nseg = 2; xg_.ksplit = 1;
+        xg_.range = p_offsets; xg_.range_idx = g;
+        hipLaunchKernelGGL((sg_kernel<false, true>), dim3((unsigned)ceil_div(T, SBM), ceil_div(d, SBN), 1), dim3(256),
+                           0, s, xg_);
+        MOE_LAUNCH_CHECK();
+    }
+    // dx = primary part (written above) + secondary rows + expert rows
+    hipLaunchKernelGGL(dx_gather_add_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s, (float4 *)dx,
+                       (const float4 *)dxg, p_inv_perm, T, d / 4, k_p);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(dx_gather_add_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s, (float4 *)dx,
+                       (const float4 *)dxs, (const int32_t *)(fw + F.inv_perm), T, d / 4, cfg->k);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
 }
