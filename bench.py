@@ -145,6 +145,8 @@ def main():
     ap.add_argument("--gating", choices=["noisy_topk", "balanced"], default="noisy_topk",
                     help="balanced: the strictly balanced gate of Appendix F on the same workload "
                          "(flat forward configs only)")
+    ap.add_argument("--backward", action="store_true",
+                    help="hierarchical config: time forward + backward (moe_layer_backward_hier) per step")
     ap.add_argument("--optimizer", action="store_true",
                     help="training configs: also time the factored-second-moment Adam step of the expert "
                          "matrices (outside the timed region; reported under \"optimizer\")")
@@ -189,8 +191,16 @@ def main():
     elif shape.hierarchical:
         inputs = W.hier_gate_inputs(shape)
         W1, W2 = G.device_weights(shape, chunk=256)
-        run = G.HierRun(api, shape, inputs, W1, W2)
+        run = G.HierRun(api, shape, inputs, W1, W2, flags=api.MOE_FLAG_SAVE_HIDDEN if args.backward else 0)
         ws = run.workspace
+        if args.backward:
+            dy = G.dev(W.upstream_grad(shape))
+            f32 = dict(dtype=torch.float32, device="cuda")
+            hg = [torch.empty((shape.T, shape.d), **f32), torch.empty((shape.d, shape.a), **f32),
+                  torch.empty((shape.d, shape.a), **f32), torch.empty((shape.a, shape.d, shape.b), **f32),
+                  torch.empty((shape.a, shape.d, shape.b), **f32), torch.empty((shape.n, shape.d, shape.h), **f32),
+                  torch.empty((shape.n, shape.h, shape.d), **f32)]
+            hbws = torch.empty(api.moe_backward_hier_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
 
         def step(events=None):
             if events is not None and events[4]:
@@ -200,6 +210,10 @@ def main():
                                        run.importance, run.load, run.losses, ws)
             if events is not None and events[5]:
                 hip.record(events[5])
+            if args.backward:
+                api.moe_layer_backward_hier(run.cfg, run.x, run.Wg_p, run.Wn_p, run.eps_p, run.Wg_s, run.Wn_s,
+                                            run.eps_s, run.W1, run.W2, dy, run.topk_idx, run.topk_gate, ws, hg[0],
+                                            hg[1], hg[2], hg[3], hg[4], hg[5], hg[6], hbws)
     else:
         x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias=shape.zipf_beta > 0)
         W1, W2 = G.device_weights(shape)
@@ -283,7 +297,8 @@ def main():
     ms_per_step = elapsed / K * 1e3
 
     out = {
-        "metric": "MoE-layer tokens/sec (%s) at d=512,h=1024" % ("fwd+bwd" if shape.backward else "fwd"),
+        "metric": "MoE-layer tokens/sec (%s) at d=512,h=1024" % (
+            "fwd+bwd" if (shape.backward or (shape.hierarchical and args.backward)) else "fwd"),
         "value": shape.T / (elapsed / K),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,

@@ -64,9 +64,9 @@ typedef struct moe_config {
     int32_t flags;         /* MOE_FLAG_* */
 } moe_config;
 
-/* With MOE_FLAG_SAVE_HIDDEN moe_layer_forward also keeps the experts' hidden activations
- * (bf16 [T*k, h], routed-row order) in its workspace, and moe_layer_backward reads them instead
- * of recomputing them.  The paper
+/* With MOE_FLAG_SAVE_HIDDEN moe_layer_forward and moe_layer_forward_hier also keep the experts' hidden activations
+ * (bf16 [T*k, h], routed-row order) in the workspace, and moe_layer_backward / _hier read them
+ * instead of recomputing them.  The paper
  * recomputes (Appendix D) to fit 12 GB devices; with 288 GB of HBM the 2*h bytes per routed row
  * are the cheaper side of the trade.  Without the flag the backward pass recomputes. */
 enum { MOE_FLAG_SAVE_HIDDEN = 1 };
@@ -347,7 +347,8 @@ int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params *hp, const
  * moe_layer_forward_hier left it.  Outputs (overwritten): dx [T,d]; dWg_p, dWn_p [d,a];
  * dWg_s, dWn_s [a,d,b] (zeros for a group no token chose); dW1 [n,d,h], dW2 [n,h,d]; all f32.
  * bf16 experts, d and h multiples of 256, a and b multiples of 32; the hidden activations are
- * recomputed (Appendix D).  workspace: moe_backward_hier_workspace_bytes().
+ * recomputed (Appendix D) unless the forward call kept them (MOE_FLAG_SAVE_HIDDEN).
+ * workspace: moe_backward_hier_workspace_bytes().
  */
 size_t moe_backward_hier_workspace_bytes(const moe_config *cfg);
 int moe_layer_backward_hier(const moe_config *cfg, const float *x, const float *Wg_p,

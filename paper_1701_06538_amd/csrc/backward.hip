@@ -357,6 +357,13 @@ struct SGArgs {
     // otherwise they are the rows of A and C (M = their number; tiles past the end exit)
     const int32_t *range;
     int range_idx;
+    // several ranges in one launch.  A_MK: blockIdx.z = g, rows range[g] .. range[g+1] are contracted
+    // into C + g * c_group_stride (ksplit must be 1).  Otherwise: blockIdx.x indexes a table of
+    // 128-row tiles that never straddle ranges (tile_group, tile_row0, num_tiles); tile t covers
+    // rows tile_row0[t] .. of range g = tile_group[t] and multiplies by B + g * b_group_stride.
+    int range_groups;
+    size_t c_group_stride, b_group_stride;
+    const int32_t *tile_group, *tile_row0, *num_tiles;
 };
 
 constexpr int SBM = 128, SBN = 128, SKC = 32, SAS = SKC + 4;
@@ -389,22 +396,32 @@ __global__ __launch_bounds__(256) void sg_kernel(SGArgs p) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, l32 = lane & 31;
-    const int m0 = blockIdx.x * SBM, n0 = blockIdx.y * SBN;
+    int m0 = blockIdx.x * SBM;
+    const int n0 = blockIdx.y * SBN;
     int which = 0, split = 0;
-    if (A_MK) {
+    if (A_MK && !p.range_groups) {
         which = blockIdx.z / p.ksplit;
         split = blockIdx.z % p.ksplit;
     }
     int M_ = p.M, K_ = p.K;
     const float *A0 = p.A[0], *A1 = p.A[1], *B0 = p.B[0], *B1 = p.B[1];
     float *C_ = p.C;
-    if (p.range) {
-        const int lo = p.range[p.range_idx], hi = p.range[p.range_idx + 1];
+    if (p.range && !A_MK && p.tile_row0) {
+        if ((int)blockIdx.x >= *p.num_tiles) return;
+        const int g = p.tile_group[blockIdx.x];
+        m0 = p.tile_row0[blockIdx.x];
+        M_ = p.range[g + 1];
+        B0 += (size_t)g * p.b_group_stride;
+        B1 += (size_t)g * p.b_group_stride;
+    } else if (p.range) {
+        const int gi = p.range_idx + (p.range_groups ? (int)blockIdx.z : 0);
+        const int lo = p.range[gi], hi = p.range[gi + 1];
         if (A_MK) {
             K_ = hi - lo;
             A0 += (size_t)lo * p.lda;
             B0 += (size_t)lo * p.ldb;
             B1 += (size_t)lo * p.ldb;
+            if (p.range_groups) C_ += (size_t)blockIdx.z * p.c_group_stride;
         } else {
             M_ = hi - lo;
             if (m0 >= M_) return;
@@ -1023,25 +1040,27 @@ extern "C" int moe_layer_backward_hier(const moe_config *cfg, const float *x, co
     hipLaunchKernelGGL(gather_rows_f32_kernel, dim3((unsigned)ceil_div(Ap, 4)), dim3(256), 0, s, (const float4 *)x,
                        p_perm, k_p, Ap, d / 4, (float4 *)xg);
     MOE_LAUNCH_CHECK();
-    // per group: its two weight gradients over its own rows, and its rows of dx.  A token picks a
-    // group at most once, so no group has more than T rows.
-    for (int g = 0; g < a; ++g) {
-        for (int which = 0; which < 2; ++which) {
-            SGArgs wg{};
-            wg.A[0] = xg; wg.B[0] = which ? draw_s : dclean_s;
-            wg.C = (which ? dWn_s : dWg_s) + (size_t)g * d * b;
-            wg.M = d; wg.N = b; wg.K = 0; wg.lda = d; wg.ldb = b; wg.ldc = b; wg.nseg = 1; wg.ksplit = 1;
-            wg.range = p_offsets; wg.range_idx = g;
-            hipLaunchKernelGGL((sg_kernel<true, false>), dim3(ceil_div(d, SBM), ceil_div(b, SBN), 1), dim3(256), 0, s, wg);
-            MOE_LAUNCH_CHECK();
-        }
-        SGArgs xg_{};
-        xg_.A[0] = dclean_s; xg_.A[1] = draw_s;
-        xg_.B[0] = Wg_s + (size_t)g * d * b; xg_.B[1] = Wn_s + (size_t)g * d * b; xg_.C = dxg;
-        xg_.M = 0; xg_.N = d; xg_.K = b; xg_.lda = b; xg_.ldb = b; xg_.ldc = d; xg_.nseg = 2; xg_.ksplit = 1;
-        xg_.range = p_offsets; xg_.range_idx = g;
-        hipLaunchKernelGGL((sg_kernel<false, true>), dim3((unsigned)ceil_div(T, SBM), ceil_div(d, SBN), 1), dim3(256),
-                           0, s, xg_);
+    // every group's two weight gradients over its own rows (one launch each, a group per blockIdx.z),
+    // then every group's rows of dx on the forward pass's 128-row tiles, which never straddle groups
+    for (int which = 0; which < 2; ++which) {
+        SGArgs wg{};
+        wg.A[0] = xg; wg.B[0] = which ? draw_s : dclean_s;
+        wg.C = which ? dWn_s : dWg_s;
+        wg.M = d; wg.N = b; wg.K = 0; wg.lda = d; wg.ldb = b; wg.ldc = b; wg.nseg = 1; wg.ksplit = 1;
+        wg.range = p_offsets; wg.range_idx = 0; wg.range_groups = a; wg.c_group_stride = (size_t)d * b;
+        hipLaunchKernelGGL((sg_kernel<true, false>), dim3(ceil_div(d, SBM), ceil_div(b, SBN), a), dim3(256), 0, s, wg);
+        MOE_LAUNCH_CHECK();
+    }
+    {
+        SGArgs xr{};
+        xr.A[0] = dclean_s; xr.A[1] = draw_s; xr.B[0] = Wg_s; xr.B[1] = Wn_s; xr.C = dxg;
+        xr.M = 0; xr.N = d; xr.K = b; xr.lda = b; xr.ldb = b; xr.ldc = d; xr.nseg = 2; xr.ksplit = 1;
+        xr.range = p_offsets; xr.b_group_stride = (size_t)d * b;
+        xr.tile_group = (const int32_t *)(fw + F.p_tile_group);
+        xr.tile_row0 = (const int32_t *)(fw + F.p_tile_row0);
+        xr.num_tiles = (const int32_t *)(fw + F.p_num_tiles);
+        const unsigned max_tiles_p = (unsigned)(ceil_div(Ap, kGateBM) + a);
+        hipLaunchKernelGGL((sg_kernel<false, true>), dim3(max_tiles_p, ceil_div(d, SBN), 1), dim3(256), 0, s, xr);
         MOE_LAUNCH_CHECK();
     }
     // dx = primary part (written above) + secondary rows + expert rows

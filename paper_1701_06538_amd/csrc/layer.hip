@@ -43,7 +43,7 @@ int workspace_layout(const moe_config *cfg, moe_workspace_layout *L) {
     L->ffn_ws = take(moe_ffn_workspace_bytes(cfg));
     L->aux_ws = take(hier ? 2 * n * 8 : aux_ws_bytes(moe_gate_partial_rows(cfg), cfg->n));
     L->hidden = (size_t)-1;
-    if (!hier && (cfg->flags & MOE_FLAG_SAVE_HIDDEN) && cfg->expert_dtype == MOE_DTYPE_BF16)
+    if ((cfg->flags & MOE_FLAG_SAVE_HIDDEN) && cfg->expert_dtype == MOE_DTYPE_BF16)
         L->hidden = take(A * (size_t)cfg->h * 2);
     if (hier) {
         const size_t a = (size_t)cfg->a, kp = (size_t)cfg->k_primary, ks = (size_t)cfg->k_secondary;
@@ -347,8 +347,9 @@ extern "C" int moe_layer_forward_hier(const moe_config *cfg, const float *x, con
     st = moe_route(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0, num_tiles,
                    ws + L.route_ws, stream);
     if (st != MOE_OK) return st;
-    st = moe_expert_ffn(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2, out_sorted,
-                        ws + L.ffn_ws, stream);
+    st = expert_ffn_with_hidden(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2, out_sorted,
+                                ws + L.ffn_ws, L.hidden == (size_t)-1 ? nullptr : (uint16_t *)(ws + L.hidden),
+                                (hipStream_t)stream);
     if (st != MOE_OK) return st;
     st = moe_combine(cfg, out_sorted, topk_gate, inv_perm, y, stream);
     if (st != MOE_OK) return st;

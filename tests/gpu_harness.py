@@ -169,9 +169,9 @@ class BalancedRun:
 class HierRun:
     """One forward pass of the hierarchical layer on the GPU through the C ABI."""
 
-    def __init__(self, api, shape, inputs, W1, W2):
+    def __init__(self, api, shape, inputs, W1, W2, flags=0):
         self.api, self.shape = api, shape
-        self.cfg = api.make_config(shape)
+        self.cfg = api.make_config(shape, flags=flags)
         x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s = inputs
         self.x = dev(x)
         self.Wg_p, self.Wn_p, self.eps_p = dev(Wg_p), dev(Wn_p), dev(eps_p)

@@ -32,10 +32,10 @@ def fro_rel(got, ref):
     return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-def run_hier_backward(api, shape, dy, gate_std=0.02):
+def run_hier_backward(api, shape, dy, gate_std=0.02, flags=0):
     inputs = W.hier_gate_inputs(shape, gate_std)
     W1, W2 = G.device_weights(shape, chunk=256)
-    run = G.HierRun(api, shape, inputs, W1, W2)
+    run = G.HierRun(api, shape, inputs, W1, W2, flags=flags)
     run.forward()
     T, d, h, n, a, b = shape.T, shape.d, shape.h, shape.n, shape.a, shape.b
     f32 = dict(dtype=torch.float32, device="cuda")
@@ -68,6 +68,7 @@ CASES = [
     # name, overrides, gate std, loss weights or None.  Most cases use 256 x 256 experts: the oracle
     # generates every used expert's weights, and both gating levels need at least 32 x 32 = 1024 experts.
     ("small", dict(T=512, a=32, b=32, d=256, h=256), 0.02, None),
+    ("saved_hidden", dict(T=512, a=32, b=32, d=256, h=256, flags=1), 0.02, None),   # MOE_FLAG_SAVE_HIDDEN
     ("ragged_empty_groups", dict(T=333, a=64, b=32, k_primary=1, k_secondary=3, d=256, h=512), 0.05, None),
     ("losses_off", dict(T=400, a=32, b=32, d=256, h=256), 0.02, (0.0, 0.0)),
     ("paper_expert", dict(T=96, a=32, b=32), 0.02, None),
@@ -78,6 +79,7 @@ CASES = [
 @pytest.mark.parametrize("name,ov,std,wl", CASES, ids=[c[0] for c in CASES])
 def test_hier_backward_parity(api, name, ov, std, wl):
     ov = dict(ov)
+    flags = ov.pop("flags", 0)
     ov["n"] = ov["a"] * ov["b"]
     kp, ks = ov.get("k_primary", 2), ov.get("k_secondary", 2)
     ov["k"] = kp * ks
@@ -86,7 +88,7 @@ def test_hier_backward_parity(api, name, ov, std, wl):
     shape = W.scaled_config(W.CONFIGS[3], **ov)
     say("case hier backward", name, shape)
     dy = W.upstream_grad(shape)
-    inputs, run, out, call = run_hier_backward(api, shape, dy, std)
+    inputs, run, out, call = run_hier_backward(api, shape, dy, std, flags)
     hf = O.hier_gate_and_losses(*inputs, shape.k_primary, shape.k_secondary, shape.w_importance, shape.w_load)
     assert np.array_equal(run.topk_idx.cpu().numpy(), hf.idx)
     gr = oracle_hier_backward(shape, inputs, dy)
