@@ -417,17 +417,21 @@ def gate_level_backward(lg: Logits, idx, g, dgate, gL, k):
     return dclean, draw
 
 
-def experts_backward(xe_all, idx, g, weight_fn, dy, experts_for_dW=None):
+def experts_backward(xe_all, idx, g, weight_fn, dy, experts_for_dW=None, only=None):
     """Backward of Eq.(1) and of the experts (Appendix C) for assignments idx [T,k] with gate values
-    g [T,k]: returns (dx through the experts [T,d], dgate [T,k] = <dy_t, E_e(x_t)>, dW1, dW2)."""
+    g [T,k]: returns (dx through the experts [T,d], dgate [T,k] = <dy_t, E_e(x_t)>, dW1, dW2).
+    only: evaluate just these experts (for sampled checks of dW1/dW2 at sizes where the whole loop
+    is too slow; dx and dgate are then partial)."""
     xe_all = np.asarray(xe_all, np.float64)
     g = np.asarray(g, np.float64)
     dx = np.zeros_like(xe_all)
     dgate = np.zeros_like(g)
     dW1, dW2 = {}, {}
     keep = None if experts_for_dW is None else set(int(e) for e in experts_for_dW)
-    for e in np.unique(idx):
+    for e in (np.unique(idx) if only is None else sorted(set(int(q) for q in only))):
         r, s = np.nonzero(idx == e)
+        if r.size == 0:
+            continue
         W1, W2 = (np.asarray(w, np.float64) for w in weight_fn(int(e)))
         xe = xe_all[r]
         z = xe @ W1

@@ -106,7 +106,7 @@ def test_cfg3_full_hierarchical(api):
     W1, W2 = G.device_weights(shape, chunk=256)
     torch.cuda.synchronize()
     say("  34 GB of expert weights generated on the GPU in %.1f s" % (time.perf_counter() - t0))
-    run = G.HierRun(api, shape, inputs, W1, W2)
+    run = G.HierRun(api, shape, inputs, W1, W2, flags=api.MOE_FLAG_SAVE_HIDDEN)
     run.forward()
     assert np.array_equal(run.topk_idx.cpu().numpy(), hf.idx), "global expert ids differ"
     assert np.abs(run.topk_gate.cpu().numpy().astype(np.float64) - hf.gates).max() <= TOL_F32
@@ -130,3 +130,46 @@ def test_cfg3_full_hierarchical(api):
     assert torch.isfinite(run.y).all()
     ms = timed(run.forward, reps=3)
     say("  moe_layer_forward_hier %.3f ms -> %.2f M tokens/s" % (ms, shape.T / ms / 1e3))
+
+    # backward at full size (69 GB of fp32 weight gradients): the weight gradients of sampled
+    # experts against the oracle, properties for everything else (the whole backward is compared
+    # with the oracle at smaller sizes in test_gpu_hier_backward.py)
+    dy = W.upstream_grad(shape)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    T, d, h, n, a, b = shape.T, shape.d, shape.h, shape.n, shape.a, shape.b
+    out = dict(dx=torch.empty((T, d), **f32), dWg_p=torch.empty((d, a), **f32), dWn_p=torch.empty((d, a), **f32),
+               dWg_s=torch.empty((a, d, b), **f32), dWn_s=torch.empty((a, d, b), **f32),
+               dW1=torch.empty((n, d, h), **f32), dW2=torch.empty((n, h, d), **f32))
+    bws = torch.empty(api.moe_backward_hier_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+    dyd = G.dev(dy)
+
+    def backward():
+        api.moe_layer_backward_hier(run.cfg, run.x, run.Wg_p, run.Wn_p, run.eps_p, run.Wg_s, run.Wn_s, run.eps_s,
+                                    run.W1, run.W2, dyd, run.topk_idx, run.topk_gate, run.workspace, out["dx"],
+                                    out["dWg_p"], out["dWn_p"], out["dWg_s"], out["dWn_s"], out["dW1"],
+                                    out["dW2"], bws)
+    backward()
+    torch.cuda.synchronize()
+    sample = [int(np.argmax(counts)), 0, 1, b - 1, b, n // 2 + 3, n - 1] + [int(e) for e in np.nonzero(counts == 0)[0][:2]]
+    _, _, dW1s, dW2s = O.experts_backward(O.round_to_bf16(x), hf.idx, hf.gates, G.oracle_weight_fn(shape), dy,
+                                          only=sample)
+    worst = 0.0
+    for e in sorted(set(sample)):
+        g1, g2 = out["dW1"][e].cpu().numpy(), out["dW2"][e].cpu().numpy()
+        if e in dW1s:
+            for got, ref in ((g1, dW1s[e]), (g2, dW2s[e])):
+                rel = float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+                worst = max(worst, rel)
+        else:
+            assert counts[e] == 0 and not g1.any() and not g2.any()
+    say("  backward: worst relative error of the sampled experts' dW1/dW2 %.2e" % worst)
+    assert worst <= TOL_BF16
+    used = torch.from_numpy(counts > 0).cuda()
+    assert not out["dW1"][~used].any() and not out["dW2"][~used].any(), "experts without tokens must get zero gradients"
+    for k_, v in out.items():
+        assert torch.isfinite(v).all(), k_
+    groups_used = torch.from_numpy(hf.group_counts > 0).cuda()
+    assert not out["dWg_s"][~groups_used].any()
+    assert out["dx"].abs().max() > 0 and out["dWg_p"].abs().max() > 0
+    ms_b = timed(backward, reps=2)
+    say("  moe_layer_backward_hier %.3f ms" % ms_b)
