@@ -153,15 +153,21 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
 
 __global__ __launch_bounds__(256) void expert_order_kernel(const int32_t *__restrict__ offsets, int n,
                                                            int32_t *__restrict__ order) {
+    __shared__ int cs[2048];                       // counts of a chunk of experts
     const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= n) return;
-    const int c = offsets[e + 1] - offsets[e];
+    const int c = e < n ? offsets[e + 1] - offsets[e] : 0;
     int rank = 0;
-    for (int o = 0; o < n; ++o) {
-        const int co = offsets[o + 1] - offsets[o];
-        rank += co > c || (co == c && o < e);
+    for (int o0 = 0; o0 < n; o0 += 2048) {
+        const int m = min(2048, n - o0);
+        __syncthreads();
+        for (int i = threadIdx.x; i < m; i += 256) cs[i] = offsets[o0 + i + 1] - offsets[o0 + i];
+        __syncthreads();
+        for (int i = 0; i < m; ++i) {
+            const int co = cs[i];
+            rank += co > c || (co == c && o0 + i < e);
+        }
     }
-    order[rank] = e;
+    if (e < n) order[rank] = e;
 }
 
 int launch_expert_order(const int32_t *offsets, int n, int32_t *order, hipStream_t st) {
