@@ -48,8 +48,8 @@ enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
  * runs on a fused kernel that keeps the hidden layer on chip, other shapes on a plain two-GEMM
  * path with the hidden layer in the workspace); fp32 experts: d and h multiples of 4;
  * 1 <= k <= min(n, 8) (per level when hierarchical); n <= 16384, at most 2048 experts per
- * gating level; T*k < 2^31.  moe_layer_backward: bf16 experts, d and h multiples of 256,
- * n a multiple of 32. */
+ * gating level; T*k < 2^31.  moe_layer_backward: n a multiple of 4; bf16 experts with d and h
+ * multiples of 256, or fp32 experts. */
 typedef struct moe_config {
     int32_t T;             /* tokens in the batch */
     int32_t d;             /* model width: expert input and output size */
@@ -225,8 +225,10 @@ int moe_layer_forward_hier(const moe_config *cfg, const float *x, const float *W
  * workspace exactly as moe_layer_forward left it (logits, permutation, expert outputs, loss sums).
  * Outputs (overwritten): dx [T,d], dW_g, dW_noise [d,n], dW1 [n,d,h], dW2 [n,h,d], all f32
  * (fp32 master gradients; experts that received no token get zeros).
- * bf16 experts only, d and h multiples of 256, n a multiple of 32; expert math in bf16 MFMA with
- * fp32 accumulation, gate math in fp32.  workspace: moe_backward_workspace_bytes().
+ * n a multiple of 4.  bf16 experts: d and h multiples of 256, expert math in bf16 MFMA with fp32
+ * accumulation.  fp32 experts: d and h multiples of 4, n <= 65535, every GEMM on the fp32 matrix
+ * cores; the hidden activations are the ones the forward pass left in its expert workspace.
+ * Gate math in fp32.  workspace: moe_backward_workspace_bytes().
  */
 size_t moe_backward_workspace_bytes(const moe_config *cfg);
 int moe_layer_backward(const moe_config *cfg, const float *x, const float *W_g,

@@ -373,7 +373,7 @@ typedef float v2f32 __attribute__((ext_vector_type(2)));
 
 // A_MK: A(m,k) = A[k*lda + m] (m contiguous; used for x^T), else A(m,k) = A[m*lda + k].
 // B_NK: B(k,n) = B[n*ldb + k] (k contiguous; used for W^T), else B(k,n) = B[k*ldb + n].
-// M, N, lda, ldb, ldc are multiples of 4; without A_MK, K is a multiple of 32.
+// M, N, K, lda, ldb, ldc are multiples of 4.
 //
 // 128 x 128 tile, four waves x (32 rows x four 32x32 tiles of v_mfma_f32_32x32x2f32).  An operand
 // whose rows are contiguous in k is staged in LDS as [row][k parity][k/2] (a lane's 16-byte read
@@ -630,10 +630,11 @@ static int bwd_layout(const moe_config *cfg, BwdLayout *L) {
         off = up256(off + (b ? b : 1));
         return at;
     };
-    L->xs = take(A * d * 2);
-    L->dout = take(A * d * 2);
+    const size_t es = cfg->expert_dtype == MOE_DTYPE_BF16 ? 2 : 4;   // fp32 experts keep fp32 rows
+    L->xs = take(A * d * es);
+    L->dout = take(A * d * es);
     L->hid = take(A * h * 2);
-    L->dz = take(A * h * 2);
+    L->dz = take(A * h * es);
     L->dxs = take(A * d * 4);
     L->dgate = take(A * 4);
     L->dclean = take(T * n * 4);
@@ -659,6 +660,98 @@ static int bwd_layout(const moe_config *cfg, BwdLayout *L) {
 
 int launch_build_tiles(const int32_t *offsets, int n, int tile_rows, int32_t *tile_expert,
                        int32_t *tile_row0, int32_t *num_tiles, hipStream_t st);
+
+// fp32 experts: the same per-row preparation without rounding
+__global__ __launch_bounds__(256) void bwd_prepare_f32_kernel(const float *__restrict__ x,
+                                                              const float *__restrict__ dy,
+                                                              const float *__restrict__ out_sorted,
+                                                              const float *__restrict__ gate,
+                                                              const int32_t *__restrict__ perm, int64_t A,
+                                                              int d, int k, float *__restrict__ xs,
+                                                              float *__restrict__ dout,
+                                                              float *__restrict__ dgate) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= A) return;
+    const int a = perm[r];
+    const int64_t t = a / k;
+    const float g = gate[a];
+    float dot = 0.f;
+    for (int c = lane * 4; c < d; c += 256) {
+        const float4 vy = *reinterpret_cast<const float4 *>(dy + t * d + c);
+        const float4 vo = *reinterpret_cast<const float4 *>(out_sorted + r * d + c);
+        dot = fmaf(vy.x, vo.x, dot); dot = fmaf(vy.y, vo.y, dot);
+        dot = fmaf(vy.z, vo.z, dot); dot = fmaf(vy.w, vo.w, dot);
+        *reinterpret_cast<float4 *>(dout + r * d + c) = make_float4(g * vy.x, g * vy.y, g * vy.z, g * vy.w);
+        *reinterpret_cast<float4 *>(xs + r * d + c) = *reinterpret_cast<const float4 *>(x + t * d + c);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+    if (lane == 0) dgate[a] = dot;
+}
+
+// dz = dh * [hid > 0]   (relu'(0) = 0: the stored hidden value is positive iff z > 0)
+__global__ __launch_bounds__(256) void relu_mask_f32_kernel(float4 *__restrict__ dz, const float4 *__restrict__ hid,
+                                                            int64_t count4) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count4) return;
+    float4 v = dz[i];
+    const float4 m = hid[i];
+    v.x = m.x > 0.f ? v.x : 0.f; v.y = m.y > 0.f ? v.y : 0.f;
+    v.z = m.z > 0.f ? v.z : 0.f; v.w = m.w > 0.f ? v.w : 0.f;
+    dz[i] = v;
+}
+
+// The experts' share of the backward pass for fp32 experts, entirely on the fp32 matrix cores:
+// the grouped forms of sg_kernel (a group = an expert's rows) serve all four GEMMs.  hid are the
+// hidden activations the fp32 forward pass keeps in its expert workspace.
+struct ExpertBwdF32 {
+    const float *x, *dy, *out_sorted, *gate;
+    const int32_t *perm, *offsets;
+    const float *W1, *W2, *hid;
+    float *xs, *dout, *dz, *dxs, *dgate;
+    int32_t *tile_expert, *tile_row0, *num_tiles;
+    float *dW1, *dW2;
+};
+
+static int run_expert_backward_f32(const moe_config *cfg, const ExpertBwdF32 &b, hipStream_t s) {
+    const int64_t A = (int64_t)cfg->T * cfg->k;
+    const int d = cfg->d, h = cfg->h, n = cfg->n, k = cfg->k;
+    if (n > 65535) return MOE_EUNSUPPORTED;   // an expert per blockIdx.z
+    int st;
+    hipLaunchKernelGGL(bwd_prepare_f32_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, s, b.x, b.dy,
+                       b.out_sorted, b.gate, b.perm, A, d, k, b.xs, b.dout, b.dgate);
+    MOE_LAUNCH_CHECK();
+    if ((st = launch_build_tiles(b.offsets, n, SBM, b.tile_expert, b.tile_row0, b.num_tiles, s)) != MOE_OK) return st;
+    const unsigned max_tiles = (unsigned)(ceil_div(A, SBM) + n);
+    auto rows_form = [&](const float *Arows, int K, const float *Bw, int N, float *C) {
+        SGArgs r{};
+        r.A[0] = Arows; r.B[0] = Bw; r.C = C;
+        r.M = 0; r.N = N; r.K = K; r.lda = K; r.ldb = K; r.ldc = N; r.nseg = 1; r.ksplit = 1;
+        r.range = b.offsets; r.b_group_stride = (size_t)K * N;
+        r.tile_group = b.tile_expert; r.tile_row0 = b.tile_row0; r.num_tiles = b.num_tiles;
+        hipLaunchKernelGGL((sg_kernel<false, true>), dim3(max_tiles, ceil_div(N, SBN), 1), dim3(256), 0, s, r);
+    };
+    auto wgrad_form = [&](const float *Arows, int M, const float *Brows, int N, float *C) {
+        SGArgs w{};
+        w.A[0] = Arows; w.B[0] = Brows; w.C = C;
+        w.M = M; w.N = N; w.K = 0; w.lda = M; w.ldb = N; w.ldc = N; w.nseg = 1; w.ksplit = 1;
+        w.range = b.offsets; w.range_idx = 0; w.range_groups = n; w.c_group_stride = (size_t)M * N;
+        hipLaunchKernelGGL((sg_kernel<true, false>), dim3(ceil_div(M, SBM), ceil_div(N, SBN), n), dim3(256), 0, s, w);
+    };
+    rows_form(b.dout, d, b.W2, h, b.dz);          // dh[r, j] = sum_c dout[r, c] W2[j, c]
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(relu_mask_f32_kernel, dim3((unsigned)ceil_div(A * h / 4, 256)), dim3(256), 0, s,
+                       (float4 *)b.dz, (const float4 *)b.hid, A * h / 4);
+    MOE_LAUNCH_CHECK();
+    wgrad_form(b.hid, h, b.dout, d, b.dW2);       // dW2_e = hid_e^T dout_e
+    MOE_LAUNCH_CHECK();
+    wgrad_form(b.xs, d, b.dz, h, b.dW1);          // dW1_e = xs_e^T dz_e
+    MOE_LAUNCH_CHECK();
+    rows_form(b.dz, h, b.W1, d, b.dxs);           // dxs[r, c] = sum_j dz[r, j] W1[c, j]
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
 
 // The experts' share of a backward pass, for any assignment list (flat or hierarchical gate):
 // Eq.(1) per routed row, the two-layer expert's backward GEMMs and both weight gradients.
@@ -723,8 +816,9 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     int st = moe_get_workspace_layout(cfg, &F);
     if (st != MOE_OK) return st;
     if (cfg->a != 0) return MOE_EUNSUPPORTED;           // flat layer only
-    if (cfg->expert_dtype != MOE_DTYPE_BF16) return MOE_EUNSUPPORTED;
-    if (cfg->d % 256 != 0 || cfg->h % 256 != 0 || cfg->n % 32 != 0) return MOE_EUNSUPPORTED;
+    const bool f32_experts = cfg->expert_dtype != MOE_DTYPE_BF16;
+    if (!f32_experts && (cfg->d % 256 != 0 || cfg->h % 256 != 0)) return MOE_EUNSUPPORTED;
+    if (cfg->d % 4 != 0 || cfg->h % 4 != 0 || cfg->n % 4 != 0) return MOE_EUNSUPPORTED;
     if (!x || !W_g || !W_noise || !W1 || !W2 || !dy || !topk_idx || !topk_gate || !fwd_workspace ||
         !dx || !dW_g || !dW_noise || !dW1 || !dW2 || !workspace)
         return MOE_EINVAL;
@@ -757,10 +851,17 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
     int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
 
-    ExpertBwd eb{x, dy, out_sorted, topk_gate, perm, offsets, W1, W2, saved_hidden ? hid : nullptr,
-                 xs, dout, saved_hidden ? nullptr : hid, dz, dxs, dgate, tile_expert, tile_row0, num_tiles,
-                 (int32_t *)(ws + L.order), dW1, dW2};
-    if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
+    if (f32_experts) {
+        ExpertBwdF32 ef{x, dy, out_sorted, topk_gate, perm, offsets, (const float *)W1, (const float *)W2,
+                        (const float *)(fw + F.ffn_ws), (float *)xs, (float *)dout, (float *)dz, dxs, dgate,
+                        tile_expert, tile_row0, num_tiles, dW1, dW2};
+        if ((st = run_expert_backward_f32(cfg, ef, s)) != MOE_OK) return st;
+    } else {
+        ExpertBwd eb{x, dy, out_sorted, topk_gate, perm, offsets, W1, W2, saved_hidden ? hid : nullptr,
+                     xs, dout, saved_hidden ? nullptr : hid, dz, dxs, dgate, tile_expert, tile_row0, num_tiles,
+                     (int32_t *)(ws + L.order), dW1, dW2};
+        if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
+    }
 
     // gate
     hipLaunchKernelGGL(loss_grad_kernel, dim3(1), dim3(256), 0, s, sums64, n, cfg->w_importance,

@@ -75,7 +75,8 @@ def oracle_backward(shape, inputs, dy, experts_for_dW=None):
     fw = G.oracle_flat(shape, x, W_g, W_noise, eps, bias)
     # bf16 workloads: the experts' input activations are bf16(x) (the ReLU mask is decided on them)
     gr = O.flat_backward(x, W_g, W_noise, fw, shape.k, G.oracle_weight_fn(shape), dy, shape.w_importance,
-                         shape.w_load, experts_for_dW=experts_for_dW, expert_input=O.round_to_bf16(x))
+                         shape.w_load, experts_for_dW=experts_for_dW,
+                         expert_input=O.round_to_bf16(x) if shape.expert_dtype == "bf16" else None)
     return fw, gr
 
 
@@ -87,7 +88,12 @@ CASES = [
     ("cfg1_shape", dict(T=2048, n=256), False, 0),           # the other flat workloads' expert counts
     ("cfg2_shape", dict(T=3000, n=2048), False, 1),          # (few rows per expert, many empty experts)
     ("d256_h512", dict(T=600, n=32, d=256, h=512), False, 0),  # experts off the fused kernel's shape
+    ("n20_bf16", dict(T=400, n=20, k=3), False, 0),            # expert count off the tile sizes
+    # fp32 experts: every GEMM on the fp32 matrix cores
+    ("cfg0_f32", dict(T=256, n=16, k=4, expert_dtype="f32"), False, 0),
+    ("f32_ragged", dict(T=150, d=64, h=96, n=8, k=2, expert_dtype="f32"), True, 0),
 ]
+TOL_F32_EXPERTS = 1e-5
 
 
 @pytest.mark.parametrize("name,ov,with_bias,flags", CASES, ids=[c[0] for c in CASES])
@@ -114,8 +120,9 @@ def test_backward_parity(api, name, ov, with_bias, flags):
             assert not dW1[e].any() and not dW2[e].any(), "expert without tokens must get zero gradients"
     errs["dW1"], errs["dW2"] = worst1, worst2
     say("  relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+    tol = TOL_BF16 if shape.expert_dtype == "bf16" else TOL_F32_EXPERTS
     for k, v in errs.items():
-        assert v <= TOL_BF16, (k, v)
+        assert v <= tol, (k, v)
     # bit-reproducible
     keep = {k: v.clone() for k, v in out.items()}
     call()
