@@ -161,6 +161,19 @@ int moe_expert_ffn(const moe_config *cfg, const float *x, const int32_t *perm,
 int moe_combine(const moe_config *cfg, const float *out_sorted, const float *topk_gate,
                 const int32_t *inv_perm, float *y, void *stream);
 
+/*
+ * moe_combine fused with what the paper's language models put behind the MoE layer (Appendix C,
+ * "Model Architecture"): sigmoid of the layer output, dropout (each activation dropped with
+ * probability drop_prob, survivors divided by 1 - drop_prob), then the residual connection:
+ *     y = x + keep * sigmoid(sum_s gate[t,s] out_sorted[row(t,s)]) / (1 - drop_prob).
+ * keep [T,d] u8 is the dropout draw (non-zero = the activation survives; 4-byte aligned), an input
+ * like every random number of the method, or NULL for no dropout (drop_prob must then be 0);
+ * x [T,d] is the layer's input, or NULL for no residual connection.  0 <= drop_prob < 1.
+ */
+int moe_combine_epilogue(const moe_config *cfg, const float *out_sorted, const float *topk_gate,
+                         const int32_t *inv_perm, const float *x, const uint8_t *keep,
+                         float drop_prob, float *y, void *stream);
+
 /* ---- a5: balancing losses, Eq.(6),(7),(10),(11) ---------------------------------------- */
 /* partials from moe_gate -> importance [n] f32, load [n] f32, losses [4] f32 =
  * {w_importance*CV^2(importance), w_load*CV^2(load), CV^2(importance), CV^2(load)}; CV^2 uses

@@ -13,6 +13,7 @@ from .generators import (  # noqa: F401
     expert_weights,
     expert_weights_all,
     zipf_gate_bias,
+    dropout_keep,
     upstream_grad,
     STREAMS,
 )

@@ -20,7 +20,7 @@ STREAMS = {
     "x": 1, "W_g": 2, "W_noise": 3, "eps": 4, "dy": 5,
     "W_g_primary": 6, "W_noise_primary": 7, "eps_primary": 8,
     "W_g_secondary": 9, "W_noise_secondary": 10, "eps_secondary": 11,
-    "zipf_perm": 12,
+    "zipf_perm": 12, "dropout": 13,
 }
 
 _M32 = 0xFFFFFFFF
@@ -60,6 +60,13 @@ def hier_gate_inputs(cfg, gate_std: float = 0.02):
 
 def upstream_grad(cfg) -> np.ndarray:
     return normal_f32(cfg.seed, "dy", (cfg.T, cfg.d))
+
+
+def dropout_keep(cfg, drop_prob: float) -> np.ndarray:
+    """The dropout draw for the layer output [T,d] as bytes: 1 = the activation survives (uniform
+    numbers from Philox keyed by (seed, "dropout"), kept where u >= drop_prob)."""
+    gen = np.random.Generator(np.random.Philox(key=[cfg.seed & _M64, STREAMS["dropout"]]))
+    return (gen.random(size=(cfg.T, cfg.d), dtype=np.float32) >= drop_prob).astype(np.uint8)
 
 
 def zipf_gate_bias(cfg, s: float = 1.1) -> np.ndarray:

@@ -712,3 +712,21 @@ def factored_adam_step(W, G, v_row, v_col, lr, beta2, eps, step):
         return W.copy(), v_row, v_col
     vhat = np.outer(v_row, v_col) / m / (1.0 - beta2 ** step)
     return W - lr * G / (np.sqrt(vhat) + eps), v_row, v_col
+
+
+# --------------------------------------------------------------------------------------
+# Appendix C, "Model Architecture": what the language models do with the MoE layer's output
+# --------------------------------------------------------------------------------------
+
+def layer_epilogue(y, x, keep, drop_prob):
+    """out = x + dropout(sigmoid(y)): the MoE output goes through a sigmoid, each activation is
+    dropped with probability drop_prob and the survivors are divided by 1 - drop_prob, then the
+    layer's input is added (residual connection).  keep [T,d] bool is the dropout draw (an input:
+    True = the activation survives); keep=None means no dropout (drop_prob must then be 0)."""
+    y = np.asarray(y, np.float64)
+    s = 1.0 / (1.0 + np.exp(-y))
+    if keep is None:
+        assert drop_prob == 0.0
+        return np.asarray(x, np.float64) + s
+    assert 0.0 <= drop_prob < 1.0
+    return np.asarray(x, np.float64) + np.where(np.asarray(keep, bool), s / (1.0 - drop_prob), 0.0)

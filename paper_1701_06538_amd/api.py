@@ -101,6 +101,8 @@ _moe_backward_hier_workspace_bytes = _proto("moe_backward_hier_workspace_bytes",
 _moe_layer_backward_hier = _proto("moe_layer_backward_hier", ctypes.c_int,
                                   [_cfgp] + [_vp] * 21 + [ctypes.c_size_t, _vp])
 
+_moe_combine_epilogue = _proto("moe_combine_epilogue", ctypes.c_int, [_cfgp] + [_vp] * 5 + [ctypes.c_float, _vp, _vp])
+
 
 class MoeAdamParams(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
@@ -362,3 +364,8 @@ def moe_layer_backward_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, W1, W2
                                     _ptr(topk_gate), _ptr(fwd_workspace), _ptr(dx), _ptr(dWg_p), _ptr(dWn_p),
                                     _ptr(dWg_s), _ptr(dWn_s), _ptr(dW1), _ptr(dW2), _ptr(workspace),
                                     _nbytes(workspace), _stream(stream)))
+
+
+def moe_combine_epilogue(cfg, out_sorted, topk_gate, inv_perm, x, keep, drop_prob, y, stream=None):
+    _check(_moe_combine_epilogue(ctypes.byref(cfg), _ptr(out_sorted), _ptr(topk_gate), _ptr(inv_perm), _ptr(x),
+                                 _ptr(keep), drop_prob, _ptr(y), _stream(stream)))

@@ -252,3 +252,37 @@ def test_empty_batch(api):
     counts = run.workspace[L.counts:L.counts + 4 * shape.n].view(torch.int32).cpu().numpy()
     assert not counts.any()
     assert not run.losses.cpu().numpy().any() and not run.importance.cpu().numpy().any()
+
+
+@pytest.mark.parametrize("which", ["cfg0_f32", "bf16_ragged"])
+def test_combine_epilogue(api, which):
+    """Appendix C: sigmoid, dropout and the residual connection fused into the combine."""
+    say("combine epilogue", which)
+    shape = W.CONFIGS[0] if which == "cfg0_f32" else _shape(1, T=300, n=8, k=2)
+    tol = TOL_F32 if which == "cfg0_f32" else TOL_BF16
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape)
+    fw = G.oracle_flat(shape, x, W_g, W_noise, eps, bias)
+    W1, W2 = G.device_weights(shape)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+    run.stages()
+    y_ref = O.moe_output(x, fw.idx, fw.gates, G.oracle_weight_fn(shape), shape.n)
+    out = torch.full_like(run.y, float("nan"))
+    for p, with_x in ((0.4, True), (0.1, False)):
+        keep = W.dropout_keep(shape, p)
+        assert 0 < keep.mean() < 1
+        api.moe_combine_epilogue(run.cfg, run.out_sorted, run.topk_gate, run.inv_perm, run.x if with_x else None,
+                                 G.dev(keep), p, out)
+        torch.cuda.synchronize()
+        ref = O.layer_epilogue(y_ref, x if with_x else np.zeros_like(x), keep.astype(bool), p)
+        row, mx = G.rel_errors(out.cpu().numpy(), ref)
+        say("  p=%.1f residual=%s: row-rel %.2e max-rel %.2e" % (p, with_x, row, mx))
+        assert mx <= tol
+        if with_x:
+            assert row <= tol
+        assert (out.cpu().numpy()[keep == 0] == (x[keep == 0] if with_x else 0)).all()   # dropped: only the residual
+    api.moe_combine_epilogue(run.cfg, run.out_sorted, run.topk_gate, run.inv_perm, run.x, None, 0.0, out)
+    torch.cuda.synchronize()
+    row, mx = G.rel_errors(out.cpu().numpy(), O.layer_epilogue(y_ref, x, None, 0.0))
+    assert row <= tol and mx <= tol
+    with pytest.raises(api.MoeError):
+        api.moe_combine_epilogue(run.cfg, run.out_sorted, run.topk_gate, run.inv_perm, run.x, None, 0.3, out)

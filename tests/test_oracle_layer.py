@@ -302,3 +302,26 @@ def test_hierarchical_backward_with_one_group_is_the_flat_backward():
     for e in fl.dW1:
         assert np.allclose(gr.dW1[e], fl.dW1[e], rtol=1e-10, atol=1e-12)
         assert np.allclose(gr.dW2[e], fl.dW2[e], rtol=1e-10, atol=1e-12)
+
+
+def test_layer_epilogue_closed_forms():
+    """Appendix C: sigmoid, inverted dropout, residual.  Checked against scipy's logistic function,
+    the p = 0 and all-dropped special cases, and the 1/(1-p) scaling that keeps the expectation."""
+    from scipy.special import expit
+    rng = np.random.default_rng(31)
+    y = 4.0 * rng.standard_normal((50, 8))
+    x = rng.standard_normal((50, 8))
+    assert np.allclose(O.layer_epilogue(y, x, None, 0.0), x + expit(y), rtol=1e-14)
+    keep_all = np.ones_like(y, bool)
+    assert np.allclose(O.layer_epilogue(y, x, keep_all, 0.25), x + expit(y) / 0.75, rtol=1e-14)
+    assert np.array_equal(O.layer_epilogue(y, x, ~keep_all, 0.25), x)
+    # averaged over every mask with exactly half the units kept, dropout with p = 1/2 is the identity
+    import itertools
+    yy, xx = y[:1, :4], x[:1, :4]
+    acc = np.zeros_like(yy)
+    masks = [m for m in itertools.product([False, True], repeat=4) if sum(m) == 2]
+    for m in masks:
+        acc += O.layer_epilogue(yy, xx, np.array(m)[None, :], 0.5)
+    assert np.allclose(acc / len(masks), xx + expit(yy), rtol=1e-13)
+    # symmetry of the logistic function: sigmoid(-y) = 1 - sigmoid(y)
+    assert np.allclose(O.layer_epilogue(-y, 0 * x, None, 0.0), 1.0 - O.layer_epilogue(y, 0 * x, None, 0.0), atol=1e-15)
