@@ -113,3 +113,32 @@ def test_workspace_layout_is_ordered_aligned_and_sized(api):
     f32 = api.make_config(T=256, d=512, h=1024, n=16, k=4, expert_dtype=api.MOE_DTYPE_F32)
     assert api.moe_ffn_workspace_bytes(f32) == 256 * 4 * 1024 * 4
     assert api.moe_ffn_workspace_bytes(cfg) == 0
+
+
+def test_widened_entry_points_validate_on_the_host(api):
+    """Balanced gating, threshold inference, the hierarchical backward, the Adam step and the combine
+    epilogue reject bad shapes and null pointers before anything is launched."""
+    flat = api.make_config(T=64, d=512, h=1024, n=16, k=4)
+    assert api.moe_balanced_rows_per_expert(flat) == 16
+    assert api.moe_balanced_workspace_bytes(flat) > 0
+    odd = api.make_config(T=63, d=512, h=1024, n=16, k=3)            # 189 rows do not split over 16 experts
+    assert api.moe_balanced_rows_per_expert(odd) == -1 and api.moe_balanced_workspace_bytes(odd) == 0
+    assert api._moe_gate_balanced(ctypes.byref(flat), *([None] * 10), 0, None) == api.MOE_EINVAL
+    assert api._moe_gate_balanced(ctypes.byref(odd), *([None] * 10), 0, None) == api.MOE_EINVAL
+    assert api._moe_layer_forward_balanced(ctypes.byref(flat), *([None] * 13), 0, None) == api.MOE_EINVAL
+    assert api.moe_threshold_workspace_bytes(flat, 1000) > api.moe_threshold_workspace_bytes(flat, 10) > 0
+    assert api.moe_threshold_workspace_bytes(flat, -1) == 0
+    assert api._moe_layer_forward_threshold(ctypes.byref(flat), *([None] * 6), 100, *([None] * 8), 0, None) == api.MOE_EINVAL
+    hier = api.make_config(T=64, d=512, h=1024, n=1024, k=4, a=32, b=32, k_primary=2, k_secondary=2)
+    assert api.moe_backward_hier_workspace_bytes(hier) > 0
+    assert api.moe_backward_hier_workspace_bytes(flat) == 0
+    small_groups = api.make_config(T=64, d=512, h=1024, n=64, k=4, a=8, b=8, k_primary=2, k_secondary=2)
+    assert api.moe_backward_hier_workspace_bytes(small_groups) == 0   # group counts off the GEMM slabs
+    assert api._moe_layer_backward_hier(ctypes.byref(hier), *([None] * 21), 0, None) == api.MOE_EINVAL
+    assert api._moe_layer_backward_hier(ctypes.byref(flat), *([None] * 21), 0, None) == api.MOE_EINVAL
+    assert api.moe_adam_workspace_bytes(flat) > 0
+    hp = api.MoeAdamParams(1e-3, 0.999, 1e-8, 1)
+    assert api._moe_expert_adam_step(ctypes.byref(flat), ctypes.byref(hp), *([None] * 11), 0, None) == api.MOE_EINVAL
+    assert api._moe_combine_epilogue(ctypes.byref(flat), *([None] * 5), 0.0, None, None) == api.MOE_EINVAL
+    # fp32 experts and expert counts off the tile sizes are accepted by the flat backward
+    assert api.moe_backward_workspace_bytes(api.make_config(T=64, d=64, h=96, n=20, k=2, expert_dtype=api.MOE_DTYPE_F32)) > 0
