@@ -279,6 +279,11 @@ int moe_gate_balanced(const moe_config *cfg, const float *x, const float *W_g,
                       const float *gate_bias, const float *thresholds, float *gsigma,
                       int32_t *tokens, uint32_t *kept, float *denom, float *loss_batchwise,
                       void *workspace, size_t workspace_bytes, void *stream);
+/* What trains the thresholds: d L_batchwise / d T_i = m - #{t : G_sigma(t,i) > T_i} (both masks of
+ * Eq.(20) are piecewise constant in T).  gsigma [T,n] as moe_gate_balanced wrote it, thresholds [n]
+ * -> dthresholds [n] f32.  cfg as for moe_gate_balanced. */
+int moe_batchwise_loss_grad(const moe_config *cfg, const float *gsigma, const float *thresholds,
+                            float *dthresholds, void *stream);
 /*
  * The whole layer with that gate: moe_gate_balanced, the experts of Section 3.2 / Appendix C on
  * their m rows each (W1 [n,d,h], W2 [n,h,d] as in moe_expert_ffn), and Eq.(1) with the gates of

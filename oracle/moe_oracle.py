@@ -668,6 +668,14 @@ def batchwise_loss(X, mask, thresholds):
     return float((diff * (X - Tv)).sum())
 
 
+def batchwise_loss_dthresholds(X, mask, thresholds):
+    """d L_batchwise / d T_i (Eq.(20)).  Both masks are piecewise constant in T, so only the factor
+    (X_ji - T_i) varies: the derivative is -sum_j (M_threshold - M_batchwise)_ji, i.e. the number of
+    tokens the batchwise mask keeps for expert i minus the number above its threshold."""
+    diff = threshold_mask(X, thresholds).astype(np.float64) - np.asarray(mask, np.float64)
+    return -diff.sum(axis=0)
+
+
 def balanced_output(x, G, weight_fn, token_subset=None):
     """Eq.(1) with the gates of Eq.(16): y_t = sum_i G(x_t)_i E_i(x_t)."""
     x64 = np.asarray(x, np.float64)

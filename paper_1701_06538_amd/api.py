@@ -103,6 +103,8 @@ _moe_layer_backward_hier = _proto("moe_layer_backward_hier", ctypes.c_int,
 
 _moe_combine_epilogue = _proto("moe_combine_epilogue", ctypes.c_int, [_cfgp] + [_vp] * 5 + [ctypes.c_float, _vp, _vp])
 
+_moe_batchwise_loss_grad = _proto("moe_batchwise_loss_grad", ctypes.c_int, [_cfgp] + [_vp] * 4)
+
 
 class MoeAdamParams(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
@@ -369,3 +371,8 @@ def moe_layer_backward_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, W1, W2
 def moe_combine_epilogue(cfg, out_sorted, topk_gate, inv_perm, x, keep, drop_prob, y, stream=None):
     _check(_moe_combine_epilogue(ctypes.byref(cfg), _ptr(out_sorted), _ptr(topk_gate), _ptr(inv_perm), _ptr(x),
                                  _ptr(keep), drop_prob, _ptr(y), _stream(stream)))
+
+
+def moe_batchwise_loss_grad(cfg, gsigma, thresholds, dthresholds, stream=None):
+    _check(_moe_batchwise_loss_grad(ctypes.byref(cfg), _ptr(gsigma), _ptr(thresholds), _ptr(dthresholds),
+                                    _stream(stream)))

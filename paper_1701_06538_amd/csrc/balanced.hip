@@ -482,6 +482,23 @@ __global__ __launch_bounds__(256) void combine_balanced_kernel(const float4 *__r
         if (lane + 64 * c < d4) y[t * d4 + lane + 64 * c] = acc[c];
 }
 
+// d L_batchwise / d T_i = m_i - #{t : G_sigma(t,i) > T_i} (both masks are piecewise constant in T).
+// A workgroup takes 64 experts (a lane each, rows read 256 bytes at a time), its four waves a
+// quarter of the tokens each; kept_count[i] is the number the batchwise mask keeps (m for all).
+__global__ __launch_bounds__(256) void threshold_grad_kernel(const float *__restrict__ G,
+                                                             const float *__restrict__ thresholds, int64_t T,
+                                                             int n, int m, float *__restrict__ dthr) {
+    __shared__ int part[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + lane;
+    const float th = i < n ? thresholds[i] : 0.f;
+    int cnt = 0;
+    for (int64_t t = wave; t < T; t += 4) cnt += (i < n && G[t * n + i] > th) ? 1 : 0;
+    part[wave][lane] = cnt;
+    __syncthreads();
+    if (wave == 0 && i < n) dthr[i] = (float)(m - (part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane]));
+}
+
 static size_t b_up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct BalancedLayout {
@@ -775,4 +792,17 @@ extern "C" int moe_layer_forward_threshold(const moe_config *cfg, const float *x
     }
     return launch_combine_balanced(cfg, out_rows, gsigma, kept, sa.pos, denom, sa.offsets, rows_total, row_capacity,
                                    y, s);
+}
+
+extern "C" int moe_batchwise_loss_grad(const moe_config *cfg, const float *gsigma, const float *thresholds,
+                                       float *dthresholds, void *stream) {
+    int st = balanced_check(cfg);
+    if (st != MOE_OK) return st;
+    if (!gsigma || !thresholds || !dthresholds) return MOE_EINVAL;
+    const int64_t T = cfg->T;
+    const int n = cfg->n, m = (int)(T * cfg->k / n);
+    hipLaunchKernelGGL(threshold_grad_kernel, dim3((unsigned)ceil_div(n, 64)), dim3(256), 0, (hipStream_t)stream,
+                       gsigma, thresholds, T, n, m, dthresholds);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
 }

@@ -56,6 +56,10 @@ def check_gate(run, x, W_g, bias, thresholds):
         ref = O.batchwise_loss(X, mask, thresholds)
         gl = float(run.loss.cpu().numpy()[0])
         assert abs(gl - ref) <= TOL_F32 * abs(ref) + 1e-9, (gl, ref)
+        dthr = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        run.api.moe_batchwise_loss_grad(c, run.gsigma, run.thr, dthr)
+        torch.cuda.synchronize()
+        assert np.array_equal(dthr.cpu().numpy().astype(np.float64), O.batchwise_loss_dthresholds(X, mask, thresholds))
     return X, mask, Gm
 
 

@@ -131,3 +131,28 @@ def test_threshold_mask_and_batchwise_loss_closed_forms():
     mr, _ = O.batchwise_mask(Xr, 10)
     for _ in range(20):
         assert O.batchwise_loss(Xr, mr, rng.random(6)) >= 0.0
+
+
+def test_threshold_gradient_by_central_differences():
+    """L_batchwise is piecewise linear in the thresholds: away from the values of X a central
+    difference is exact, and the gradient is (kept by the batchwise mask) - (above the threshold)."""
+    rng = np.random.default_rng(41)
+    T, n, m = 40, 6, 10
+    X = rng.random((T, n)).astype(np.float32)
+    mask, _ = O.batchwise_mask(X, m)
+    thr = np.quantile(X, 1 - m / T, axis=0) * (1 + 0.2 * rng.standard_normal(n))
+    g = O.batchwise_loss_dthresholds(X, mask, thr)
+    step = 1e-7
+    assert np.abs(X.astype(np.float64) - thr[None, :]).min() > 10 * step
+    for i in range(n):
+        p, q = thr.copy(), thr.copy()
+        p[i] += step
+        q[i] -= step
+        num = (O.batchwise_loss(X, mask, p) - O.batchwise_loss(X, mask, q)) / (2 * step)
+        assert abs(num - g[i]) < 1e-6, (i, num, g[i])
+    counts_thr = (X.astype(np.float64) > thr[None, :]).sum(axis=0)
+    assert np.array_equal(g, m - counts_thr)
+    # at the batchwise optimum (threshold between the m-th and (m+1)-th largest) the gradient vanishes
+    s = np.sort(X.astype(np.float64), axis=0)
+    best = 0.5 * (s[T - m] + s[T - m - 1])
+    assert not O.batchwise_loss_dthresholds(X, mask, best).any()
