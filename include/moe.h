@@ -69,7 +69,11 @@ typedef struct moe_config {
  * instead of recomputing them.  The paper
  * recomputes (Appendix D) to fit 12 GB devices; with 288 GB of HBM the 2*h bytes per routed row
  * are the cheaper side of the trade.  Without the flag the backward pass recomputes. */
-enum { MOE_FLAG_SAVE_HIDDEN = 1 };
+/* With MOE_FLAG_ADAM_MOMENTS moe_layer_backward (bf16 experts) also leaves, in its workspace, the
+ * per-block sums of squares of dW1 and dW2 that the weight-gradient kernels have in registers
+ * anyway; moe_expert_adam_step then skips its own pass over the gradients when it is handed that
+ * workspace. */
+enum { MOE_FLAG_SAVE_HIDDEN = 1, MOE_FLAG_ADAM_MOMENTS = 2 };
 
 int moe_version(void);
 const char *moe_strerror(int status);
@@ -344,7 +348,11 @@ int moe_layer_forward_threshold(const moe_config *cfg, const float *x, const flo
  * v_col1 [n,h], v_row2 [n,h], v_col2 [n,d] f32 (zero before the first step).
  * Device outputs: W1_copy, W2_copy: the bf16 weights the layer reads (nearest-even rounding of the
  * updated parameters), or both NULL for fp32 experts, whose parameters are the weights themselves.
- * d and h multiples of 4; workspace: moe_adam_workspace_bytes().  cfg->T and cfg->k are not used.
+ * d and h multiples of 4; workspace: moe_adam_workspace_bytes().
+ * backward_workspace: NULL, or the workspace moe_layer_backward has just filled under a cfg with
+ * MOE_FLAG_ADAM_MOMENTS (the same cfg is passed here): the sums of squares of the gradients are
+ * then taken from it instead of from a pass over dW1 and dW2.  Without it cfg->T and cfg->k are
+ * not used.
  */
 typedef struct moe_adam_params {
     float lr, beta2, eps;
@@ -354,7 +362,8 @@ size_t moe_adam_workspace_bytes(const moe_config *cfg);
 int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params *hp, const float *dW1,
                          const float *dW2, float *W1_master, float *W2_master, void *W1_copy,
                          void *W2_copy, float *v_row1, float *v_col1, float *v_row2, float *v_col2,
-                         void *workspace, size_t workspace_bytes, void *stream);
+                         const void *backward_workspace, void *workspace, size_t workspace_bytes,
+                         void *stream);
 
 /* ---- backward pass of the hierarchical layer (Appendix B, Eq.(12)-(14)) ------------------- */
 /*

@@ -11,6 +11,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 MOE_OK, MOE_EINVAL, MOE_EUNSUPPORTED, MOE_EWORKSPACE, MOE_EHIP = 0, -1, -2, -3, -4
 MOE_DTYPE_F32, MOE_DTYPE_BF16 = 0, 1
 MOE_FLAG_SAVE_HIDDEN = 1
+MOE_FLAG_ADAM_MOMENTS = 2
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -113,7 +114,7 @@ class MoeAdamParams(ctypes.Structure):
 
 _moe_adam_workspace_bytes = _proto("moe_adam_workspace_bytes", ctypes.c_size_t, [_cfgp])
 _moe_expert_adam_step = _proto("moe_expert_adam_step", ctypes.c_int,
-                               [_cfgp, ctypes.POINTER(MoeAdamParams)] + [_vp] * 11 + [ctypes.c_size_t, _vp])
+                               [_cfgp, ctypes.POINTER(MoeAdamParams)] + [_vp] * 12 + [ctypes.c_size_t, _vp])
 
 
 class MoeError(RuntimeError):
@@ -347,12 +348,12 @@ def moe_adam_workspace_bytes(cfg):
 
 
 def moe_expert_adam_step(cfg, lr, beta2, eps, step, dW1, dW2, W1_master, W2_master, W1_copy, W2_copy, v_row1,
-                         v_col1, v_row2, v_col2, workspace, stream=None):
+                         v_col1, v_row2, v_col2, workspace, stream=None, backward_workspace=None):
     hp = MoeAdamParams(lr, beta2, eps, step)
     _check(_moe_expert_adam_step(ctypes.byref(cfg), ctypes.byref(hp), _ptr(dW1), _ptr(dW2), _ptr(W1_master),
                                  _ptr(W2_master), _ptr(W1_copy), _ptr(W2_copy), _ptr(v_row1), _ptr(v_col1),
-                                 _ptr(v_row2), _ptr(v_col2), _ptr(workspace), _nbytes(workspace),
-                                 _stream(stream)))
+                                 _ptr(v_row2), _ptr(v_col2), _ptr(backward_workspace), _ptr(workspace),
+                                 _nbytes(workspace), _stream(stream)))
 
 
 def moe_backward_hier_workspace_bytes(cfg):

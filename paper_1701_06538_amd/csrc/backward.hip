@@ -618,7 +618,7 @@ static size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct BwdLayout {
     size_t xs, dout, hid, dz, dxs, dgate, dclean, draw, gI, gL, wpart, tile_expert, tile_row0,
-        num_tiles, order, total;
+        num_tiles, order, mom[4], total;
     int ksplit;
 };
 
@@ -654,6 +654,12 @@ static int bwd_layout(const moe_config *cfg, BwdLayout *L) {
     L->tile_row0 = take(MT * 4);
     L->num_tiles = take(16);
     L->order = take(n * 4);
+    // MOE_FLAG_ADAM_MOMENTS: per-block sums of squares of dW1 [d,h] and dW2 [h,d] (see GGWgrad)
+    const bool mom = (cfg->flags & MOE_FLAG_ADAM_MOMENTS) && cfg->expert_dtype == MOE_DTYPE_BF16;
+    L->mom[0] = mom ? take(n * (h / 256) * d * 4) : (size_t)-1;
+    L->mom[1] = mom ? take(n * (d / 256) * h * 4) : (size_t)-1;
+    L->mom[2] = mom ? take(n * (d / 256) * h * 4) : (size_t)-1;
+    L->mom[3] = mom ? take(n * (h / 256) * d * 4) : (size_t)-1;
     L->total = off;
     return MOE_OK;
 }
@@ -764,6 +770,7 @@ struct ExpertBwd {
     float *dxs, *dgate;                        // out: [T*k, d] expert part of dx per routed row; [T*k]
     int32_t *tile_expert, *tile_row0, *num_tiles, *order;
     float *dW1, *dW2;
+    float *mom[4];                             // optional sums of squares for the optimiser, or nulls
 };
 
 static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStream_t s) {
@@ -787,9 +794,9 @@ static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStr
     GGRows g2{b.dout, (const uint16_t *)b.W2, b.dz, hid, d, h, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
     if ((st = launch_gg_rows256(g2, EPI_MASK_BF16, max_tiles256, s)) != MOE_OK) return st;
     if ((st = launch_expert_order(b.offsets, n, b.order, s)) != MOE_OK) return st;
-    GGWgrad w2{hid, b.dout, b.dW2, h, d, b.offsets, b.order};
+    GGWgrad w2{hid, b.dout, b.dW2, h, d, b.offsets, b.order, b.mom[2], b.mom[3]};
     if ((st = launch_gg_wgrad(w2, n, s)) != MOE_OK) return st;
-    GGWgrad w1{b.xs, b.dz, b.dW1, d, h, b.offsets, b.order};
+    GGWgrad w1{b.xs, b.dz, b.dW1, d, h, b.offsets, b.order, b.mom[0], b.mom[1]};
     if ((st = launch_gg_wgrad(w1, n, s)) != MOE_OK) return st;
     GGRows g5{b.dz, (const uint16_t *)b.W1, b.dxs, nullptr, h, d, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
     return launch_gg_rows256(g5, EPI_F32, max_tiles256, s);
@@ -798,6 +805,19 @@ static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStr
 }  // namespace moe
 
 using namespace moe;
+
+namespace moe {
+int backward_moments_offsets(const moe_config *cfg, size_t off[4]) {
+    if (check_config(cfg) != MOE_OK || cfg->a != 0) return MOE_EINVAL;
+    BwdLayout L;
+    bwd_layout(cfg, &L);
+    for (int q = 0; q < 4; ++q) {
+        if (L.mom[q] == (size_t)-1) return MOE_EINVAL;
+        off[q] = L.mom[q];
+    }
+    return MOE_OK;
+}
+}  // namespace moe
 
 extern "C" size_t moe_backward_workspace_bytes(const moe_config *cfg) {
     if (check_config(cfg) != MOE_OK || cfg->a != 0) return 0;
@@ -859,7 +879,9 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     } else {
         ExpertBwd eb{x, dy, out_sorted, topk_gate, perm, offsets, W1, W2, saved_hidden ? hid : nullptr,
                      xs, dout, saved_hidden ? nullptr : hid, dz, dxs, dgate, tile_expert, tile_row0, num_tiles,
-                     (int32_t *)(ws + L.order), dW1, dW2};
+                     (int32_t *)(ws + L.order), dW1, dW2, {nullptr, nullptr, nullptr, nullptr}};
+        for (int q = 0; q < 4; ++q)
+            if (L.mom[q] != (size_t)-1) eb.mom[q] = (float *)(ws + L.mom[q]);
         if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
     }
 
@@ -1078,7 +1100,7 @@ extern "C" int moe_layer_backward_hier(const moe_config *cfg, const float *x, co
                  saved_hidden ? (const uint16_t *)(fw + F.hidden) : nullptr, (uint16_t *)(ws + L.xs),
                  (uint16_t *)(ws + L.dout), (uint16_t *)(ws + L.hid), (uint16_t *)(ws + L.dz), dxs, dgate,
                  (int32_t *)(ws + L.tile_expert), (int32_t *)(ws + L.tile_row0), (int32_t *)(ws + L.num_tiles),
-                 (int32_t *)(ws + L.order), dW1, dW2};
+                 (int32_t *)(ws + L.order), dW1, dW2, {nullptr, nullptr, nullptr, nullptr}};
     if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
 
     // Eq.(13),(14): gradients of both CV^2 with respect to Importance_H and Load_H, then into the levels

@@ -148,6 +148,48 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
             float *dst = Ce + (size_t)row * p.N + n0 + 128 * (wn >> 1) + 8 * c + 4 * (wn & 1);
             *reinterpret_cast<v4f *>(dst) = v4f{acc[i][0][q], acc[i][1][q], acc[i][2][q], acc[i][3][q]};
         }
+    // Optional: this block's share of the row and column sums of squares of the gradient, which
+    // the factored second-moment estimator of the optimiser needs (Appendix D) -- taken here, where
+    // the gradient is in registers, instead of re-reading it from memory.
+    // rowpart [n][N/256][M], colpart [n][M/256][N]; every partial is written by exactly one
+    // workgroup and summed by the consumer in a fixed order.
+    if (p.rowpart) {
+        float *red = reinterpret_cast<float *>(stage_mem);        // the operand stages are dead
+        float *rrow = red;                                        // [4 wn][256 rows]
+        float *rcol = red + 4 * WG_TILE;                          // [2 wm][256 cols]
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float rs = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) rs = fmaf(acc[i][j][q], acc[i][j][q], rs);
+#pragma unroll
+                for (int off = 1; off < 16; off <<= 1) rs += __shfl_xor(rs, off);    // over c
+                if (c == 0) rrow[wn * WG_TILE + 128 * wm + 8 * (4 * g + q) + i] = rs;
+            }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float cs = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) cs = fmaf(acc[i][j][q], acc[i][j][q], cs);
+            cs += __shfl_xor(cs, 16);                                                  // over g
+            cs += __shfl_xor(cs, 32);
+            if (g == 0) rcol[wm * WG_TILE + 128 * (wn >> 1) + 8 * c + 4 * (wn & 1) + j] = cs;
+        }
+        __syncthreads();
+        const int tn = n0 / WG_TILE, tm = m0 / WG_TILE;
+        if (tid < WG_TILE) {
+            const float v = ((rrow[tid] + rrow[WG_TILE + tid]) + rrow[2 * WG_TILE + tid]) + rrow[3 * WG_TILE + tid];
+            p.rowpart[((size_t)e * tiles_n + tn) * p.M + m0 + tid] = v;
+        } else {
+            const int cc = tid - WG_TILE;
+            p.colpart[((size_t)e * tiles_m + tm) * p.N + n0 + cc] = rcol[cc] + rcol[WG_TILE + cc];
+        }
+    }
     WG_STAMP(2);
 }
 

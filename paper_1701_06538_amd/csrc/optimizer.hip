@@ -114,7 +114,9 @@ __global__ __launch_bounds__(256) void adam_moments_wide_kernel(AdamMat m) {
 }
 
 struct AdamVec {
-    const double *rowsum, *colpart;
+    const double *rowsum, *colpart;      // own moments pass: rowsum [count, R], colpart [count, nrb, C]
+    const float *rowpart_f, *colpart_f;  // or the weight-gradient kernel's: [count, nrp, R], [count, ncp, C]
+    int nrp, ncp;
     float *v_row, *v_col;   // [count, R], [count, C]
     float *scale;           // [count]: 1 / (mean(v_row) * (1 - beta2^step)), or -1 when the mean is 0
     int R, C;
@@ -128,14 +130,24 @@ __global__ __launch_bounds__(256) void adam_vectors_kernel(AdamVec a) {
     const double b2 = (double)a.beta2, ob2 = 1.0 - b2;
     double msum = 0.0;
     for (int r = tid; r < R; r += 256) {
-        const double v = b2 * (double)a.v_row[(size_t)e * R + r] + ob2 * (a.rowsum[(size_t)e * R + r] / C);
+        double rsum = 0.0;
+        if (a.rowpart_f) {
+            for (int q = 0; q < a.nrp; ++q) rsum += (double)a.rowpart_f[((size_t)e * a.nrp + q) * R + r];
+        } else {
+            rsum = a.rowsum[(size_t)e * R + r];
+        }
+        const double v = b2 * (double)a.v_row[(size_t)e * R + r] + ob2 * (rsum / C);
         const float vf = (float)v;
         a.v_row[(size_t)e * R + r] = vf;
         msum += (double)vf;
     }
     for (int c = tid; c < C; c += 256) {
         double s = 0.0;
-        for (int rb = 0; rb < nrb; ++rb) s += a.colpart[((size_t)e * nrb + rb) * C + c];
+        if (a.colpart_f) {
+            for (int q = 0; q < a.ncp; ++q) s += (double)a.colpart_f[((size_t)e * a.ncp + q) * C + c];
+        } else {
+            for (int rb = 0; rb < nrb; ++rb) s += a.colpart[((size_t)e * nrb + rb) * C + c];
+        }
         a.v_col[(size_t)e * C + c] = (float)(b2 * (double)a.v_col[(size_t)e * C + c] + ob2 * (s / R));
     }
     red[tid] = msum;
@@ -236,7 +248,8 @@ extern "C" size_t moe_adam_workspace_bytes(const moe_config *cfg) {
 extern "C" int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params *hp, const float *dW1,
                                     const float *dW2, float *W1_master, float *W2_master, void *W1_copy,
                                     void *W2_copy, float *v_row1, float *v_col1, float *v_row2,
-                                    float *v_col2, void *workspace, size_t workspace_bytes, void *stream) {
+                                    float *v_col2, const void *backward_workspace, void *workspace,
+                                    size_t workspace_bytes, void *stream) {
     int st = adam_check(cfg);
     if (st != MOE_OK) return st;
     if (!hp || !dW1 || !dW2 || !W1_master || !W2_master || !v_row1 || !v_col1 || !v_row2 || !v_col2 || !workspace)
@@ -251,6 +264,11 @@ extern "C" int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params
     AdamLayout L;
     adam_layout(cfg, &L);
     if (workspace_bytes < L.total) return MOE_EWORKSPACE;
+    size_t mom_off[4] = {0, 0, 0, 0};
+    if (backward_workspace) {
+        if (!(cfg->flags & MOE_FLAG_ADAM_MOMENTS) || cfg->d % 256 || cfg->h % 256) return MOE_EINVAL;
+        if ((st = backward_moments_offsets(cfg, mom_off)) != MOE_OK) return st;
+    }
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
     const int n = cfg->n;
@@ -264,7 +282,13 @@ extern "C" int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params
         double *rowsum = (double *)(ws + L.rowsum[w]), *colpart = (double *)(ws + L.colpart[w]);
         float *scale = (float *)(ws + L.scale[w]);
         AdamMat am{G[w], R[w], C[w], n, rowsum, colpart};
+        const float *rp = nullptr, *cp = nullptr;
+        if (backward_workspace) {   // the weight-gradient kernels already summed the squares per block
+            rp = (const float *)((const char *)backward_workspace + mom_off[2 * w]);
+            cp = (const float *)((const char *)backward_workspace + mom_off[2 * w + 1]);
+        }
         const dim3 mgrid((unsigned)ceil_div(R[w], kAdamRB), (unsigned)n);
+        if (!backward_workspace) {
         const size_t mlds = (size_t)4 * C[w] * sizeof(double);
         if (C[w] <= 1024) hipLaunchKernelGGL(adam_moments_kernel<4>, mgrid, dim3(256), mlds, s, am);
         else if (C[w] <= 2048) {
@@ -277,7 +301,8 @@ extern "C" int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params
             hipLaunchKernelGGL(adam_moments_kernel<8>, mgrid, dim3(256), mlds, s, am);
         } else hipLaunchKernelGGL(adam_moments_wide_kernel, mgrid, dim3(256), 0, s, am);
         MOE_LAUNCH_CHECK();
-        AdamVec av{rowsum, colpart, vr[w], vc[w], scale, R[w], C[w], hp->beta2, bias_corr};
+        }
+        AdamVec av{rowsum, colpart, rp, cp, C[w] / 256, R[w] / 256, vr[w], vc[w], scale, R[w], C[w], hp->beta2, bias_corr};
         hipLaunchKernelGGL(adam_vectors_kernel, dim3((unsigned)n), dim3(256), 0, s, av);
         MOE_LAUNCH_CHECK();
         AdamUpd au{G[w], M[w], Cp[w], vr[w], vc[w], scale, R[w], C[w], hp->lr, hp->eps};

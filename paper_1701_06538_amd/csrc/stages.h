@@ -89,8 +89,13 @@ struct GGWgrad {
     int M, N;
     const int32_t *offsets;
     const int32_t *order;   // experts by decreasing row count (launch_expert_order)
+    // optional: per-block sums of squares for the optimiser, rowpart [n][N/256][M], colpart [n][M/256][N]
+    float *rowpart, *colpart;
 };
 int launch_gg_wgrad(const GGWgrad &p, int n, hipStream_t st);
+// byte offsets, inside the backward workspace, of the sums of squares that moe_layer_backward leaves
+// with MOE_FLAG_ADAM_MOMENTS: {rowpart(dW1), colpart(dW1), rowpart(dW2), colpart(dW2)}
+int backward_moments_offsets(const moe_config *cfg, size_t off[4]);
 // order[r] = the expert with the r-th most rows (equal counts: lower index first)
 int launch_expert_order(const int32_t *offsets, int n, int32_t *order, hipStream_t st);
 

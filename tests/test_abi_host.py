@@ -138,7 +138,7 @@ def test_widened_entry_points_validate_on_the_host(api):
     assert api._moe_layer_backward_hier(ctypes.byref(flat), *([None] * 21), 0, None) == api.MOE_EINVAL
     assert api.moe_adam_workspace_bytes(flat) > 0
     hp = api.MoeAdamParams(1e-3, 0.999, 1e-8, 1)
-    assert api._moe_expert_adam_step(ctypes.byref(flat), ctypes.byref(hp), *([None] * 11), 0, None) == api.MOE_EINVAL
+    assert api._moe_expert_adam_step(ctypes.byref(flat), ctypes.byref(hp), *([None] * 12), 0, None) == api.MOE_EINVAL
     assert api._moe_combine_epilogue(ctypes.byref(flat), *([None] * 5), 0.0, None, None) == api.MOE_EINVAL
     # fp32 experts and expert counts off the tile sizes are accepted by the flat backward
     assert api.moe_backward_workspace_bytes(api.make_config(T=64, d=64, h=96, n=20, k=2, expert_dtype=api.MOE_DTYPE_F32)) > 0

@@ -101,3 +101,51 @@ def test_adam_rejects_bad_arguments(api):
     with pytest.raises(api.MoeError) as e:
         api.moe_expert_adam_step(cfg, 1e-3, 0.9, 1e-8, 1, t, t, t, t, None, None, t, t, t, t, ws[:16])
     assert e.value.status == api.MOE_EWORKSPACE
+
+
+def test_adam_step_with_sums_from_the_backward_pass(api):
+    """MOE_FLAG_ADAM_MOMENTS: the weight-gradient kernels leave per-block sums of squares in the
+    backward workspace; the step that uses them must agree with the step that makes its own pass
+    over the gradients, and with the oracle."""
+    from tests import gpu_harness as G
+    say("adam fused moments")
+    shape = W.scaled_config(W.CONFIGS[4], T=700, n=32, k=3, d=256, h=512)
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape)
+    W1, W2 = G.device_weights(shape)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2, flags=api.MOE_FLAG_ADAM_MOMENTS)
+    run.fused()
+    T, d, h, n = shape.T, shape.d, shape.h, shape.n
+    f32 = dict(dtype=torch.float32, device="cuda")
+    grads = [torch.empty((T, d), **f32), torch.empty((d, n), **f32), torch.empty((d, n), **f32),
+             torch.empty((n, d, h), **f32), torch.empty((n, h, d), **f32)]
+    bws = torch.empty(api.moe_backward_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+    dy = G.dev(W.upstream_grad(shape))
+    api.moe_layer_backward(run.cfg, run.x, run.W_g, run.W_noise, run.eps, run.W1, run.W2, dy, run.topk_idx,
+                           run.topk_gate, run.workspace, grads[0], grads[1], grads[2], grads[3], grads[4], bws)
+    torch.cuda.synchronize()
+    ows = torch.empty(max(256, api.moe_adam_workspace_bytes(run.cfg)), dtype=torch.uint8, device="cuda")
+    results = []
+    for fused in (False, True):
+        masters = [run.W1.to(torch.float32), run.W2.to(torch.float32)]
+        copies = [torch.zeros_like(run.W1), torch.zeros_like(run.W2)]
+        st = [torch.zeros((n, d), **f32), torch.zeros((n, h), **f32), torch.zeros((n, h), **f32), torch.zeros((n, d), **f32)]
+        api.moe_expert_adam_step(run.cfg, 1e-2, 0.9, 1e-8, 1, grads[3], grads[4], masters[0], masters[1], copies[0],
+                                 copies[1], st[0], st[1], st[2], st[3], ows, backward_workspace=bws if fused else None)
+        torch.cuda.synchronize()
+        results.append((masters, st, copies))
+    (m0, s0, c0), (m1, s1, c1) = results
+    for a, b in zip(s0, s1):
+        assert rel(b.cpu().numpy(), a.cpu().numpy().astype(np.float64)) <= TOL
+    for a, b in zip(m0, m1):
+        assert rel(b.cpu().numpy(), a.cpu().numpy().astype(np.float64)) <= TOL
+    # and against the oracle, expert by expert, from the gradients the backward pass wrote
+    g1 = grads[3].cpu().numpy()
+    w1 = run.W1.to(torch.float32).cpu().numpy()
+    for e in (0, 7, n - 1):
+        ref_W, ref_vr, ref_vc = O.factored_adam_step(w1[e], g1[e], np.zeros(d), np.zeros(h), 1e-2, 0.9, 1e-8, 1)
+        assert rel(m1[0][e].cpu().numpy(), ref_W) <= TOL
+        assert rel(s1[0][e].cpu().numpy(), ref_vr) <= TOL and rel(s1[1][e].cpu().numpy(), ref_vc) <= TOL
+    with pytest.raises(api.MoeError):      # the flag is what sizes and fills those sums
+        plain = api.make_config(shape)
+        api.moe_expert_adam_step(plain, 1e-2, 0.9, 1e-8, 1, grads[3], grads[4], m0[0], m0[1], c0[0], c0[1],
+                                 s0[0], s0[1], s0[2], s0[3], ows, backward_workspace=bws)
