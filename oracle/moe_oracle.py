@@ -692,6 +692,90 @@ def balanced_output(x, G, weight_fn, token_subset=None):
     return y
 
 
+@dataclass
+class BalancedGrads:
+    dx: np.ndarray
+    dW_g: np.ndarray
+    dbias: np.ndarray
+    dW1: dict
+    dW2: dict
+    dlogits: np.ndarray
+
+
+def balanced_backward(x, W_g, Gs, mask, thresholds, weight_fn, dy, w_batchwise=0.0,
+                      experts_for_dW=None, expert_input=None) -> BalancedGrads:
+    """Gradients of J = <dy, y> + w_batchwise * L_batchwise for the layer with strictly balanced
+    gating (Appendix F), with respect to x, W_g (and a bias added to the logits) and the experts.
+
+    Both masks are piecewise constant, so the gradient reaches the gate only through the values
+    G_sigma: through the quotient of Eq.(16), through the factor (G_sigma - T_i) of Eq.(20) as
+    printed, and from there through the softmax of Eq.(15) over all n experts.  relu'(0) = 0.
+    Gs [T,n]: the softmax values the forward pass used; mask [T,n] bool: M_batchwise.
+    expert_input / experts_for_dW as in flat_backward."""
+    x = np.asarray(x, np.float64)
+    xe_all = x if expert_input is None else np.asarray(expert_input, np.float64)
+    dy = np.asarray(dy, np.float64)
+    W_g = np.asarray(W_g, np.float64)
+    Gs = np.asarray(Gs, np.float64)
+    mask = np.asarray(mask, bool)
+    T, n = Gs.shape
+    G, denom = balanced_gates(Gs, mask)
+    keep = None if experts_for_dW is None else set(int(e) for e in experts_for_dW)
+    dx = np.zeros_like(x)
+    dG = np.zeros((T, n))
+    dW1, dW2 = {}, {}
+    for e in range(n):
+        r = np.nonzero(mask[:, e])[0]
+        if r.size == 0:
+            continue
+        W1, W2 = (np.asarray(w, np.float64) for w in weight_fn(e))
+        xe = xe_all[r]
+        z = xe @ W1
+        hid = np.maximum(z, 0.0)
+        out = hid @ W2
+        dG[r, e] = np.einsum("ij,ij->i", dy[r], out)          # Eq.(1)
+        dout = G[r, e][:, None] * dy[r]
+        dz = (dout @ W2.T) * (z > 0.0)
+        dx[r] += dz @ W1.T
+        if keep is None or e in keep:
+            dW2[e] = hid.T @ dout
+            dW1[e] = xe.T @ dz
+    # Eq.(16): G_i = Gs_i M_i / D, D = sum_j Gs_j M_j
+    inner = (G * dG).sum(axis=1)
+    live = denom > 0
+    dGs = np.zeros((T, n))
+    dGs[live] = np.where(mask[live], (dG[live] - inner[live, None]) / denom[live, None], 0.0)
+    # Eq.(20)
+    if w_batchwise != 0.0:
+        dGs += w_batchwise * (threshold_mask(Gs, thresholds).astype(np.float64) - mask.astype(np.float64))
+    # Eq.(15)
+    dlogits = Gs * (dGs - (Gs * dGs).sum(axis=1)[:, None])
+    dW_g = x.T @ dlogits
+    dx += dlogits @ W_g.T
+    return BalancedGrads(dx, dW_g, dlogits.sum(axis=0), dW1, dW2, dlogits)
+
+
+def balanced_objective(x, W_g, bias, thresholds, m, weight_fn, dy, w_batchwise, fixed_masks=None):
+    """J = <dy, y> + w_batchwise * L_batchwise of the balanced layer entirely in binary64 (for
+    finite differences).  fixed_masks = (M_batchwise, M_threshold) freezes both masks so that J is
+    smooth.  Returns (J, M_batchwise, M_threshold, G_sigma)."""
+    x = np.asarray(x, np.float64)
+    logits = x @ np.asarray(W_g, np.float64)
+    if bias is not None:
+        logits = logits + np.asarray(bias, np.float64)[None, :]
+    ex = np.exp(logits - logits.max(axis=1, keepdims=True))
+    Gs = ex / ex.sum(axis=1, keepdims=True)
+    if fixed_masks is None:
+        mb, _ = batchwise_mask(Gs, m)
+        mt = threshold_mask(Gs, thresholds)
+    else:
+        mb, mt = fixed_masks
+    G, _ = balanced_gates(Gs, mb)
+    y = balanced_output(x, G, weight_fn)
+    Lb = ((mt.astype(np.float64) - mb.astype(np.float64)) * (Gs - np.asarray(thresholds, np.float64)[None, :])).sum()
+    return float((np.asarray(dy, np.float64) * y).sum() + w_batchwise * Lb), mb, mt, Gs
+
+
 # --------------------------------------------------------------------------------------
 # Appendix D: Adam with beta1 = 0 and a factored second-moment estimator for the expert matrices
 # --------------------------------------------------------------------------------------

@@ -156,3 +156,83 @@ def test_threshold_gradient_by_central_differences():
     s = np.sort(X.astype(np.float64), axis=0)
     best = 0.5 * (s[T - m] + s[T - m - 1])
     assert not O.batchwise_loss_dthresholds(X, mask, best).any()
+
+
+# ---- backward through Eq.(15), (16), (20) and the experts -----------------------------------------
+
+def _tiny_balanced_problem(seed, T=12, n=4, k=2, d=6, h=5):
+    rng = np.random.default_rng(seed)
+    x = rng.normal(size=(T, d))
+    W_g = rng.normal(size=(d, n)) * 0.5
+    bias = rng.normal(size=n) * 0.1
+    W1 = rng.normal(size=(n, d, h)) * 0.5
+    W2 = rng.normal(size=(n, h, d)) * 0.5
+    dy = rng.normal(size=(T, d))
+    thr = np.full(n, 1.0 / n) + rng.normal(size=n) * 0.02
+    return x, W_g, bias, W1, W2, dy, thr, k * T // n
+
+
+@pytest.mark.parametrize("seed,w_b", [(0, 0.0), (1, 0.3), (2, 1.0)])
+def test_balanced_backward_by_central_differences(seed, w_b):
+    """Every gradient the oracle returns against central differences of the binary64 objective.
+    The masks are recomputed at every perturbed point and must not change (the step is far below
+    the gaps of these inputs), so the differences see the true piecewise-smooth function."""
+    x, W_g, bias, W1, W2, dy, thr, m = _tiny_balanced_problem(seed)
+    wf = lambda e, W1=W1, W2=W2: (W1[e], W2[e])
+    J0, mb, mt, Gs = O.balanced_objective(x, W_g, bias, thr, m, wf, dy, w_b)
+    g = O.balanced_backward(x, W_g, Gs, mb, thr, wf, dy, w_b)
+    step = 1e-6
+
+    def fd(arr, index, weight_fn=None):
+        vals = []
+        for sgn in (+1, -1):
+            old = arr[index]
+            arr[index] = old + sgn * step
+            J, mb2, mt2, _ = O.balanced_objective(x, W_g, bias, thr, m, weight_fn or wf, dy, w_b)
+            arr[index] = old
+            assert (mb2 == mb).all() and (mt2 == mt).all(), "a mask flipped: pick another seed"
+            vals.append(J)
+        return (vals[0] - vals[1]) / (2 * step)
+
+    rng = np.random.default_rng(100 + seed)
+    for _ in range(10):
+        i = (rng.integers(x.shape[0]), rng.integers(x.shape[1]))
+        assert fd(x, i) == pytest.approx(g.dx[i], rel=2e-5, abs=2e-7)
+        i = (rng.integers(W_g.shape[0]), rng.integers(W_g.shape[1]))
+        assert fd(W_g, i) == pytest.approx(g.dW_g[i], rel=2e-5, abs=2e-7)
+        i = (rng.integers(W1.shape[0]), rng.integers(W1.shape[1]), rng.integers(W1.shape[2]))
+        assert fd(W1, i) == pytest.approx(g.dW1[i[0]][i[1:]], rel=2e-5, abs=2e-7)
+        i = (rng.integers(W2.shape[0]), rng.integers(W2.shape[1]), rng.integers(W2.shape[2]))
+        assert fd(W2, i) == pytest.approx(g.dW2[i[0]][i[1:]], rel=2e-5, abs=2e-7)
+    for i in range(bias.shape[0]):
+        assert fd(bias, i) == pytest.approx(g.dbias[i], rel=2e-5, abs=2e-7)
+
+
+def test_balanced_backward_closed_forms():
+    """(a) one expert: G = 1 whatever the logits, so nothing reaches W_g.  (b) m = T: every expert
+    keeps every token, G = G_sigma, and the gate gradient is that of a dense softmax mixture,
+    dlogit_i = G_i (c_i - sum_j G_j c_j) with c_i = <dy, E_i(x)>.  (c) the logit gradients of a
+    token sum to zero (the softmax is shift invariant)."""
+    x, W_g, bias, W1, W2, dy, thr, m = _tiny_balanced_problem(5, T=8, n=1, k=1)
+    wf = lambda e: (W1[e], W2[e])
+    _, mb, _, Gs = O.balanced_objective(x, W_g, bias, thr, m, wf, dy, 0.0)
+    g = O.balanced_backward(x, W_g, Gs, mb, thr, wf, dy, 0.0)
+    assert np.abs(g.dW_g).max() == 0.0
+    z = x @ W1[0]
+    assert np.allclose(g.dx, (dy @ W2[0].T * (z > 0)) @ W1[0].T, rtol=1e-12, atol=1e-12)
+
+    x, W_g, bias, W1, W2, dy, thr, _ = _tiny_balanced_problem(6, T=8, n=4, k=4)
+    wf = lambda e: (W1[e], W2[e])
+    _, mb, _, Gs = O.balanced_objective(x, W_g, bias, thr, 8, wf, dy, 0.0)
+    assert mb.all()
+    g = O.balanced_backward(x, W_g, Gs, mb, thr, wf, dy, 0.0)
+    c = np.stack([np.einsum("td,td->t", dy, np.maximum(x @ W1[e], 0) @ W2[e]) for e in range(4)], axis=1)
+    ref = Gs * (c - (Gs * c).sum(axis=1, keepdims=True))
+    assert np.allclose(g.dlogits, ref, rtol=1e-10, atol=1e-12)
+    assert np.allclose(g.dW_g, x.T @ ref, rtol=1e-10, atol=1e-12)
+
+    x, W_g, bias, W1, W2, dy, thr, m = _tiny_balanced_problem(7)
+    wf = lambda e: (W1[e], W2[e])
+    _, mb, _, Gs = O.balanced_objective(x, W_g, bias, thr, m, wf, dy, 0.7)
+    g = O.balanced_backward(x, W_g, Gs, mb, thr, wf, dy, 0.7)
+    assert np.abs(g.dlogits.sum(axis=1)).max() < 1e-12
