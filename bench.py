@@ -146,7 +146,7 @@ def main():
                     help="balanced: the strictly balanced gate of Appendix F on the same workload "
                          "(flat forward configs only)")
     ap.add_argument("--backward", action="store_true",
-                    help="hierarchical config: time forward + backward (moe_layer_backward_hier) per step")
+                    help="hierarchical config, or --gating balanced: time forward + backward per step")
     ap.add_argument("--optimizer", action="store_true",
                     help="training configs: also time the factored-second-moment Adam step of the expert "
                          "matrices (outside the timed region; reported under \"optimizer\")")
@@ -183,11 +183,22 @@ def main():
         run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
         ws = run.ws
 
+        if args.backward:
+            dy = G.dev(W.upstream_grad(shape))
+            f32 = dict(dtype=torch.float32, device="cuda")
+            bg = [torch.empty((shape.T, shape.d), **f32), torch.empty((shape.d, shape.n), **f32),
+                  torch.empty((shape.n, shape.d, shape.h), **f32), torch.empty((shape.n, shape.h, shape.d), **f32)]
+            bbws = torch.empty(api.moe_backward_balanced_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+
         def step(events=None):
             ev = None if events is None else [0, 0, events[4], events[5], 0]
             api.moe_layer_forward_balanced_profiled(run.cfg, run.x, run.W_g, run.bias, run.thr, run.W1, run.W2,
                                                     run.y, run.gsigma, run.tokens, run.kept, run.denom,
                                                     run.loss, ws, ev)
+            if args.backward:
+                api.moe_layer_backward_balanced(run.cfg, run.x, run.W_g, run.thr, run.W1, run.W2, dy, run.gsigma,
+                                                run.tokens, run.kept, run.denom, ws, 0.1, bg[0], bg[1], bg[2],
+                                                bg[3], bbws)
     elif shape.hierarchical:
         inputs = W.hier_gate_inputs(shape)
         W1, W2 = G.device_weights(shape, chunk=256)
@@ -299,7 +310,7 @@ def main():
 
     out = {
         "metric": "MoE-layer tokens/sec (%s) at d=512,h=1024" % (
-            "fwd+bwd" if (shape.backward or (shape.hierarchical and args.backward)) else "fwd"),
+            "fwd+bwd" if (shape.backward or ((shape.hierarchical or balanced) and args.backward)) else "fwd"),
         "value": shape.T / (elapsed / K),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,

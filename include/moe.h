@@ -289,6 +289,32 @@ int moe_gate_balanced(const moe_config *cfg, const float *x, const float *W_g,
 int moe_batchwise_loss_grad(const moe_config *cfg, const float *gsigma, const float *thresholds,
                             float *dthresholds, void *stream);
 /*
+ * Backward pass of moe_layer_forward_balanced: gradients of
+ *   J = <dy, y> + w_batchwise * L_batchwise
+ * with respect to x, W_g and the expert matrices.  Both masks are piecewise constant, so the gate
+ * is reached only through the values G_sigma: through the quotient of Eq.(16),
+ *   dG_sigma_i = M_i (dG_i - sum_j G_j dG_j) / denom,   dG_i = <dy, E_i(x)>        (Eq.(1), Eq.(16))
+ * through the factor (G_sigma - T_i) of Eq.(20) as printed, + w_batchwise (M_threshold - M_batchwise),
+ * and from there through the softmax of Eq.(15) over all n experts; the experts as in
+ * moe_layer_backward (hidden activations recomputed for bf16 experts, Appendix D; relu'(0) = 0).
+ * The thresholds' own gradient is moe_batchwise_loss_grad's.
+ * cfg as for moe_layer_forward_balanced, with moe_layer_backward's shape restrictions
+ * (n % 4 == 0; bf16 experts: d, h multiples of 256; fp32 experts: d, h multiples of 4, n <= 65535);
+ * MOE_FLAG_ADAM_MOMENTS is honoured as there.
+ * Device inputs: x, W_g, W1, W2 as in the forward call; thresholds [n] (may be NULL if
+ * w_batchwise == 0); dy [T,d] f32; gsigma, tokens, kept, denom and fwd_workspace as the forward
+ * call left them (read-only).
+ * Device outputs (overwritten): dx [T,d], dW_g [d,n], dW1 [n,d,h], dW2 [n,h,d], all f32 (matrices of
+ * an expert without rows are zero).  workspace: moe_backward_balanced_workspace_bytes().
+ */
+size_t moe_backward_balanced_workspace_bytes(const moe_config *cfg);
+int moe_layer_backward_balanced(const moe_config *cfg, const float *x, const float *W_g,
+                                const float *thresholds, const void *W1, const void *W2,
+                                const float *dy, const float *gsigma, const int32_t *tokens,
+                                const uint32_t *kept, const float *denom, const void *fwd_workspace,
+                                float w_batchwise, float *dx, float *dW_g, float *dW1, float *dW2,
+                                void *workspace, size_t workspace_bytes, void *stream);
+/*
  * The whole layer with that gate: moe_gate_balanced, the experts of Section 3.2 / Appendix C on
  * their m rows each (W1 [n,d,h], W2 [n,h,d] as in moe_expert_ffn), and Eq.(1) with the gates of
  * Eq.(16) -> y [T,d] f32, each token adding its kept experts in ascending expert order.

@@ -105,6 +105,9 @@ _moe_layer_backward_hier = _proto("moe_layer_backward_hier", ctypes.c_int,
 _moe_combine_epilogue = _proto("moe_combine_epilogue", ctypes.c_int, [_cfgp] + [_vp] * 5 + [ctypes.c_float, _vp, _vp])
 
 _moe_batchwise_loss_grad = _proto("moe_batchwise_loss_grad", ctypes.c_int, [_cfgp] + [_vp] * 4)
+_moe_backward_balanced_workspace_bytes = _proto("moe_backward_balanced_workspace_bytes", ctypes.c_size_t, [_cfgp])
+_moe_layer_backward_balanced = _proto("moe_layer_backward_balanced", ctypes.c_int,
+                                      [_cfgp] + [_vp] * 11 + [ctypes.c_float] + [_vp] * 5 + [ctypes.c_size_t, _vp])
 
 
 class MoeAdamParams(ctypes.Structure):
@@ -372,6 +375,18 @@ def moe_layer_backward_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, W1, W2
 def moe_combine_epilogue(cfg, out_sorted, topk_gate, inv_perm, x, keep, drop_prob, y, stream=None):
     _check(_moe_combine_epilogue(ctypes.byref(cfg), _ptr(out_sorted), _ptr(topk_gate), _ptr(inv_perm), _ptr(x),
                                  _ptr(keep), drop_prob, _ptr(y), _stream(stream)))
+
+
+def moe_backward_balanced_workspace_bytes(cfg):
+    return _moe_backward_balanced_workspace_bytes(ctypes.byref(cfg))
+
+
+def moe_layer_backward_balanced(cfg, x, W_g, thresholds, W1, W2, dy, gsigma, tokens, kept, denom, fwd_workspace,
+                                w_batchwise, dx, dW_g, dW1, dW2, workspace, stream=None):
+    _check(_moe_layer_backward_balanced(ctypes.byref(cfg), _ptr(x), _ptr(W_g), _ptr(thresholds), _ptr(W1),
+                                        _ptr(W2), _ptr(dy), _ptr(gsigma), _ptr(tokens), _ptr(kept), _ptr(denom),
+                                        _ptr(fwd_workspace), w_batchwise, _ptr(dx), _ptr(dW_g), _ptr(dW1),
+                                        _ptr(dW2), _ptr(workspace), _nbytes(workspace), _stream(stream)))
 
 
 def moe_batchwise_loss_grad(cfg, gsigma, thresholds, dthresholds, stream=None):

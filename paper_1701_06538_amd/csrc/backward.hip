@@ -38,14 +38,16 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const float *__restric
                                                           const float *__restrict__ out_sorted,
                                                           const float *__restrict__ gate,
                                                           const int32_t *__restrict__ perm, int64_t A,
-                                                          int d, int k, uint16_t *__restrict__ xs,
+                                                          int d, int k, int by_row,
+                                                          uint16_t *__restrict__ xs,
                                                           uint16_t *__restrict__ dout,
                                                           float *__restrict__ dgate) {
     const int lane = threadIdx.x & 63;
     const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= A) return;
-    const int a = perm[r];
-    const int64_t t = a / k;
+    // by_row: perm lists tokens, gate and dgate are indexed by the routed row itself
+    const int64_t a = by_row ? r : perm[r];
+    const int64_t t = by_row ? perm[r] : a / k;
     const float g = gate[a];
     float dot = 0.f;
     for (int c = lane * 4; c < d; c += 256) {
@@ -673,14 +675,15 @@ __global__ __launch_bounds__(256) void bwd_prepare_f32_kernel(const float *__res
                                                               const float *__restrict__ out_sorted,
                                                               const float *__restrict__ gate,
                                                               const int32_t *__restrict__ perm, int64_t A,
-                                                              int d, int k, float *__restrict__ xs,
+                                                              int d, int k, int by_row,
+                                                              float *__restrict__ xs,
                                                               float *__restrict__ dout,
                                                               float *__restrict__ dgate) {
     const int lane = threadIdx.x & 63;
     const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= A) return;
-    const int a = perm[r];
-    const int64_t t = a / k;
+    const int64_t a = by_row ? r : perm[r];
+    const int64_t t = by_row ? perm[r] : a / k;
     const float g = gate[a];
     float dot = 0.f;
     for (int c = lane * 4; c < d; c += 256) {
@@ -718,6 +721,7 @@ struct ExpertBwdF32 {
     float *xs, *dout, *dz, *dxs, *dgate;
     int32_t *tile_expert, *tile_row0, *num_tiles;
     float *dW1, *dW2;
+    bool by_row;   // perm lists tokens; gate and dgate are per routed row (balanced gating)
 };
 
 static int run_expert_backward_f32(const moe_config *cfg, const ExpertBwdF32 &b, hipStream_t s) {
@@ -726,7 +730,7 @@ static int run_expert_backward_f32(const moe_config *cfg, const ExpertBwdF32 &b,
     if (n > 65535) return MOE_EUNSUPPORTED;   // an expert per blockIdx.z
     int st;
     hipLaunchKernelGGL(bwd_prepare_f32_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, s, b.x, b.dy,
-                       b.out_sorted, b.gate, b.perm, A, d, k, b.xs, b.dout, b.dgate);
+                       b.out_sorted, b.gate, b.perm, A, d, k, b.by_row ? 1 : 0, b.xs, b.dout, b.dgate);
     MOE_LAUNCH_CHECK();
     if ((st = launch_build_tiles(b.offsets, n, SBM, b.tile_expert, b.tile_row0, b.num_tiles, s)) != MOE_OK) return st;
     const unsigned max_tiles = (unsigned)(ceil_div(A, SBM) + n);
@@ -771,6 +775,7 @@ struct ExpertBwd {
     int32_t *tile_expert, *tile_row0, *num_tiles, *order;
     float *dW1, *dW2;
     float *mom[4];                             // optional sums of squares for the optimiser, or nulls
+    bool by_row;                               // perm lists tokens; gate and dgate are per routed row
 };
 
 static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStream_t s) {
@@ -778,7 +783,7 @@ static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStr
     const int d = cfg->d, h = cfg->h, n = cfg->n, k = cfg->k;
     int st;
     hipLaunchKernelGGL(bwd_prepare_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, s, b.x, b.dy,
-                       b.out_sorted, b.gate, b.perm, A, d, k, b.xs, b.dout, b.dgate);
+                       b.out_sorted, b.gate, b.perm, A, d, k, b.by_row ? 1 : 0, b.xs, b.dout, b.dgate);
     MOE_LAUNCH_CHECK();
     const uint16_t *hid = b.saved_hid;
     if (!hid) {   // Appendix D: recompute the hidden activations
@@ -921,6 +926,96 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
                        (float4 *)dx, (const float4 *)dxs, inv_perm, T, d / 4, k);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// strictly balanced gating (Appendix F): backward through Eq.(16), Eq.(20), Eq.(15) and the experts
+// ---------------------------------------------------------------------------------------
+extern "C" size_t moe_backward_balanced_workspace_bytes(const moe_config *cfg) {
+    BalancedFwdView V;
+    if (balanced_forward_view(cfg, &V) != MOE_OK) return 0;
+    BwdLayout L;
+    bwd_layout(cfg, &L);
+    return L.total;
+}
+
+extern "C" int moe_layer_backward_balanced(const moe_config *cfg, const float *x, const float *W_g,
+                                           const float *thresholds, const void *W1, const void *W2,
+                                           const float *dy, const float *gsigma, const int32_t *tokens,
+                                           const uint32_t *kept, const float *denom,
+                                           const void *fwd_workspace, float w_batchwise, float *dx,
+                                           float *dW_g, float *dW1, float *dW2, void *workspace,
+                                           size_t workspace_bytes, void *stream) {
+    BalancedFwdView V;
+    int st = balanced_forward_view(cfg, &V);
+    if (st != MOE_OK) return st;
+    const bool f32_experts = cfg->expert_dtype != MOE_DTYPE_BF16;
+    if (!f32_experts && (cfg->d % 256 != 0 || cfg->h % 256 != 0)) return MOE_EUNSUPPORTED;
+    if (cfg->d % 4 != 0 || cfg->h % 4 != 0 || cfg->n % 4 != 0) return MOE_EUNSUPPORTED;
+    if (!x || !W_g || !W1 || !W2 || !dy || !gsigma || !tokens || !kept || !denom || !fwd_workspace || !dx ||
+        !dW_g || !dW1 || !dW2 || !workspace)
+        return MOE_EINVAL;
+    if (w_batchwise != 0.f && !thresholds) return MOE_EINVAL;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(W1) || !aligned16(W2) ||
+        !aligned16(dW1) || !aligned16(dW2) || !aligned16(dW_g) || !aligned16(W_g) || !aligned16(gsigma) ||
+        !aligned16(workspace) || !aligned16(fwd_workspace))
+        return MOE_EINVAL;
+    BwdLayout L;
+    bwd_layout(cfg, &L);
+    if (workspace_bytes < L.total) return MOE_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t T = cfg->T, A = T * cfg->k;
+    const int d = cfg->d, n = cfg->n;
+    if (T == 0) return MOE_OK;
+    const char *fw = (const char *)fwd_workspace;   // read-only here
+    char *ws = (char *)workspace;
+    const int32_t *pos = (const int32_t *)(fw + V.pos), *offsets = (const int32_t *)(fw + V.offsets);
+    const float *out_rows = (const float *)(fw + V.out_rows);
+    float *dxs = (float *)(ws + L.dxs), *drow = (float *)(ws + L.dgate);
+    float *dlogit = (float *)(ws + L.dclean), *row_gate = (float *)(ws + L.draw);   // A <= T*n floats
+    float *wpart = (float *)(ws + L.wpart);
+    int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
+    int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
+
+    // the experts: an expert's rows are its kept tokens, in the order of `tokens`
+    if ((st = launch_balanced_row_gates(gsigma, denom, tokens, offsets, n, A, row_gate, s)) != MOE_OK) return st;
+    if (f32_experts) {
+        ExpertBwdF32 ef{x, dy, out_rows, row_gate, tokens, offsets, (const float *)W1, (const float *)W2,
+                        (const float *)(fw + V.ffn_ws), (float *)(ws + L.xs), (float *)(ws + L.dout),
+                        (float *)(ws + L.dz), dxs, drow, tile_expert, tile_row0, num_tiles, dW1, dW2, true};
+        if ((st = run_expert_backward_f32(cfg, ef, s)) != MOE_OK) return st;
+    } else {
+        ExpertBwd eb{x, dy, out_rows, row_gate, tokens, offsets, W1, W2, nullptr, (uint16_t *)(ws + L.xs),
+                     (uint16_t *)(ws + L.dout), (uint16_t *)(ws + L.hid), (uint16_t *)(ws + L.dz), dxs, drow,
+                     tile_expert, tile_row0, num_tiles, (int32_t *)(ws + L.order), dW1, dW2,
+                     {nullptr, nullptr, nullptr, nullptr}, true};
+        for (int q = 0; q < 4; ++q)
+            if (L.mom[q] != (size_t)-1) eb.mom[q] = (float *)(ws + L.mom[q]);
+        if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
+    }
+
+    // the gate: d/dlogits per token, then the two GEMMs
+    if ((st = launch_balanced_gate_bwd(cfg, gsigma, kept, pos, denom, offsets, drow,
+                                       w_batchwise != 0.f ? thresholds : nullptr, w_batchwise, dlogit, s)) != MOE_OK)
+        return st;
+    SGArgs wa{};
+    wa.A[0] = x; wa.B[0] = dlogit; wa.C = wpart;
+    wa.M = d; wa.N = n; wa.K = (int)T; wa.lda = d; wa.ldb = n; wa.ldc = n; wa.nseg = 1;
+    wa.ksplit = L.ksplit;
+    wa.c_split_stride = (size_t)d * n;
+    hipLaunchKernelGGL((sg_kernel<true, false>), dim3(ceil_div(d, SBM), ceil_div(n, SBN), L.ksplit), dim3(256), 0,
+                       s, wa);
+    MOE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(split_sum_kernel, dim3((unsigned)ceil_div((int64_t)d * n, 256)), dim3(256), 0, s, wpart,
+                       L.ksplit, (size_t)d * n, (size_t)d * n, dW_g);
+    MOE_LAUNCH_CHECK();
+    SGArgs xa{};
+    xa.A[0] = dlogit; xa.B[0] = W_g; xa.C = dx;
+    xa.M = (int)T; xa.N = d; xa.K = n; xa.lda = n; xa.ldb = n; xa.ldc = d; xa.nseg = 1; xa.ksplit = 1;
+    hipLaunchKernelGGL((sg_kernel<false, true>), dim3((unsigned)ceil_div(T, SBM), ceil_div(d, SBN), 1), dim3(256),
+                       0, s, xa);
+    MOE_LAUNCH_CHECK();
+    return launch_add_kept_rows(cfg, dxs, kept, pos, offsets, dx, s);
 }
 
 // ---------------------------------------------------------------------------------------

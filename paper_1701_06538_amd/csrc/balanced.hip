@@ -406,7 +406,9 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const double *__restr
 // ascending order (row in the dispatch and gate value, 64 at a time in LDS), then every lane adds
 // the listed rows for its columns, so the row loads are independent of each other.
 // NC: float4 columns per lane (d/4 <= 64*NC).
-template <int NC>
+// ADD: the backward pass's use of the same walk -- y[t] += the plain sum of the token's rows (G,
+// denom and rows_total unused).
+template <int NC, bool ADD>
 __global__ __launch_bounds__(256) void combine_balanced_kernel(const float4 *__restrict__ out_rows,
                                                                const float *__restrict__ G,
                                                                const uint32_t *__restrict__ kept,
@@ -421,13 +423,13 @@ __global__ __launch_bounds__(256) void combine_balanced_kernel(const float4 *__r
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t t = (int64_t)blockIdx.x * 4 + wave;
     if (t >= T) return;
-    if (rows_total && rows_total[0] > capacity) {      // the dispatch did not fit: no rows were computed
+    if (!ADD && rows_total && rows_total[0] > capacity) {   // the dispatch did not fit: no rows were computed
 #pragma unroll
         for (int c = 0; c < NC; ++c)
             if (lane + 64 * c < d4) y[t * d4 + lane + 64 * c] = make_float4(0.f, 0.f, 0.f, 0.f);
         return;
     }
-    const float dn = denom[t];
+    const float dn = ADD ? 1.f : denom[t];
     const uint32_t bits = lane < kept_words ? kept[t * kept_words + lane] : 0u;   // kept_words <= 64
     const int cnt = __popc(bits);
     int inc = cnt;
@@ -449,7 +451,7 @@ __global__ __launch_bounds__(256) void combine_balanced_kernel(const float4 *__r
             b &= b - 1;
             if (idx >= r0 && idx < r0 + 64) {
                 l_row[wave][idx - r0] = offsets[e] + pos[t * n + e];
-                l_g[wave][idx - r0] = G[t * n + e] / dn;
+                l_g[wave][idx - r0] = ADD ? 1.f : G[t * n + e] / dn;
             }
             ++idx;
         }
@@ -479,7 +481,75 @@ __global__ __launch_bounds__(256) void combine_balanced_kernel(const float4 *__r
     }
 #pragma unroll
     for (int c = 0; c < NC; ++c)
-        if (lane + 64 * c < d4) y[t * d4 + lane + 64 * c] = acc[c];
+        if (lane + 64 * c < d4) {
+            if (ADD) {
+                const float4 v = y[t * d4 + lane + 64 * c];
+                acc[c] = make_float4(v.x + acc[c].x, v.y + acc[c].y, v.z + acc[c].z, v.w + acc[c].w);
+            }
+            y[t * d4 + lane + 64 * c] = acc[c];
+        }
+}
+
+// gate value of every dispatched row: row r belongs to the expert e with offsets[e] <= r <
+// offsets[e+1] and holds token tokens[r]; G = G_sigma(t,e) / denom[t] as the combine forms it
+__global__ __launch_bounds__(256) void balanced_row_gate_kernel(const float *__restrict__ G,
+                                                                const float *__restrict__ denom,
+                                                                const int32_t *__restrict__ tokens,
+                                                                const int32_t *__restrict__ offsets, int n,
+                                                                int64_t rows, float *__restrict__ row_gate) {
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    int lo = 0, hi = n;   // the last e with offsets[e] <= r (never an empty expert)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (offsets[mid] <= r) lo = mid; else hi = mid;
+    }
+    const int64_t t = tokens[r];
+    row_gate[r] = G[t * n + lo] / denom[t];
+}
+
+// Backward of Eq.(16), Eq.(20) and Eq.(15) for one token per wavefront.  drow[r] = <dy_t, E_e(x_t)>
+// of the token's row at expert e.  With D = denom and G_i = G_sigma_i M_i / D:
+//   dG_sigma_i = M_i (dG_i - sum_j G_j dG_j) / D  +  w_b ((G_sigma_i > T_i) - M_i)
+//   dlogit_i   = G_sigma_i (dG_sigma_i - sum_j G_sigma_j dG_sigma_j)
+// (the masks are piecewise constant).  Sums in binary64, lanes strided over the experts, butterfly
+// reduction (the same total in every lane).
+__global__ __launch_bounds__(256) void balanced_gate_bwd_kernel(const float *__restrict__ G,
+                                                                const uint32_t *__restrict__ kept,
+                                                                const int32_t *__restrict__ pos,
+                                                                const float *__restrict__ denom,
+                                                                const int32_t *__restrict__ offsets,
+                                                                const float *__restrict__ drow,
+                                                                const float *__restrict__ thresholds,
+                                                                float w_b, int64_t T, int n, int kept_words,
+                                                                float *__restrict__ dlogit) {
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const float dn = denom[t];
+    const float *g = G + t * n;
+    const int32_t *ps = pos + t * n;
+    const uint32_t *kb = kept + t * kept_words;
+    auto is_kept = [&](int i) { return ((kb[i >> 5] >> (i & 31)) & 1u) != 0u; };
+    auto wave_sum = [&](double v) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+        return v;
+    };
+    double inner = 0.0;
+    for (int i = lane; i < n; i += 64)
+        if (is_kept(i)) inner += (double)(g[i] / dn) * (double)drow[offsets[i] + ps[i]];
+    inner = wave_sum(inner);
+    auto dsigma = [&](int i) {
+        const bool kp = is_kept(i);
+        double v = kp ? ((double)drow[offsets[i] + ps[i]] - inner) / (double)dn : 0.0;
+        if (thresholds) v += (double)w_b * ((g[i] > thresholds[i] ? 1.0 : 0.0) - (kp ? 1.0 : 0.0));
+        return v;
+    };
+    double u = 0.0;
+    for (int i = lane; i < n; i += 64) u += (double)g[i] * dsigma(i);
+    u = wave_sum(u);
+    for (int i = lane; i < n; i += 64) dlogit[t * n + i] = (float)((double)g[i] * (dsigma(i) - u));
 }
 
 // d L_batchwise / d T_i = m_i - #{t : G_sigma(t,i) > T_i} (both masks are piecewise constant in T).
@@ -619,13 +689,60 @@ static int launch_combine_balanced(const moe_config *cfg, const float *out_rows,
     const int n = cfg->n, kw = (n + 31) / 32, d4 = cfg->d / 4;
     const dim3 grid((unsigned)ceil_div(T, 4));
 #define MOE_COMBINE(NC)                                                                                    \
-    hipLaunchKernelGGL(combine_balanced_kernel<NC>, grid, dim3(256), 0, s, (const float4 *)out_rows, gsigma, \
+    hipLaunchKernelGGL((combine_balanced_kernel<NC, false>), grid, dim3(256), 0, s, (const float4 *)out_rows, gsigma, \
                        kept, pos, denom, offsets, rows_total, capacity, T, n, kw, d4, (float4 *)y)
     if (d4 <= 64) MOE_COMBINE(1);
     else if (d4 <= 128) MOE_COMBINE(2);
     else if (d4 <= 256) MOE_COMBINE(4);
     else MOE_COMBINE(8);
 #undef MOE_COMBINE
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+// ---- pieces of the backward pass (the entry point sits with the other backward code) ----------
+int balanced_forward_view(const moe_config *cfg, BalancedFwdView *v) {
+    int st = balanced_check(cfg);
+    if (st != MOE_OK) return st;
+    BalancedLayout L;
+    balanced_layout(cfg, (int64_t)cfg->T * cfg->k, &L);
+    v->pos = L.pos; v->offsets = L.offsets; v->out_rows = L.out_rows; v->ffn_ws = L.ffn_ws; v->total = L.total;
+    return MOE_OK;
+}
+
+int launch_balanced_row_gates(const float *gsigma, const float *denom, const int32_t *tokens,
+                              const int32_t *offsets, int n, int64_t rows, float *row_gate, hipStream_t s) {
+    if (rows == 0) return MOE_OK;
+    hipLaunchKernelGGL(balanced_row_gate_kernel, dim3((unsigned)ceil_div(rows, 256)), dim3(256), 0, s, gsigma,
+                       denom, tokens, offsets, n, rows, row_gate);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+int launch_balanced_gate_bwd(const moe_config *cfg, const float *gsigma, const uint32_t *kept, const int32_t *pos,
+                             const float *denom, const int32_t *offsets, const float *drow,
+                             const float *thresholds, float w_batchwise, float *dlogit, hipStream_t s) {
+    hipLaunchKernelGGL(balanced_gate_bwd_kernel, dim3((unsigned)ceil_div((int64_t)cfg->T, 4)), dim3(256), 0, s,
+                       gsigma, kept, pos, denom, offsets, drow, thresholds, w_batchwise, (int64_t)cfg->T, cfg->n,
+                       (cfg->n + 31) / 32, dlogit);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
+
+int launch_add_kept_rows(const moe_config *cfg, const float *rows_mat, const uint32_t *kept, const int32_t *pos,
+                         const int32_t *offsets, float *dx, hipStream_t s) {
+    const int64_t T = cfg->T;
+    const int n = cfg->n, kw = (n + 31) / 32, d4 = cfg->d / 4;
+    const dim3 grid((unsigned)ceil_div(T, 4));
+#define MOE_ADD(NC)                                                                                          \
+    hipLaunchKernelGGL((combine_balanced_kernel<NC, true>), grid, dim3(256), 0, s, (const float4 *)rows_mat,  \
+                       (const float *)nullptr, kept, pos, (const float *)nullptr, offsets,                   \
+                       (const int32_t *)nullptr, (int64_t)0, T, n, kw, d4, (float4 *)dx)
+    if (d4 <= 64) MOE_ADD(1);
+    else if (d4 <= 128) MOE_ADD(2);
+    else if (d4 <= 256) MOE_ADD(4);
+    else MOE_ADD(8);
+#undef MOE_ADD
     MOE_LAUNCH_CHECK();
     return MOE_OK;
 }

@@ -99,6 +99,23 @@ int backward_moments_offsets(const moe_config *cfg, size_t off[4]);
 // order[r] = the expert with the r-th most rows (equal counts: lower index first)
 int launch_expert_order(const int32_t *offsets, int n, int32_t *order, hipStream_t st);
 
+// strictly balanced gating (Appendix F): what its backward pass needs from the forward code.
+// Byte offsets, inside the forward workspace of moe_layer_forward_balanced, of pos [T,n] (a kept
+// token's place in its expert's list), offsets [n+1], the expert outputs [k*T, d] and the expert
+// kernels' own workspace.
+struct BalancedFwdView {
+    size_t pos, offsets, out_rows, ffn_ws, total;
+};
+int balanced_forward_view(const moe_config *cfg, BalancedFwdView *v);
+int launch_balanced_row_gates(const float *gsigma, const float *denom, const int32_t *tokens,
+                              const int32_t *offsets, int n, int64_t rows, float *row_gate, hipStream_t st);
+int launch_balanced_gate_bwd(const moe_config *cfg, const float *gsigma, const uint32_t *kept, const int32_t *pos,
+                             const float *denom, const int32_t *offsets, const float *drow,
+                             const float *thresholds, float w_batchwise, float *dlogit, hipStream_t st);
+// dx[t] += sum of the rows of rows_mat [k*T, d] that belong to token t
+int launch_add_kept_rows(const moe_config *cfg, const float *rows_mat, const uint32_t *kept, const int32_t *pos,
+                         const int32_t *offsets, float *dx, hipStream_t st);
+
 int launch_route(RouteArgs a, hipStream_t st);
 bool route_is_small(int64_t A, int n);   // one-launch path (few experts, short assignment list)
 // fused launches of the layer forward (small path only; aux_ws as in aux_ws_bytes)

@@ -1,0 +1,141 @@
+"""GPU parity of the backward pass with strictly balanced gating (Appendix F: Eq.(15), (16), (20),
+and the experts of Appendix C) against the oracle's gradients, which central differences pin on
+the CPU."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import moe_workloads as W
+from oracle import moe_oracle as O
+from tests import gpu_harness as G
+
+pytestmark = pytest.mark.gpu
+TOL_BF16 = 2e-2
+TOL_F32 = 1e-5
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_1701_06538_amd import api as _api
+    assert torch.cuda.is_available()
+    return _api
+
+
+def fro_rel(got, ref):
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+CASES = {
+    # name: (T, n, k, d, h, dtype, w_batchwise, flags)
+    "small_bf16": (256, 8, 2, 512, 1024, "bf16", 0.0, 0),
+    "ragged_bf16_loss": (1000, 40, 4, 512, 1024, "bf16", 0.5, 0),
+    "d256_h512": (640, 16, 2, 256, 512, "bf16", 0.25, 0),
+    "n256_moments": (2048, 256, 4, 256, 256, "bf16", 0.1, 2),      # MOE_FLAG_ADAM_MOMENTS
+    "small_f32": (192, 8, 2, 512, 1024, "f32", 0.5, 0),
+    "f32_ragged": (150, 12, 2, 64, 96, "f32", 1.0, 0),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_balanced_backward_parity(api, name):
+    T, n, k, d, h, dtype, w_b, flags = CASES[name]
+    say("balanced backward", name)
+    shape = W.scaled_config(W.CONFIGS[1], T=T, n=n, k=k, d=d, h=h, expert_dtype=dtype)
+    x, W_g, _, _, bias = G.flat_inputs(shape, with_bias=True, gate_std=0.05)
+    W1, W2 = G.device_weights(shape)
+    if dtype == "bf16":
+        W1, W2 = W1.to(torch.bfloat16), W2.to(torch.bfloat16)
+    _, X = O.softmax_gate_f32(x, W_g, bias)
+    m = T * k // n
+    rng = np.random.default_rng(9)
+    kth = -np.sort(-X.astype(np.float64), axis=0)[m - 1]
+    thr = (kth * rng.uniform(0.7, 1.3, size=n)).astype(np.float32)
+    run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
+    run.cfg = api.make_config(shape, flags=flags)
+    run.layer()
+    mask, _ = O.batchwise_mask(X, m)
+    assert np.array_equal(run.kept_mask(), mask)
+    assert np.array_equal(run.gsigma.cpu().numpy()[:T], X)
+
+    dy = W.upstream_grad(shape)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    out = dict(dx=torch.full((T, d), float("nan"), **f32), dW_g=torch.full((d, n), float("nan"), **f32),
+               dW1=torch.full((n, d, h), float("nan"), **f32), dW2=torch.full((n, h, d), float("nan"), **f32))
+    bws = torch.empty(api.moe_backward_balanced_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+    dyd = G.dev(dy)
+
+    def call():
+        api.moe_layer_backward_balanced(run.cfg, run.x, run.W_g, run.thr, run.W1, run.W2, dyd, run.gsigma,
+                                        run.tokens, run.kept, run.denom, run.ws, w_b, out["dx"], out["dW_g"],
+                                        out["dW1"], out["dW2"], bws)
+        torch.cuda.synchronize()
+    call()
+    gr = O.balanced_backward(x, W_g, X, mask, thr, G.oracle_weight_fn(shape), dy, w_b,
+                             expert_input=O.round_to_bf16(x) if dtype == "bf16" else None)
+    errs = dict(dx=G.rel_errors(out["dx"].cpu().numpy(), gr.dx)[0], dW_g=fro_rel(out["dW_g"].cpu().numpy(), gr.dW_g))
+    dW1, dW2 = out["dW1"].cpu().numpy(), out["dW2"].cpu().numpy()
+    errs["dW1"] = max(fro_rel(dW1[e], gr.dW1[e]) for e in range(n))
+    errs["dW2"] = max(fro_rel(dW2[e], gr.dW2[e]) for e in range(n))
+    say("  relative errors:", {q: "%.2e" % v for q, v in errs.items()})
+    tol = TOL_BF16 if dtype == "bf16" else TOL_F32
+    for q, v in errs.items():
+        assert v <= tol, (q, v)
+    keep = {q: v.clone() for q, v in out.items()}     # bit-reproducible
+    call()
+    for q in keep:
+        assert torch.equal(keep[q], out[q]), q
+
+
+def test_balanced_backward_gate_part_is_fp32_accurate(api):
+    """dW_g at fp32 accuracy when the experts' part of the chain is fp32 too, with and without the
+    term of Eq.(20): the difference of the two runs is w_b * x^T softmax'(M_threshold - M_batchwise)."""
+    say("balanced backward: Eq.(20) term")
+    T, n, k, d, h = 256, 16, 2, 64, 64
+    shape = W.scaled_config(W.CONFIGS[1], T=T, n=n, k=k, d=d, h=h, expert_dtype="f32")
+    x, W_g, _, _, bias = G.flat_inputs(shape, with_bias=True, gate_std=0.05)
+    W1, W2 = G.device_weights(shape)
+    _, X = O.softmax_gate_f32(x, W_g, bias)
+    m = T * k // n
+    thr = (-np.sort(-X.astype(np.float64), axis=0)[m - 1] * 0.9).astype(np.float32)
+    run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
+    run.layer()
+    mask, _ = O.batchwise_mask(X, m)
+    dy = W.upstream_grad(shape)
+    dyd = G.dev(dy)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    bws = torch.empty(api.moe_backward_balanced_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+    got = {}
+    for w_b in (0.0, 2.0):
+        dx, dWg = torch.empty((T, d), **f32), torch.empty((d, n), **f32)
+        dW1, dW2 = torch.empty((n, d, h), **f32), torch.empty((n, h, d), **f32)
+        api.moe_layer_backward_balanced(run.cfg, run.x, run.W_g, run.thr if w_b else None, run.W1, run.W2, dyd,
+                                        run.gsigma, run.tokens, run.kept, run.denom, run.ws, w_b, dx, dWg, dW1,
+                                        dW2, bws)
+        torch.cuda.synchronize()
+        gr = O.balanced_backward(x, W_g, X, mask, thr, G.oracle_weight_fn(shape), dy, w_b)
+        assert fro_rel(dWg.cpu().numpy(), gr.dW_g) <= TOL_F32
+        assert G.rel_errors(dx.cpu().numpy(), gr.dx)[0] <= TOL_F32
+        got[w_b] = dWg.cpu().numpy().astype(np.float64)
+    X64 = X.astype(np.float64)
+    dGs = 2.0 * (O.threshold_mask(X, thr).astype(np.float64) - mask)
+    extra = x.astype(np.float64).T @ (X64 * (dGs - (X64 * dGs).sum(axis=1, keepdims=True)))
+    assert np.linalg.norm(got[2.0] - got[0.0] - extra) <= 1e-4 * np.linalg.norm(extra)
+
+
+def test_balanced_backward_validates_on_the_host(api):
+    shape = W.scaled_config(W.CONFIGS[1], T=64, n=8, k=2, d=256, h=256)
+    cfg = api.make_config(shape)
+    one = torch.zeros(64, dtype=torch.float32, device="cuda")
+    with pytest.raises(api.MoeError):      # a weight for Eq.(20) needs the thresholds
+        api.moe_layer_backward_balanced(cfg, one, one, None, one, one, one, one, one, one, one, one, 0.5, one, one,
+                                        one, one, one)
+    bad = api.make_config(W.scaled_config(shape, T=65))     # k*T not a multiple of n
+    assert api.moe_backward_balanced_workspace_bytes(bad) == 0
