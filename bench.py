@@ -180,7 +180,8 @@ def main():
         x, W_g, _, _, bias = G.flat_inputs(shape, with_bias=shape.zipf_beta > 0)
         W1, W2 = G.device_weights(shape, chunk=256)
         thr = np.full((shape.n,), 1.0 / shape.n, np.float32)
-        run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
+        run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2,
+                            flags=api.MOE_FLAG_SAVE_HIDDEN if args.backward else 0)
         ws = run.ws
 
         if args.backward:

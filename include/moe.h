@@ -64,12 +64,13 @@ typedef struct moe_config {
     int32_t flags;         /* MOE_FLAG_* */
 } moe_config;
 
-/* With MOE_FLAG_SAVE_HIDDEN moe_layer_forward and moe_layer_forward_hier also keep the experts' hidden activations
- * (bf16 [T*k, h], routed-row order) in the workspace, and moe_layer_backward / _hier read them
- * instead of recomputing them.  The paper
+/* With MOE_FLAG_SAVE_HIDDEN moe_layer_forward, moe_layer_forward_hier and moe_layer_forward_balanced
+ * also keep the experts' hidden activations (bf16 [T*k, h], routed-row order) in the workspace, and
+ * moe_layer_backward / _hier / _balanced read them instead of recomputing them.  The paper
  * recomputes (Appendix D) to fit 12 GB devices; with 288 GB of HBM the 2*h bytes per routed row
  * are the cheaper side of the trade.  Without the flag the backward pass recomputes. */
-/* With MOE_FLAG_ADAM_MOMENTS moe_layer_backward (bf16 experts) also leaves, in its workspace, the
+/* With MOE_FLAG_ADAM_MOMENTS moe_layer_backward and moe_layer_backward_balanced (bf16 experts) also
+ * leave, in the backward workspace, the
  * per-block sums of squares of dW1 and dW2 that the weight-gradient kernels have in registers
  * anyway; moe_expert_adam_step then skips its own pass over the gradients when it is handed that
  * workspace. */
@@ -296,7 +297,8 @@ int moe_batchwise_loss_grad(const moe_config *cfg, const float *gsigma, const fl
  *   dG_sigma_i = M_i (dG_i - sum_j G_j dG_j) / denom,   dG_i = <dy, E_i(x)>        (Eq.(1), Eq.(16))
  * through the factor (G_sigma - T_i) of Eq.(20) as printed, + w_batchwise (M_threshold - M_batchwise),
  * and from there through the softmax of Eq.(15) over all n experts; the experts as in
- * moe_layer_backward (hidden activations recomputed for bf16 experts, Appendix D; relu'(0) = 0).
+ * moe_layer_backward (for bf16 experts the hidden activations are recomputed, Appendix D, unless the
+ * forward call ran with MOE_FLAG_SAVE_HIDDEN in the same cfg; relu'(0) = 0).
  * The thresholds' own gradient is moe_batchwise_loss_grad's.
  * cfg as for moe_layer_forward_balanced, with moe_layer_backward's shape restrictions
  * (n % 4 == 0; bf16 experts: d, h multiples of 256; fp32 experts: d, h multiples of 4, n <= 65535);

@@ -985,7 +985,8 @@ extern "C" int moe_layer_backward_balanced(const moe_config *cfg, const float *x
                         (float *)(ws + L.dz), dxs, drow, tile_expert, tile_row0, num_tiles, dW1, dW2, true};
         if ((st = run_expert_backward_f32(cfg, ef, s)) != MOE_OK) return st;
     } else {
-        ExpertBwd eb{x, dy, out_rows, row_gate, tokens, offsets, W1, W2, nullptr, (uint16_t *)(ws + L.xs),
+        const uint16_t *saved = V.hidden != (size_t)-1 ? (const uint16_t *)(fw + V.hidden) : nullptr;
+        ExpertBwd eb{x, dy, out_rows, row_gate, tokens, offsets, W1, W2, saved, (uint16_t *)(ws + L.xs),
                      (uint16_t *)(ws + L.dout), (uint16_t *)(ws + L.hid), (uint16_t *)(ws + L.dz), dxs, drow,
                      tile_expert, tile_row0, num_tiles, (int32_t *)(ws + L.order), dW1, dW2,
                      {nullptr, nullptr, nullptr, nullptr}, true};

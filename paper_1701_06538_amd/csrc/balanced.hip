@@ -572,7 +572,8 @@ __global__ __launch_bounds__(256) void threshold_grad_kernel(const float *__rest
 static size_t b_up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct BalancedLayout {
-    size_t clean, Gt, pos, loss_part, counts, offsets, tile_expert, tile_row0, num_tiles, out_rows, ffn_ws, total;
+    size_t clean, Gt, pos, loss_part, counts, offsets, tile_expert, tile_row0, num_tiles, out_rows, ffn_ws,
+        hidden, total;   // hidden: bf16 [rows, h] with MOE_FLAG_SAVE_HIDDEN and bf16 experts, else (size_t)-1
 };
 
 // the experts see `rows` dispatched rows, each one token: a flat layer of `rows` tokens with k = 1
@@ -606,6 +607,8 @@ static void balanced_layout(const moe_config *cfg, int64_t rows, BalancedLayout 
     L->num_tiles = take(16);
     L->out_rows = take((size_t)rows * cfg->d * 4);
     L->ffn_ws = take(moe_ffn_workspace_bytes(&f));
+    const bool keep_hidden = (cfg->flags & MOE_FLAG_SAVE_HIDDEN) && cfg->expert_dtype == MOE_DTYPE_BF16;
+    L->hidden = keep_hidden ? take((size_t)rows * cfg->h * 2) : (size_t)-1;
     L->total = off;
 }
 
@@ -706,7 +709,8 @@ int balanced_forward_view(const moe_config *cfg, BalancedFwdView *v) {
     if (st != MOE_OK) return st;
     BalancedLayout L;
     balanced_layout(cfg, (int64_t)cfg->T * cfg->k, &L);
-    v->pos = L.pos; v->offsets = L.offsets; v->out_rows = L.out_rows; v->ffn_ws = L.ffn_ws; v->total = L.total;
+    v->pos = L.pos; v->offsets = L.offsets; v->out_rows = L.out_rows; v->ffn_ws = L.ffn_ws;
+    v->hidden = L.hidden; v->total = L.total;
     return MOE_OK;
 }
 
@@ -841,7 +845,7 @@ extern "C" int moe_layer_forward_balanced_profiled(const moe_config *cfg, const 
     if ((st = record_event(ev, 2, s)) != MOE_OK) return st;
     st = expert_ffn_with_hidden(&f, x, tokens, offsets, (const int32_t *)(ws + L.tile_expert),
                                 (const int32_t *)(ws + L.tile_row0), (const int32_t *)(ws + L.num_tiles), W1, W2,
-                                out_rows, ws + L.ffn_ws, nullptr, s);
+                                out_rows, ws + L.ffn_ws, L.hidden != (size_t)-1 ? (uint16_t *)(ws + L.hidden) : nullptr, s);
     if (st != MOE_OK) return st;
     if ((st = record_event(ev, 3, s)) != MOE_OK) return st;
     st = launch_combine_balanced(cfg, out_rows, gsigma, kept, (const int32_t *)(ws + L.pos), denom, offsets,

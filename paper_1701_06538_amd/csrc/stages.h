@@ -102,9 +102,10 @@ int launch_expert_order(const int32_t *offsets, int n, int32_t *order, hipStream
 // strictly balanced gating (Appendix F): what its backward pass needs from the forward code.
 // Byte offsets, inside the forward workspace of moe_layer_forward_balanced, of pos [T,n] (a kept
 // token's place in its expert's list), offsets [n+1], the expert outputs [k*T, d] and the expert
-// kernels' own workspace.
+// kernels' own workspace; hidden: the bf16 hidden activations [k*T, h] kept under
+// MOE_FLAG_SAVE_HIDDEN, or (size_t)-1.
 struct BalancedFwdView {
-    size_t pos, offsets, out_rows, ffn_ws, total;
+    size_t pos, offsets, out_rows, ffn_ws, hidden, total;
 };
 int balanced_forward_view(const moe_config *cfg, BalancedFwdView *v);
 int launch_balanced_row_gates(const float *gsigma, const float *denom, const int32_t *tokens,

@@ -128,9 +128,9 @@ def rel_errors(got, ref):
 class BalancedRun:
     """One forward pass with strictly balanced gating (Appendix F) on the GPU."""
 
-    def __init__(self, api, shape, x, W_g, bias, thresholds, W1=None, W2=None):
+    def __init__(self, api, shape, x, W_g, bias, thresholds, W1=None, W2=None, flags=0):
         self.api = api
-        self.cfg = c = api.make_config(shape)
+        self.cfg = c = api.make_config(shape, flags=flags)
         T, n, d = c.T, c.n, c.d
         self.m = api.moe_balanced_rows_per_expert(c)
         assert self.m == T * c.k // n

@@ -140,5 +140,12 @@ def test_widened_entry_points_validate_on_the_host(api):
     hp = api.MoeAdamParams(1e-3, 0.999, 1e-8, 1)
     assert api._moe_expert_adam_step(ctypes.byref(flat), ctypes.byref(hp), *([None] * 12), 0, None) == api.MOE_EINVAL
     assert api._moe_combine_epilogue(ctypes.byref(flat), *([None] * 5), 0.0, None, None) == api.MOE_EINVAL
+    # backward with balanced gating: needs a balanced batch, and the flat backward's expert shapes
+    assert api.moe_backward_balanced_workspace_bytes(flat) > 0
+    assert api.moe_backward_balanced_workspace_bytes(odd) == 0
+    assert api._moe_layer_backward_balanced(ctypes.byref(flat), *([None] * 11), 0.0, *([None] * 5), 0, None) == api.MOE_EINVAL
+    assert api._moe_layer_backward_balanced(ctypes.byref(odd), *([None] * 11), 0.0, *([None] * 5), 0, None) == api.MOE_EINVAL
+    off_tile = api.make_config(T=64, d=384, h=1024, n=16, k=4)          # bf16 experts: d, h multiples of 256
+    assert api._moe_layer_backward_balanced(ctypes.byref(off_tile), *([None] * 11), 0.0, *([None] * 5), 0, None) == api.MOE_EUNSUPPORTED
     # fp32 experts and expert counts off the tile sizes are accepted by the flat backward
     assert api.moe_backward_workspace_bytes(api.make_config(T=64, d=64, h=96, n=20, k=2, expert_dtype=api.MOE_DTYPE_F32)) > 0

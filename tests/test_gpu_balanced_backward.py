@@ -39,6 +39,8 @@ CASES = {
     "ragged_bf16_loss": (1000, 40, 4, 512, 1024, "bf16", 0.5, 0),
     "d256_h512": (640, 16, 2, 256, 512, "bf16", 0.25, 0),
     "n256_moments": (2048, 256, 4, 256, 256, "bf16", 0.1, 2),      # MOE_FLAG_ADAM_MOMENTS
+    "saved_hidden": (1000, 40, 4, 512, 1024, "bf16", 0.5, 1),      # MOE_FLAG_SAVE_HIDDEN: no recomputation
+    "saved_hidden_d256": (640, 16, 2, 256, 512, "bf16", 0.0, 1),
     "small_f32": (192, 8, 2, 512, 1024, "f32", 0.5, 0),
     "f32_ragged": (150, 12, 2, 64, 96, "f32", 1.0, 0),
 }
@@ -58,8 +60,7 @@ def test_balanced_backward_parity(api, name):
     rng = np.random.default_rng(9)
     kth = -np.sort(-X.astype(np.float64), axis=0)[m - 1]
     thr = (kth * rng.uniform(0.7, 1.3, size=n)).astype(np.float32)
-    run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
-    run.cfg = api.make_config(shape, flags=flags)
+    run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2, flags=flags)
     run.layer()
     mask, _ = O.batchwise_mask(X, m)
     assert np.array_equal(run.kept_mask(), mask)
