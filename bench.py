@@ -322,7 +322,7 @@ def main():
                    "k": shape.k, "experts_used": used,
                    "gating": "strictly balanced (softmax, batchwise mask)" if balanced else "fp32 noisy top-k",
                    "expert_math": "bf16 MFMA, fp32 accumulate" if wbytes == 2 else "fp32"},
-        "roofline": {"kernel": "ffn_bf16_kernel" if wbytes == 2 else "ffn_f32_kernel",
+        "roofline": {"kernel": "ffn_bf16_kernel" if wbytes == 2 else "ffn_f32_mfma_kernel (two launches)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic("ffn_bf16_%s_pmc.txt" % shape.name.split("_")[0]),
                      "kernel_ms": ffn_ms, "algorithmic_bytes": ffn_bytes,

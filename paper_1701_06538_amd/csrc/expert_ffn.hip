@@ -10,7 +10,8 @@
 // and then the hidden tile live in LDS (the hidden layer never reaches HBM); accumulation is
 // fp32 in v_mfma_f32_32x32x16_bf16.
 //
-// fp32 path (ffn_f32_kernel): plain LDS-tiled grouped GEMM, hidden layer kept in a workspace.
+// fp32 path (ffn_f32_mfma_kernel): LDS-tiled grouped GEMM on the fp32 matrix cores, hidden layer
+// kept in a workspace.
 #include "stages.h"
 
 namespace moe {
@@ -460,67 +461,90 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
 // fp32 experts: C[rows, N] = act(A[rows, K] W_e[K, N]) per row tile; A rows either gathered
 // from x through perm or read from the sorted hidden buffer.
 // ---------------------------------------------------------------------------------------
+// On the fp32 matrix cores: 64 x 64 tile, four waves of one 32 x 32 block each
+// (v_mfma_f32_32x32x2f32: a lane supplies A(row = lane % 32, k) and B(k, col = lane % 32) for
+// k = lane / 32 of the instruction's two k values).  k-slabs of 32 double-buffered in LDS, the next
+// slab prefetched into registers under the current one's 16 matrix instructions.  Which two k values
+// an instruction takes is free as long as both operands agree: step (j, u) uses k = 8j + u from
+// lanes 0-31 and 8j + 4 + u from lanes 32-63, so a lane's A values for four steps are one 16-byte
+// LDS read.  Every output keeps one accumulator over the whole of K (a sequential fp32 fma chain).
+typedef float v16f32 __attribute__((ext_vector_type(16)));
 template <bool GATHER, bool RELU>
-__global__ __launch_bounds__(256) void ffn_f32_kernel(FfnArgs p, const float *A, const float *Wall,
-                                                      float *C, int K, int N) {
-    constexpr int TM = kFfnTM, TN = 64, TK = 16;
-    __shared__ float As[TK][TM + 4];
-    __shared__ float Bs[TK][TN + 4];
+__global__ __launch_bounds__(256) void ffn_f32_mfma_kernel(FfnArgs p, const float *A, const float *Wall,
+                                                           float *C, int K, int N) {
+    constexpr int TM = kFfnTM, TN = 64, TK = 32, AS = TK + 4, BS = TN + 8;
+    static_assert(TM == 64, "four waves cover 64 x 64");
+    __shared__ __attribute__((aligned(16))) float As[2][TM][AS];   // [row][k]; 36-float rows: conflict-free 16-byte reads
+    __shared__ __attribute__((aligned(16))) float Bs[2][TK][BS];   // [k][col]; 72-float rows: k and k+4 hit different bank halves
     const int num_tiles = *p.num_tiles;
     const int tile = blockIdx.x;
     if (tile >= num_tiles) return;
     const int e = p.tile_expert[tile];
     const int row0 = p.tile_row0[tile];
     const int rows = min(TM, p.offsets[e + 1] - row0);
+    if (rows <= 0) return;
     const int col0 = blockIdx.y * TN;
     const float *W = Wall + (size_t)e * K * N;
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, l32 = lane & 31, wm = wave >> 1, wn = wave & 1;
 
-    // A loader: 64 rows x 16 k, one float4 along k per thread
-    const int ar = tid >> 2, ak = (tid & 3) * 4;
-    const float *a_src = nullptr;
-    if (ar < rows) {
-        const int64_t src_row = GATHER ? (int64_t)(p.perm[row0 + ar] / p.k) : (int64_t)(row0 + ar);
-        a_src = A + src_row * K + ak;
-    }
-    // B loader: 16 k x 64 cols, one float4 along cols per thread
+    // loaders: A 64 rows x 32 k and B 32 k x 64 cols, two float4 per thread each
+    const int ar = tid >> 3, akq = (tid & 7) * 4;
     const int bk = tid >> 4, bc = (tid & 15) * 4;
-
-    float acc[4][4] = {};
-    for (int k0 = 0; k0 < K; k0 += TK) {
-        float4 av = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (a_src && k0 + ak < K) av = *reinterpret_cast<const float4 *>(a_src + k0);
-        As[ak + 0][ar] = av.x; As[ak + 1][ar] = av.y; As[ak + 2][ar] = av.z; As[ak + 3][ar] = av.w;
-        float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (k0 + bk < K && col0 + bc < N)
-            bv = *reinterpret_cast<const float4 *>(W + (size_t)(k0 + bk) * N + col0 + bc);
-        *reinterpret_cast<float4 *>(&Bs[bk][bc]) = bv;
-        __syncthreads();
+    const float *a_src[2];
 #pragma unroll
-        for (int kk = 0; kk < TK; ++kk) {
-            float a[4], b[4];
+    for (int i = 0; i < 2; ++i) {
+        const int r = min(ar + 32 * i, rows - 1);   // rows past the end re-read a valid row; their results are not stored
+        const int64_t src_row = GATHER ? (int64_t)(p.perm[row0 + r] / p.k) : (int64_t)(row0 + r);
+        a_src[i] = A + src_row * K;
+    }
+    const bool b_in = col0 + bc < N;
+    float4 areg[2], breg[2];
+    auto load_slab = [&](int k0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        for (int i = 0; i < 2; ++i) {
+            const int ka = k0 + akq, kb = k0 + bk + 16 * i;
+            const float4 av = *reinterpret_cast<const float4 *>(a_src[i] + min(ka, K - 4));
+            areg[i] = ka < K ? av : make_float4(0.f, 0.f, 0.f, 0.f);
+            const float4 bv = *reinterpret_cast<const float4 *>(W + (size_t)min(kb, K - 1) * N + (b_in ? col0 + bc : 0));
+            breg[i] = (kb < K && b_in) ? bv : make_float4(0.f, 0.f, 0.f, 0.f);
         }
+    };
+    auto store_slab = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            *reinterpret_cast<float4 *>(&As[buf][ar + 32 * i][akq]) = areg[i];
+            *reinterpret_cast<float4 *>(&Bs[buf][bk + 16 * i][bc]) = breg[i];
+        }
+    };
+    v16f32 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const int nslab = (K + TK - 1) / TK;
+    load_slab(0);
+    store_slab(0);
+    __syncthreads();
+    for (int s = 0; s < nslab; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < nslab) load_slab((s + 1) * TK);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float4 a4 = *reinterpret_cast<const float4 *>(&As[buf][32 * wm + l32][8 * j + 4 * half]);
+            const float av[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], Bs[buf][8 * j + 4 * half + u][32 * wn + l32], acc, 0, 0, 0);
+        }
+        if (s + 1 < nslab) store_slab(buf ^ 1);
         __syncthreads();
     }
+    const int c = col0 + 32 * wn + l32;
+    if (c < N) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = ty * 4 + i;
-        if (r >= rows) continue;
-        const int c = col0 + tx * 4;
-        if (c >= N) continue;
-        float4 o = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
-        if (RELU) {
-            o.x = fmaxf(o.x, 0.f); o.y = fmaxf(o.y, 0.f); o.z = fmaxf(o.z, 0.f); o.w = fmaxf(o.w, 0.f);
+        for (int r = 0; r < 16; ++r) {
+            const int row = 32 * wm + 8 * (r / 4) + 4 * half + (r % 4);
+            if (row < rows) C[(size_t)(row0 + row) * N + c] = RELU ? fmaxf(acc[r], 0.f) : acc[r];
         }
-        *reinterpret_cast<float4 *>(C + (size_t)(row0 + r) * N + c) = o;
     }
 }
 
@@ -594,11 +618,11 @@ int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles
     }
     if (cfg->d % 4 || cfg->h % 4) return MOE_EUNSUPPORTED;
     dim3 g1((unsigned)max_tiles, (unsigned)ceil_div(cfg->h, 64));
-    hipLaunchKernelGGL((ffn_f32_kernel<true, true>), g1, dim3(256), 0, st, a, a.x,
+    hipLaunchKernelGGL((ffn_f32_mfma_kernel<true, true>), g1, dim3(256), 0, st, a, a.x,
                        (const float *)a.W1, a.hidden, cfg->d, cfg->h);
     MOE_LAUNCH_CHECK();
     dim3 g2((unsigned)max_tiles, (unsigned)ceil_div(cfg->d, 64));
-    hipLaunchKernelGGL((ffn_f32_kernel<false, false>), g2, dim3(256), 0, st, a, a.hidden,
+    hipLaunchKernelGGL((ffn_f32_mfma_kernel<false, false>), g2, dim3(256), 0, st, a, a.hidden,
                        (const float *)a.W2, a.out, cfg->h, cfg->d);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
