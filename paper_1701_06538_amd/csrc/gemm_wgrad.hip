@@ -193,28 +193,39 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
     WG_STAMP(2);
 }
 
+// A workgroup ranks 64 experts (one per lane); its four waves each compare them against a quarter
+// of every 2048-expert chunk, and the four partial ranks are added at the end.
 __global__ __launch_bounds__(256) void expert_order_kernel(const int32_t *__restrict__ offsets, int n,
                                                            int32_t *__restrict__ order) {
-    __shared__ int cs[2048];                       // counts of a chunk of experts
-    const int e = blockIdx.x * 256 + threadIdx.x;
+    __shared__ __attribute__((aligned(16))) int cs[2048];   // counts of a chunk of experts (-1 past the end)
+    __shared__ int part[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int e = blockIdx.x * 64 + lane;
     const int c = e < n ? offsets[e + 1] - offsets[e] : 0;
     int rank = 0;
     for (int o0 = 0; o0 < n; o0 += 2048) {
         const int m = min(2048, n - o0);
         __syncthreads();
-        for (int i = threadIdx.x; i < m; i += 256) cs[i] = offsets[o0 + i + 1] - offsets[o0 + i];
+        for (int i = threadIdx.x; i < 2048; i += 256) cs[i] = i < m ? offsets[o0 + i + 1] - offsets[o0 + i] : -1;
         __syncthreads();
-        for (int i = 0; i < m; ++i) {
-            const int co = cs[i];
-            rank += co > c || (co == c && o0 + i < e);
+        const int lo = 512 * wave, hi = min(lo + 512, (m + 3) & ~3);
+        // every lane reads the same four counts per step (a broadcast 16-byte LDS read)
+#pragma unroll 4
+        for (int i = lo; i < hi; i += 4) {
+            const int4 v = *reinterpret_cast<const int4 *>(&cs[i]);
+            const int j = o0 + i;
+            rank += (v.x > c || (v.x == c && j < e)) + (v.y > c || (v.y == c && j + 1 < e)) +
+                    (v.z > c || (v.z == c && j + 2 < e)) + (v.w > c || (v.w == c && j + 3 < e));
         }
     }
-    if (e < n) order[rank] = e;
+    part[wave][lane] = rank;
+    __syncthreads();
+    if (wave == 0 && e < n) order[part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane]] = e;
 }
 
 int launch_expert_order(const int32_t *offsets, int n, int32_t *order, hipStream_t st) {
     if (n <= 0) return MOE_OK;
-    hipLaunchKernelGGL(expert_order_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, offsets, n, order);
+    hipLaunchKernelGGL(expert_order_kernel, dim3((unsigned)ceil_div(n, 64)), dim3(256), 0, st, offsets, n, order);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
 }
