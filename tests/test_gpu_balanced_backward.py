@@ -41,6 +41,7 @@ CASES = {
     "n256_moments": (2048, 256, 4, 256, 256, "bf16", 0.1, 2),      # MOE_FLAG_ADAM_MOMENTS
     "saved_hidden": (1000, 40, 4, 512, 1024, "bf16", 0.5, 1),      # MOE_FLAG_SAVE_HIDDEN: no recomputation
     "saved_hidden_d256": (640, 16, 2, 256, 512, "bf16", 0.0, 1),
+    "cfg1_shape": (8192, 256, 4, 512, 1024, "bf16", 0.1, 1),      # the metric's workload at full size
     "small_f32": (192, 8, 2, 512, 1024, "f32", 0.5, 0),
     "f32_ragged": (150, 12, 2, 64, 96, "f32", 1.0, 0),
 }
