@@ -150,12 +150,16 @@ def main():
     ap.add_argument("--optimizer", action="store_true",
                     help="training configs: also time the factored-second-moment Adam step of the expert "
                          "matrices (outside the timed region; reported under \"optimizer\")")
-    ap.add_argument("--cpu-sample", type=int, default=2048)
+    ap.add_argument("--cpu-sample", type=int, default=None,
+                    help="tokens of the workload the oracle is timed on (default: all 8192 of the metric's "
+                         "workload, about 20 s of host time; 2048 for the other configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel, so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
     args = ap.parse_args()
+    if args.cpu_sample is None:
+        args.cpu_sample = 8192 if args.config == 1 else 2048
     if args.steps is None:
         args.steps = 200 if args.config <= 1 else 20
     if args.gpus != 1:
