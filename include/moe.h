@@ -382,6 +382,9 @@ int moe_layer_forward_threshold(const moe_config *cfg, const float *x, const flo
  * then taken from it instead of from a pass over dW1 and dW2.  Without it cfg->T and cfg->k are
  * not used.
  */
+/* The hyper-parameters are fp32 as passed: 1 - beta2 and 1 - beta2^step are formed from the fp32
+ * value of beta2 (0.999f is 0.99900001287...: a reference fed the decimal 0.999 differs by 1.3e-5
+ * in 1 - beta2). */
 typedef struct moe_adam_params {
     float lr, beta2, eps;
     int32_t step;          /* 1 for the first update */

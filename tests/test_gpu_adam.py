@@ -149,3 +149,53 @@ def test_adam_step_with_sums_from_the_backward_pass(api):
         plain = api.make_config(shape)
         api.moe_expert_adam_step(plain, 1e-2, 0.9, 1e-8, 1, grads[3], grads[4], m0[0], m0[1], c0[0], c0[1],
                                  s0[0], s0[1], s0[2], s0[3], ows, backward_workspace=bws)
+
+
+def test_training_step_with_adam_at_full_size(api):
+    """The training workload at full size (T = 65536, 512 experts, skewed loads): forward, backward
+    with the sums of squares taken in the weight-gradient kernels, then the Adam step of all 1024
+    matrices; sampled experts against the oracle's step applied to the gradients the GPU produced
+    (the gradients themselves are checked at this size by the backward tests)."""
+    from tests import gpu_harness as G
+    shape = W.CONFIGS[4]
+    say("adam at full size", shape.name)
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape, True)
+    W1, W2 = G.device_weights(shape)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2,
+                    flags=api.MOE_FLAG_SAVE_HIDDEN | api.MOE_FLAG_ADAM_MOMENTS)
+    run.fused()
+    T, d, h, n = shape.T, shape.d, shape.h, shape.n
+    f32 = dict(dtype=torch.float32, device="cuda")
+    grads = [torch.empty((T, d), **f32), torch.empty((d, n), **f32), torch.empty((d, n), **f32),
+             torch.empty((n, d, h), **f32), torch.empty((n, h, d), **f32)]
+    bws = torch.empty(api.moe_backward_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+    dy = G.dev(W.upstream_grad(shape))
+    api.moe_layer_backward(run.cfg, run.x, run.W_g, run.W_noise, run.eps, run.W1, run.W2, dy, run.topk_idx,
+                           run.topk_gate, run.workspace, grads[0], grads[1], grads[2], grads[3], grads[4], bws)
+    masters = [run.W1.to(torch.float32), run.W2.to(torch.float32)]
+    before = [m.clone() for m in masters]
+    copies = [torch.zeros_like(run.W1), torch.zeros_like(run.W2)]
+    st = [torch.zeros((n, d), **f32), torch.zeros((n, h), **f32), torch.zeros((n, h), **f32), torch.zeros((n, d), **f32)]
+    ows = torch.empty(max(256, api.moe_adam_workspace_bytes(run.cfg)), dtype=torch.uint8, device="cuda")
+    # the hyper-parameters cross the C ABI as fp32: the oracle gets the same (rounded) values, or
+    # 1 - beta2 would differ by 1.3e-5 of itself
+    lr, beta2, eps_adam = (float(np.float32(v)) for v in (1e-3, 0.999, 1e-8))
+    api.moe_expert_adam_step(run.cfg, lr, beta2, eps_adam, 1, grads[3], grads[4], masters[0], masters[1], copies[0],
+                             copies[1], st[0], st[1], st[2], st[3], ows, backward_workspace=bws)
+    torch.cuda.synchronize()
+    counts = np.bincount(run.topk_idx.cpu().numpy().reshape(-1), minlength=n)
+    sample = sorted({0, 17, 300, 511, int(np.argmax(counts)), int(np.argmin(counts))})
+    for w, (R, C) in enumerate(((d, h), (h, d))):
+        for e in sample:
+            g = grads[3 + w][e].cpu().numpy()
+            ref_W, ref_vr, ref_vc = O.factored_adam_step(before[w][e].cpu().numpy(), g, np.zeros(R), np.zeros(C),
+                                                         lr, beta2, eps_adam, 1)
+            got = masters[w][e].cpu().numpy()
+            assert rel(got, ref_W) <= TOL, (w, e)
+            assert rel(st[2 * w][e].cpu().numpy(), ref_vr) <= TOL and rel(st[2 * w + 1][e].cpu().numpy(), ref_vc) <= TOL
+            upd_ref = ref_W - before[w][e].cpu().numpy().astype(np.float64)
+            upd_got = got.astype(np.float64) - before[w][e].cpu().numpy().astype(np.float64)
+            assert np.abs(upd_got - upd_ref).max() <= 1e-4 * np.abs(upd_ref).max() + 1e-9
+            bits = copies[w][e].view(torch.int16).cpu().numpy().view(np.uint16)
+            assert np.array_equal(bits, (O.round_to_bf16(got).view(np.uint32) >> 16).astype(np.uint16))
+    assert all(torch.isfinite(m).all() for m in masters)
