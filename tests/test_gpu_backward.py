@@ -192,3 +192,41 @@ def test_cfg4_full_training_step(api):
         step()
     ms = (time.perf_counter() - t0) / 3 * 1e3
     say("  forward+backward step %.3f ms -> %.2f M tokens/s" % (ms, shape.T / ms / 1e3))
+
+
+def test_side_streams_give_the_same_results(api):
+    """Every kernel goes to the caller's stream: forward + backward issued on two non-blocking side
+    streams at once (own buffers and workspaces each, no synchronisation in between) reproduce the
+    default-stream results bit for bit."""
+    shape = W.scaled_config(W.CONFIGS[4], T=1024, n=64, k=3, zipf_beta=0.5)
+    say("side streams", shape)
+    dy = W.upstream_grad(shape)
+    _, inputs, run0, out0, _ = run_backward(api, shape, True, dy, flags=api.MOE_FLAG_SAVE_HIDDEN)
+    x, W_g, W_noise, eps, bias = inputs
+    f32 = dict(dtype=torch.float32, device="cuda")
+    T, d, h, n = shape.T, shape.d, shape.h, shape.n
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    held = []
+    for s in streams:
+        with torch.cuda.stream(s):
+            W1, W2 = G.device_weights(shape)
+            run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2, flags=api.MOE_FLAG_SAVE_HIDDEN)
+            ws = torch.empty(api.moe_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+            out = dict(dx=torch.empty((T, d), **f32), dW_g=torch.empty((d, n), **f32), dW_noise=torch.empty((d, n), **f32),
+                       dW1=torch.empty((n, d, h), **f32), dW2=torch.empty((n, h, d), **f32))
+            bws = torch.empty(api.moe_backward_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+            dyd = G.dev(dy)
+            api.moe_layer_forward(run.cfg, run.x, run.W_g, run.W_noise, run.bias, run.eps, run.W1, run.W2, run.y,
+                                  run.topk_idx, run.topk_gate, run.importance, run.load, run.losses, ws)
+            api.moe_layer_backward(run.cfg, run.x, run.W_g, run.W_noise, run.eps, run.W1, run.W2, dyd, run.topk_idx,
+                                   run.topk_gate, ws, out["dx"], out["dW_g"], out["dW_noise"], out["dW1"],
+                                   out["dW2"], bws)
+            held.append((run, out, ws, bws, dyd, W1, W2))
+    for s in streams:
+        s.synchronize()
+    torch.cuda.synchronize()
+    for run, out, *_ in held:
+        assert torch.equal(run.y, run0.y) and torch.equal(run.topk_idx, run0.topk_idx)
+        assert torch.equal(run.losses[:2], run0.losses[:2])
+        for q in out0:
+            assert torch.equal(out[q], out0[q]), q
