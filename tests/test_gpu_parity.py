@@ -286,3 +286,34 @@ def test_combine_epilogue(api, which):
     assert row <= tol and mx <= tol
     with pytest.raises(api.MoeError):
         api.moe_combine_epilogue(run.cfg, run.out_sorted, run.topk_gate, run.inv_perm, run.x, None, 0.3, out)
+
+
+def test_layer_forward_in_a_hip_graph(api):
+    """The layer call allocates nothing, clears nothing with memset nodes and never synchronises, so
+    it can be captured: three replays with fresh inputs copied into the captured buffers, with eager
+    work in between, each equal to the eager call on the same inputs bit for bit."""
+    shape = _shape(1, T=1024, n=64, k=4)
+    say("hip graph", shape)
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape, True)
+    W1, W2 = G.device_weights(shape)
+    cap = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+    cap.fused()                                   # warm-up outside the capture (one-time function attributes)
+    eager = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+    ws = cap.workspace
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        api.moe_layer_forward(cap.cfg, cap.x, cap.W_g, cap.W_noise, cap.bias, cap.eps, cap.W1, cap.W2, cap.y,
+                              cap.topk_idx, cap.topk_gate, cap.importance, cap.load, cap.losses, ws)
+    rng = np.random.default_rng(5)
+    for rep in range(3):
+        xi = (x * np.float32(1.0 + 0.25 * rep) + rng.standard_normal(x.shape).astype(np.float32) * np.float32(0.1 * rep))
+        cap.x.copy_(G.dev(xi))
+        cap.y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eager.x.copy_(G.dev(xi))
+        eager.fused()                             # the program's own eager work between replays
+        assert torch.equal(cap.topk_idx, eager.topk_idx), rep
+        assert torch.equal(cap.y, eager.y), rep
+        assert torch.equal(cap.losses[:2], eager.losses[:2]), rep
+        assert torch.equal(cap.importance, eager.importance) and torch.equal(cap.load, eager.load)
