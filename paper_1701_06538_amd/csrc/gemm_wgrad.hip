@@ -5,16 +5,12 @@
 // One workgroup of eight wavefronts owns a 256 x 256 block of C_e, each wavefront 128 x 64 as 8 x 4
 // v_mfma_f32_16x16x32_bf16 tiles (128 accumulators, two wavefronts per SIMD so that one's LDS and
 // vector work runs under the other's matrix work).  The matrix cores want, per lane, eight
-// CONSECUTIVE contracted rows of one column, but memory has the columns consecutive.  So every
-// thread loads a 4 x 8 block (four 16-byte loads), transposes it in registers with byte permutes
-// and writes eight 8-byte column pieces to LDS; the operand reads are then plain 16-byte LDS
-// reads, and the wavefronts share one copy of both panels.  Column 8c+j of a 128-column group is
-// stored in slot 16j+c (80-byte slots), so that a lane ends up holding four consecutive columns of
-// a row of C and a pair of wavefronts fills whole 32-byte pieces.
-// Pipeline per 32 contracted rows: slab s is multiplied from LDS while slab s+1 is transposed into
+// CONSECUTIVE contracted rows of one column, but memory has the columns consecutive: the
+// transposing LDS reads described at the kernel deliver exactly that from row-major slabs.
+// Pipeline per 32 contracted rows: slab s is multiplied from LDS while slab s+1 is stored into
 // the other LDS buffer and slab s+2 is in flight from memory; every load and store is
-// unconditional (clamped rows, selected values).  The kernel is bound by LDS traffic: per slab the
-// wavefronts read 96 KB and write 32 KB, about 1700 cycles, against 1024 cycles of matrix work.
+// unconditional (clamped rows, selected values).  Per slab the wavefronts read 96 KB of LDS and
+// write 32 KB, about as many LDS cycles as the 1024 cycles of matrix work per SIMD.
 #include "stages.h"
 
 namespace moe {
@@ -22,7 +18,6 @@ namespace moe {
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
 #ifdef MOE_WGRAD_TIMING
 __device__ long long g_wgrad_timing[8192 * 4];
@@ -36,20 +31,41 @@ extern "C" int moe_debug_read_wgrad_timing(long long *host_out) {
 
 constexpr int WG_TILE = 256;    // rows and columns of C per workgroup
 constexpr int WG_K = 32;        // contracted rows per slab
-constexpr int WG_SLOT = 80;     // bytes per staged column: 32 rows of bf16 + 16 bytes of padding
-constexpr int WG_STAGE = 2 * WG_TILE * WG_SLOT;   // both panels
+// Operand staging: the slabs go to LDS as they are in memory
+// (row = contracted row, columns contiguous; 16-byte stores, a wavefront per row), and gfx950's
+// ds_read_b64_tr_b16 hands every lane four CONSECUTIVE contracted rows of one column: within a
+// block of 16 lanes, lane j receives element j % 4 of the 8 bytes addressed by lanes j / 4,
+// j / 4 + 4, j / 4 + 8, j / 4 + 12.  Lane i of block b therefore addresses row 8 b + 4 half + i / 4,
+// columns 4 (i % 4) .. + 3 of the 16-column tile, and two such reads (half = 0, 1) make one
+// matrix-core operand (k = 8 b .. 8 b + 7 of the slab in lane group b).  No register transpose and
+// no scattered LDS stores.  B is the matrix instruction's first operand, so a lane holds four
+// consecutive columns of one row of C:
+//   acc[i][j][r] = C[m0 + 128 wm + 16 i + c][n0 + 64 wn + 16 j + 4 g + r].
+constexpr int WT_PITCH = 2 * WG_TILE + 32;            // bytes per slab row of one panel: 136 words = 8 mod 64 banks
+constexpr int WT_PANEL = WG_K * WT_PITCH;
+constexpr int WT_STAGE = 2 * WT_PANEL;
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ v8bf read_tr_operand(const char *panel_tile) {
+    // panel_tile: this lane's address for half 0; half 1 is four slab rows further
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3))) *)panel_tile);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (v4s __attribute__((address_space(3))) *)(panel_tile + 4 * WT_PITCH));
+    return __builtin_bit_cast(v8bf, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
 
 __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
     extern __shared__ __attribute__((aligned(16))) char stage_mem[];   // two stages
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
+    const int tiles_m = p.M / WG_TILE, tiles_n = p.N / WG_TILE, per_e = tiles_m * tiles_n;
+    const int n_experts = gridDim.x / per_e;
+    int rank = blockIdx.x / per_e, sub = blockIdx.x % per_e;
     // A workgroup contracts ALL rows of its expert, so with a skewed gate the workgroups differ
     // widely in length: the experts are taken by decreasing row count (longest first), rank r on
     // XCD r % 8 (workgroup i goes to XCD i % 8), so that the long ones start first, spread over the
     // chip, and the workgroups of one expert share one L2's copy of its rows.
-    const int tiles_m = p.M / WG_TILE, tiles_n = p.N / WG_TILE, per_e = tiles_m * tiles_n;
-    const int n_experts = gridDim.x / per_e;
-    int rank = blockIdx.x / per_e, sub = blockIdx.x % per_e;
     if (n_experts % 8 == 0) {
         const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8, round = slot / per_e;
         rank = round * 8 + ((round & 1) ? 7 - xcd : xcd);   // serpentine: the XCDs' row totals stay close
@@ -65,48 +81,38 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    // staging role: rows 4*sg .. 4*sg+3 of the slab, columns 8*cb .. 8*cb+7 of panel A (cb < 32) or B
-    const int sg = lane & 7, cb = wave * 8 + (lane >> 3);
-    const bool is_b = cb >= 32;
-    const int cbl = cb & 31;
-    const uint16_t *src = is_b ? p.B + n0 + 8 * cbl : p.A + m0 + 8 * cbl;
+    // staging role: a wavefront moves slab rows wave, wave + 8, wave + 16, wave + 24; lanes 0-31 the
+    // 32 16-byte chunks of the A panel's row, lanes 32-63 those of the B panel's
+    const bool is_b = lane >= 32;
+    const int chunk = lane & 31;
+    const uint16_t *src = is_b ? p.B + n0 + 8 * chunk : p.A + m0 + 8 * chunk;
     const int64_t ld = is_b ? p.N : p.M;
-    // slot of column 8*cbl + j within its panel: group of 128 columns, then 16*j + (cbl % 16)
-    const int slot0 = (is_b ? WG_TILE : 0) + 128 * (cbl >> 4) + (cbl & 15);
-    const int st_off = slot0 * WG_SLOT + 8 * sg;        // + 16*j*WG_SLOT for column j
+    const int st_off = (is_b ? WT_PANEL : 0) + 16 * chunk;      // + row * WT_PITCH
 
-    // multiply role: wave (wm, wn) owns rows 128 wm .. +127 of the block and, of the 128-column group
-    // wn / 2, the columns 8 c + 4 (wn % 2) + j, j < 4: slots 16 (4 (wn % 2) + j) + c
+    // multiply role
     const int c = lane & 15, g = lane >> 4;
     const int wm = wave >> 2, wn = wave & 3;
-    const int a_off = (128 * wm + c) * WG_SLOT + 16 * g;                // + 16*i*WG_SLOT for tile i
-    const int b_off = (WG_TILE + 128 * (wn >> 1) + 64 * (wn & 1) + c) * WG_SLOT + 16 * g;
+    const int rd = (8 * g + (c >> 2)) * WT_PITCH + 8 * (c & 3);  // this lane's row and 8-byte piece within a tile
+    const int a_off = rd + 2 * (128 * wm);                       // + 32 * i for tile i
+    const int b_off = WT_PANEL + rd + 2 * (64 * wn);             // + 32 * j for tile j
 
     const int nslab = (r1 - r0 + WG_K - 1) / WG_K;
     v4u raw[4];
     auto fetch = [&](int s) {   // slab s (clamped) -> registers; rows past the end re-read a valid row
-        const int row = r0 + min(s, nslab - 1) * WG_K + 4 * sg;
+        const int row = r0 + min(s, nslab - 1) * WG_K + wave;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            raw[i] = *reinterpret_cast<const v4u *>(src + (int64_t)min(row + i, r1 - 1) * ld);
+            raw[i] = *reinterpret_cast<const v4u *>(src + (int64_t)min(row + 8 * i, r1 - 1) * ld);
     };
-    auto put = [&](int s, char *buf) {   // transpose the 4 x 8 block, zero the rows past the end
-        const int row = r0 + s * WG_K + 4 * sg;
-        v4u z[4];
+    auto put = [&](int s, char *buf) {   // rows past the end become zeros
+        const int row = r0 + s * WG_K + wave;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const bool in = row + i < r1;
-            z[i].x = in ? raw[i].x : 0u; z[i].y = in ? raw[i].y : 0u;
-            z[i].z = in ? raw[i].z : 0u; z[i].w = in ? raw[i].w : 0u;
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
-            const int w = j >> 1;
-            v2u o;
-            o.x = __builtin_amdgcn_perm(z[1][w], z[0][w], sel);
-            o.y = __builtin_amdgcn_perm(z[3][w], z[2][w], sel);
-            *reinterpret_cast<v2u *>(buf + st_off + 16 * j * WG_SLOT) = o;
+            const bool in = row + 8 * i < r1;
+            v4u z;
+            z.x = in ? raw[i].x : 0u; z.y = in ? raw[i].y : 0u;
+            z.z = in ? raw[i].z : 0u; z.w = in ? raw[i].w : 0u;
+            *reinterpret_cast<v4u *>(buf + st_off + (wave + 8 * i) * WT_PITCH) = z;
         }
     };
 
@@ -117,37 +123,33 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
         fetch(1);
         __syncthreads();
         for (int s = 0; s < nslab; ++s) {
-            const char *cur = stage_mem + (s & 1) * WG_STAGE;
+            const char *cur = stage_mem + (s & 1) * WT_STAGE;
             v8bf a[8], b[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                a[i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4u *>(cur + a_off + 16 * i * WG_SLOT));
+            for (int i = 0; i < 8; ++i) a[i] = read_tr_operand(cur + a_off + 32 * i);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                b[j] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4u *>(cur + b_off + 16 * j * WG_SLOT));
-            put(s + 1, stage_mem + ((s + 1) & 1) * WG_STAGE);     // past the last slab: zeros nobody reads
+            for (int j = 0; j < 4; ++j) b[j] = read_tr_operand(cur + b_off + 32 * j);
+            put(s + 1, stage_mem + ((s + 1) & 1) * WT_STAGE);     // past the last slab: zeros nobody reads
             fetch(s + 2);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
             __syncthreads();
         }
     }
 
     WG_STAMP(1);
     WG_STAMP(3);
-    // acc[i][j][q] = C[m0 + 128 wm + 8 (4g + q) + i][n0 + 128 (wn/2) + 8 c + 4 (wn%2) + j]
     float *Ce = p.C + (size_t)e * p.M * p.N;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 8; ++i) {
+        const int row = m0 + 128 * wm + 16 * i + c;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int row = m0 + 128 * wm + 8 * (4 * g + q) + i;
-            float *dst = Ce + (size_t)row * p.N + n0 + 128 * (wn >> 1) + 8 * c + 4 * (wn & 1);
-            *reinterpret_cast<v4f *>(dst) = v4f{acc[i][0][q], acc[i][1][q], acc[i][2][q], acc[i][3][q]};
-        }
+        for (int j = 0; j < 4; ++j)
+            *reinterpret_cast<v4f *>(Ce + (size_t)row * p.N + n0 + 64 * wn + 16 * j + 4 * g) = acc[i][j];
+    }
     // Optional: this block's share of the row and column sums of squares of the gradient, which
     // the factored second-moment estimator of the optimiser needs (Appendix D) -- taken here, where
     // the gradient is in registers, instead of re-reading it from memory.
@@ -159,27 +161,27 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
         float *rcol = red + 4 * WG_TILE;                          // [2 wm][256 cols]
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < 8; ++i) {
+            float rs = 0.f;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float rs = 0.f;
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) rs = fmaf(acc[i][j][q], acc[i][j][q], rs);
-#pragma unroll
-                for (int off = 1; off < 16; off <<= 1) rs += __shfl_xor(rs, off);    // over c
-                if (c == 0) rrow[wn * WG_TILE + 128 * wm + 8 * (4 * g + q) + i] = rs;
-            }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float cs = 0.f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) cs = fmaf(acc[i][j][q], acc[i][j][q], cs);
-            cs += __shfl_xor(cs, 16);                                                  // over g
-            cs += __shfl_xor(cs, 32);
-            if (g == 0) rcol[wm * WG_TILE + 128 * (wn >> 1) + 8 * c + 4 * (wn & 1) + j] = cs;
+                for (int r = 0; r < 4; ++r) rs = fmaf(acc[i][j][r], acc[i][j][r], rs);
+            rs += __shfl_xor(rs, 16);                                                  // over g
+            rs += __shfl_xor(rs, 32);
+            if (g == 0) rrow[wn * WG_TILE + 128 * wm + 16 * i + c] = rs;
         }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float cs = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) cs = fmaf(acc[i][j][r], acc[i][j][r], cs);
+#pragma unroll
+                for (int off = 1; off < 16; off <<= 1) cs += __shfl_xor(cs, off);    // over c
+                if (c == 0) rcol[wm * WG_TILE + 64 * wn + 16 * j + 4 * g + r] = cs;
+            }
         __syncthreads();
         const int tn = n0 / WG_TILE, tm = m0 / WG_TILE;
         if (tid < WG_TILE) {
@@ -234,7 +236,7 @@ int launch_gg_wgrad(const GGWgrad &p, int n, hipStream_t st) {
     if (p.M % WG_TILE || p.N % WG_TILE) return MOE_EUNSUPPORTED;
     if (n <= 0) return MOE_OK;
     const unsigned grid = (unsigned)((p.M / WG_TILE) * (p.N / WG_TILE) * n);
-    constexpr int lds = 2 * WG_STAGE;
+    constexpr int lds = 2 * WT_STAGE;
     static bool attr_set = false;
     if (!attr_set) {
         MOE_HIP_TRY(hipFuncSetAttribute((const void *)gg_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
