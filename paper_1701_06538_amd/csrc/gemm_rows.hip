@@ -152,58 +152,64 @@ __global__ __launch_bounds__(64 * NW, 1) void gg_rows256_kernel(GGRows p, int co
         }
     }
 
-    // Epilogue straight from the accumulators.  The matrix instructions computed the transposed
-    // product (weights as the first operand), so a lane holds, for ONE row of C, groups of four
-    // adjacent columns: 16-byte fp32 stores or 8-byte bf16 stores (and 8-byte mask loads), no LDS
-    // round trip and no barrier.
+    // Epilogue through LDS, half a tile (128 rows) at a time: the waves that own the half write
+    // their accumulators into a [128][256] fp32 image (the operand slabs are dead), then every wave
+    // stores whole rows -- 1 KB (fp32) or 512 B (bf16) contiguous per row instead of the 32-byte
+    // pieces a lane's own columns would make; the relu mask is read the same way.
     GG_STAMP(2);
+    constexpr int CS = RT + 4;                       // fp32 words per staged row (rows stay 16-byte aligned)
+    static_assert(128 * CS * 4 <= 4 * SLAB, "the staged half tile fits the operand buffers");
+    float *Ct = reinterpret_cast<float *>(smem);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = 128 * wm + 32 * i + l32;
-        const bool live = row < rows;
-        const size_t at0 = (size_t)(row0 + min(row, rows - 1)) * N + col0 + WCOLS * wn + 4 * kg;
-        if (EPI == EPI_F32) {
-            float *dst = reinterpret_cast<float *>(p.C) + at0;
+    for (int hf = 0; hf < 2; ++hf) {
+        __syncthreads();   // the operand buffers (hf = 0) / the first half's image (hf = 1) are no longer read
+        if (wm == hf) {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (live)
-                        *reinterpret_cast<v4f *>(dst + 32 * j + 8 * q) =
-                            v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        } else {
-            uint16_t *dst = reinterpret_cast<uint16_t *>(p.C) + at0;
-            uint2 m[NJ][4];
-            if (EPI == EPI_MASK_BF16) {   // all loads of the strip in flight together
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
-                        m[j][q] = *reinterpret_cast<const uint2 *>(p.mask + at0 + 32 * j + 8 * q);
+                        *reinterpret_cast<v4f *>(&Ct[(32 * i + l32) * CS + WCOLS * wn + 32 * j + 8 * q + 4 * kg]) =
+                            v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        }
+        __syncthreads();
+        if (EPI == EPI_F32) {
+            float *C = reinterpret_cast<float *>(p.C);
+            for (int r = wave; r < 128; r += NW) {          // a wavefront per row: 64 lanes x 16 bytes
+                const int row = 128 * hf + r;
+                if (row < rows)
+                    *reinterpret_cast<v4f *>(C + (size_t)(row0 + row) * N + col0 + 4 * lane) =
+                        *reinterpret_cast<const v4f *>(&Ct[r * CS + 4 * lane]);
             }
+        } else {
+            uint16_t *C = reinterpret_cast<uint16_t *>(p.C);
+            const int c8 = 8 * (lane & 31);
+            for (int r = 2 * wave + (lane >> 5); r < 128; r += 2 * NW) {   // half a wavefront per row: 32 lanes x 8 columns
+                const int row = 128 * hf + r;
+                if (row >= rows) continue;
+                const size_t at = (size_t)(row0 + row) * N + col0 + c8;
+                const v4f lo = *reinterpret_cast<const v4f *>(&Ct[r * CS + c8]);
+                const v4f hi = *reinterpret_cast<const v4f *>(&Ct[r * CS + c8 + 4]);
+                float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                if (EPI == EPI_MASK_BF16) {
+                    // relu'(z) with relu'(0) = 0: the stored hidden value is positive iff z > 0
+                    const v4u m = *reinterpret_cast<const v4u *>(p.mask + at);
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                    if (EPI == EPI_MASK_BF16) {
-                        // relu'(z) with relu'(0) = 0: the stored hidden value is positive iff z > 0
-                        const uint32_t mw[2] = {m[j][q].x, m[j][q].y};
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            const uint32_t hbits = (mw[t >> 1] >> (16 * (t & 1))) & 0xffffu;
-                            const bool on = (hbits & 0x7fffu) != 0 && (hbits & 0x8000u) == 0;
-                            v[t] = on ? v[t] : 0.f;
-                        }
-                    } else {
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) v[t] = fmaxf(v[t], 0.f);
+                    for (int t = 0; t < 8; ++t) {
+                        const uint32_t hbits = (m[t >> 1] >> (16 * (t & 1))) & 0xffffu;
+                        const bool on = (hbits & 0x7fffu) != 0 && (hbits & 0x8000u) == 0;
+                        v[t] = on ? v[t] : 0.f;
                     }
-                    uint2 o;
-                    o.x = bf16_rne_bits(v[0]) | (bf16_rne_bits(v[1]) << 16);
-                    o.y = bf16_rne_bits(v[2]) | (bf16_rne_bits(v[3]) << 16);
-                    if (live) *reinterpret_cast<uint2 *>(dst + 32 * j + 8 * q) = o;
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) v[t] = fmaxf(v[t], 0.f);
                 }
+                v4u o;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) o[t] = bf16_rne_bits(v[2 * t]) | (bf16_rne_bits(v[2 * t + 1]) << 16);
+                *reinterpret_cast<v4u *>(C + at) = o;
+            }
         }
     }
     GG_STAMP(3);
