@@ -165,13 +165,15 @@ __global__ __launch_bounds__(64 * NW, 1) void gg_rows256_kernel(GGRows p, int co
         __syncthreads();   // the operand buffers (hf = 0) / the first half's image (hf = 1) are no longer read
         if (wm == hf) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i) {
+                if (128 * hf + 32 * i >= rows) continue;   // a short tile: nothing of this strip is stored
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         *reinterpret_cast<v4f *>(&Ct[(32 * i + l32) * CS + WCOLS * wn + 32 * j + 8 * q + 4 * kg]) =
                             v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+            }
         }
         __syncthreads();
         if (EPI == EPI_F32) {

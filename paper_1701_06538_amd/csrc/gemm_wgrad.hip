@@ -44,6 +44,8 @@ constexpr int WG_K = 32;        // contracted rows per slab
 constexpr int WT_PITCH = 2 * WG_TILE + 32;            // bytes per slab row of one panel: 136 words = 8 mod 64 banks
 constexpr int WT_PANEL = WG_K * WT_PITCH;
 constexpr int WT_STAGE = 2 * WT_PANEL;
+constexpr int WT_CS = WG_TILE + 4;                    // fp32 words per row of the epilogue's image of half a block
+constexpr int WT_LDS = 2 * WT_STAGE > 128 * WT_CS * 4 ? 2 * WT_STAGE : 128 * WT_CS * 4;
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef short v8s __attribute__((ext_vector_type(8)));
@@ -142,13 +144,25 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
 
     WG_STAMP(1);
     WG_STAMP(3);
+    // The block leaves through LDS, 128 rows at a time (the operand stages are dead): the four
+    // wavefronts that own the half write their accumulators into a [128][256] image, then every
+    // wavefront stores whole 1 KB rows instead of the 64-byte pieces its own lanes would make.
     float *Ce = p.C + (size_t)e * p.M * p.N;
+    float *Ct = reinterpret_cast<float *>(stage_mem);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int row = m0 + 128 * wm + 16 * i + c;
+    for (int hf = 0; hf < 2; ++hf) {
+        __syncthreads();
+        if (wm == hf) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            *reinterpret_cast<v4f *>(Ce + (size_t)row * p.N + n0 + 64 * wn + 16 * j + 4 * g) = acc[i][j];
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<v4f *>(&Ct[(16 * i + c) * WT_CS + 64 * wn + 16 * j + 4 * g]) = acc[i][j];
+        }
+        __syncthreads();
+        for (int r = wave; r < 128; r += 8)
+            *reinterpret_cast<v4f *>(Ce + (size_t)(m0 + 128 * hf + r) * p.N + n0 + 4 * lane) =
+                *reinterpret_cast<const v4f *>(&Ct[r * WT_CS + 4 * lane]);
     }
     // Optional: this block's share of the row and column sums of squares of the gradient, which
     // the factored second-moment estimator of the optimiser needs (Appendix D) -- taken here, where
@@ -236,7 +250,7 @@ int launch_gg_wgrad(const GGWgrad &p, int n, hipStream_t st) {
     if (p.M % WG_TILE || p.N % WG_TILE) return MOE_EUNSUPPORTED;
     if (n <= 0) return MOE_OK;
     const unsigned grid = (unsigned)((p.M / WG_TILE) * (p.N / WG_TILE) * n);
-    constexpr int lds = 2 * WT_STAGE;
+    constexpr int lds = WT_LDS;
     static bool attr_set = false;
     if (!attr_set) {
         MOE_HIP_TRY(hipFuncSetAttribute((const void *)gg_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
