@@ -255,6 +255,10 @@ struct GateBwdArgs {
     int groups;
 };
 
+// NG > 0: n <= 256 * NG (n is a multiple of 4): a lane owns NG groups of four adjacent experts
+// (16-byte loads and stores) and keeps their terms of the first pass in registers for the second;
+// NG = 0: any n, one expert per lane and step, the terms recomputed.
+template <int NG>
 __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
     const int lane = threadIdx.x & 63;
     const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -298,16 +302,82 @@ __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
         thr_in = e_row ? __fmaf_rn(e_row[j_in], s_row[j_in], c_row[j_in]) : c_row[j_in];
         thr_out = e_row ? __fmaf_rn(e_row[j_out], s_row[j_out], c_row[j_out]) : c_row[j_out];
     }
-    // first pass: sums of c = gL * phi(u) / sp over the kept and the other experts
-    float S_in = 0.f, S_out = 0.f;
+    auto kept_dh = [&](int i, float &dh) {   // is expert i one of the kept, and its softmax term
+        bool kept = false;
+        dh = 0.f;
+#pragma unroll
+        for (int s = 0; s < kMaxK; ++s)
+            if (ki[s] == i) {
+                kept = true;
+                dh = dH[s];
+            }
+        return kept;
+    };
+    // c = gL * phi(u) / sp, u = (clean - threshold) / sp: the Load term of expert i (Eq.(9))
+    auto load_term = [&](bool kept, float clean, float sp, float gl, float &u) {
+        u = (clean - (kept ? thr_in : thr_out)) / sp;
+        return gl * 0.3989422804014327f * expf(-0.5f * u * u) / sp;
+    };
+    float S_in = 0.f, S_out = 0.f;   // sums of c over the kept and over the other experts
+    if (NG > 0) {
+        float4 cv[NG > 0 ? NG : 1], uv[NG > 0 ? NG : 1], sv[NG > 0 ? NG : 1];
+#pragma unroll
+        for (int q = 0; q < NG; ++q) {
+            const int i0 = 4 * lane + 256 * q;
+            cv[q] = uv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            sv[q] = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (i0 >= n) continue;
+            sv[q] = *reinterpret_cast<const float4 *>(s_row + i0);
+            if (!with_load) continue;
+            const float4 c4 = *reinterpret_cast<const float4 *>(c_row + i0);
+            const float4 g4 = *reinterpret_cast<const float4 *>(gL_row + i0);
+            const float cl[4] = {c4.x, c4.y, c4.z, c4.w}, gl[4] = {g4.x, g4.y, g4.z, g4.w};
+            const float sp[4] = {sv[q].x, sv[q].y, sv[q].z, sv[q].w};
+            float c[4], u[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float dh;
+                const bool kept = kept_dh(i0 + e, dh);
+                c[e] = load_term(kept, cl[e], sp[e], gl[e], u[e]);
+                if (kept) S_in += c[e];
+                else S_out += c[e];
+            }
+            cv[q] = make_float4(c[0], c[1], c[2], c[3]);
+            uv[q] = make_float4(u[0], u[1], u[2], u[3]);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            S_in += __shfl_xor(S_in, off);
+            S_out += __shfl_xor(S_out, off);
+        }
+#pragma unroll
+        for (int q = 0; q < NG; ++q) {
+            const int i0 = 4 * lane + 256 * q;
+            if (i0 >= n) continue;
+            const float4 e4 = e_row ? *reinterpret_cast<const float4 *>(e_row + i0) : make_float4(0.f, 0.f, 0.f, 0.f);
+            const float ev[4] = {e4.x, e4.y, e4.z, e4.w};
+            const float c[4] = {cv[q].x, cv[q].y, cv[q].z, cv[q].w}, u[4] = {uv[q].x, uv[q].y, uv[q].z, uv[q].w};
+            const float sp[4] = {sv[q].x, sv[q].y, sv[q].z, sv[q].w};
+            float dc[4], dr[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float dh;
+                kept_dh(i0 + e, dh);
+                if (with_load && i0 + e == j_in) dh -= S_in;     // the threshold of the kept experts
+                if (with_load && i0 + e == j_out) dh -= S_out;   // the threshold of all the others
+                dc[e] = c[e] + dh;
+                dr[e] = fmaf(dh, ev[e], -c[e] * u[e]) * (1.0f - expf(-sp[e]));   // softplus' = 1 - exp(-sp)
+            }
+            *reinterpret_cast<float4 *>(p.dclean + t * n + i0) = make_float4(dc[0], dc[1], dc[2], dc[3]);
+            *reinterpret_cast<float4 *>(p.draw + t * n + i0) = make_float4(dr[0], dr[1], dr[2], dr[3]);
+        }
+        return;
+    }
     if (with_load) {
         for (int i = lane; i < n; i += 64) {
-            bool kept = false;
-#pragma unroll
-            for (int s = 0; s < kMaxK; ++s) kept |= (ki[s] == i);
-            const float sp = s_row[i];
-            const float u = (c_row[i] - (kept ? thr_in : thr_out)) / sp;
-            const float c = gL_row[i] * 0.3989422804014327f * expf(-0.5f * u * u) / sp;
+            float dh, u;
+            const bool kept = kept_dh(i, dh);
+            const float c = load_term(kept, c_row[i], s_row[i], gL_row[i], u);
             if (kept) S_in += c;
             else S_out += c;
         }
@@ -317,29 +387,34 @@ __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
             S_out += __shfl_xor(S_out, off);
         }
     }
-    // second pass: dclean, draw
     for (int i = lane; i < n; i += 64) {
-        bool kept = false;
-        float dh = 0.f;
-#pragma unroll
-        for (int s = 0; s < kMaxK; ++s)
-            if (ki[s] == i) {
-                kept = true;
-                dh = dH[s];
-            }
+        float dh;
+        const bool kept = kept_dh(i, dh);
         const float sp = s_row[i];
         float c = 0.f, u = 0.f;
         if (with_load) {
-            u = (c_row[i] - (kept ? thr_in : thr_out)) / sp;
-            c = gL_row[i] * 0.3989422804014327f * expf(-0.5f * u * u) / sp;
-            if (i == j_in) dh -= S_in;     // the threshold of the kept experts
-            if (i == j_out) dh -= S_out;   // the threshold of all the others
+            c = load_term(kept, c_row[i], sp, gL_row[i], u);
+            if (i == j_in) dh -= S_in;
+            if (i == j_out) dh -= S_out;
         }
         const float ev = e_row ? e_row[i] : 0.f;
-        const float dsp = fmaf(dh, ev, -c * u);
         p.dclean[t * n + i] = c + dh;
-        p.draw[t * n + i] = dsp * (1.0f - expf(-sp));   // softplus' = sigmoid(raw) = 1 - exp(-sp)
+        p.draw[t * n + i] = fmaf(dh, ev, -c * u) * (1.0f - expf(-sp));
     }
+}
+
+static int launch_gate_bwd_rows(const GateBwdArgs &a, int64_t rows, hipStream_t s) {
+    if (rows <= 0) return MOE_OK;
+    const dim3 grid((unsigned)ceil_div(rows, 4));
+#define MOE_GBR(NG) hipLaunchKernelGGL(gate_bwd_rows_kernel<NG>, grid, dim3(256), 0, s, a)
+    if (a.n % 4 != 0 || a.n > 2048) MOE_GBR(0);
+    else if (a.n <= 256) MOE_GBR(1);
+    else if (a.n <= 512) MOE_GBR(2);
+    else if (a.n <= 1024) MOE_GBR(4);
+    else MOE_GBR(8);
+#undef MOE_GBR
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -895,8 +970,7 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
                        cfg->w_load, gI, gL);
     MOE_LAUNCH_CHECK();
     GateBwdArgs gb{cleanb, sp, eps, topk_idx, topk_gate, dgate, next_idx, gI, gL, dclean, draw, T, n, k};
-    hipLaunchKernelGGL(gate_bwd_rows_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s, gb);
-    MOE_LAUNCH_CHECK();
+    if ((st = launch_gate_bwd_rows(gb, T, s)) != MOE_OK) return st;
 
     // dW_g = x^T dclean, dW_noise = x^T draw: split over tokens, then a fixed-order sum
     SGArgs wa{};
@@ -1223,8 +1297,7 @@ extern "C" int moe_layer_backward_hier(const moe_config *cfg, const float *x, co
     float *dclean_p = (float *)(ws + L.dclean_p), *draw_p = (float *)(ws + L.draw_p);
     GateBwdArgs gp{(const float *)(fw + F.p_cleanb), (const float *)(fw + F.p_sp), eps_p, p_idx, p_gate, dGp,
                    (const int32_t *)(fw + F.p_next_idx), nullptr, dLoad_p, dclean_p, draw_p, T, a, k_p};
-    hipLaunchKernelGGL(gate_bwd_rows_kernel, dim3((unsigned)ceil_div(T, 4)), dim3(256), 0, s, gp);
-    MOE_LAUNCH_CHECK();
+    if ((st = launch_gate_bwd_rows(gp, T, s)) != MOE_OK) return st;
     float *wpart = (float *)(ws + L.wpart);
     SGArgs wa{};
     wa.A[0] = x; wa.B[0] = dclean_p; wa.B[1] = draw_p; wa.C = wpart;
@@ -1253,8 +1326,7 @@ extern "C" int moe_layer_backward_hier(const moe_config *cfg, const float *x, co
     GateBwdArgs gs{(const float *)(fw + F.cleanb), (const float *)(fw + F.sp), eps_s, s_idx, s_gate, dGs,
                    (const int32_t *)(fw + F.next_idx), nullptr, dLoad_s, dclean_s, draw_s, Ap, b, k_s,
                    p_perm, p_offsets, a};
-    hipLaunchKernelGGL(gate_bwd_rows_kernel, dim3((unsigned)ceil_div(Ap, 4)), dim3(256), 0, s, gs);
-    MOE_LAUNCH_CHECK();
+    if ((st = launch_gate_bwd_rows(gs, Ap, s)) != MOE_OK) return st;
     float *xg = (float *)(ws + L.xg), *dxg = (float *)(ws + L.dxg);
     hipLaunchKernelGGL(gather_rows_f32_kernel, dim3((unsigned)ceil_div(Ap, 4)), dim3(256), 0, s, (const float4 *)x,
                        p_perm, k_p, Ap, d / 4, (float4 *)xg);
