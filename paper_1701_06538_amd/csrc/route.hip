@@ -55,18 +55,25 @@ __global__ __launch_bounds__(256) void route_colscan_kernel(RouteArgs p) {
     const int per = (p.num_chunks + 7) / 8;
     const int c0 = cg * per, c1 = min(p.num_chunks, c0 + per);
     int sum = 0;
-    if (e < p.n)
-        for (int c = c0; c < c1; ++c) sum += p.hist[(size_t)c * p.n + e];
+    if (e < p.n) {
+#pragma unroll 8
+        for (int c = c0; c < c1; ++c) sum += p.hist[(size_t)c * p.n + e];   // independent loads, eight in flight
+    }
     grp[cg][ex] = sum;
     __syncthreads();
     int run = 0;
     for (int q = 0; q < cg; ++q) run += grp[q][ex];
     if (e < p.n) {
-        for (int c = c0; c < c1; ++c) {
-            int32_t *cell = p.hist + (size_t)c * p.n + e;
-            const int v = *cell;
-            *cell = run;
-            run += v;
+        for (int cb = c0; cb < c1; cb += 8) {   // eight cells at a time: the loads first, then the running prefix
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = cb + u < c1 ? p.hist[(size_t)(cb + u) * p.n + e] : 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (cb + u < c1) {
+                    p.hist[(size_t)(cb + u) * p.n + e] = run;
+                    run += v[u];
+                }
         }
         if (cg == 7) {
             int total = 0;
