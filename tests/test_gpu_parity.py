@@ -113,6 +113,37 @@ def test_gate_route_losses_parity(api, name, base, ov, with_bias, noise):
     check_losses(run, fw)
 
 
+def test_gate_route_losses_random_shapes(api):
+    """A seeded sweep of odd shapes (T, n, k, d drawn at random, some with a bias, some noise-free,
+    some with duplicated token rows so that whole rows of logits tie): logits, top-k indices, the
+    next-best expert, counts, offsets, permutation and tile table bit for bit, gate values and
+    losses within the fp32 tolerance."""
+    rng = np.random.default_rng(20240607)
+    for case in range(16):
+        n = int(rng.choice([4, 6, 12, 20, 33, 64, 100, 128, 257, 300, 512, 640]))
+        k = int(rng.integers(1, min(n, 8) + 1))
+        T = int(rng.integers(1, 1500))
+        d = int(rng.choice([32, 64, 96, 256, 512]))
+        with_bias, noise = bool(rng.integers(2)), bool(rng.integers(4))
+        shape = _shape(1, T=T, n=n, k=k, d=d, h=64)
+        if with_bias:
+            shape = W.scaled_config(shape, zipf_beta=0.5)
+        say("random case", case, dict(T=T, n=n, k=k, d=d, bias=with_bias, noise=noise))
+        x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias)
+        if T > 8 and case % 3 == 0:       # tokens with identical rows (and identical noise): identical decisions
+            x[T // 2:T // 2 + 4] = x[0]
+            eps[T // 2:T // 2 + 4] = eps[0]
+        if not noise:
+            eps = None
+        fw = G.oracle_flat(shape, x, W_g, W_noise, eps, bias)
+        run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, None, None)
+        run.gate(); run.route(); run.losses_()
+        torch.cuda.synchronize()
+        check_gate(run, fw, shape)
+        check_route(run, fw.idx, shape.n)
+        check_losses(run, fw)
+
+
 def test_gate_zero_initialised_matrices(api):
     """W_g = W_noise = 0 (the paper's initialisation): selection = top-k of the noise."""
     shape = _shape(1, T=512, n=256)
