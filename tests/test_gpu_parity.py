@@ -214,6 +214,14 @@ def test_layer_fp32_ragged_small_dims(api):
     _ffn_case(api, _shape(0, T=150, d=64, h=96, n=5, k=2), TOL_F32, "fp32 ragged small")
 
 
+def test_layer_fp32_expert_shapes_off_the_tiles(api):
+    """fp32 experts whose sizes do not divide the matrix-core kernel's 64 x 64 tile or its 32-deep
+    slab: hidden sizes 20, 36 and 100 (tail columns, tail of k in the second product), d = 32, 96, 160."""
+    _ffn_case(api, _shape(0, T=90, d=32, h=36, n=6, k=2), TOL_F32, "fp32 d=32 h=36")
+    _ffn_case(api, _shape(0, T=201, d=96, h=100, n=9, k=3), TOL_F32, "fp32 d=96 h=100")
+    _ffn_case(api, _shape(0, T=70, d=160, h=20, n=4, k=1), TOL_F32, "fp32 h=20")
+
+
 def test_layer_bf16_small(api):
     _ffn_case(api, _shape(1, T=300, n=8, k=2), TOL_BF16, "bf16 T=300 n=8")
 
