@@ -89,6 +89,7 @@ CASES = [
     ("cfg2_shape", dict(T=800, n=2048), False, 1),          # (few rows per expert, many empty experts)
     ("d256_h512", dict(T=600, n=32, d=256, h=512), False, 0),  # experts off the fused kernel's shape
     ("n20_bf16", dict(T=400, n=20, k=3), False, 0),            # expert count off the tile sizes
+    ("n640_small_experts", dict(T=900, n=640, k=2, d=256, h=256), True, 0),   # 512 < n <= 1024: four column groups per lane in the gate kernel
     # fp32 experts: every GEMM on the fp32 matrix cores
     ("cfg0_f32", dict(T=256, n=16, k=4, expert_dtype="f32"), False, 0),
     ("f32_ragged", dict(T=150, d=64, h=96, n=8, k=2, expert_dtype="f32"), True, 0),
