@@ -152,7 +152,7 @@ def main():
                          "matrices (outside the timed region; reported under \"optimizer\")")
     ap.add_argument("--cpu-sample", type=int, default=None,
                     help="tokens of the workload the oracle is timed on (default: all 8192 of the metric's "
-                         "workload, about 20 s of host time; 2048 for the other configs)")
+                         "workload, a few seconds of host time; 2048 for the other configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel, so that rocprofv3 --pmc "
