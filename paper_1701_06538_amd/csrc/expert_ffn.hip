@@ -499,34 +499,40 @@ __global__ __launch_bounds__(256) void ffn_f32_mfma_kernel(FfnArgs p, const floa
         a_src[i] = A + src_row * K;
     }
     const bool b_in = col0 + bc < N;
-    float4 areg[2], breg[2];
-    auto load_slab = [&](int k0) {
+    // Two register sets: the slab stored to LDS in step s was requested two steps earlier, so a
+    // global round trip has two slabs of matrix work to hide behind (these launches are small and
+    // latency-sized: with one set the loop ran at the memory latency per slab).
+    float4 areg[2][2], breg[2][2];
+    auto load_slab = [&](int s, float4 (&ar_)[2], float4 (&br_)[2]) {
+        const int k0 = s * TK;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int ka = k0 + akq, kb = k0 + bk + 16 * i;
             const float4 av = *reinterpret_cast<const float4 *>(a_src[i] + min(ka, K - 4));
-            areg[i] = ka < K ? av : make_float4(0.f, 0.f, 0.f, 0.f);
+            ar_[i] = ka < K ? av : make_float4(0.f, 0.f, 0.f, 0.f);
             const float4 bv = *reinterpret_cast<const float4 *>(W + (size_t)min(kb, K - 1) * N + (b_in ? col0 + bc : 0));
-            breg[i] = (kb < K && b_in) ? bv : make_float4(0.f, 0.f, 0.f, 0.f);
+            br_[i] = (kb < K && b_in) ? bv : make_float4(0.f, 0.f, 0.f, 0.f);
         }
     };
-    auto store_slab = [&](int buf) {
+    auto store_slab = [&](int buf, const float4 (&ar_)[2], const float4 (&br_)[2]) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<float4 *>(&As[buf][ar + 32 * i][akq]) = areg[i];
-            *reinterpret_cast<float4 *>(&Bs[buf][bk + 16 * i][bc]) = breg[i];
+            *reinterpret_cast<float4 *>(&As[buf][ar + 32 * i][akq]) = ar_[i];
+            *reinterpret_cast<float4 *>(&Bs[buf][bk + 16 * i][bc]) = br_[i];
         }
     };
     v16f32 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const int nslab = (K + TK - 1) / TK;
-    load_slab(0);
-    store_slab(0);
+    load_slab(0, areg[0], breg[0]);
+    store_slab(0, areg[0], breg[0]);
+    load_slab(min(1, nslab - 1), areg[0], breg[0]);      // clamped: a short K re-reads a valid slab nobody uses
+    load_slab(min(2, nslab - 1), areg[1], breg[1]);
     __syncthreads();
-    for (int s = 0; s < nslab; ++s) {
+    // step s: multiply slab s from LDS, store slab s+1 (held in `ra`, `rb`), request slab s+3 into them
+    auto step = [&](int s, float4 (&ra)[2], float4 (&rb)[2]) {
         const int buf = s & 1;
-        if (s + 1 < nslab) load_slab((s + 1) * TK);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float4 a4 = *reinterpret_cast<const float4 *>(&As[buf][32 * wm + l32][8 * j + 4 * half]);
@@ -535,8 +541,13 @@ __global__ __launch_bounds__(256) void ffn_f32_mfma_kernel(FfnArgs p, const floa
             for (int u = 0; u < 4; ++u)
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u], Bs[buf][8 * j + 4 * half + u][32 * wn + l32], acc, 0, 0, 0);
         }
-        if (s + 1 < nslab) store_slab(buf ^ 1);
+        if (s + 1 < nslab) store_slab(buf ^ 1, ra, rb);
+        if (s + 3 < nslab) load_slab(s + 3, ra, rb);
         __syncthreads();
+    };
+    for (int s = 0; s < nslab; s += 2) {
+        step(s, areg[0], breg[0]);
+        if (s + 1 < nslab) step(s + 1, areg[1], breg[1]);
     }
     const int c = col0 + 32 * wn + l32;
     if (c < N) {
