@@ -66,7 +66,9 @@ typedef struct moe_config {
 
 /* With MOE_FLAG_SAVE_HIDDEN moe_layer_forward, moe_layer_forward_hier and moe_layer_forward_balanced
  * also keep the experts' hidden activations (bf16 [T*k, h], routed-row order) in the workspace, and
- * moe_layer_backward / _hier / _balanced read them instead of recomputing them.  The paper
+ * moe_layer_backward / _hier / _balanced read them instead of recomputing them (the flat layer also
+ * keeps the routed input rows as the experts saw them, bf16 [T*k, d], which its backward pass would
+ * otherwise gather and round again).  The paper
  * recomputes (Appendix D) to fit 12 GB devices; with 288 GB of HBM the 2*h bytes per routed row
  * are the cheaper side of the trade.  Without the flag the backward pass recomputes. */
 /* With MOE_FLAG_ADAM_MOMENTS moe_layer_backward and moe_layer_backward_balanced (bf16 experts) also
@@ -109,6 +111,9 @@ typedef struct moe_workspace_layout {
     size_t p_cleanb, p_sp, p_next_idx, p_partials, p_idx, p_gate, p_counts, p_offsets, p_perm,
         p_inv_perm, p_tile_group, p_tile_row0, p_num_tiles, p_tile_offsets, p_route_ws, p_aux_ws,
         s_idx, s_gate;
+    /* flat layer with MOE_FLAG_SAVE_HIDDEN and bf16 experts: the routed input rows rounded to bf16
+     * [T*k, d], kept for moe_layer_backward; (size_t)-1 if absent */
+    size_t xs;
 } moe_workspace_layout;
 int moe_get_workspace_layout(const moe_config *cfg, moe_workspace_layout *out);
 

@@ -33,7 +33,7 @@ _LAYOUT_FIELDS = ["cleanb", "sp", "next_idx", "partials", "counts", "offsets", "
                   "aux_ws", "hidden", "total", "p_cleanb", "p_sp", "p_next_idx", "p_partials", "p_idx",
                   "p_gate", "p_counts", "p_offsets", "p_perm", "p_inv_perm", "p_tile_group",
                   "p_tile_row0", "p_num_tiles", "p_tile_offsets", "p_route_ws", "p_aux_ws",
-                  "s_idx", "s_gate"]
+                  "s_idx", "s_gate", "xs"]
 
 
 class MoeWorkspaceLayout(ctypes.Structure):

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const float *__restric
                                                           const float *__restrict__ gate,
                                                           const int32_t *__restrict__ perm, int64_t A,
                                                           int d, int k, int by_row,
-                                                          uint16_t *__restrict__ xs,
+                                                          uint16_t *__restrict__ xs,   // null: the forward pass kept these rows
                                                           uint16_t *__restrict__ dout,
                                                           float *__restrict__ dgate) {
     const int lane = threadIdx.x & 63;
@@ -53,11 +53,13 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const float *__restric
     for (int c = lane * 4; c < d; c += 256) {
         const float4 vy = *reinterpret_cast<const float4 *>(dy + t * d + c);
         const float4 vo = *reinterpret_cast<const float4 *>(out_sorted + r * d + c);
-        const float4 vx = *reinterpret_cast<const float4 *>(x + t * d + c);
         dot = fmaf(vy.x, vo.x, dot); dot = fmaf(vy.y, vo.y, dot);
         dot = fmaf(vy.z, vo.z, dot); dot = fmaf(vy.w, vo.w, dot);
         *reinterpret_cast<uint2 *>(dout + r * d + c) = make_uint2(pack2(g * vy.x, g * vy.y), pack2(g * vy.z, g * vy.w));
-        *reinterpret_cast<uint2 *>(xs + r * d + c) = make_uint2(pack2(vx.x, vx.y), pack2(vx.z, vx.w));
+        if (xs) {
+            const float4 vx = *reinterpret_cast<const float4 *>(x + t * d + c);
+            *reinterpret_cast<uint2 *>(xs + r * d + c) = make_uint2(pack2(vx.x, vx.y), pack2(vx.z, vx.w));
+        }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
@@ -851,20 +853,23 @@ struct ExpertBwd {
     float *dW1, *dW2;
     float *mom[4];                             // optional sums of squares for the optimiser, or nulls
     bool by_row;                               // perm lists tokens; gate and dgate are per routed row
+    const uint16_t *saved_xs;                  // routed input rows (bf16) kept by the forward pass, or null
 };
 
 static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStream_t s) {
     const int64_t A = (int64_t)cfg->T * cfg->k;
     const int d = cfg->d, h = cfg->h, n = cfg->n, k = cfg->k;
     int st;
+    const uint16_t *xs = b.saved_xs ? b.saved_xs : b.xs;
     hipLaunchKernelGGL(bwd_prepare_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, s, b.x, b.dy,
-                       b.out_sorted, b.gate, b.perm, A, d, k, b.by_row ? 1 : 0, b.xs, b.dout, b.dgate);
+                       b.out_sorted, b.gate, b.perm, A, d, k, b.by_row ? 1 : 0, b.saved_xs ? nullptr : b.xs,
+                       b.dout, b.dgate);
     MOE_LAUNCH_CHECK();
     const uint16_t *hid = b.saved_hid;
     if (!hid) {   // Appendix D: recompute the hidden activations
         if ((st = launch_build_tiles(b.offsets, n, GBM, b.tile_expert, b.tile_row0, b.num_tiles, s)) != MOE_OK) return st;
         const unsigned max_tiles = (unsigned)(ceil_div(A, GBM) + n);
-        GGRows g1{b.xs, (const uint16_t *)b.W1, b.hid, nullptr, d, h, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
+        GGRows g1{xs, (const uint16_t *)b.W1, b.hid, nullptr, d, h, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
         if ((st = launch_gg_rows128(g1, true, EPI_RELU_BF16, max_tiles, s)) != MOE_OK) return st;
         hid = b.hid;
     }
@@ -876,7 +881,7 @@ static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStr
     if ((st = launch_expert_order(b.offsets, n, b.order, s)) != MOE_OK) return st;
     GGWgrad w2{hid, b.dout, b.dW2, h, d, b.offsets, b.order, b.mom[2], b.mom[3]};
     if ((st = launch_gg_wgrad(w2, n, s)) != MOE_OK) return st;
-    GGWgrad w1{b.xs, b.dz, b.dW1, d, h, b.offsets, b.order, b.mom[0], b.mom[1]};
+    GGWgrad w1{xs, b.dz, b.dW1, d, h, b.offsets, b.order, b.mom[0], b.mom[1]};
     if ((st = launch_gg_wgrad(w1, n, s)) != MOE_OK) return st;
     GGRows g5{b.dz, (const uint16_t *)b.W1, b.dxs, nullptr, h, d, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
     return launch_gg_rows256(g5, EPI_F32, max_tiles256, s);
@@ -962,6 +967,7 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
                      (int32_t *)(ws + L.order), dW1, dW2, {nullptr, nullptr, nullptr, nullptr}};
         for (int q = 0; q < 4; ++q)
             if (L.mom[q] != (size_t)-1) eb.mom[q] = (float *)(ws + L.mom[q]);
+        if (F.xs != (size_t)-1) eb.saved_xs = (const uint16_t *)(fw + F.xs);
         if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
     }
 

@@ -199,6 +199,15 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
     }
     __syncthreads();
     FFN_STAMP(1);
+    if (p.xs_out) {   // training: keep the rounded input rows for the backward pass (the tile is only read from here on)
+        constexpr int U4 = D / 8;
+        for (int i = tid; i < TM * U4; i += 512) {
+            const int r = i / U4, cc = i % U4;
+            if (r < rows)
+                *reinterpret_cast<uint4 *>(p.xs_out + (size_t)(row0 + r) * D + 8 * cc) =
+                    *reinterpret_cast<const uint4 *>(lds + (size_t)r * XS + 8 * cc);
+        }
+    }
 
     // hidden = relu(x W1): wave w owns hidden columns [128w, 128w+128)
     const int cg = wave & 3, kh = wave >> 2;
@@ -396,6 +405,15 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
         }
     }
     __syncthreads();
+    if (p.xs_out) {   // training: keep the rounded input rows for the backward pass
+        constexpr int U4 = D / 8;
+        for (int i = tid; i < TM * U4; i += 256) {
+            const int r = i / U4, cc = i % U4;
+            if (r < rows)
+                *reinterpret_cast<uint4 *>(p.xs_out + (size_t)(row0 + r) * D + 8 * cc) =
+                    *reinterpret_cast<const uint4 *>(lds + (size_t)r * XS + 8 * cc);
+        }
+    }
 
     WeightStream4<H, D, FFN4_STAGES2, 1> s2;
     const int col2 = 128 * wave + 8 * c;
@@ -584,7 +602,7 @@ static int launch_expert_ffn_general(const moe_config *cfg, const FfnArgs &a, in
                                      hipStream_t st) {
     if (cfg->d % 128 || cfg->h % 128) return MOE_EUNSUPPORTED;
     const int64_t A = (int64_t)cfg->T * cfg->k;
-    uint16_t *xs = reinterpret_cast<uint16_t *>(a.hidden);
+    uint16_t *xs = a.xs_out ? a.xs_out : reinterpret_cast<uint16_t *>(a.hidden);
     uint16_t *hid = a.hid_out ? a.hid_out
                               : reinterpret_cast<uint16_t *>(reinterpret_cast<char *>(a.hidden) +
                                                              ffn_up256((size_t)A * cfg->d * 2));
@@ -666,7 +684,7 @@ int expert_ffn_with_hidden(const moe_config *cfg, const float *x, const int32_t 
                            const int32_t *offsets, const int32_t *tile_expert,
                            const int32_t *tile_row0, const int32_t *num_tiles, const void *W1,
                            const void *W2, float *out_sorted, void *workspace, uint16_t *hid_out,
-                           hipStream_t st) {
+                           hipStream_t st, uint16_t *xs_out) {
     int rc = check_config(cfg);
     if (rc != MOE_OK) return rc;
     if (!x || !perm || !offsets || !tile_expert || !tile_row0 || !num_tiles || !W1 || !W2 ||
@@ -680,6 +698,7 @@ int expert_ffn_with_hidden(const moe_config *cfg, const float *x, const int32_t 
     a.tile_expert = tile_expert; a.tile_row0 = tile_row0; a.num_tiles = num_tiles;
     a.W1 = W1; a.W2 = W2; a.out = out_sorted; a.hidden = (float *)workspace;
     a.hid_out = hid_out;
+    a.xs_out = cfg->expert_dtype == MOE_DTYPE_BF16 ? xs_out : nullptr;
     a.d = cfg->d; a.h = cfg->h; a.k = cfg->k;
     a.k_shift = (cfg->k & (cfg->k - 1)) == 0 ? __builtin_ctz(cfg->k) : -1;
     return launch_expert_ffn(cfg, a, moe_max_tiles(cfg), st);

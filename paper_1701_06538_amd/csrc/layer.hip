@@ -42,9 +42,11 @@ int workspace_layout(const moe_config *cfg, moe_workspace_layout *L) {
     L->out_sorted = take(A * (size_t)cfg->d * 4);
     L->ffn_ws = take(moe_ffn_workspace_bytes(cfg));
     L->aux_ws = take(hier ? 2 * n * 8 : aux_ws_bytes(moe_gate_partial_rows(cfg), cfg->n));
-    L->hidden = (size_t)-1;
-    if ((cfg->flags & MOE_FLAG_SAVE_HIDDEN) && cfg->expert_dtype == MOE_DTYPE_BF16)
+    L->hidden = L->xs = (size_t)-1;
+    if ((cfg->flags & MOE_FLAG_SAVE_HIDDEN) && cfg->expert_dtype == MOE_DTYPE_BF16) {
         L->hidden = take(A * (size_t)cfg->h * 2);
+        if (!hier) L->xs = take(A * (size_t)cfg->d * 2);   // the routed input rows as the experts saw them
+    }
     if (hier) {
         const size_t a = (size_t)cfg->a, kp = (size_t)cfg->k_primary, ks = (size_t)cfg->k_secondary;
         const size_t Ap = T * kp;
@@ -192,7 +194,8 @@ extern "C" int moe_layer_forward_profiled(const moe_config *cfg, const float *x,
     MOE_STAGE(2, expert_ffn_with_hidden(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2,
                                         out_sorted, ws + L.ffn_ws,
                                         L.hidden == (size_t)-1 ? nullptr : (uint16_t *)(ws + L.hidden),
-                                        (hipStream_t)stream))
+                                        (hipStream_t)stream,
+                                        L.xs == (size_t)-1 ? nullptr : (uint16_t *)(ws + L.xs)))
     if (fuse) {
         MOE_STAGE(3, launch_combine_losses(out_sorted, topk_gate, inv_perm, y, cfg->T, cfg->d, cfg->k,
                                            prow, cfg->n, (double *)(ws + L.aux_ws), cfg->w_importance,

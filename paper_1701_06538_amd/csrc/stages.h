@@ -56,6 +56,7 @@ struct FfnArgs {
     float *out;               // [A,d]
     float *hidden;            // fp32 path workspace [A,h]
     uint16_t *hid_out;        // bf16 path: optional copy of the hidden activations [A,h], or null
+    uint16_t *xs_out;         // bf16 path: optional copy of the routed input rows, rounded to bf16 [A,d], or null
     int d, h, k;
     int k_shift;              // log2(k) when k is a power of two, else -1
 };
@@ -130,7 +131,7 @@ int expert_ffn_with_hidden(const moe_config *cfg, const float *x, const int32_t 
                            const int32_t *offsets, const int32_t *tile_expert,
                            const int32_t *tile_row0, const int32_t *num_tiles, const void *W1,
                            const void *W2, float *out_sorted, void *workspace, uint16_t *hid_out,
-                           hipStream_t st);
+                           hipStream_t st, uint16_t *xs_out = nullptr);
 int launch_combine(const float *out_sorted, const float *gate, const int32_t *inv_perm, float *y,
                    int64_t T, int d, int k, hipStream_t st);
 int launch_aux_losses(const float *partials, int64_t rows, int n, float w_imp, float w_load,

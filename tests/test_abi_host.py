@@ -93,6 +93,17 @@ def test_backward_workspace_and_flags(api):
     cfg1 = api.make_config(T=65536, d=512, h=1024, n=512, k=4, flags=api.MOE_FLAG_SAVE_HIDDEN)
     L1 = api.moe_get_workspace_layout(cfg1)
     assert L1.hidden != 2 ** 64 - 1 and L1.total - L0.total >= 262144 * 1024 * 2
+    # the kept input rows: absent without the flag, and their own block after the hidden rows with it
+    assert L0.xs == 2 ** 64 - 1
+    assert L1.xs >= L1.hidden + 262144 * 1024 * 2 and L1.xs + 262144 * 512 * 2 <= L1.total
+    f32s = api.make_config(T=64, d=512, h=1024, n=32, k=4, expert_dtype=api.MOE_DTYPE_F32,
+                           flags=api.MOE_FLAG_SAVE_HIDDEN)
+    Lf = api.moe_get_workspace_layout(f32s)
+    assert Lf.hidden == 2 ** 64 - 1 and Lf.xs == 2 ** 64 - 1
+    hs = api.make_config(T=64, d=512, h=1024, n=64, k=4, a=8, b=8, k_primary=2, k_secondary=2,
+                         flags=api.MOE_FLAG_SAVE_HIDDEN)
+    Lh = api.moe_get_workspace_layout(hs)
+    assert Lh.hidden != 2 ** 64 - 1 and Lh.xs == 2 ** 64 - 1
     f32 = api.make_config(T=64, d=512, h=1024, n=32, k=4, expert_dtype=api.MOE_DTYPE_F32)
     assert api.moe_backward_workspace_bytes(f32) > 0
     hier = api.make_config(T=64, d=512, h=1024, n=64, k=4, a=8, b=8, k_primary=2, k_secondary=2)

@@ -88,6 +88,7 @@ CASES = [
     ("cfg1_shape", dict(T=2048, n=256), False, 0),           # the other flat workloads' expert counts
     ("cfg2_shape", dict(T=800, n=2048), False, 1),          # (few rows per expert, many empty experts)
     ("d256_h512", dict(T=600, n=32, d=256, h=512), False, 0),  # experts off the fused kernel's shape
+    ("d256_h512_saved", dict(T=600, n=32, d=256, h=512), False, 1),  # kept hidden and input rows on the unfused path
     ("n20_bf16", dict(T=400, n=20, k=3), False, 0),            # expert count off the tile sizes
     ("n640_small_experts", dict(T=900, n=640, k=2, d=256, h=256), True, 0),   # 512 < n <= 1024: four column groups per lane in the gate kernel
     # fp32 experts: every GEMM on the fp32 matrix cores
