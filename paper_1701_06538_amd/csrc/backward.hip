@@ -66,6 +66,43 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const float *__restric
     if (lane == 0) dgate[a] = dot;
 }
 
+// The same quantities with one wavefront per token (flat layer): the token's dy (and x) row comes
+// from HBM once and serves its k routed rows, found through inv_perm; per routed row the
+// arithmetic and its order are those of bwd_prepare_kernel.
+__global__ __launch_bounds__(256) void bwd_prepare_tokens_kernel(const float *__restrict__ x,
+                                                                 const float *__restrict__ dy,
+                                                                 const float *__restrict__ out_sorted,
+                                                                 const float *__restrict__ gate,
+                                                                 const int32_t *__restrict__ inv_perm,
+                                                                 int64_t T, int d, int k,
+                                                                 uint16_t *__restrict__ xs,   // null: kept by the forward pass
+                                                                 uint16_t *__restrict__ dout,
+                                                                 float *__restrict__ dgate) {
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    for (int j = 0; j < k; ++j) {
+        const int64_t a = t * k + j;
+        const int64_t r = inv_perm[a];
+        const float g = gate[a];
+        float dot = 0.f;
+        for (int c = lane * 4; c < d; c += 256) {
+            const float4 vy = *reinterpret_cast<const float4 *>(dy + t * d + c);
+            const float4 vo = *reinterpret_cast<const float4 *>(out_sorted + r * d + c);
+            dot = fmaf(vy.x, vo.x, dot); dot = fmaf(vy.y, vo.y, dot);
+            dot = fmaf(vy.z, vo.z, dot); dot = fmaf(vy.w, vo.w, dot);
+            *reinterpret_cast<uint2 *>(dout + r * d + c) = make_uint2(pack2(g * vy.x, g * vy.y), pack2(g * vy.z, g * vy.w));
+            if (xs) {
+                const float4 vx = *reinterpret_cast<const float4 *>(x + t * d + c);
+                *reinterpret_cast<uint2 *>(xs + r * d + c) = make_uint2(pack2(vx.x, vx.y), pack2(vx.z, vx.w));
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+        if (lane == 0) dgate[a] = dot;
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // bf16 MFMA block GEMM shared by the expert backward kernels: 128 x 128 tile, 4 waves (2 x 2),
 // k-slabs of 32 staged in LDS with k contiguous for both operands.
@@ -854,6 +891,7 @@ struct ExpertBwd {
     float *mom[4];                             // optional sums of squares for the optimiser, or nulls
     bool by_row;                               // perm lists tokens; gate and dgate are per routed row
     const uint16_t *saved_xs;                  // routed input rows (bf16) kept by the forward pass, or null
+    const int32_t *inv_perm;                   // flat layer: sorted row of each (token, slot), or null
 };
 
 static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStream_t s) {
@@ -861,9 +899,14 @@ static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStr
     const int d = cfg->d, h = cfg->h, n = cfg->n, k = cfg->k;
     int st;
     const uint16_t *xs = b.saved_xs ? b.saved_xs : b.xs;
-    hipLaunchKernelGGL(bwd_prepare_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, s, b.x, b.dy,
-                       b.out_sorted, b.gate, b.perm, A, d, k, b.by_row ? 1 : 0, b.saved_xs ? nullptr : b.xs,
-                       b.dout, b.dgate);
+    if (b.inv_perm && !b.by_row)
+        hipLaunchKernelGGL(bwd_prepare_tokens_kernel, dim3((unsigned)ceil_div(cfg->T, 4)), dim3(256), 0, s, b.x,
+                           b.dy, b.out_sorted, b.gate, b.inv_perm, (int64_t)cfg->T, d, k,
+                           b.saved_xs ? nullptr : b.xs, b.dout, b.dgate);
+    else
+        hipLaunchKernelGGL(bwd_prepare_kernel, dim3((unsigned)ceil_div(A, 4)), dim3(256), 0, s, b.x, b.dy,
+                           b.out_sorted, b.gate, b.perm, A, d, k, b.by_row ? 1 : 0, b.saved_xs ? nullptr : b.xs,
+                           b.dout, b.dgate);
     MOE_LAUNCH_CHECK();
     const uint16_t *hid = b.saved_hid;
     if (!hid) {   // Appendix D: recompute the hidden activations
@@ -968,6 +1011,7 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
         for (int q = 0; q < 4; ++q)
             if (L.mom[q] != (size_t)-1) eb.mom[q] = (float *)(ws + L.mom[q]);
         if (F.xs != (size_t)-1) eb.saved_xs = (const uint16_t *)(fw + F.xs);
+        eb.inv_perm = inv_perm;
         if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
     }
 
