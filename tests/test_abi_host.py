@@ -110,6 +110,30 @@ def test_backward_workspace_and_flags(api):
     assert api.moe_backward_workspace_bytes(hier) == 0   # flat layer only
 
 
+def test_layout_struct_of_the_binding_matches_the_library(api):
+    """The library fills exactly the fields the binding declares: bytes past the binding's struct stay
+    untouched and its last field is written."""
+    import ctypes
+    size = ctypes.sizeof(api.MoeWorkspaceLayout)
+    buf = (ctypes.c_ubyte * (size + 64))(*([0xAB] * (size + 64)))
+    cfg = api.make_config(T=8192, d=512, h=1024, n=256, k=4)
+    fn = api._lib.moe_get_workspace_layout
+    assert fn(ctypes.byref(cfg), ctypes.cast(buf, ctypes.POINTER(api.MoeWorkspaceLayout))) == 0
+    assert bytes(buf[size:]) == b"\xab" * 64
+    L = api.MoeWorkspaceLayout.from_buffer_copy(bytes(buf[:size]))
+    assert L.xs == 2 ** 64 - 1 and L.hidden == 2 ** 64 - 1 and L.total == api.moe_workspace_bytes(cfg)
+    fields = [getattr(L, f) for f, _ in api.MoeWorkspaceLayout._fields_]
+    assert 0xABABABABABABABAB not in fields
+    # the header lists the same fields in the same order
+    import re
+    from pathlib import Path
+    text = Path(__file__).resolve().parents[1].joinpath("include", "moe.h").read_text()
+    body = text[text.index("typedef struct moe_workspace_layout {"):text.index("} moe_workspace_layout;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*[,;]", body)
+    assert names == [f for f, _ in api.MoeWorkspaceLayout._fields_]
+
+
 def test_workspace_layout_is_ordered_aligned_and_sized(api):
     cfg = api.make_config(T=8192, d=512, h=1024, n=256, k=4)
     L = api.moe_get_workspace_layout(cfg)
