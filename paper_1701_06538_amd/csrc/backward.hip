@@ -22,12 +22,8 @@ namespace moe {
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ uint32_t bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return bf16_rne(lo) | (bf16_rne(hi) << 16); }
+__device__ __forceinline__ uint32_t bf16_rne(float f) { return bf16_bits_of(f); }
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return pack_bf16_pair(lo, hi); }
 __device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
 // ---------------------------------------------------------------------------------------

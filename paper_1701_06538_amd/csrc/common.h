@@ -38,4 +38,15 @@ constexpr int kMaxGateExperts = 2048;  // experts of one gating level (top-k ker
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Two fp32 values rounded to bf16 (nearest, ties to even) and packed, lo in bits 0-15: one
+// v_cvt_pk_bf16_f32 on gfx950.  For every finite input, denormals included, the result equals
+// the integer form (bits + 0x7fff + bit 16, shifted right by 16); NaNs are quieted, and no
+// input here is one.
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
+}
+__device__ __forceinline__ uint32_t bf16_bits_of(float f) { return pack_bf16_pair(f, 0.f) & 0xffffu; }
+
 }  // namespace moe

@@ -25,14 +25,7 @@ constexpr int kFfnTM = 64;  // rows per tile
 #define FFN_STAGES2 2
 #endif
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);  // inputs are finite
-    return u >> 16;
-}
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return f32_to_bf16_rne(lo) | (f32_to_bf16_rne(hi) << 16);
-}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) { return pack_bf16_pair(lo, hi); }
 
 
 // XCD-aware tile order: consecutive workgroup ids go to different XCDs (one L2 each), so

@@ -28,11 +28,6 @@ constexpr int RT = 256;            // tile rows and columns
 constexpr int RKC = GG_RKC;        // slab depth
 constexpr int RLD = RKC + 8;       // bf16 elements per LDS row (+16 bytes: 16-byte reads of 8 rows hit 32 banks)
 
-__device__ __forceinline__ uint32_t bf16_rne_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
 
 #ifdef MOE_GG_TIMING
 __device__ long long g_gg_timing[8192 * 4];
@@ -198,10 +193,9 @@ __global__ __launch_bounds__(64 * NW, 1) void gg_rows256_kernel(GGRows p, int co
                     // relu'(z) with relu'(0) = 0: the stored hidden value is positive iff z > 0
                     const v4u m = *reinterpret_cast<const v4u *>(p.mask + at);
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const uint32_t hbits = (m[t >> 1] >> (16 * (t & 1))) & 0xffffu;
-                        const bool on = (hbits & 0x7fffu) != 0 && (hbits & 0x8000u) == 0;
-                        v[t] = on ? v[t] : 0.f;
+                    for (int t = 0; t < 4; ++t) {   // a bf16 is positive iff its bits, moved to the top of a word, are > 0 as an integer
+                        v[2 * t] = (int32_t)(m[t] << 16) > 0 ? v[2 * t] : 0.f;
+                        v[2 * t + 1] = (int32_t)(m[t] & 0xffff0000u) > 0 ? v[2 * t + 1] : 0.f;
                     }
                 } else {
 #pragma unroll
@@ -209,7 +203,7 @@ __global__ __launch_bounds__(64 * NW, 1) void gg_rows256_kernel(GGRows p, int co
                 }
                 v4u o;
 #pragma unroll
-                for (int t = 0; t < 4; ++t) o[t] = bf16_rne_bits(v[2 * t]) | (bf16_rne_bits(v[2 * t + 1]) << 16);
+                for (int t = 0; t < 4; ++t) o[t] = pack_bf16_pair(v[2 * t], v[2 * t + 1]);
                 *reinterpret_cast<v4u *>(C + at) = o;
             }
         }

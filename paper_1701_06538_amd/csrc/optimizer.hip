@@ -169,10 +169,6 @@ struct AdamUpd {
     float lr, eps;
 };
 
-__device__ __forceinline__ uint32_t adam_bf16_bits(float f) {   // round to nearest even
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
 
 // one workgroup per 4 rows of one matrix (blockIdx.y = matrix)
 __global__ __launch_bounds__(256) void adam_update_kernel(AdamUpd a) {
@@ -199,8 +195,7 @@ __global__ __launch_bounds__(256) void adam_update_kernel(AdamUpd a) {
             }
             if (a.copy)
                 reinterpret_cast<uint2 *>(a.copy)[base + c4] =
-                    make_uint2(adam_bf16_bits(w.x) | (adam_bf16_bits(w.y) << 16),
-                               adam_bf16_bits(w.z) | (adam_bf16_bits(w.w) << 16));
+                    make_uint2(pack_bf16_pair(w.x, w.y), pack_bf16_pair(w.z, w.w));   // round to nearest even
         }
     }
 }
