@@ -323,7 +323,7 @@ extern "C" int moe_debug_read_gate_timing(long long *host_out) {
 // matters; the sums of P(x,.) over a batch need far less).
 __device__ __forceinline__ float normal_cdf(float u) {
     const float x = fabsf(u) * 0.70710678118654752f;
-    const float t = __frcp_rn(fmaf(0.5f, x, 1.0f));
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.5f, x, 1.0f));   // v_rcp_f32 (1 ulp); the argument is >= 1
     float p = 8.192740381e-03f;
     p = fmaf(p, t, 1.299090832e-01f);
     p = fmaf(p, t, -7.351043820e-01f);
@@ -338,6 +338,12 @@ __device__ __forceinline__ float normal_cdf(float u) {
     const float half_erfc = 0.5f * t * __expf(fmaf(-x, x, p));   // = Phi(-|u|)
     return u < 0.f ? half_erfc : 1.0f - half_erfc;
 }
+
+// 1 / (noise standard deviation) for the argument of Phi in Eq.(9): the hardware reciprocal (1 ulp)
+// in place of a correctly rounded division, which changes Phi by less than 1e-7.  Deviations below
+// 1e-30 (Softplus of a logit under -69; the reciprocal instruction does not take denormals) are
+// raised to 1e-30: the argument is then +-inf-like or exactly 0 either way.
+__device__ __forceinline__ float load_inv_sigma(float sp) { return __builtin_amdgcn_rcpf(fmaxf(sp, 1e-30f)); }
 
 // Selection key: one unsigned 64-bit integer per (logit, expert) whose order is the order the
 // top-k must follow: larger logit first, equal logits -> lower expert index first, +0 = -0.
@@ -527,7 +533,7 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
 #pragma unroll
             for (int q = 0; q < NCH; ++q) {
                 const int i = lane + 64 * q;
-                const float u = (cv[q] - (hv[q] >= thr_out ? thr_in : thr_out)) * __frcp_rn(sv[q]);
+                const float u = (cv[q] - (hv[q] >= thr_out ? thr_in : thr_out)) * load_inv_sigma(sv[q]);
                 const float P = normal_cdf(u);
                 acc_load[q] += i < n ? P : 0.f;
                 if (NCH >= 16 && (q & 3) == 3) __builtin_amdgcn_sched_barrier(0);
@@ -720,7 +726,7 @@ __global__ __launch_bounds__(256, 2) void gate_topk_wide_kernel(TopkArgs p) {
 #pragma unroll
             for (int q = 0; q < NCH; ++q) {
                 const int i = col_base + lane + 64 * q;
-                const float u = (cv[q] - (hv[q] >= thr_out ? thr_in : thr_out)) * __frcp_rn(sv[q]);
+                const float u = (cv[q] - (hv[q] >= thr_out ? thr_in : thr_out)) * load_inv_sigma(sv[q]);
                 const float P = normal_cdf(u);
                 acc_load[q] += i < n ? P : 0.f;
             }
