@@ -71,8 +71,8 @@ typedef struct moe_config {
  * otherwise gather and round again).  The paper
  * recomputes (Appendix D) to fit 12 GB devices; with 288 GB of HBM the 2*h bytes per routed row
  * are the cheaper side of the trade.  Without the flag the backward pass recomputes. */
-/* With MOE_FLAG_ADAM_MOMENTS moe_layer_backward and moe_layer_backward_balanced (bf16 experts) also
- * leave, in the backward workspace, the
+/* With MOE_FLAG_ADAM_MOMENTS moe_layer_backward, moe_layer_backward_balanced and moe_layer_backward_hier
+ * (bf16 experts) also leave, in the backward workspace, the
  * per-block sums of squares of dW1 and dW2 that the weight-gradient kernels have in registers
  * anyway; moe_expert_adam_step then skips its own pass over the gradients when it is handed that
  * workspace. */
@@ -382,7 +382,7 @@ int moe_layer_forward_threshold(const moe_config *cfg, const float *x, const flo
  * Device outputs: W1_copy, W2_copy: the bf16 weights the layer reads (nearest-even rounding of the
  * updated parameters), or both NULL for fp32 experts, whose parameters are the weights themselves.
  * d and h multiples of 4; workspace: moe_adam_workspace_bytes().
- * backward_workspace: NULL, or the workspace moe_layer_backward has just filled under a cfg with
+ * backward_workspace: NULL, or the workspace moe_layer_backward (or _hier) has just filled under a cfg with
  * MOE_FLAG_ADAM_MOMENTS (the same cfg is passed here): the sums of squares of the gradients are
  * then taken from it instead of from a pass over dW1 and dW2.  Without it cfg->T and cfg->k are
  * not used.

@@ -931,8 +931,10 @@ static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStr
 using namespace moe;
 
 namespace moe {
+static int hier_moments_offsets(const moe_config *cfg, size_t off[4]);
 int backward_moments_offsets(const moe_config *cfg, size_t off[4]) {
-    if (check_config(cfg) != MOE_OK || cfg->a != 0) return MOE_EINVAL;
+    if (check_config(cfg) != MOE_OK) return MOE_EINVAL;
+    if (cfg->a != 0) return hier_moments_offsets(cfg, off);
     BwdLayout L;
     bwd_layout(cfg, &L);
     for (int q = 0; q < 4; ++q) {
@@ -1213,7 +1215,7 @@ __global__ __launch_bounds__(256) void gather_rows_f32_kernel(const float4 *__re
 
 struct HierBwdLayout {
     size_t xs, dout, hid, dz, dxs, dgate, gI, gL, tile_expert, tile_row0, num_tiles, order;
-    size_t dGp, dGs, dLoad_p, dLoad_s, dclean_p, draw_p, dclean_s, draw_s, xg, dxg, wpart, total;
+    size_t dGp, dGs, dLoad_p, dLoad_s, dclean_p, draw_p, dclean_s, draw_s, xg, dxg, wpart, mom[4], total;
     int ksplit;
 };
 
@@ -1256,7 +1258,23 @@ static void hier_bwd_layout(const moe_config *cfg, HierBwdLayout *L) {
     if (ks < 1) ks = 1;
     L->ksplit = ks;
     L->wpart = take((size_t)ks * 2 * d * a * 4);
+    // MOE_FLAG_ADAM_MOMENTS: per-block sums of squares of dW1 [d,h] and dW2 [h,d] (see GGWgrad)
+    const bool mom = (cfg->flags & MOE_FLAG_ADAM_MOMENTS) && cfg->expert_dtype == MOE_DTYPE_BF16;
+    L->mom[0] = mom ? take(n * (h / 256) * d * 4) : (size_t)-1;
+    L->mom[1] = mom ? take(n * (d / 256) * h * 4) : (size_t)-1;
+    L->mom[2] = mom ? take(n * (d / 256) * h * 4) : (size_t)-1;
+    L->mom[3] = mom ? take(n * (h / 256) * d * 4) : (size_t)-1;
     L->total = off;
+}
+
+static int hier_moments_offsets(const moe_config *cfg, size_t off[4]) {
+    HierBwdLayout L;
+    hier_bwd_layout(cfg, &L);
+    for (int q = 0; q < 4; ++q) {
+        if (L.mom[q] == (size_t)-1) return MOE_EINVAL;
+        off[q] = L.mom[q];
+    }
+    return MOE_OK;
 }
 
 static int hier_bwd_check(const moe_config *cfg) {
@@ -1317,6 +1335,8 @@ extern "C" int moe_layer_backward_hier(const moe_config *cfg, const float *x, co
                  (uint16_t *)(ws + L.dout), (uint16_t *)(ws + L.hid), (uint16_t *)(ws + L.dz), dxs, dgate,
                  (int32_t *)(ws + L.tile_expert), (int32_t *)(ws + L.tile_row0), (int32_t *)(ws + L.num_tiles),
                  (int32_t *)(ws + L.order), dW1, dW2, {nullptr, nullptr, nullptr, nullptr}};
+    for (int q = 0; q < 4; ++q)
+        if (L.mom[q] != (size_t)-1) eb.mom[q] = (float *)(ws + L.mom[q]);
     if ((st = run_expert_backward(cfg, eb, s)) != MOE_OK) return st;
 
     // Eq.(13),(14): gradients of both CV^2 with respect to Importance_H and Load_H, then into the levels

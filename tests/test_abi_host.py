@@ -108,6 +108,12 @@ def test_backward_workspace_and_flags(api):
     assert api.moe_backward_workspace_bytes(f32) > 0
     hier = api.make_config(T=64, d=512, h=1024, n=64, k=4, a=8, b=8, k_primary=2, k_secondary=2)
     assert api.moe_backward_workspace_bytes(hier) == 0   # flat layer only
+    # the hierarchical backward workspace grows by the sums of squares when they are asked for
+    hm = api.make_config(T=64, d=512, h=1024, n=1024, k=4, a=32, b=32, k_primary=2, k_secondary=2)
+    hm2 = api.make_config(T=64, d=512, h=1024, n=1024, k=4, a=32, b=32, k_primary=2, k_secondary=2,
+                          flags=api.MOE_FLAG_ADAM_MOMENTS)
+    grow = api.moe_backward_hier_workspace_bytes(hm2) - api.moe_backward_hier_workspace_bytes(hm)
+    assert api.moe_backward_hier_workspace_bytes(hm) > 0 and grow >= 1024 * (4 * 512 + 2 * 1024) * 2 * 4
 
 
 def test_layout_struct_of_the_binding_matches_the_library(api):

@@ -151,6 +151,52 @@ def test_adam_step_with_sums_from_the_backward_pass(api):
                                  s0[0], s0[1], s0[2], s0[3], ows, backward_workspace=bws)
 
 
+def test_adam_step_with_sums_from_the_hierarchical_backward_pass(api):
+    """The same sums of squares left by moe_layer_backward_hier: the step that takes them from the
+    backward workspace must agree with the step that makes its own pass over the gradients."""
+    from tests import gpu_harness as G
+    say("adam fused moments, hierarchical")
+    shape = W.scaled_config(W.CONFIGS[3], T=600, a=32, b=32, n=1024, k_primary=2, k_secondary=2, k=4,
+                            d=256, h=256)
+    inputs = W.hier_gate_inputs(shape, 0.02)
+    W1, W2 = G.device_weights(shape, chunk=256)
+    run = G.HierRun(api, shape, inputs, W1, W2, flags=api.MOE_FLAG_ADAM_MOMENTS)
+    run.forward()
+    T, d, h, n, a, b = shape.T, shape.d, shape.h, shape.n, shape.a, shape.b
+    f32 = dict(dtype=torch.float32, device="cuda")
+    out = [torch.empty((T, d), **f32), torch.empty((d, a), **f32), torch.empty((d, a), **f32),
+           torch.empty((a, d, b), **f32), torch.empty((a, d, b), **f32), torch.empty((n, d, h), **f32),
+           torch.empty((n, h, d), **f32)]
+    plain_cfg = api.make_config(shape)
+    assert api.moe_backward_hier_workspace_bytes(run.cfg) > api.moe_backward_hier_workspace_bytes(plain_cfg)
+    bws = torch.empty(api.moe_backward_hier_workspace_bytes(run.cfg), dtype=torch.uint8, device="cuda")
+    dy = G.dev(W.upstream_grad(shape))
+    api.moe_layer_backward_hier(run.cfg, run.x, run.Wg_p, run.Wn_p, run.eps_p, run.Wg_s, run.Wn_s, run.eps_s,
+                                run.W1, run.W2, dy, run.topk_idx, run.topk_gate, run.workspace, *out, bws)
+    torch.cuda.synchronize()
+    ows = torch.empty(max(256, api.moe_adam_workspace_bytes(run.cfg)), dtype=torch.uint8, device="cuda")
+    results = []
+    for fused in (False, True):
+        masters = [run.W1.to(torch.float32), run.W2.to(torch.float32)]
+        copies = [torch.zeros_like(run.W1), torch.zeros_like(run.W2)]
+        st = [torch.zeros((n, d), **f32), torch.zeros((n, h), **f32), torch.zeros((n, h), **f32), torch.zeros((n, d), **f32)]
+        api.moe_expert_adam_step(run.cfg, 1e-2, 0.9, 1e-8, 1, out[5], out[6], masters[0], masters[1], copies[0],
+                                 copies[1], st[0], st[1], st[2], st[3], ows, backward_workspace=bws if fused else None)
+        torch.cuda.synchronize()
+        results.append((masters, st, copies))
+    (m0, s0, c0), (m1, s1, c1) = results
+    used = (out[5].abs().amax(dim=(1, 2)) > 0).sum().item()
+    assert used > n // 4          # most experts got rows, so the comparison is not of zeros
+    for x0, x1 in zip(s0 + m0, s1 + m1):
+        assert rel(x1.cpu().numpy(), x0.cpu().numpy().astype(np.float64)) <= TOL
+    g2 = out[6].cpu().numpy()
+    w2 = run.W2.to(torch.float32).cpu().numpy()
+    e = int(torch.argmax(out[6].abs().amax(dim=(1, 2))).item())
+    ref_W, ref_vr, ref_vc = O.factored_adam_step(w2[e], g2[e], np.zeros(h), np.zeros(d), 1e-2, 0.9, 1e-8, 1)
+    assert rel(m1[1][e].cpu().numpy(), ref_W) <= TOL
+    assert rel(s1[2][e].cpu().numpy(), ref_vr) <= TOL and rel(s1[3][e].cpu().numpy(), ref_vc) <= TOL
+
+
 def test_training_step_with_adam_at_full_size(api):
     """The training workload at full size (T = 65536, 512 experts, skewed loads): forward, backward
     with the sums of squares taken in the weight-gradient kernels, then the Adam step of all 1024
