@@ -435,6 +435,15 @@ int moe_layer_forward_profiled(const moe_config *cfg, const float *x, const floa
                                void *workspace, size_t workspace_bytes, void *const *stage_events,
                                void *stream);
 
+/* moe_layer_forward_hier with the same timing hooks (10 events: gate = both levels, route,
+ * experts, combine, losses). */
+int moe_layer_forward_hier_profiled(const moe_config *cfg, const float *x, const float *Wg_p,
+                                    const float *Wn_p, const float *eps_p, const float *Wg_s,
+                                    const float *Wn_s, const float *eps_s, const void *W1,
+                                    const void *W2, float *y, int32_t *topk_idx, float *topk_gate,
+                                    float *importance, float *load, float *losses, void *workspace,
+                                    size_t workspace_bytes, void *const *stage_events, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -136,58 +136,3 @@ void oracle_noisy_logits_f32(const float *clean, const float *raw, const float *
         }
     }
 }
-
-/*
- * Softmax over all n experts, G_sigma(x) = Softmax(x . W_g) (Section 2.1, the plain softmax
- * gate; Appendix F builds the strictly balanced gate on it).  The batchwise mask of Appendix F
- * compares these values across tokens, so "bit-exact mask" needs their fp32 bits pinned.
- * Reading (R18) used on both sides of the parity tests, per row:
- *   mx  = largest logit (fp32 comparison);
- *   e_i = exp(-(min((double)mx - (double)l_i, 64))) in binary64 with the exponential of (R2)
- *         (q = rint(a*log2e), r = fma(-q, ln2, a), degree-13 Taylor polynomial, exact scaling);
- *   s   = 64 interleaved partial sums p_l = sum_q e_{l+64q} (q ascending), then the tree
- *         p_l += p_{l+off} for off = 32, 16, 8, 4, 2, 1 (l < off); s = p_0;
- *   G_sigma_i = (float)(e_i / s)   (one binary64 division, one rounding to binary32).
- */
-static double oracle_exp_neg(double a)
-{
-    const double LOG2E = 1.4426950408889634;
-    const double LN2 = 0.6931471805599453;
-    if (a > 64.0) a = 64.0;
-    double q = rint(a * LOG2E);
-    double r = fma(-q, LN2, a);
-    double m = -r;
-    double p = 1.0 / 6227020800.0;
-    p = fma(p, m, 1.0 / 479001600.0);
-    p = fma(p, m, 1.0 / 39916800.0);
-    p = fma(p, m, 1.0 / 3628800.0);
-    p = fma(p, m, 1.0 / 362880.0);
-    p = fma(p, m, 1.0 / 40320.0);
-    p = fma(p, m, 1.0 / 5040.0);
-    p = fma(p, m, 1.0 / 720.0);
-    p = fma(p, m, 1.0 / 120.0);
-    p = fma(p, m, 1.0 / 24.0);
-    p = fma(p, m, 1.0 / 6.0);
-    p = fma(p, m, 0.5);
-    p = fma(p, m, 1.0);
-    p = fma(p, m, 1.0);
-    return ldexp(p, -(int)q);
-}
-
-void oracle_softmax_rows_f32(const float *logits, int64_t T, int64_t n, float *out)
-{
-#pragma omp parallel for schedule(static)
-    for (int64_t t = 0; t < T; ++t) {
-        const float *l = logits + t * n;
-        float mx = l[0];
-        for (int64_t i = 1; i < n; ++i) if (l[i] > mx) mx = l[i];
-        double p[64];
-        for (int j = 0; j < 64; ++j) p[j] = 0.0;
-        for (int64_t i = 0; i < n; ++i) p[i & 63] += oracle_exp_neg((double)mx - (double)l[i]);
-        for (int off = 32; off > 0; off >>= 1)
-            for (int j = 0; j < off; ++j) p[j] += p[j + off];
-        const double s = p[0];
-        for (int64_t i = 0; i < n; ++i)
-            out[t * n + i] = (float)(oracle_exp_neg((double)mx - (double)l[i]) / s);
-    }
-}

@@ -50,8 +50,6 @@ def _lib():
         lib.oracle_noisy_logits_f32.argtypes = [f32p, f32p, f32p, f32p, ctypes.c_int64,
                                                 ctypes.c_int64, f32p, f32p, f32p]
         lib.oracle_noisy_logits_f32.restype = None
-        lib.oracle_softmax_rows_f32.argtypes = [f32p, ctypes.c_int64, ctypes.c_int64, f32p]
-        lib.oracle_softmax_rows_f32.restype = None
         _LIB = lib
     return _LIB
 
@@ -448,6 +446,18 @@ def experts_backward(xe_all, idx, g, weight_fn, dy, experts_for_dW=None, only=No
     return dx, dgate, dW1, dW2
 
 
+def expert_input_grad(xe, dout, W1, W2, relu_mask=None):
+    """Gradient of <dout, E(xe)> with respect to the rows xe of ONE expert (Appendix C):
+    ((dout W2^T) * [z > 0]) W1^T with z = xe W1.  relu_mask [rows,h] (bool) replaces the sign test
+    z > 0: parity tests use it to evaluate a row on the other side's decision at hidden units whose
+    pre-activation is zero to within rounding, where either decision is a correct evaluation."""
+    xe, dout = np.asarray(xe, np.float64), np.asarray(dout, np.float64)
+    W1, W2 = np.asarray(W1, np.float64), np.asarray(W2, np.float64)
+    z = xe @ W1
+    mask = (z > 0.0) if relu_mask is None else np.asarray(relu_mask, bool)
+    return ((dout @ W2.T) * mask) @ W1.T
+
+
 def flat_backward(x, W_g, W_noise, fwd: FlatForward, k, weight_fn, dy,
                   w_importance=0.1, w_load=0.1, experts_for_dW=None, expert_input=None) -> Grads:
     """Gradients of J = <dy, y> + L_importance + L_load for the flat layer.
@@ -620,16 +630,19 @@ def hier_objective(x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, k_p, k_s, weight_fn,
 # --------------------------------------------------------------------------------------
 
 def softmax_gate_f32(x, W_g, bias=None):
-    """Eq.(15): G_sigma(x) = Softmax(x W_g) over all n experts, in the pinned fp32 arithmetic
-    (logits by R1, softmax by R18 of gate_arith.c).  Returns (logits, G_sigma), both fp32."""
+    """Eq.(15): G_sigma(x) = Softmax(x W_g) over all n experts.  The logits are the fp32 values of
+    reading R1 (the same ones noisy top-k gating selects on); the softmax itself is the plain
+    definition in binary64 -- exponentials of (logit - row maximum), ONE accumulator summing them
+    over i ascending, one division -- rounded once to fp32.  Returns (logits, G_sigma), both fp32."""
     clean = dot_chain_f32(x, W_g)
     if bias is not None:
         clean = (clean + np.asarray(bias, np.float32)[None, :]).astype(np.float32)
-    clean, cp = _f32(clean)
-    out = np.empty_like(clean)
-    _lib().oracle_softmax_rows_f32(cp, clean.shape[0], clean.shape[1],
-                                   out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
-    return clean, out
+    l = clean.astype(np.float64)
+    e = np.exp(l - l.max(axis=1, keepdims=True))
+    s = np.zeros(l.shape[0])
+    for i in range(l.shape[1]):          # sequential, i ascending (numpy's sum is pairwise)
+        s = s + e[:, i]
+    return clean, (e / s[:, None]).astype(np.float32)
 
 
 def batchwise_mask(X, m):

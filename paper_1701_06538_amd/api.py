@@ -83,6 +83,9 @@ _moe_layer_forward_hier = _proto("moe_layer_forward_hier", ctypes.c_int,
                                  [_cfgp] + [_vp] * 16 + [ctypes.c_size_t, _vp])
 
 
+_moe_layer_forward_hier_profiled = _proto("moe_layer_forward_hier_profiled", ctypes.c_int,
+                                          [_cfgp] + [_vp] * 16 + [ctypes.c_size_t, ctypes.POINTER(_vp), _vp])
+
 _moe_backward_workspace_bytes = _proto("moe_backward_workspace_bytes", ctypes.c_size_t, [_cfgp])
 _moe_layer_backward = _proto("moe_layer_backward", ctypes.c_int,
                              [_cfgp] + [_vp] * 16 + [ctypes.c_size_t, _vp])
@@ -285,6 +288,19 @@ def moe_layer_forward_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, W1, W2,
                                    _ptr(Wg_s), _ptr(Wn_s), _ptr(eps_s), _ptr(W1), _ptr(W2), _ptr(y),
                                    _ptr(topk_idx), _ptr(topk_gate), _ptr(importance), _ptr(load),
                                    _ptr(losses), _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def moe_layer_forward_hier_profiled(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, W1, W2, y, topk_idx, topk_gate,
+                                    importance, load, losses, workspace, stage_events, stream=None):
+    """stage_events: None or a sequence of 10 hipEvent_t handles (ints, 0/None to skip)."""
+    ev = None
+    if stage_events is not None:
+        ev = (_vp * 10)(*[(e or None) for e in stage_events])
+    _check(_moe_layer_forward_hier_profiled(ctypes.byref(cfg), _ptr(x), _ptr(Wg_p), _ptr(Wn_p), _ptr(eps_p),
+                                            _ptr(Wg_s), _ptr(Wn_s), _ptr(eps_s), _ptr(W1), _ptr(W2), _ptr(y),
+                                            _ptr(topk_idx), _ptr(topk_gate), _ptr(importance), _ptr(load),
+                                            _ptr(losses), _ptr(workspace), _nbytes(workspace), ev,
+                                            _stream(stream)))
 
 
 def moe_backward_workspace_bytes(cfg):

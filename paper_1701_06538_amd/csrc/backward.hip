@@ -401,7 +401,7 @@ __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
                 if (with_load && i0 + e == j_in) dh -= S_in;     // the threshold of the kept experts
                 if (with_load && i0 + e == j_out) dh -= S_out;   // the threshold of all the others
                 dc[e] = c[e] + dh;
-                dr[e] = fmaf(dh, ev[e], -c[e] * u[e]) * (1.0f - expf(-sp[e]));   // softplus' = 1 - exp(-sp)
+                dr[e] = fmaf(dh, ev[e], -c[e] * u[e]) * -expm1f(-sp[e]);   // softplus' = sigmoid(raw) = 1 - exp(-sp), without the cancellation at small sp
             }
             *reinterpret_cast<float4 *>(p.dclean + t * n + i0) = make_float4(dc[0], dc[1], dc[2], dc[3]);
             *reinterpret_cast<float4 *>(p.draw + t * n + i0) = make_float4(dr[0], dr[1], dr[2], dr[3]);
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(256) void gate_bwd_rows_kernel(GateBwdArgs p) {
         }
         const float ev = e_row ? e_row[i] : 0.f;
         p.dclean[t * n + i] = c + dh;
-        p.draw[t * n + i] = fmaf(dh, ev, -c * u) * (1.0f - expf(-sp));
+        p.draw[t * n + i] = fmaf(dh, ev, -c * u) * -expm1f(-sp);
     }
 }
 
@@ -931,6 +931,19 @@ static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStr
 using namespace moe;
 
 namespace moe {
+// An empty batch still owes the caller fully written outputs: every gradient is zero.
+__global__ __launch_bounds__(256) void zero_f32x4_kernel(float4 *out, size_t count4) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count4; i += (size_t)gridDim.x * 256)
+        out[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+static int launch_zero(float *out, size_t count, hipStream_t s) {   // count: a multiple of 4
+    if (count == 0) return MOE_OK;
+    const size_t c4 = count / 4;
+    const unsigned grid = (unsigned)(c4 < 256 * 2048 ? ceil_div((int64_t)c4, 256) : 2048);
+    hipLaunchKernelGGL(zero_f32x4_kernel, dim3(grid), dim3(256), 0, s, reinterpret_cast<float4 *>(out), c4);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
+}
 static int hier_moments_offsets(const moe_config *cfg, size_t off[4]);
 int backward_moments_offsets(const moe_config *cfg, size_t off[4]) {
     if (check_config(cfg) != MOE_OK) return MOE_EINVAL;
@@ -965,9 +978,9 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     const bool f32_experts = cfg->expert_dtype != MOE_DTYPE_BF16;
     if (!f32_experts && (cfg->d % 256 != 0 || cfg->h % 256 != 0)) return MOE_EUNSUPPORTED;
     if (cfg->d % 4 != 0 || cfg->h % 4 != 0 || cfg->n % 4 != 0) return MOE_EUNSUPPORTED;
-    if (!x || !W_g || !W_noise || !W1 || !W2 || !dy || !topk_idx || !topk_gate || !fwd_workspace ||
-        !dx || !dW_g || !dW_noise || !dW1 || !dW2 || !workspace)
+    if (!W_g || !W_noise || !W1 || !W2 || !fwd_workspace || !dW_g || !dW_noise || !dW1 || !dW2 || !workspace)
         return MOE_EINVAL;
+    if (cfg->T > 0 && (!x || !dy || !topk_idx || !topk_gate || !dx)) return MOE_EINVAL;   // [T, .] tensors
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(W1) || !aligned16(W2) ||
         !aligned16(dW1) || !aligned16(dW2) || !aligned16(dW_g) || !aligned16(dW_noise) ||
         !aligned16(workspace) || !aligned16(fwd_workspace) || (eps && !aligned16(eps)))
@@ -978,7 +991,12 @@ extern "C" int moe_layer_backward(const moe_config *cfg, const float *x, const f
     hipStream_t s = (hipStream_t)stream;
     const int64_t T = cfg->T, A = T * cfg->k;
     const int d = cfg->d, h = cfg->h, n = cfg->n, k = cfg->k;
-    if (T == 0) return MOE_OK;
+    if (T == 0) {
+        MOE_TRY(launch_zero(dW_g, (size_t)d * n, s));
+        MOE_TRY(launch_zero(dW_noise, (size_t)d * n, s));
+        MOE_TRY(launch_zero(dW1, (size_t)n * d * h, s));
+        return launch_zero(dW2, (size_t)n * d * h, s);
+    }
     char *fw = (char *)fwd_workspace;   // read-only here
     char *ws = (char *)workspace;
     const float *cleanb = (const float *)(fw + F.cleanb), *sp = (const float *)(fw + F.sp);
@@ -1088,7 +1106,11 @@ extern "C" int moe_layer_backward_balanced(const moe_config *cfg, const float *x
     hipStream_t s = (hipStream_t)stream;
     const int64_t T = cfg->T, A = T * cfg->k;
     const int d = cfg->d, n = cfg->n;
-    if (T == 0) return MOE_OK;
+    if (T == 0) {
+        MOE_TRY(launch_zero(dW_g, (size_t)d * n, s));
+        MOE_TRY(launch_zero(dW1, (size_t)n * d * cfg->h, s));
+        return launch_zero(dW2, (size_t)n * d * cfg->h, s);
+    }
     const char *fw = (const char *)fwd_workspace;   // read-only here
     char *ws = (char *)workspace;
     const int32_t *pos = (const int32_t *)(fw + V.pos), *offsets = (const int32_t *)(fw + V.offsets);
@@ -1308,9 +1330,10 @@ extern "C" int moe_layer_backward_hier(const moe_config *cfg, const float *x, co
     if (st != MOE_OK) return st;
     moe_workspace_layout F;
     if ((st = moe_get_workspace_layout(cfg, &F)) != MOE_OK) return st;
-    if (!x || !Wg_p || !Wn_p || !Wg_s || !Wn_s || !W1 || !W2 || !dy || !topk_idx || !topk_gate ||
-        !fwd_workspace || !dx || !dWg_p || !dWn_p || !dWg_s || !dWn_s || !dW1 || !dW2 || !workspace)
+    if (!Wg_p || !Wn_p || !Wg_s || !Wn_s || !W1 || !W2 || !fwd_workspace || !dWg_p || !dWn_p || !dWg_s ||
+        !dWn_s || !dW1 || !dW2 || !workspace)
         return MOE_EINVAL;
+    if (cfg->T > 0 && (!x || !dy || !topk_idx || !topk_gate || !dx)) return MOE_EINVAL;   // [T, .] tensors
     const void *ptrs[] = {x, Wg_p, Wn_p, Wg_s, Wn_s, W1, W2, dy, fwd_workspace, dx, dWg_p, dWn_p, dWg_s, dWn_s,
                           dW1, dW2, workspace};
     for (const void *q : ptrs)
@@ -1322,7 +1345,14 @@ extern "C" int moe_layer_backward_hier(const moe_config *cfg, const float *x, co
     hipStream_t s = (hipStream_t)stream;
     const int64_t T = cfg->T, A = T * cfg->k, Ap = T * cfg->k_primary;
     const int d = cfg->d, n = cfg->n, a = cfg->a, b = cfg->b, k_p = cfg->k_primary, k_s = cfg->k_secondary;
-    if (T == 0) return MOE_OK;
+    if (T == 0) {
+        MOE_TRY(launch_zero(dWg_p, (size_t)d * a, s));
+        MOE_TRY(launch_zero(dWn_p, (size_t)d * a, s));
+        MOE_TRY(launch_zero(dWg_s, (size_t)a * d * b, s));
+        MOE_TRY(launch_zero(dWn_s, (size_t)a * d * b, s));
+        MOE_TRY(launch_zero(dW1, (size_t)n * d * cfg->h, s));
+        return launch_zero(dW2, (size_t)n * d * cfg->h, s);
+    }
     char *fw = (char *)fwd_workspace;   // read-only here
     char *ws = (char *)workspace;
 

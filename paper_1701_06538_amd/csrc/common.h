@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/moe.h"
 
 namespace moe {
@@ -23,6 +25,25 @@ inline int hip_fail(hipError_t e) {
 
 // after a kernel launch: catches bad launch configurations without synchronising
 #define MOE_LAUNCH_CHECK() MOE_HIP_TRY(hipGetLastError())
+
+// Raises a kernel's dynamic-LDS limit the first time it is needed.  Entry points may be called
+// from several host threads (distinct streams and buffers), so the "first time" is a
+// std::call_once; the attribute call's status is kept and reported by every caller.
+struct LdsLimitOnce {
+    std::once_flag flag;
+    hipError_t status = hipSuccess;
+    int set(const void *kernel, size_t bytes) {
+        std::call_once(flag, [&] {
+            status = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+        });
+        return status == hipSuccess ? (int)MOE_OK : hip_fail(status);
+    }
+};
+#define MOE_TRY(expr)                    \
+    do {                                 \
+        const int rc__ = (expr);         \
+        if (rc__ != MOE_OK) return rc__; \
+    } while (0)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -129,12 +129,6 @@ struct WeightStream {
     }
 };
 
-#ifdef MOE_FFN_TIMING
-__device__ long long g_ffn_timing[1024 * 8 * 8];
-#define FFN_STAMP(i) do { if (lane == 0 && tile < 1024) g_ffn_timing[(tile * 8 + wave) * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define FFN_STAMP(i) do { } while (0)
-#endif
 
 template <int D, int H>
 __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
@@ -158,7 +152,6 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
     const uint16_t *W1 = (const uint16_t *)p.W1 + (size_t)e * D * H;
     const uint16_t *W2 = (const uint16_t *)p.W2 + (size_t)e * H * D;
 
-    FFN_STAMP(0);
     // gather the tile's token rows (rounded to bf16, nearest even).  Order of issue: row ids,
     // then the first weight fragments (they do not depend on x), then the token rows, so the
     // two dependent round trips of the gather overlap the weights' first trip.
@@ -191,7 +184,6 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
         }
     }
     __syncthreads();
-    FFN_STAMP(1);
     if (p.xs_out) {   // training: keep the rounded input rows for the backward pass (the tile is only read from here on)
         constexpr int U4 = D / 8;
         for (int i = tid; i < TM * U4; i += 512) {
@@ -213,7 +205,6 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[rt][j] = v4f{0.f, 0.f, 0.f, 0.f};
         s1.run(acc, lds, XS, c, g);
-        FFN_STAMP(2);
         // second matrix starts streaming during the hand-over below
         s2.start(W2 + (size_t)(H / 2) * kh * D, col2, g);
         __syncthreads();  // every wave is done reading the x tile; the hidden tile overwrites it
@@ -230,7 +221,6 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
                 *reinterpret_cast<uint4 *>(lds + (size_t)row * HS + col1) = w;
             }
         __syncthreads();
-        FFN_STAMP(3);
     }
     if (p.hid_out) {   // training: keep the hidden activations for the backward pass
         constexpr int U4 = H / 8;   // 16-byte pieces per row
@@ -251,7 +241,6 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) acc[rt][j] = v4f{0.f, 0.f, 0.f, 0.f};
         s2.run(acc, lds + (H / 2) * kh, HS, c, g);
-        FFN_STAMP(4);
         __syncthreads();  // the hidden tile is dead; its LDS now carries the partial sums
         float *part = reinterpret_cast<float *>(lds);
         if (kh == 1) {
@@ -267,7 +256,6 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
                 }
         }
         __syncthreads();
-        FFN_STAMP(5);
         if (kh == 0) {
 #pragma unroll
             for (int rt = 0; rt < 4; ++rt)
@@ -287,14 +275,8 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
                                     acc[rt][7][r] + p1.w);
                 }
         }
-        FFN_STAMP(6);
     }
 }
-#ifdef MOE_FFN_TIMING
-extern "C" int moe_debug_read_ffn_timing(long long *host_out) {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_ffn_timing), sizeof(long long) * 1024 * 8 * 8);
-}
-#endif
 
 // ---------------------------------------------------------------------------------------
 // Four-wave variant: one wave per SIMD with the whole 512-register budget.  Each wave owns 256
@@ -616,23 +598,14 @@ int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles
     if (cfg->expert_dtype == MOE_DTYPE_BF16) {
         if (cfg->d != 512 || cfg->h != 1024) return launch_expert_ffn_general(cfg, a, max_tiles, st);
         constexpr size_t lds = (size_t)kFfnTM * (1024 + 8) * sizeof(uint16_t);
-        static bool attr_set = false;
-        if (!attr_set) {
-            MOE_HIP_TRY(hipFuncSetAttribute((const void *)ffn_bf16_kernel<512, 1024>,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            attr_set = true;
-        }
+        static LdsLimitOnce lds8, lds4;
         const unsigned grid = (unsigned)(ceil_div(max_tiles, 8) * 8);
         // One tile per expert (<= 64 rows on average): every tile streams its weights from HBM, and
         // the four-wave kernel's deeper load pipeline pays.  Several tiles per expert: the tiles
         // share weights through L2 and the eight-wave kernel is marginally faster.
         const bool four_waves = (int64_t)cfg->T * cfg->k <= (int64_t)cfg->n * kFfnTM;
-        static bool attr4_set = false;
-        if (four_waves && !attr4_set) {
-            MOE_HIP_TRY(hipFuncSetAttribute((const void *)ffn_bf16_w4_kernel<512, 1024>,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            attr4_set = true;
-        }
+        if (four_waves) MOE_TRY(lds4.set((const void *)ffn_bf16_w4_kernel<512, 1024>, lds));
+        else MOE_TRY(lds8.set((const void *)ffn_bf16_kernel<512, 1024>, lds));
         if (four_waves) hipLaunchKernelGGL((ffn_bf16_w4_kernel<512, 1024>), dim3(grid), dim3(256), lds, st, a);
         else hipLaunchKernelGGL((ffn_bf16_kernel<512, 1024>), dim3(grid), dim3(512), lds, st, a);
         MOE_LAUNCH_CHECK();

@@ -81,12 +81,6 @@ __device__ __forceinline__ float softplus_spec(float zf) {
 
 constexpr int BM = kGateBM;  // 128 rows: 4 waves x 32
 
-#if defined(MOE_GATE_TIMING) || defined(MOE_TOPK_TIMING)
-__device__ long long g_gate_timing[4096 * 40];
-#define GATE_STAMP(i) do { const unsigned b_ = blockIdx.y * gridDim.x + blockIdx.x; if (threadIdx.x == 0 && b_ < 4096) g_gate_timing[b_ * 40 + (i)] = wall_clock64(); } while (0)
-#else
-#define GATE_STAMP(i) do { } while (0)
-#endif
 
 // RN: the block tile is BM x (32*RN) columns of ONE of the two matrices.  VEC: n is a multiple of
 // four, so weight rows can be read 16 bytes at a time.
@@ -206,21 +200,17 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(LogitsArgs p) {
 #pragma unroll
             for (int c = 0; c < RN; ++c) b_grp[slot][u][c] = b_col[2 * (kk4 + u) * BN + 32 * c];
     };
-    GATE_STAMP(0);
     load_global(0);
     store_lds(0);
     load_global(min(KC, d - KC));
     __syncthreads();
     read_group(0, 0, 0);
-    GATE_STAMP(1);
     for (int k0 = 0; k0 < d; k0 += KC) {
         const int buf = (k0 / KC) & 1;
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
             if (g == NG - 1) {
-                GATE_STAMP(2 + 2 * (k0 / KC));
                 __syncthreads();
-                GATE_STAMP(3 + 2 * (k0 / KC));
                 read_group((g + 1) & 1, buf ^ 1, 0);   // after the last slab: unused
             } else {
                 read_group((g + 1) & 1, buf, 4 * (g + 1));
@@ -264,7 +254,6 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(LogitsArgs p) {
                 Ct[i * CS + 32 * c + l32] = acc[c0 + c][r];
             }
         __syncthreads();
-        GATE_STAMP(34);
         const int col = col0 + 32 * c0 + 4 * cq;
         float bias[4] = {0.f, 0.f, 0.f, 0.f};
         if (add_bias) {
@@ -306,13 +295,7 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(LogitsArgs p) {
             }
         }
     }
-    GATE_STAMP(36);
 }
-#if defined(MOE_GATE_TIMING) || defined(MOE_TOPK_TIMING)
-extern "C" int moe_debug_read_gate_timing(long long *host_out) {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_gate_timing), sizeof(long long) * 4096 * 40);
-}
-#endif
 
 // ---------------------------------------------------------------------------------------
 // top-k, softmax, P(x,i) and partial sums
@@ -397,13 +380,6 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
         re = min(rb + RPB, p.R);
     }
     const int kp1 = (k < n) ? k + 1 : k;
-#ifdef MOE_TOPK_TIMING
-    int stamp_i = 0;
-#define TOPK_STAMP() do { if ((threadIdx.x & 63) == 0 && blockIdx.x < 1024 && stamp_i < 10) g_gate_timing[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 10 + stamp_i++] = wall_clock64(); } while (0)
-#else
-#define TOPK_STAMP() do { } while (0)
-#endif
-    TOPK_STAMP();
     // Load: every expert of every row contributes, so the sums stay in registers.  Importance:
     // only the k kept experts of a row contribute, so k lanes add their gate values to the
     // wave's own LDS array (distinct addresses inside one instruction, rows in order: the sum
@@ -442,10 +418,6 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
 #pragma unroll
             for (int q = 0; q < NCH; ++q) hv[q] = cv[q];
         }
-#ifdef MOE_TOPK_TIMING
-        if (hv[0] == 12345.678f) stamp_i = 100;   // forces the loads to have completed
-#endif
-        TOPK_STAMP();
 
         // per-lane sorted candidate list: branch-free compare-exchange insertion
         uint64_t lk[L];
@@ -542,9 +514,7 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
 #pragma unroll
             for (int q = 0; q < NCH; ++q) acc_load[q] += (lane + 64 * q) < n ? 1.0f : 0.f;
         }
-        TOPK_STAMP();
     }
-    TOPK_STAMP();
     // the four waves' sums, added in wave order
     float *load_s = lds_acc + 4 * n;
     for (int w = 0; w < 4; ++w) {
@@ -557,13 +527,11 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
         }
         __syncthreads();
     }
-    TOPK_STAMP();
     float *out = p.partials + (size_t)blockIdx.x * 2 * n;
     for (int i = tid; i < n; i += 256) {
         out[i] = (((0.f + lds_acc[i]) + lds_acc[n + i]) + lds_acc[2 * n + i]) + lds_acc[3 * n + i];
         out[n + i] = load_s[i];
     }
-    TOPK_STAMP();
 }
 
 // Long rows (n > 1024): the four wavefronts of a workgroup share one row, a quarter each, so a lane

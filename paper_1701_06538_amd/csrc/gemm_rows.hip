@@ -29,15 +29,6 @@ constexpr int RKC = GG_RKC;        // slab depth
 constexpr int RLD = RKC + 8;       // bf16 elements per LDS row (+16 bytes: 16-byte reads of 8 rows hit 32 banks)
 
 
-#ifdef MOE_GG_TIMING
-__device__ long long g_gg_timing[8192 * 4];
-#define GG_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_gg_timing[blockIdx.x * 4 + (i)] = wall_clock64(); } while (0)
-extern "C" int moe_debug_read_gg_timing(long long *host_out) {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_gg_timing), sizeof(long long) * 8192 * 4);
-}
-#else
-#define GG_STAMP(i) do { } while (0)
-#endif
 
 // NW wavefronts: four own 128 x 128 each (256 accumulators, one wave per SIMD), eight own 128 x 64
 // (two waves per SIMD: one's LDS reads and stores run under the other's matrix work).
@@ -112,13 +103,11 @@ __global__ __launch_bounds__(64 * NW, 1) void gg_rows256_kernel(GGRows p, int co
     };
 
     constexpr int NS = RKC / 16;   // k-steps per slab
-    GG_STAMP(0);
     load_global(0);
     store_lds(0);
     load_global(min(RKC, K - RKC));
     __syncthreads();
     read_ops(0, 0, 0);
-    GG_STAMP(1);
     for (int k0 = 0; k0 < K; k0 += RKC) {
         const int buf = (k0 / RKC) & 1;
 #pragma unroll
@@ -151,7 +140,6 @@ __global__ __launch_bounds__(64 * NW, 1) void gg_rows256_kernel(GGRows p, int co
     // their accumulators into a [128][256] fp32 image (the operand slabs are dead), then every wave
     // stores whole rows -- 1 KB (fp32) or 512 B (bf16) contiguous per row instead of the 32-byte
     // pieces a lane's own columns would make; the relu mask is read the same way.
-    GG_STAMP(2);
     constexpr int CS = RT + 4;                       // fp32 words per staged row (rows stay 16-byte aligned)
     static_assert(128 * CS * 4 <= 4 * SLAB, "the staged half tile fits the operand buffers");
     float *Ct = reinterpret_cast<float *>(smem);
@@ -208,7 +196,6 @@ __global__ __launch_bounds__(64 * NW, 1) void gg_rows256_kernel(GGRows p, int co
             }
         }
     }
-    GG_STAMP(3);
 }
 
 // p's tile table must hold 256-row tiles; max_tiles bounds *p.num_tiles.

@@ -19,15 +19,6 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
-#ifdef MOE_WGRAD_TIMING
-__device__ long long g_wgrad_timing[8192 * 4];
-#define WG_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_wgrad_timing[blockIdx.x * 4 + (i)] = (i) == 3 ? (long long)nslab : wall_clock64(); } while (0)
-extern "C" int moe_debug_read_wgrad_timing(long long *host_out) {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_wgrad_timing), sizeof(long long) * 8192 * 4);
-}
-#else
-#define WG_STAMP(i) do { } while (0)
-#endif
 
 constexpr int WG_TILE = 256;    // rows and columns of C per workgroup
 constexpr int WG_K = 32;        // contracted rows per slab
@@ -118,7 +109,6 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
         }
     };
 
-    WG_STAMP(0);
     if (nslab > 0) {
         fetch(0);
         put(0, stage_mem);
@@ -142,8 +132,6 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
         }
     }
 
-    WG_STAMP(1);
-    WG_STAMP(3);
     // The block leaves through LDS, 128 rows at a time (the operand stages are dead): the four
     // wavefronts that own the half write their accumulators into a [128][256] image, then every
     // wavefront stores whole 1 KB rows instead of the 64-byte pieces its own lanes would make.
@@ -206,7 +194,6 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
             p.colpart[((size_t)e * tiles_m + tm) * p.N + n0 + cc] = rcol[cc] + rcol[WG_TILE + cc];
         }
     }
-    WG_STAMP(2);
 }
 
 // A workgroup ranks 64 experts (one per lane); its four waves each compare them against a quarter
@@ -251,11 +238,8 @@ int launch_gg_wgrad(const GGWgrad &p, int n, hipStream_t st) {
     if (n <= 0) return MOE_OK;
     const unsigned grid = (unsigned)((p.M / WG_TILE) * (p.N / WG_TILE) * n);
     constexpr int lds = WT_LDS;
-    static bool attr_set = false;
-    if (!attr_set) {
-        MOE_HIP_TRY(hipFuncSetAttribute((const void *)gg_wgrad_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
-        attr_set = true;
-    }
+    static LdsLimitOnce lds_once;
+    MOE_TRY(lds_once.set((const void *)gg_wgrad_kernel, lds));
     hipLaunchKernelGGL(gg_wgrad_kernel, dim3(grid), dim3(512), lds, st, p);
     MOE_LAUNCH_CHECK();
     return MOE_OK;

@@ -325,12 +325,13 @@ extern "C" int moe_aux_losses_hier(const moe_config *cfg, const float *topk_gate
     return launch_hier_losses(ha, cfg->w_importance, cfg->w_load, losses, s);
 }
 
-extern "C" int moe_layer_forward_hier(const moe_config *cfg, const float *x, const float *Wg_p,
-                                      const float *Wn_p, const float *eps_p, const float *Wg_s,
-                                      const float *Wn_s, const float *eps_s, const void *W1,
-                                      const void *W2, float *y, int32_t *topk_idx, float *topk_gate,
-                                      float *importance, float *load, float *losses, void *workspace,
-                                      size_t workspace_bytes, void *stream) {
+extern "C" int moe_layer_forward_hier_profiled(const moe_config *cfg, const float *x, const float *Wg_p,
+                                               const float *Wn_p, const float *eps_p, const float *Wg_s,
+                                               const float *Wn_s, const float *eps_s, const void *W1,
+                                               const void *W2, float *y, int32_t *topk_idx,
+                                               float *topk_gate, float *importance, float *load,
+                                               float *losses, void *workspace, size_t workspace_bytes,
+                                               void *const *stage_events, void *stream) {
     moe_workspace_layout L;
     int st = workspace_layout(cfg, &L);
     if (st != MOE_OK) return st;
@@ -339,23 +340,38 @@ extern "C" int moe_layer_forward_hier(const moe_config *cfg, const float *x, con
     if (!aligned16(y) || !aligned16(W1) || !aligned16(W2)) return MOE_EINVAL;
     if (workspace_bytes < L.total) return MOE_EWORKSPACE;
     char *ws = (char *)workspace;
-    st = moe_gate_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, topk_idx, topk_gate, workspace,
-                       workspace_bytes, stream);
-    if (st != MOE_OK) return st;
+    void *const *ev = stage_events;
     int32_t *counts = (int32_t *)(ws + L.counts), *offsets = (int32_t *)(ws + L.offsets);
     int32_t *perm = (int32_t *)(ws + L.perm), *inv_perm = (int32_t *)(ws + L.inv_perm);
     int32_t *tile_expert = (int32_t *)(ws + L.tile_expert), *tile_row0 = (int32_t *)(ws + L.tile_row0);
     int32_t *num_tiles = (int32_t *)(ws + L.num_tiles);
     float *out_sorted = (float *)(ws + L.out_sorted);
-    st = moe_route(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0, num_tiles,
-                   ws + L.route_ws, stream);
-    if (st != MOE_OK) return st;
-    st = expert_ffn_with_hidden(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2, out_sorted,
-                                ws + L.ffn_ws, L.hidden == (size_t)-1 ? nullptr : (uint16_t *)(ws + L.hidden),
-                                (hipStream_t)stream);
-    if (st != MOE_OK) return st;
-    st = moe_combine(cfg, out_sorted, topk_gate, inv_perm, y, stream);
-    if (st != MOE_OK) return st;
-    return moe_aux_losses_hier(cfg, topk_gate, perm, offsets, workspace, workspace_bytes, importance,
-                               load, losses, stream);
+#define MOE_STAGE(i, call)                                        \
+    if ((st = record(ev, 2 * (i), stream)) != MOE_OK) return st;  \
+    if ((st = (call)) != MOE_OK) return st;                       \
+    if ((st = record(ev, 2 * (i) + 1, stream)) != MOE_OK) return st;
+    MOE_STAGE(0, moe_gate_hier(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, topk_idx, topk_gate, workspace,
+                               workspace_bytes, stream))
+    MOE_STAGE(1, moe_route(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0, num_tiles,
+                           ws + L.route_ws, stream))
+    MOE_STAGE(2, expert_ffn_with_hidden(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2,
+                                        out_sorted, ws + L.ffn_ws,
+                                        L.hidden == (size_t)-1 ? nullptr : (uint16_t *)(ws + L.hidden),
+                                        (hipStream_t)stream))
+    MOE_STAGE(3, moe_combine(cfg, out_sorted, topk_gate, inv_perm, y, stream))
+    MOE_STAGE(4, moe_aux_losses_hier(cfg, topk_gate, perm, offsets, workspace, workspace_bytes, importance,
+                                     load, losses, stream))
+#undef MOE_STAGE
+    return MOE_OK;
+}
+
+extern "C" int moe_layer_forward_hier(const moe_config *cfg, const float *x, const float *Wg_p,
+                                      const float *Wn_p, const float *eps_p, const float *Wg_s,
+                                      const float *Wn_s, const float *eps_s, const void *W1,
+                                      const void *W2, float *y, int32_t *topk_idx, float *topk_gate,
+                                      float *importance, float *load, float *losses, void *workspace,
+                                      size_t workspace_bytes, void *stream) {
+    return moe_layer_forward_hier_profiled(cfg, x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, W1, W2, y, topk_idx,
+                                           topk_gate, importance, load, losses, workspace, workspace_bytes,
+                                           nullptr, stream);
 }

@@ -287,12 +287,8 @@ extern "C" int moe_expert_adam_step(const moe_config *cfg, const moe_adam_params
         const size_t mlds = (size_t)4 * C[w] * sizeof(double);
         if (C[w] <= 1024) hipLaunchKernelGGL(adam_moments_kernel<4>, mgrid, dim3(256), mlds, s, am);
         else if (C[w] <= 2048) {
-            static bool attr_set = false;
-            if (!attr_set) {
-                MOE_HIP_TRY(hipFuncSetAttribute((const void *)adam_moments_kernel<8>,
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 2048 * 8));
-                attr_set = true;
-            }
+            static LdsLimitOnce lds_once;
+            MOE_TRY(lds_once.set((const void *)adam_moments_kernel<8>, (size_t)4 * 2048 * 8));
             hipLaunchKernelGGL(adam_moments_kernel<8>, mgrid, dim3(256), mlds, s, am);
         } else hipLaunchKernelGGL(adam_moments_wide_kernel, mgrid, dim3(256), 0, s, am);
         MOE_LAUNCH_CHECK();

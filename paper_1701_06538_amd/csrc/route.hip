@@ -251,14 +251,9 @@ extern "C" size_t moe_route_workspace_bytes(const moe_config *cfg) {
     return route_ws_bytes((int64_t)cfg->T * cfg->k, cfg->n);
 }
 
-extern "C" int moe_route(const moe_config *cfg, const int32_t *topk_idx, int32_t *counts,
-                         int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *tile_expert,
-                         int32_t *tile_row0, int32_t *num_tiles, void *workspace, void *stream) {
-    int st = check_config(cfg);
-    if (st != MOE_OK) return st;
-    if (!topk_idx || !counts || !offsets || !perm || !inv_perm || !tile_expert || !tile_row0 ||
-        !num_tiles || !workspace)
-        return MOE_EINVAL;
+static int route_with_scratch(const moe_config *cfg, const int32_t *topk_idx, int32_t *counts,
+                              int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *tile_expert,
+                              int32_t *tile_row0, int32_t *num_tiles, void *workspace, void *stream) {
     RouteArgs a{};
     a.idx = topk_idx;
     a.A = (int64_t)cfg->T * cfg->k;
@@ -269,4 +264,16 @@ extern "C" int moe_route(const moe_config *cfg, const int32_t *topk_idx, int32_t
     a.tile_offsets = nullptr;
     a.hist = (int32_t *)workspace;
     return launch_route(a, (hipStream_t)stream);
+}
+
+extern "C" int moe_route(const moe_config *cfg, const int32_t *topk_idx, int32_t *counts,
+                         int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *tile_expert,
+                         int32_t *tile_row0, int32_t *num_tiles, void *workspace, void *stream) {
+    int st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (!topk_idx || !counts || !offsets || !perm || !inv_perm || !tile_expert || !tile_row0 ||
+        !num_tiles || !workspace)
+        return MOE_EINVAL;
+    return route_with_scratch(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0,
+                              num_tiles, workspace, stream);
 }

@@ -1,104 +1,12 @@
-"""Helpers for the GPU parity tests: run the HIP path through the C ABI binding and the oracle
-on the same seeded inputs.  Test infrastructure: the library never imports this; bench.py borrows
-the GPU-side helpers (buffers, device-side weight generation), which do not touch the oracle."""
+"""Helpers for the GPU parity tests: the oracle side of a comparison on the same seeded inputs
+the HIP path gets (the GPU-side buffer plumbing lives in paper_1701_06538_amd/runner.py, the device
+input generation in moe_workloads/device.py; both are re-exported here for the tests)."""
 import numpy as np
 import torch
 
 import moe_workloads as W
-
-
-def dev(a, dtype=None):
-    t = torch.from_numpy(np.ascontiguousarray(a))
-    if dtype is not None:
-        t = t.to(dtype)
-    return t.cuda()
-
-
-class FlatRun:
-    """One forward pass of the flat layer on the GPU, stage by stage or fused."""
-
-    def __init__(self, api, shape, x, W_g, W_noise, eps, bias, W1, W2, flags=0):
-        self.api = api
-        self.shape = shape
-        self.cfg = api.make_config(shape, flags=flags)
-        c = self.cfg
-        self.x, self.W_g, self.W_noise = dev(x), dev(W_g), dev(W_noise)
-        self.eps = None if eps is None else dev(eps)
-        self.bias = None if bias is None else dev(bias)
-        self.W1, self.W2 = W1, W2                     # device tensors [n,d,h], [n,h,d]
-        T, n, k, d = c.T, c.n, c.k, c.d
-        A = T * k
-        i32 = dict(dtype=torch.int32, device="cuda")
-        f32 = dict(dtype=torch.float32, device="cuda")
-        self.topk_idx = torch.full((T, k), -7, **i32)
-        self.topk_gate = torch.full((T, k), float("nan"), **f32)
-        self.cleanb = torch.full((T, n), float("nan"), **f32)
-        self.sp = torch.full((T, n), float("nan"), **f32)
-        self.next_idx = torch.full((T,), -7, **i32)
-        self.partials = torch.full((max(1, api.moe_gate_partial_rows(c)), 2, n), float("nan"), **f32)
-        self.counts = torch.full((n,), -7, **i32)
-        self.offsets = torch.full((n + 1,), -7, **i32)
-        self.perm = torch.full((max(A, 1),), -7, **i32)
-        self.inv_perm = torch.full((max(A, 1),), -7, **i32)
-        mt = api.moe_max_tiles(c) + 8
-        self.tile_expert = torch.full((mt,), -7, **i32)
-        self.tile_row0 = torch.full((mt,), -7, **i32)
-        self.num_tiles = torch.full((4,), -7, **i32)
-        self.route_ws = torch.empty(max(16, api.moe_route_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
-        self.out_sorted = torch.full((max(A, 1), d), float("nan"), **f32)
-        self.ffn_ws = torch.empty(max(16, api.moe_ffn_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
-        self.aux_ws = torch.empty(max(16, api.moe_aux_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
-        self.y = torch.full((max(T, 1), d), float("nan"), **f32)
-        self.importance = torch.full((n,), float("nan"), **f32)
-        self.load = torch.full((n,), float("nan"), **f32)
-        self.losses = torch.full((4,), float("nan"), **f32)
-
-    def gate(self):
-        self.api.moe_gate(self.cfg, self.x, self.W_g, self.W_noise, self.bias, self.eps, self.topk_idx,
-                          self.topk_gate, self.cleanb, self.sp, self.next_idx, self.partials)
-
-    def route(self, idx=None):
-        self.api.moe_route(self.cfg, self.topk_idx if idx is None else idx, self.counts, self.offsets,
-                           self.perm, self.inv_perm, self.tile_expert, self.tile_row0, self.num_tiles,
-                           self.route_ws)
-
-    def ffn(self):
-        self.api.moe_expert_ffn(self.cfg, self.x, self.perm, self.offsets, self.tile_expert, self.tile_row0,
-                                self.num_tiles, self.W1, self.W2, self.out_sorted, self.ffn_ws)
-
-    def combine(self):
-        self.api.moe_combine(self.cfg, self.out_sorted, self.topk_gate, self.inv_perm, self.y)
-
-    def losses_(self):
-        self.api.moe_aux_losses(self.cfg, self.partials, self.importance, self.load, self.losses, self.aux_ws)
-
-    def stages(self):
-        self.gate(); self.route(); self.ffn(); self.combine(); self.losses_()
-        torch.cuda.synchronize()
-
-    def fused(self):
-        ws = torch.empty(self.api.moe_workspace_bytes(self.cfg), dtype=torch.uint8, device="cuda")
-        self.workspace = ws
-        self.api.moe_layer_forward(self.cfg, self.x, self.W_g, self.W_noise, self.bias, self.eps, self.W1,
-                                   self.W2, self.y, self.topk_idx, self.topk_gate, self.importance,
-                                   self.load, self.losses, ws)
-        torch.cuda.synchronize()
-
-
-def flat_inputs(shape, with_bias=False, gate_std=0.02):
-    x, W_g, W_noise, eps = W.gate_inputs(shape, gate_std)
-    bias = W.zipf_gate_bias(shape) if with_bias else None
-    return x, W_g, W_noise, eps, bias
-
-
-def device_weights(shape, chunk=64):
-    """Expert weights generated on the GPU in the paper's plain layout."""
-    outs = []
-    for which in (0, 1):
-        parts = [W.expert_weights_all(shape, which, range(e0, min(shape.n, e0 + chunk)), device="cuda")
-                 for e0 in range(0, shape.n, chunk)]
-        outs.append(torch.cat(parts, dim=0).contiguous())
-    return outs
+from moe_workloads.device import device_weights, flat_inputs  # noqa: F401
+from paper_1701_06538_amd.runner import BalancedRun, FlatRun, HierRun, dev  # noqa: F401
 
 
 def oracle_weight_fn(shape):
@@ -109,8 +17,37 @@ def oracle_weight_fn(shape):
     return fn
 
 
+def device_weight_fn(shape, W1, W2, block=1, progress=None):
+    """weight_fn for the oracle that reads the expert matrices from the device tensors the input
+    generator filled (moe_workloads.device.device_weights: the same integer hash as
+    moe_workloads.expert_weights on the CPU, evaluated by torch on the GPU -- inputs, not results of
+    the HIP path), widened to binary64 on the device and copied `block` experts at a time.
+    Regenerating a matrix on the host costs ~30 ms; a full-size check visits up to 16384 experts.
+    check_device_weights() ties the two generators together bit for bit."""
+    cache = {"b0": -1}
+
+    def fn(e):
+        e = int(e)
+        b0 = e // block * block
+        if cache["b0"] != b0:
+            cache["b0"] = b0
+            cache["w1"] = W1[b0:b0 + block].to(torch.float64).cpu().numpy()
+            cache["w2"] = W2[b0:b0 + block].to(torch.float64).cpu().numpy()
+            if progress is not None:
+                progress(b0)
+        return cache["w1"][e - b0], cache["w2"][e - b0]
+    return fn
+
+
+def check_device_weights(shape, W1, W2, experts):
+    """The device tensors hold exactly what the host generator gives for these experts."""
+    for e in experts:
+        assert torch.equal(W1[e].cpu(), W.expert_weights(shape, 0, int(e))), e
+        assert torch.equal(W2[e].cpu(), W.expert_weights(shape, 1, int(e))), e
+
+
 def oracle_flat(shape, x, W_g, W_noise, eps, bias):
-    from oracle import moe_oracle as O   # here, not at the top: bench.py's timed path uses this module's GPU helpers only
+    from oracle import moe_oracle as O
     lg = O.noisy_logits_f32(x, W_g, W_noise, eps, bias)
     return O.gate_and_losses(lg, shape.k, shape.w_importance, shape.w_load)
 
@@ -126,83 +63,47 @@ def rel_errors(got, ref):
     return row, mx
 
 
-class BalancedRun:
-    """One forward pass with strictly balanced gating (Appendix F) on the GPU."""
-
-    def __init__(self, api, shape, x, W_g, bias, thresholds, W1=None, W2=None, flags=0):
-        self.api = api
-        self.cfg = c = api.make_config(shape, flags=flags)
-        T, n, d = c.T, c.n, c.d
-        self.m = api.moe_balanced_rows_per_expert(c)
-        assert self.m == T * c.k // n
-        self.x, self.W_g = dev(x), dev(W_g)
-        self.bias = None if bias is None else dev(bias)
-        self.thr = None if thresholds is None else dev(thresholds)
-        self.W1, self.W2 = W1, W2
-        f32 = dict(dtype=torch.float32, device="cuda")
-        self.gsigma = torch.full((max(T, 1), n), float("nan"), **f32)
-        self.tokens = torch.full((n, max(self.m, 1)), -7, dtype=torch.int32, device="cuda")
-        self.kw = (n + 31) // 32
-        self.kept = torch.full((max(T, 1), self.kw), 0x5a5a5a5a, dtype=torch.int32, device="cuda")
-        self.denom = torch.full((max(T, 1),), float("nan"), **f32)
-        self.loss = torch.full((4,), float("nan"), **f32)
-        self.y = torch.full((max(T, 1), d), float("nan"), **f32)
-        self.ws = torch.empty(max(256, api.moe_balanced_workspace_bytes(c)), dtype=torch.uint8, device="cuda")
-
-    def gate(self):
-        self.api.moe_gate_balanced(self.cfg, self.x, self.W_g, self.bias, self.thr, self.gsigma, self.tokens,
-                                   self.kept, self.denom, self.loss, self.ws)
-        torch.cuda.synchronize()
-
-    def layer(self):
-        self.api.moe_layer_forward_balanced(self.cfg, self.x, self.W_g, self.bias, self.thr, self.W1, self.W2,
-                                            self.y, self.gsigma, self.tokens, self.kept, self.denom,
-                                            self.loss, self.ws)
-        torch.cuda.synchronize()
-
-    def kept_mask(self):
-        words = self.kept.cpu().numpy().view(np.uint32)
-        T, n = self.cfg.T, self.cfg.n
-        bits = (words[:, :, None] >> np.arange(32, dtype=np.uint32)[None, None, :]) & 1
-        return bits.reshape(words.shape[0], -1)[:T, :n].astype(bool)
+def fro_rel(got, ref):
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-class HierRun:
-    """One forward pass of the hierarchical layer on the GPU through the C ABI."""
+def check_dx_rows(got_dx, ref_dx, x_experts, dy, idx, gates, weight_fn, gpu_hidden_row, tol, tau=2e-5):
+    """Row-by-row comparison of dx at sizes where single hidden units sit on the ReLU kink.
 
-    def __init__(self, api, shape, inputs, W1, W2, flags=0):
-        self.api, self.shape = api, shape
-        self.cfg = api.make_config(shape, flags=flags)
-        x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s = inputs
-        self.x = dev(x)
-        self.Wg_p, self.Wn_p, self.eps_p = dev(Wg_p), dev(Wn_p), dev(eps_p)
-        self.Wg_s, self.Wn_s, self.eps_s = dev(Wg_s), dev(Wn_s), dev(eps_s)
-        self.W1, self.W2 = W1, W2
-        T, n, k, d = shape.T, shape.n, shape.k, shape.d
-        i32 = dict(dtype=torch.int32, device="cuda")
-        f32 = dict(dtype=torch.float32, device="cuda")
-        self.topk_idx = torch.full((T, k), -7, **i32)
-        self.topk_gate = torch.full((T, k), float("nan"), **f32)
-        self.y = torch.full((T, d), float("nan"), **f32)
-        self.importance = torch.full((n,), float("nan"), **f32)
-        self.load = torch.full((n,), float("nan"), **f32)
-        self.losses = torch.full((4,), float("nan"), **f32)
-        self.workspace = torch.empty(api.moe_workspace_bytes(self.cfg), dtype=torch.uint8, device="cuda")
-        self.layout = api.moe_get_workspace_layout(self.cfg)
-
-    def ws_view(self, field, count, dtype):
-        off = getattr(self.layout, field)
-        nbytes = count * torch.tensor([], dtype=dtype).element_size()
-        return self.workspace[off:off + nbytes].view(dtype)
-
-    def gate(self):
-        self.api.moe_gate_hier(self.cfg, self.x, self.Wg_p, self.Wn_p, self.eps_p, self.Wg_s, self.Wn_s,
-                               self.eps_s, self.topk_idx, self.topk_gate, self.workspace)
-        torch.cuda.synchronize()
-
-    def forward(self):
-        self.api.moe_layer_forward_hier(self.cfg, self.x, self.Wg_p, self.Wn_p, self.eps_p, self.Wg_s,
-                                        self.Wn_s, self.eps_s, self.W1, self.W2, self.y, self.topk_idx,
-                                        self.topk_gate, self.importance, self.load, self.losses,
-                                        self.workspace)
-        torch.cuda.synchronize()
+    Every row must be within `tol` (relative L2) of the oracle's.  A row that is not is accepted only
+    if it is explained: some hidden unit of one of its experts has a pre-activation of magnitude
+    <= tau in the oracle's binary64 (the kernel's fp32 accumulation can land on the other side of
+    zero, and relu' is a binary decision: either side is a correct evaluation), and the oracle's
+    row re-evaluated with the kernel's decision AT THOSE UNITS ONLY (O.expert_input_grad with an
+    explicit mask) is within `tol`.  gpu_hidden_row(t, s) -> the kernel's hidden activations [h] of
+    assignment (t, s).  Returns (Frobenius relative error, number of explained rows, largest |z| of
+    a unit whose decision differed)."""
+    from oracle import moe_oracle as O
+    got = np.asarray(got_dx, np.float64)
+    ref = np.asarray(ref_dx, np.float64)
+    dy = np.asarray(dy, np.float64)
+    xe = np.asarray(x_experts, np.float64)
+    rel = np.linalg.norm(got - ref, axis=1) / np.maximum(np.linalg.norm(ref, axis=1), 1e-300)
+    bad = np.nonzero(rel > tol)[0]
+    worst_z = 0.0
+    for t in bad:
+        alt = ref[t].copy()
+        flips = 0
+        for s in range(idx.shape[1]):
+            W1, W2 = weight_fn(int(idx[t, s]))
+            z = xe[t] @ np.asarray(W1, np.float64)
+            ambiguous = np.abs(z) <= tau
+            mask_alt = np.where(ambiguous, np.asarray(gpu_hidden_row(int(t), s)) > 0, z > 0)
+            differ = mask_alt != (z > 0)
+            if differ.any():
+                flips += int(differ.sum())
+                worst_z = max(worst_z, float(np.abs(z[differ]).max()))
+                dout = (gates[t, s] * dy[t])[None, :]
+                alt += (O.expert_input_grad(xe[t:t + 1], dout, W1, W2, relu_mask=mask_alt[None, :])
+                        - O.expert_input_grad(xe[t:t + 1], dout, W1, W2))[0]
+        rel_alt = float(np.linalg.norm(got[t] - alt) / max(np.linalg.norm(alt), 1e-300))
+        assert flips > 0, "dx row %d is off by %.2e and no hidden unit of its experts sits on the ReLU kink" % (t, rel[t])
+        assert rel_alt <= tol, "dx row %d: %.2e even with the kernel's decisions at %d kink units" % (t, rel_alt, flips)
+    return fro_rel(got, ref), int(bad.size), worst_z

@@ -9,6 +9,7 @@ import torch
 
 import moe_workloads as W
 from oracle import moe_oracle as O
+from tests import balanced_checks as BC
 from tests import gpu_harness as G
 
 pytestmark = pytest.mark.gpu
@@ -63,9 +64,9 @@ def test_balanced_backward_parity(api, name):
     thr = (kth * rng.uniform(0.7, 1.3, size=n)).astype(np.float32)
     run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2, flags=flags)
     run.layer()
-    mask, _ = O.batchwise_mask(X, m)
-    assert np.array_equal(run.kept_mask(), mask)
-    assert np.array_equal(run.gsigma.cpu().numpy()[:T], X)
+    mask = run.kept_mask()          # validated: Eq.(18) on the kernel's G_sigma, the oracle's where decided
+    BC.check_gsigma(run.gsigma.cpu().numpy()[:T], X)
+    BC.check_batchwise_mask(run.gsigma.cpu().numpy()[:T], mask, run.tokens.cpu().numpy(), X, m)
 
     dy = W.upstream_grad(shape)
     f32 = dict(dtype=torch.float32, device="cuda")
@@ -109,7 +110,9 @@ def test_balanced_backward_gate_part_is_fp32_accurate(api):
     thr = (-np.sort(-X.astype(np.float64), axis=0)[m - 1] * 0.9).astype(np.float32)
     run = G.BalancedRun(api, shape, x, W_g, bias, thr, W1, W2)
     run.layer()
-    mask, _ = O.batchwise_mask(X, m)
+    mask = run.kept_mask()
+    BC.check_gsigma(run.gsigma.cpu().numpy()[:T], X)
+    BC.check_batchwise_mask(run.gsigma.cpu().numpy()[:T], mask, run.tokens.cpu().numpy(), X, m)
     dy = W.upstream_grad(shape)
     dyd = G.dev(dy)
     f32 = dict(dtype=torch.float32, device="cuda")

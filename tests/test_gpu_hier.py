@@ -57,6 +57,7 @@ CASES = [
     ("ragged", dict(T=1111, a=5, b=40)),
     ("k_p1_k_s3", dict(T=257, a=6, b=12, k_primary=1, k_secondary=3)),
     ("medium", dict(T=4096, a=16, b=64)),
+    ("wide_secondary_b1280", dict(T=600, a=2, b=1280, d=128, h=128)),   # secondary rows on the four-waves-per-row top-k
 ]
 
 

@@ -132,5 +132,5 @@ def test_hier_gate_gradients_alone_are_fp32_accurate(api):
     e = {k: fro_rel(out[k].cpu().numpy(), getattr(gr, k)) for k in ("dx", "dWg_p", "dWn_p", "dWg_s", "dWn_s")}
     say("  relative errors:", {k: "%.2e" % v for k, v in e.items()})
     for k, v in e.items():
-        assert v <= 1e-4, (k, v)
+        assert v <= 1e-5, (k, v)
     assert not out["dW1"].any() and not out["dW2"].any()

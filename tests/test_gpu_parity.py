@@ -144,6 +144,47 @@ def test_gate_route_losses_random_shapes(api):
         check_losses(run, fw)
 
 
+WIDE_CASES = [
+    # the four-waves-per-row top-k kernel (1024 < n <= 2048): widths off every tile size, k from 1 to
+    # 8 (both list-length instantiations), with a bias, noise-free, and with tied rows
+    # name, n, k, T, with_bias, noise
+    ("n1025_k1", 1025, 1, 130, False, True),
+    ("n1025_k8", 1025, 8, 97, True, True),
+    ("n1500_k3", 1500, 3, 200, False, True),
+    ("n1500_k8_noise_free", 1500, 8, 64, False, False),
+    ("n2047_k1_noise_free", 2047, 1, 75, True, False),
+    ("n2047_k3", 2047, 3, 140, True, True),
+    ("n2047_k8", 2047, 8, 50, False, True),
+]
+
+
+@pytest.mark.parametrize("name,n,k,T,with_bias,noise", WIDE_CASES, ids=[c[0] for c in WIDE_CASES])
+def test_gate_wide_rows(api, name, n, k, T, with_bias, noise):
+    shape = _shape(1, T=T, n=n, k=k, d=128, h=64)
+    if with_bias:
+        shape = W.scaled_config(shape, zipf_beta=0.5)
+    say("case wide", name, shape)
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias)
+    # in-row ties: duplicated gate columns (same clean and raw logit) with the same noise draw give
+    # equal H at different experts, some of them across the quarters the four waves own
+    for src, dst in ((3, 700), (3, n - 1), (510, 511), (1023, 1024)):
+        W_g[:, dst], W_noise[:, dst], eps[:, dst] = W_g[:, src], W_noise[:, src], eps[:, src]
+        if bias is not None:
+            bias[dst] = bias[src]
+    x[T // 2:T // 2 + 3] = x[1]            # and whole rows that tie with each other
+    eps[T // 2:T // 2 + 3] = eps[1]
+    if not noise:
+        eps = None
+    fw = G.oracle_flat(shape, x, W_g, W_noise, eps, bias)
+    assert (fw.logits.H[:, 3] == fw.logits.H[:, 700]).all()
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, None, None)
+    run.gate(); run.route(); run.losses_()
+    torch.cuda.synchronize()
+    check_gate(run, fw, shape)
+    check_route(run, fw.idx, shape.n)
+    check_losses(run, fw)
+
+
 def test_gate_zero_initialised_matrices(api):
     """W_g = W_noise = 0 (the paper's initialisation): selection = top-k of the noise."""
     shape = _shape(1, T=512, n=256)

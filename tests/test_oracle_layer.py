@@ -325,3 +325,36 @@ def test_layer_epilogue_closed_forms():
     assert np.allclose(acc / len(masks), xx + expit(yy), rtol=1e-13)
     # symmetry of the logistic function: sigmoid(-y) = 1 - sigmoid(y)
     assert np.allclose(O.layer_epilogue(-y, 0 * x, None, 0.0), 1.0 - O.layer_epilogue(y, 0 * x, None, 0.0), atol=1e-15)
+
+
+def test_expert_input_grad_by_central_differences_and_mask_override():
+    """expert_input_grad is the derivative of <dout, relu(x W1) W2> in x (checked numerically away
+    from the kink); with an explicit mask it is linear in the mask: switching one hidden unit on
+    adds exactly that unit's path dout.W2[u,:] * W1[:,u]."""
+    rng = np.random.default_rng(21)
+    d, h, rows = 6, 9, 4
+    W1, W2 = rng.standard_normal((d, h)), rng.standard_normal((h, d))
+    xe, dout = rng.standard_normal((rows, d)), rng.standard_normal((rows, d))
+    assert np.abs(xe @ W1).min() > 1e-3
+    g = O.expert_input_grad(xe, dout, W1, W2)
+    f = lambda xx: float((dout * O.expert_ffn(xx, W1, W2)).sum())
+    step = 1e-6
+    for r in range(rows):
+        for j in range(d):
+            e = np.zeros_like(xe)
+            e[r, j] = step
+            assert g[r, j] == pytest.approx((f(xe + e) - f(xe - e)) / (2 * step), rel=1e-6, abs=1e-8)
+    mask = (xe @ W1) > 0
+    r, u = np.argwhere(~mask)[0]
+    flipped = mask.copy()
+    flipped[r, u] = True
+    delta = O.expert_input_grad(xe, dout, W1, W2, relu_mask=flipped) - g
+    expect = np.zeros_like(g)
+    expect[r] = (dout[r] @ W2[u, :]) * W1[:, u]
+    assert np.abs(delta - expect).max() <= 1e-12
+    # and it is what experts_backward accumulates into dx for a batch that uses one expert
+    idx = np.zeros((rows, 1), np.int64)
+    gates = rng.random((rows, 1)) + 0.5
+    dy = rng.standard_normal((rows, d))
+    dx, _, _, _ = O.experts_backward(xe, idx, gates, lambda e: (W1, W2), dy)
+    assert np.abs(dx - O.expert_input_grad(xe, gates * dy, W1, W2)).max() <= 1e-12
