@@ -150,6 +150,24 @@ int moe_route(const moe_config *cfg, const int32_t *topk_idx, int32_t *counts, i
               int32_t *perm, int32_t *inv_perm, int32_t *tile_expert, int32_t *tile_row0,
               int32_t *num_tiles, void *workspace, void *stream);
 
+/*
+ * moe_route for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs
+ * and results as moe_route; the chunk histograms live in a 4 MiB device array inside the library
+ * image instead of a caller workspace (each GPU the library runs on holds that array until the
+ * process ends).  The call allocates nothing.  Shapes whose moe_route_workspace_bytes() exceeds
+ * MOE_ROUTE_STATIC_MAX_WORKSPACE_BYTES are rejected with MOE_EWORKSPACE before anything is
+ * launched (the limit admits e.g. T*k = 131072 assignments over 2048 experts; few experts and a
+ * short assignment list, n <= 512 and T*k <= 65536, need no scratch at all).  All calls on one GPU
+ * share the one array: calls that overlap in time on the same GPU (different streams or host
+ * threads) race; calls on one stream, or ordered by events, are safe.  Nothing has to be cleared
+ * between calls: every cell read is written earlier in the same call.
+ */
+#define MOE_ROUTE_STATIC_MAX_WORKSPACE_BYTES ((size_t)4 << 20)
+int moe_route_static(const moe_config *cfg, const int32_t *topk_idx, int32_t *counts,
+                     int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *tile_expert,
+                     int32_t *tile_row0, int32_t *num_tiles, void *stream);
+
 /* ---- a3: the experts, E_i(x) = relu(x W1_i) W2_i (Appendix C) ------------------------ */
 /*
  * x [T,d] f32; W1 [n,d,h] and W2 [n,h,d] in the paper's plain layout (input x hidden,

@@ -65,6 +65,7 @@ _moe_get_workspace_layout = _proto("moe_get_workspace_layout", ctypes.c_int,
                                    [_cfgp, ctypes.POINTER(MoeWorkspaceLayout)])
 _moe_gate = _proto("moe_gate", ctypes.c_int, [_cfgp] + [_vp] * 12)
 _moe_route = _proto("moe_route", ctypes.c_int, [_cfgp] + [_vp] * 10)
+_moe_route_static = _proto("moe_route_static", ctypes.c_int, [_cfgp] + [_vp] * 9)
 _moe_expert_ffn = _proto("moe_expert_ffn", ctypes.c_int, [_cfgp] + [_vp] * 11)
 _moe_combine = _proto("moe_combine", ctypes.c_int, [_cfgp] + [_vp] * 5)
 _moe_aux_losses = _proto("moe_aux_losses", ctypes.c_int, [_cfgp] + [_vp] * 6)
@@ -224,6 +225,16 @@ def moe_route(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_
     _check(_moe_route(ctypes.byref(cfg), _ptr(topk_idx), _ptr(counts), _ptr(offsets), _ptr(perm),
                       _ptr(inv_perm), _ptr(tile_expert), _ptr(tile_row0), _ptr(num_tiles),
                       _ptr(workspace), _stream(stream)))
+
+
+MOE_ROUTE_STATIC_MAX_WORKSPACE_BYTES = 4 << 20
+
+
+def moe_route_static(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0, num_tiles,
+                     stream=None):
+    _check(_moe_route_static(ctypes.byref(cfg), _ptr(topk_idx), _ptr(counts), _ptr(offsets), _ptr(perm),
+                             _ptr(inv_perm), _ptr(tile_expert), _ptr(tile_row0), _ptr(num_tiles),
+                             _stream(stream)))
 
 
 def moe_expert_ffn(cfg, x, perm, offsets, tile_expert, tile_row0, num_tiles, W1, W2, out_sorted,

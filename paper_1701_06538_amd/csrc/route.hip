@@ -277,3 +277,49 @@ extern "C" int moe_route(const moe_config *cfg, const int32_t *topk_idx, int32_t
     return route_with_scratch(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0,
                               num_tiles, workspace, stream);
 }
+
+// ---- moe_route for callers that cannot allocate -----------------------------------------
+// The chunk histograms live in a device array that is part of the library image: every GPU the
+// library runs on holds its own copy until the process ends.  The array's name is only a
+// host-side stand-in; its device address is looked up once per device and that address is what
+// the kernels receive.
+constexpr size_t kRouteScratchBytes = MOE_ROUTE_STATIC_MAX_WORKSPACE_BYTES;   // 4 MiB: 512 chunks x 2048 experts
+static __device__ __align__(256) int32_t scratch[kRouteScratchBytes / sizeof(int32_t)];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t *g_scratch_ptr[kMaxDevices] = {};
+
+int route_scratch_for_current_device(int32_t **out) {
+    int dev = 0;
+    MOE_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return MOE_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        MOE_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return MOE_EHIP;
+        g_scratch_ptr[dev] = (int32_t *)ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+}  // namespace
+
+extern "C" int moe_route_static(const moe_config *cfg, const int32_t *topk_idx, int32_t *counts,
+                                int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                                int32_t *tile_expert, int32_t *tile_row0, int32_t *num_tiles,
+                                void *stream) {
+    int st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (!topk_idx || !counts || !offsets || !perm || !inv_perm || !tile_expert || !tile_row0 || !num_tiles)
+        return MOE_EINVAL;
+    if (route_ws_bytes((int64_t)cfg->T * cfg->k, cfg->n) > kRouteScratchBytes) return MOE_EWORKSPACE;
+    int32_t *ptr = nullptr;
+    if ((st = route_scratch_for_current_device(&ptr)) != MOE_OK) return st;
+    // every histogram cell a kernel reads is written earlier in the same call (route_hist_kernel
+    // fills all num_chunks x n cells), so nothing of the previous call's contents has to be cleared
+    return route_with_scratch(cfg, topk_idx, counts, offsets, perm, inv_perm, tile_expert, tile_row0,
+                              num_tiles, ptr, stream);
+}
