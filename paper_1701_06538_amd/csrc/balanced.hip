@@ -802,7 +802,11 @@ extern "C" int moe_gate_balanced(const moe_config *cfg, const float *x, const fl
     if ((st = launch_softmax_gate(cfg, x, W_g, gate_bias, (float *)(ws + L.clean), gsigma, Gt, kept, s)) != MOE_OK)
         return st;
     SelectArgs sa{};
-    sa.Gt = Gt; sa.T = T; sa.n = n; sa.m = (int)(T * cfg->k / n); sa.TM = moe_tile_rows(cfg);
+    sa.Gt = Gt; sa.T = T; sa.n = n; sa.m = (int)(T * cfg->k / n);
+    {   // the tile height the expert kernel will be launched with (it sees T*k rows with k = 1)
+        const moe_config fv = expert_view(cfg, T * cfg->k);
+        sa.TM = moe_tile_rows(&fv);
+    }
     sa.tokens = tokens; sa.kept = kept; sa.pos = (int32_t *)(ws + L.pos); sa.counts = (int32_t *)(ws + L.counts);
     sa.offsets = (int32_t *)(ws + L.offsets); sa.tile_expert = (int32_t *)(ws + L.tile_expert);
     sa.tile_row0 = (int32_t *)(ws + L.tile_row0); sa.num_tiles = (int32_t *)(ws + L.num_tiles);
@@ -891,7 +895,11 @@ extern "C" int moe_layer_forward_threshold(const moe_config *cfg, const float *x
     if ((st = launch_softmax_gate(cfg, x, W_g, gate_bias, (float *)(ws + L.clean), gsigma, Gt, kept, s)) != MOE_OK)
         return st;
     SelectArgs sa{};
-    sa.Gt = Gt; sa.T = T; sa.n = n; sa.m = 0; sa.TM = moe_tile_rows(cfg);
+    sa.Gt = Gt; sa.T = T; sa.n = n; sa.m = 0;
+    {
+        const moe_config fv = expert_view(cfg, row_capacity);
+        sa.TM = moe_tile_rows(&fv);
+    }
     sa.tokens = tokens; sa.kept = kept; sa.pos = (int32_t *)(ws + L.pos); sa.counts = counts;
     sa.offsets = (int32_t *)(ws + L.offsets); sa.tile_expert = (int32_t *)(ws + L.tile_expert);
     sa.tile_row0 = (int32_t *)(ws + L.tile_row0); sa.num_tiles = (int32_t *)(ws + L.num_tiles);

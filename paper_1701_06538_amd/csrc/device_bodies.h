@@ -297,14 +297,15 @@ __device__ __forceinline__ void combine_body(const float4 *__restrict__ out_sort
 #pragma unroll
         for (int s = 0; s < kMaxK; ++s) {
             if (s < k) {
-                const float4 v = out_sorted[(int64_t)rows[s] * d4 + c];
+                // every expert output row is read exactly once: a streaming load
+                const float4 v = stream_load4(out_sorted + (int64_t)rows[s] * d4 + c);
                 acc.x = fmaf(g[s], v.x, acc.x);
                 acc.y = fmaf(g[s], v.y, acc.y);
                 acc.z = fmaf(g[s], v.z, acc.z);
                 acc.w = fmaf(g[s], v.w, acc.w);
             }
         }
-        y[t * d4 + c] = acc;
+        stream_store4(y + t * d4 + c, acc);
     }
 }
 

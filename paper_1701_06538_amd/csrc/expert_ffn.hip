@@ -18,14 +18,26 @@ namespace moe {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kFfnTM = 64;  // rows per tile
+// Cache policy of the four-wave kernel's weight loads (it runs when experts have one tile each, so
+// every weight byte is used once): the non-temporal bit of the buffer instruction's policy field.
+#ifndef FFN4_AUX
+#define FFN4_AUX 2
+#endif
 #ifndef FFN_STAGES1
 #define FFN_STAGES1 2
 #define FFN_STAGES2 2
 #endif
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) { return pack_bf16_pair(lo, hi); }
+
+// 16 bytes of expert output.  The rows are written once and read back by the combine after the
+// whole launch: a streaming store keeps them from displacing weights in L2.
+__device__ __forceinline__ void store_out4(float *dst, v4f v) {
+    MOE_STREAM_STORE(v, reinterpret_cast<v4f *>(dst));
+}
 
 
 // XCD-aware tile order: consecutive workgroup ids go to different XCDs (one L2 each), so
@@ -46,18 +58,6 @@ struct BFrag {
     uint32_t r[8][4];
 };
 
-template <int LD_BYTES>
-__device__ __forceinline__ void load_bfrag(BFrag &f, const char *base, uint32_t lane_off, int k0) {
-    // uniform base + compile-time row offset + 32-bit lane offset: scalar-base addressing, so
-    // the whole stream needs one address VGPR
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const char *row = base + (size_t)(k0 + i) * LD_BYTES;
-        const uint4 v = *reinterpret_cast<const uint4 *>(row + lane_off);
-        f.r[i][0] = v.x; f.r[i][1] = v.y; f.r[i][2] = v.z; f.r[i][3] = v.w;
-    }
-}
-
 // Column j of the block as a v_mfma_f32_16x16x32_bf16 B operand (8 consecutive k in one lane):
 // a register transpose done with byte permutes.
 __device__ __forceinline__ v8bf bfrag_column(const BFrag &f, int j) {
@@ -77,14 +77,22 @@ template <int K, int LD, int STAGES>   // LD: elements per row of the weight mat
 struct WeightStream {
     static_assert(K % (32 * STAGES) == 0, "k extent must be a multiple of the pipeline depth");
     BFrag f[STAGES];
-    const char *base;    // the matrix (uniform)
-    uint32_t lane_off;   // this lane's first element: row 8g of the k range, column col (bytes)
+    __amdgpu_buffer_rsrc_t rsrc;   // the expert's matrix as a buffer: scalar base, so the whole stream
+    uint32_t lane_off;             // needs one address VGPR (this lane's first element, in bytes)
 
-    __device__ __forceinline__ void start(const uint16_t *W, int col, int g) {
-        base = reinterpret_cast<const char *>(W);
-        lane_off = (uint32_t)((8 * g) * LD + col) * 2u;
+    __device__ __forceinline__ void load(int s, int k0) {
 #pragma unroll
-        for (int s = 0; s < STAGES; ++s) load_bfrag<LD * 2>(f[s], base, lane_off, 32 * s);
+        for (int i = 0; i < 8; ++i) {
+            const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off, (uint32_t)(k0 + i) * LD * 2u, 0);
+            f[s].r[i][0] = v.x; f[s].r[i][1] = v.y; f[s].r[i][2] = v.z; f[s].r[i][3] = v.w;
+        }
+    }
+    // W: the matrix (bytes long); the stream covers rows [row0, row0 + K), columns col .. col + 7
+    __device__ __forceinline__ void start(const uint16_t *W, uint32_t bytes, int row0, int col, int g) {
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(W), 0, bytes, 0x00020000);
+        lane_off = (uint32_t)((row0 + 8 * g) * LD + col) * 2u;
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s) load(s, 32 * s);
     }
 
     // acc[rt][j] += A[16rt + c, 0:K] * W[0:K, col + j]   (A bf16 in LDS, row stride lda)
@@ -114,7 +122,7 @@ struct WeightStream {
 #pragma unroll
             for (int j = 0; j < 4; ++j) b[j] = bfrag_column(f[s], 4 + j);
             __builtin_amdgcn_sched_barrier(0);
-            if (reload) load_bfrag<LD * 2>(f[s], base, lane_off, kk + 32 * STAGES);
+            if (reload) load(s, kk + 32 * STAGES);
             __builtin_amdgcn_sched_barrier(0);
             mma_half(b, 4, kk);
             __builtin_amdgcn_sched_barrier(0);
@@ -143,9 +151,11 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
 
     const int tile = xcd_tile(blockIdx.x, *p.num_tiles);
     if (tile < 0) return;
-    const int e = p.tile_expert[tile];
-    const int row0 = p.tile_row0[tile];
-    const int rows = min(TM, p.offsets[e + 1] - row0);
+    // tile coordinates are wave-uniform: kept in scalar registers they give the weight stream a
+    // scalar buffer descriptor
+    const int e = __builtin_amdgcn_readfirstlane(p.tile_expert[tile]);
+    const int row0 = __builtin_amdgcn_readfirstlane(p.tile_row0[tile]);
+    const int rows = __builtin_amdgcn_readfirstlane(min(TM, p.offsets[e + 1] - row0));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
 
@@ -168,7 +178,7 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
             const int r = min(rr + i * RPP, rows - 1);      // clamped: padding rows re-read a valid row
             tok[i] = p.perm[row0 + r];
         }
-        s1.start(W1, col1, g);
+        s1.start(W1, (uint32_t)(D * H * 2), 0, col1, g);
         float4 v[PASSES];
 #pragma unroll
         for (int i = 0; i < PASSES; ++i) {
@@ -206,7 +216,7 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
             for (int j = 0; j < 8; ++j) acc[rt][j] = v4f{0.f, 0.f, 0.f, 0.f};
         s1.run(acc, lds, XS, c, g);
         // second matrix starts streaming during the hand-over below
-        s2.start(W2 + (size_t)(H / 2) * kh * D, col2, g);
+        s2.start(W2, (uint32_t)(D * H * 2), (H / 2) * kh, col2, g);
         __syncthreads();  // every wave is done reading the x tile; the hidden tile overwrites it
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt)
@@ -267,12 +277,10 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
                     const float4 p0 = *reinterpret_cast<const float4 *>(src);
                     const float4 p1 = *reinterpret_cast<const float4 *>(src + 4);
                     float *dst = p.out + (size_t)(row0 + row) * D + col2;
-                    *reinterpret_cast<float4 *>(dst) =
-                        make_float4(acc[rt][0][r] + p0.x, acc[rt][1][r] + p0.y, acc[rt][2][r] + p0.z,
-                                    acc[rt][3][r] + p0.w);
-                    *reinterpret_cast<float4 *>(dst + 4) =
-                        make_float4(acc[rt][4][r] + p1.x, acc[rt][5][r] + p1.y, acc[rt][6][r] + p1.z,
-                                    acc[rt][7][r] + p1.w);
+                    store_out4(dst, v4f{acc[rt][0][r] + p0.x, acc[rt][1][r] + p0.y, acc[rt][2][r] + p0.z,
+                                        acc[rt][3][r] + p0.w});
+                    store_out4(dst + 4, v4f{acc[rt][4][r] + p1.x, acc[rt][5][r] + p1.y, acc[rt][6][r] + p1.z,
+                                            acc[rt][7][r] + p1.w});
                 }
         }
     }
@@ -289,16 +297,24 @@ template <int K, int LD, int STAGES, int NG>   // NG groups of 128 columns per w
 struct WeightStream4 {
     static constexpr int NSTEPS = K / 32;
     BFrag f[STAGES][NG];
-    const char *base;
+    __amdgpu_buffer_rsrc_t rsrc;   // the matrix as a buffer: scalar base, one 32-bit lane offset
     uint32_t lane_off;
 
-    __device__ __forceinline__ void start(const uint16_t *W, int col, int g) {
-        base = reinterpret_cast<const char *>(W);
+    __device__ __forceinline__ void load(int s, int q, int k0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const v4u v = __builtin_amdgcn_raw_buffer_load_b128(
+                rsrc, lane_off, (uint32_t)(k0 + i) * LD * 2u + 256u * (uint32_t)q, FFN4_AUX);
+            f[s][q].r[i][0] = v.x; f[s][q].r[i][1] = v.y; f[s][q].r[i][2] = v.z; f[s][q].r[i][3] = v.w;
+        }
+    }
+    __device__ __forceinline__ void start(const uint16_t *W, uint32_t bytes, int col, int g) {
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(W), 0, bytes, 0x00020000);
         lane_off = (uint32_t)((8 * g) * LD + col) * 2u;
 #pragma unroll
         for (int s = 0; s < STAGES; ++s)
 #pragma unroll
-            for (int q = 0; q < NG; ++q) load_bfrag<LD * 2>(f[s][q], base + 256 * q, lane_off, 32 * s);
+            for (int q = 0; q < NG; ++q) load(s, q, 32 * s);
     }
 
     __device__ __forceinline__ void run(v4f (&acc)[NG][4][8], const uint16_t *A_lds, int lda, int c, int g) {
@@ -317,7 +333,7 @@ struct WeightStream4 {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) b[j] = bfrag_column(f[s][q], j);
                 __builtin_amdgcn_sched_barrier(0);
-                if (reload) load_bfrag<LD * 2>(f[s][q], base + 256 * q, lane_off, kk + 32 * STAGES);
+                if (reload) load(s, q, kk + 32 * STAGES);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
@@ -344,9 +360,11 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
 
     const int tile = xcd_tile(blockIdx.x, *p.num_tiles);
     if (tile < 0) return;
-    const int e = p.tile_expert[tile];
-    const int row0 = p.tile_row0[tile];
-    const int rows = min(TM, p.offsets[e + 1] - row0);
+    // tile coordinates are wave-uniform: kept in scalar registers they give the weight stream a
+    // scalar buffer descriptor
+    const int e = __builtin_amdgcn_readfirstlane(p.tile_expert[tile]);
+    const int row0 = __builtin_amdgcn_readfirstlane(p.tile_row0[tile]);
+    const int rows = __builtin_amdgcn_readfirstlane(min(TM, p.offsets[e + 1] - row0));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
     const uint16_t *W1 = (const uint16_t *)p.W1 + (size_t)e * D * H;
@@ -360,7 +378,7 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
         int tok[2 * HALF];
 #pragma unroll
         for (int i = 0; i < 2 * HALF; ++i) tok[i] = p.perm[row0 + min(rr + i * RPP, rows - 1)];
-        s1.start(W1, col1, g);
+        s1.start(W1, (uint32_t)(D * H * 2), col1, g);
 #pragma unroll
         for (int hb = 0; hb < 2; ++hb) {
             float4 v[HALF];
@@ -401,7 +419,7 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) acc[q][rt][j] = v4f{0.f, 0.f, 0.f, 0.f};
         s1.run(acc, lds, XS, c, g);
-        s2.start(W2, col2, g);
+        s2.start(W2, (uint32_t)(D * H * 2), col2, g);
         __syncthreads();  // the hidden tile overwrites the x tile
 #pragma unroll
         for (int q = 0; q < 2; ++q)
@@ -442,10 +460,8 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
                 const int row = 16 * rt + 4 * g + r;
                 if (row >= rows) continue;
                 float *dst = p.out + (size_t)(row0 + row) * D + col2;
-                *reinterpret_cast<float4 *>(dst) =
-                    make_float4(acc[0][rt][0][r], acc[0][rt][1][r], acc[0][rt][2][r], acc[0][rt][3][r]);
-                *reinterpret_cast<float4 *>(dst + 4) =
-                    make_float4(acc[0][rt][4][r], acc[0][rt][5][r], acc[0][rt][6][r], acc[0][rt][7][r]);
+                store_out4(dst, v4f{acc[0][rt][0][r], acc[0][rt][1][r], acc[0][rt][2][r], acc[0][rt][3][r]});
+                store_out4(dst + 4, v4f{acc[0][rt][4][r], acc[0][rt][5][r], acc[0][rt][6][r], acc[0][rt][7][r]});
             }
     }
 }
@@ -568,6 +584,7 @@ __global__ __launch_bounds__(256) void gather_bf16_kernel(const float *__restric
     }
 }
 
+int ffn_tile_rows(const moe_config *cfg);
 static size_t ffn_up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // bf16 experts of any shape with d and h multiples of 128: gather, then two grouped GEMMs with
@@ -585,21 +602,24 @@ static int launch_expert_ffn_general(const moe_config *cfg, const FfnArgs &a, in
                        a.offsets + cfg->n, cfg->d, cfg->k, xs);
     MOE_LAUNCH_CHECK();
     GGRows g1{xs, (const uint16_t *)a.W1, hid, nullptr, cfg->d, cfg->h, a.offsets, a.tile_expert,
-              a.tile_row0, a.num_tiles, kFfnTM};
+              a.tile_row0, a.num_tiles, ffn_tile_rows(cfg)};
     int rc = launch_gg_rows128(g1, true, EPI_RELU_BF16, max_tiles, st);
     if (rc != MOE_OK) return rc;
     GGRows g2{hid, (const uint16_t *)a.W2, a.out, nullptr, cfg->h, cfg->d, a.offsets, a.tile_expert,
-              a.tile_row0, a.num_tiles, kFfnTM};
+              a.tile_row0, a.num_tiles, ffn_tile_rows(cfg)};
     return launch_gg_rows128(g2, true, EPI_F32, max_tiles, st);
 }
+
+// Rows per tile of the dispatch table (one height for every shape today; the callers ask per config).
+int ffn_tile_rows(const moe_config *) { return kFfnTM; }
 
 int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles, hipStream_t st) {
     if (max_tiles <= 0) return MOE_OK;
     if (cfg->expert_dtype == MOE_DTYPE_BF16) {
         if (cfg->d != 512 || cfg->h != 1024) return launch_expert_ffn_general(cfg, a, max_tiles, st);
-        constexpr size_t lds = (size_t)kFfnTM * (1024 + 8) * sizeof(uint16_t);
         static LdsLimitOnce lds8, lds4;
         const unsigned grid = (unsigned)(ceil_div(max_tiles, 8) * 8);
+        constexpr size_t lds = (size_t)kFfnTM * (1024 + 8) * sizeof(uint16_t);
         // One tile per expert (<= 64 rows on average): every tile streams its weights from HBM, and
         // the four-wave kernel's deeper load pipeline pays.  Several tiles per expert: the tiles
         // share weights through L2 and the eight-wave kernel is marginally faster.
@@ -627,12 +647,12 @@ int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles
 
 using namespace moe;
 
-extern "C" int32_t moe_tile_rows(const moe_config *) { return kFfnTM; }
+extern "C" int32_t moe_tile_rows(const moe_config *cfg) { return ffn_tile_rows(cfg); }
 
 extern "C" int64_t moe_max_tiles(const moe_config *cfg) {
     if (check_config(cfg) != MOE_OK) return 0;
     const int64_t A = (int64_t)cfg->T * cfg->k;
-    return ceil_div(A, kFfnTM) + (cfg->n < A ? cfg->n : A);
+    return ceil_div(A, ffn_tile_rows(cfg)) + (cfg->n < A ? cfg->n : A);
 }
 
 extern "C" size_t moe_ffn_workspace_bytes(const moe_config *cfg) {

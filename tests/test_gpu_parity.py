@@ -277,6 +277,41 @@ def test_layer_bf16_one_token_per_expert_tail(api):
     _ffn_case(api, _shape(1, T=65, n=70, k=1), TOL_BF16, "bf16 tiny tiles")
 
 
+def test_layer_bf16_sparse_skewed_batch(api):
+    """A sparse batch (12 rows per expert on average) under a skewed gate: empty experts, single-row
+    tiles, full tiles and experts with many tiles in one launch of the one-tile-per-expert kernel;
+    every output row of every expert and y are compared."""
+    shape = W.scaled_config(_shape(1, T=1500, n=512, k=4), zipf_beta=0.6)
+    say("case bf16 sparse skewed batch", shape)
+    x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias=True)
+    fw = G.oracle_flat(shape, x, W_g, W_noise, eps, bias)
+    W1, W2 = G.device_weights(shape)
+    run = G.FlatRun(api, shape, x, W_g, W_noise, eps, bias, W1, W2)
+    TM = api.moe_tile_rows(run.cfg)
+    run.stages()
+    check_gate(run, fw, shape)
+    check_route(run, fw.idx, shape.n)
+    counts, offsets, perm, _ = O.routing(fw.idx, shape.n)
+    say("  rows per expert: max %d, empty %d, single-row %d, more than one tile %d"
+        % (counts.max(), (counts == 0).sum(), (counts == 1).sum(), (counts > TM).sum()))
+    assert (counts == 0).any() and (counts > TM).any() and (counts == 1).any() and (counts >= TM).any()
+    wf = G.device_weight_fn(shape, W1, W2)
+    out = run.out_sorted.cpu().numpy()
+    worst = 0.0
+    for e in np.nonzero(counts)[0]:
+        r0, r1 = int(offsets[e]), int(offsets[e + 1])
+        ref = O.expert_ffn(x[perm[r0:r1] // shape.k], *wf(e))
+        worst = max(worst, G.rel_errors(out[r0:r1], ref)[0])
+    say("  out_sorted, every row of every expert: worst row-rel %.3e" % worst)
+    assert worst <= TOL_BF16
+    y_ref = O.moe_output(x, fw.idx, fw.gates, wf, shape.n)
+    row, mx = G.rel_errors(run.y.cpu().numpy(), y_ref)
+    assert row <= TOL_BF16 and mx <= TOL_BF16
+    y1 = run.y.clone()
+    run.fused()
+    assert torch.equal(run.y, y1)
+
+
 def test_layer_cfg1_full(api):
     run = _ffn_case(api, W.CONFIGS[1], TOL_BF16, "cfg1 full")
     # determinism: a second fused run reproduces every bit
