@@ -50,6 +50,32 @@ __device__ __forceinline__ int xcd_tile(int bid, int num_tiles) {
     return ((bid >> 3) < per && tile < num_tiles) ? tile : -1;
 }
 
+// A workgroup's tile: expert, first sorted row, rows (<= TM).  All wave-uniform and kept in scalar
+// registers (they give the weight stream a scalar buffer descriptor).  The row count comes from
+// the NEXT table entry, fetched in the same round trip as this one, instead of from the offsets
+// array one dependent round trip later: tiles of one expert are consecutive and only its last one
+// is short, and the next expert's first row is where this expert's rows end (experts in between
+// have none).  Only the table's very last tile has to look at the offsets.
+struct TileCoord {
+    int e, row0, rows;
+};
+__device__ __forceinline__ bool load_tile(const FfnArgs &p, int TM, TileCoord &t) {
+    const int num = *p.num_tiles;
+    const int tile = xcd_tile(blockIdx.x, num);
+    if (tile < 0) return false;
+    const bool has_next = tile + 1 < num;
+    const int nx = has_next ? tile + 1 : tile;
+    const int e = p.tile_expert[tile], row0 = p.tile_row0[tile];
+    const int e2 = p.tile_expert[nx], r2 = p.tile_row0[nx];
+    t.e = __builtin_amdgcn_readfirstlane(e);
+    t.row0 = __builtin_amdgcn_readfirstlane(row0);
+    int rows;
+    if (has_next) rows = e2 == e ? TM : r2 - row0;
+    else rows = min(TM, p.offsets[t.e + 1] - t.row0);
+    t.rows = __builtin_amdgcn_readfirstlane(rows);
+    return true;
+}
+
 // One 32-deep k-step of B-operand data for 8 adjacent columns of a row-major [K, N] bf16
 // matrix: lane (c = lane % 16, g = lane / 16) holds rows k0+8g .. k0+8g+7, columns col .. col+7,
 // fetched as eight 16-byte loads (the vector memory pipe moves 16 B per lane per instruction at
@@ -149,13 +175,9 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
     static_assert(TM * PS * 4 <= TM * HS * 2, "partial sums reuse the hidden tile's LDS");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
 
-    const int tile = xcd_tile(blockIdx.x, *p.num_tiles);
-    if (tile < 0) return;
-    // tile coordinates are wave-uniform: kept in scalar registers they give the weight stream a
-    // scalar buffer descriptor
-    const int e = __builtin_amdgcn_readfirstlane(p.tile_expert[tile]);
-    const int row0 = __builtin_amdgcn_readfirstlane(p.tile_row0[tile]);
-    const int rows = __builtin_amdgcn_readfirstlane(min(TM, p.offsets[e + 1] - row0));
+    TileCoord tc;
+    if (!load_tile(p, TM, tc)) return;
+    const int e = tc.e, row0 = tc.row0, rows = tc.rows;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
 
@@ -358,13 +380,9 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
     static_assert(H == 4 * 256 && D == 4 * 128, "four waves: 256 hidden / 128 output columns each");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
 
-    const int tile = xcd_tile(blockIdx.x, *p.num_tiles);
-    if (tile < 0) return;
-    // tile coordinates are wave-uniform: kept in scalar registers they give the weight stream a
-    // scalar buffer descriptor
-    const int e = __builtin_amdgcn_readfirstlane(p.tile_expert[tile]);
-    const int row0 = __builtin_amdgcn_readfirstlane(p.tile_row0[tile]);
-    const int rows = __builtin_amdgcn_readfirstlane(min(TM, p.offsets[e + 1] - row0));
+    TileCoord tc;
+    if (!load_tile(p, TM, tc)) return;
+    const int e = tc.e, row0 = tc.row0, rows = tc.rows;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
     const uint16_t *W1 = (const uint16_t *)p.W1 + (size_t)e * D * H;
