@@ -344,6 +344,30 @@ __device__ __forceinline__ float key_logit(uint64_t key) {
 }
 __device__ __forceinline__ int key_index(uint64_t key) { return 0x7fffffff - (int)(uint32_t)key; }
 
+// Maximum of one 32-bit value per lane over the whole wavefront, returned wave-uniform.  Four
+// data-parallel-primitive steps (swap within pairs, within quads, mirror within 8 and within 16
+// lanes) leave every 16-lane row holding its maximum; the four rows meet in scalar registers.
+// No LDS permutes and no waits: the chain is a dozen short-latency instructions.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true));   // row_half_mirror
+    v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true));   // row_mirror
+    const uint32_t r0 = __builtin_amdgcn_readlane((int)v, 0), r1 = __builtin_amdgcn_readlane((int)v, 16);
+    const uint32_t r2 = __builtin_amdgcn_readlane((int)v, 32), r3 = __builtin_amdgcn_readlane((int)v, 48);
+    return max(max(r0, r1), max(r2, r3));
+}
+
+// Largest selection key of the wavefront.  Keys are unique (the index is part of the key), so the
+// maximum is found in two 32-bit passes: the largest logit word, then the largest index word among
+// the lanes that hold that logit.  An all-empty wavefront (every key 0) gives 0.
+__device__ __forceinline__ uint64_t wave_max_key(uint64_t key) {
+    const uint32_t hi = (uint32_t)(key >> 32), lo = (uint32_t)key;
+    const uint32_t hmax = wave_max_u32(hi);
+    const uint32_t lmax = wave_max_u32(hi == hmax ? lo : 0u);
+    return ((uint64_t)hmax << 32) | lmax;
+}
+
 // The same pointer in scalar registers (all lanes hold the same value): loads through it can use
 // scalar-base addressing with one 32-bit lane offset.
 __device__ __forceinline__ const float *uniform_ptr(const float *ptr) {
@@ -446,12 +470,7 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
             tv[j] = -INFINITY;
             ti[j] = 0x7fffffff;
             if (j < kp1) {
-                uint64_t v = lk[0];
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) {
-                    const uint64_t o = __shfl_xor(v, off);
-                    v = o > v ? o : v;
-                }
+                const uint64_t v = wave_max_key(lk[0]);
                 tv[j] = key_logit(v);
                 ti[j] = key_index(v);
                 const bool pop = lk[0] == v;
@@ -617,12 +636,7 @@ __global__ __launch_bounds__(256, 2) void gate_topk_wide_kernel(TopkArgs p) {
 #pragma unroll
         for (int j = 0; j < L; ++j) {
             if (j < kp1) {
-                uint64_t v = lk[0];
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) {
-                    const uint64_t o = __shfl_xor(v, off);
-                    v = o > v ? o : v;
-                }
+                const uint64_t v = wave_max_key(lk[0]);
                 mine = lane == j ? v : mine;
                 const bool pop = lk[0] == v;
 #pragma unroll
@@ -641,12 +655,7 @@ __global__ __launch_bounds__(256, 2) void gate_topk_wide_kernel(TopkArgs p) {
             tv[j] = -INFINITY;
             ti[j] = 0x7fffffff;
             if (j < kp1) {
-                uint64_t v = ck;
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) {
-                    const uint64_t o = __shfl_xor(v, off);
-                    v = o > v ? o : v;
-                }
+                const uint64_t v = wave_max_key(ck);
                 tv[j] = key_logit(v);
                 ti[j] = key_index(v);
                 ck = ck == v ? 0 : ck;
