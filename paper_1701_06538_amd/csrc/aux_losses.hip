@@ -65,11 +65,28 @@ __global__ __launch_bounds__(256) void hier_losses_kernel(HierLossArgs p) {
     const int e = blockIdx.x * 256 + threadIdx.x;
     if (e >= n) return;
     const int i = e / p.b, j = e % p.b;
+    // both sums fetch eight terms at a time (independent loads) and add them in ascending order
     double imp = 0.0;
-    for (int r = p.offsets[e]; r < p.offsets[e + 1]; ++r) imp += (double)p.gate[p.perm[r]];
+    const int r1 = p.offsets[e + 1];
+    for (int r0 = p.offsets[e]; r0 < r1; r0 += 8) {
+        int a[8];
+        float g[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] = p.perm[min(r0 + u, r1 - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) g[u] = p.gate[a[u]];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) imp += r0 + u < r1 ? (double)g[u] : 0.0;
+    }
     double ls = 0.0;
     const int blk0 = p.p_tile_offsets[i] * p.sub, blk1 = p.p_tile_offsets[i + 1] * p.sub;
-    for (int blk = blk0; blk < blk1; ++blk) ls += (double)p.s_partials[((size_t)blk * 2 + 1) * p.b + j];
+    for (int b0 = blk0; b0 < blk1; b0 += 8) {
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = p.s_partials[((size_t)min(b0 + u, blk1 - 1) * 2 + 1) * p.b + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ls += b0 + u < blk1 ? (double)t[u] : 0.0;
+    }
     const int cnt = p.p_counts[i];
     const double ld = cnt > 0 ? p.p_sums[p.a + i] * ls / (double)cnt : 0.0;
     p.sums64[e] = imp;

@@ -708,7 +708,7 @@ __global__ __launch_bounds__(256) void dx_gather_add_kernel(float4 *__restrict__
 #pragma unroll
         for (int s = 0; s < kMaxK; ++s)
             if (s < k) {
-                const float4 v = dxs[(int64_t)rows[s] * d4 + c];
+                const float4 v = stream_load4(dxs + (int64_t)rows[s] * d4 + c);   // each row is read once
                 acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
             }
         dx[t * d4 + c] = acc;

@@ -250,12 +250,23 @@ __device__ __forceinline__ double block_sum256(double v, double *scratch4) {
 
 // one block of 256 threads: CV^2 of v[0..n) in fp64 (population variance, no epsilon)
 __device__ __forceinline__ double block_cv2(const double *v, int n, double *scratch4) {
+    // a thread's elements are fetched eight at a time (independent loads, one round trip) and
+    // added in ascending order, so the sum does not depend on how the loads are batched
     double s = 0.0, s2 = 0.0;
-    for (int i = threadIdx.x; i < n; i += 256) s += v[i];
+    for (int i0 = threadIdx.x; i0 < n; i0 += 8 * 256) {
+        double t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = i0 + 256 * u < n ? v[i0 + 256 * u] : 0.0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += t[u];
+    }
     const double mean = block_sum256(s, scratch4) / n;
-    for (int i = threadIdx.x; i < n; i += 256) {
-        const double dlt = v[i] - mean;
-        s2 += dlt * dlt;
+    for (int i0 = threadIdx.x; i0 < n; i0 += 8 * 256) {
+        double t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = i0 + 256 * u < n ? v[i0 + 256 * u] - mean : 0.0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s2 += t[u] * t[u];
     }
     const double var = block_sum256(s2, scratch4) / n;
     return var / (mean * mean);

@@ -164,8 +164,8 @@ __global__ __launch_bounds__(64 * NW, 1) void gg_rows256_kernel(GGRows p, int co
             for (int r = wave; r < 128; r += NW) {          // a wavefront per row: 64 lanes x 16 bytes
                 const int row = 128 * hf + r;
                 if (row < rows)
-                    *reinterpret_cast<v4f *>(C + (size_t)(row0 + row) * N + col0 + 4 * lane) =
-                        *reinterpret_cast<const v4f *>(&Ct[r * CS + 4 * lane]);
+                    MOE_STREAM_STORE(*reinterpret_cast<const v4f *>(&Ct[r * CS + 4 * lane]),   // read once, by the row gather
+                                     reinterpret_cast<v4f *>(C + (size_t)(row0 + row) * N + col0 + 4 * lane));
             }
         } else {
             uint16_t *C = reinterpret_cast<uint16_t *>(p.C);

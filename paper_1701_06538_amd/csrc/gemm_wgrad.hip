@@ -149,8 +149,9 @@ __global__ __launch_bounds__(512) void gg_wgrad_kernel(GGWgrad p) {
         }
         __syncthreads();
         for (int r = wave; r < 128; r += 8)
-            *reinterpret_cast<v4f *>(Ce + (size_t)(m0 + 128 * hf + r) * p.N + n0 + 4 * lane) =
-                *reinterpret_cast<const v4f *>(&Ct[r * WT_CS + 4 * lane]);
+            // the gradient is written once and read once, much later, by the optimiser: a streaming store
+            MOE_STREAM_STORE(*reinterpret_cast<const v4f *>(&Ct[r * WT_CS + 4 * lane]),
+                             reinterpret_cast<v4f *>(Ce + (size_t)(m0 + 128 * hf + r) * p.N + n0 + 4 * lane));
     }
     // Optional: this block's share of the row and column sums of squares of the gradient, which
     // the factored second-moment estimator of the optimiser needs (Appendix D) -- taken here, where

@@ -183,15 +183,16 @@ __global__ __launch_bounds__(256) void adam_update_kernel(AdamUpd a) {
         const float vr = a.v_row[(size_t)e * a.R + r] * s;
         const size_t base = ((size_t)e * a.R + r) * C4;
         for (int c4 = threadIdx.x; c4 < C4; c4 += 256) {
-            const float4 g = reinterpret_cast<const float4 *>(a.G)[base + c4];
-            float4 w = reinterpret_cast<const float4 *>(a.master)[base + c4];
+            // gradient and parameter cross HBM once per step: streaming loads and stores
+            const float4 g = stream_load4(reinterpret_cast<const float4 *>(a.G) + base + c4);
+            float4 w = stream_load4(reinterpret_cast<const float4 *>(a.master) + base + c4);
             const float4 vc = reinterpret_cast<const float4 *>(vcol)[c4];
             if (moves) {
                 w.x -= a.lr * g.x / (sqrtf(vr * vc.x) + a.eps);
                 w.y -= a.lr * g.y / (sqrtf(vr * vc.y) + a.eps);
                 w.z -= a.lr * g.z / (sqrtf(vr * vc.z) + a.eps);
                 w.w -= a.lr * g.w / (sqrtf(vr * vc.w) + a.eps);
-                reinterpret_cast<float4 *>(a.master)[base + c4] = w;
+                stream_store4(reinterpret_cast<float4 *>(a.master) + base + c4, w);
             }
             if (a.copy)
                 reinterpret_cast<uint2 *>(a.copy)[base + c4] =
