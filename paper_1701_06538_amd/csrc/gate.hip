@@ -97,7 +97,8 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(LogitsArgs p) {
     constexpr int ARP = 256 / APT, APASS = BM / ARP;   // x rows per pass, passes
     constexpr int A_BYTES = 2 * BM * ASTR * 4, B_BYTES = 2 * KC * BN * 4;
     // the epilogue stages EC of the RN column tiles at a time in the (then dead) operand buffers
-    constexpr int EC = BM * (BN + 4) * 4 <= A_BYTES + B_BYTES ? RN : RN / 2;
+    constexpr int EC = BM * (BN + 4) * 4 <= A_BYTES + B_BYTES ? RN
+                       : BM * (BN / 2 + 4) * 4 <= A_BYTES + B_BYTES ? RN / 2 : RN / 4;
     constexpr int CS = 32 * EC + 4;   // floats per LDS row of the staged output tile
     static_assert(EC >= 1 && BM * CS * 4 <= A_BYTES + B_BYTES, "the output tile reuses the operand buffers");
     __shared__ __attribute__((aligned(16))) char smem[A_BYTES + B_BYTES];
@@ -751,9 +752,8 @@ int launch_hier_compose(const int32_t *p_idx, const float *p_gate, const int32_t
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-template <int RN>
+template <int RN, int KC = 32>
 static void launch_logits_rn(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
-    constexpr int KC = 32;
     // without a noise matrix only the clean half of the grid exists
     dim3 grid((unsigned)row_tiles, (a.Wn ? 2u : 1u) * (unsigned)ceil_div(a.n, 32 * RN));
     if (a.n % 4 == 0) hipLaunchKernelGGL((gate_logits_kernel<RN, true, KC>), grid, dim3(256), 0, st, a);
@@ -766,6 +766,10 @@ int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
     else if (a.n <= 64) launch_logits_rn<2>(a, row_tiles, st);
     // few tiles: narrower column tiles so that every CU holds at least two workgroups
     else if (row_tiles * 2 * ceil_div(a.n, 128) < 1024) launch_logits_rn<2>(a, row_tiles, st);
+    // wide flat gates with many rounds of tiles: 256-column tiles over 16-deep slabs (same LDS and
+    // register budget, two workgroups per CU) halve the prologues and epilogues per flop: 3 % at
+    // 2048 and 512 experts; slower for the grouped secondary gates of the hierarchical layer
+    else if (a.n % 256 == 0 && a.n >= 512 && !a.tile_row0) launch_logits_rn<8, 16>(a, row_tiles, st);
     else launch_logits_rn<4>(a, row_tiles, st);
     MOE_LAUNCH_CHECK();
     return MOE_OK;
