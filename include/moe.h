@@ -270,6 +270,8 @@ int moe_layer_forward_hier(const moe_config *cfg, const float *x, const float *W
  * accumulation.  fp32 experts: d and h multiples of 4, n <= 65535, every GEMM on the fp32 matrix
  * cores; the hidden activations are the ones the forward pass left in its expert workspace.
  * Gate math in fp32.  workspace: moe_backward_workspace_bytes().
+ * T = 0 is accepted (the [T, .] tensors may then be NULL): every weight gradient is written as zero.
+ * The same holds for moe_layer_backward_hier and moe_layer_backward_balanced.
  */
 size_t moe_backward_workspace_bytes(const moe_config *cfg);
 int moe_layer_backward(const moe_config *cfg, const float *x, const float *W_g,

@@ -1092,9 +1092,8 @@ extern "C" int moe_layer_backward_balanced(const moe_config *cfg, const float *x
     const bool f32_experts = cfg->expert_dtype != MOE_DTYPE_BF16;
     if (!f32_experts && (cfg->d % 256 != 0 || cfg->h % 256 != 0)) return MOE_EUNSUPPORTED;
     if (cfg->d % 4 != 0 || cfg->h % 4 != 0 || cfg->n % 4 != 0) return MOE_EUNSUPPORTED;
-    if (!x || !W_g || !W1 || !W2 || !dy || !gsigma || !tokens || !kept || !denom || !fwd_workspace || !dx ||
-        !dW_g || !dW1 || !dW2 || !workspace)
-        return MOE_EINVAL;
+    if (!W_g || !W1 || !W2 || !fwd_workspace || !dW_g || !dW1 || !dW2 || !workspace) return MOE_EINVAL;
+    if (cfg->T > 0 && (!x || !dy || !gsigma || !tokens || !kept || !denom || !dx)) return MOE_EINVAL;   // [T, .] tensors
     if (w_batchwise != 0.f && !thresholds) return MOE_EINVAL;
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(W1) || !aligned16(W2) ||
         !aligned16(dW1) || !aligned16(dW2) || !aligned16(dW_g) || !aligned16(W_g) || !aligned16(gsigma) ||
