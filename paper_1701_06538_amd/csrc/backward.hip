@@ -48,7 +48,7 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const float *__restric
     float dot = 0.f;
     for (int c = lane * 4; c < d; c += 256) {
         const float4 vy = *reinterpret_cast<const float4 *>(dy + t * d + c);
-        const float4 vo = *reinterpret_cast<const float4 *>(out_sorted + r * d + c);
+        const float4 vo = stream_load4(reinterpret_cast<const float4 *>(out_sorted + r * d + c));   // read once here
         dot = fmaf(vy.x, vo.x, dot); dot = fmaf(vy.y, vo.y, dot);
         dot = fmaf(vy.z, vo.z, dot); dot = fmaf(vy.w, vo.w, dot);
         *reinterpret_cast<uint2 *>(dout + r * d + c) = make_uint2(pack2(g * vy.x, g * vy.y), pack2(g * vy.z, g * vy.w));
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void bwd_prepare_tokens_kernel(const float *__
         float dot = 0.f;
         for (int c = lane * 4; c < d; c += 256) {
             const float4 vy = *reinterpret_cast<const float4 *>(dy + t * d + c);
-            const float4 vo = *reinterpret_cast<const float4 *>(out_sorted + r * d + c);
+            const float4 vo = stream_load4(reinterpret_cast<const float4 *>(out_sorted + r * d + c));   // read once here
             dot = fmaf(vy.x, vo.x, dot); dot = fmaf(vy.y, vo.y, dot);
             dot = fmaf(vy.z, vo.z, dot); dot = fmaf(vy.w, vo.w, dot);
             *reinterpret_cast<uint2 *>(dout + r * d + c) = make_uint2(pack2(g * vy.x, g * vy.y), pack2(g * vy.z, g * vy.w));
@@ -798,7 +798,7 @@ __global__ __launch_bounds__(256) void bwd_prepare_f32_kernel(const float *__res
     float dot = 0.f;
     for (int c = lane * 4; c < d; c += 256) {
         const float4 vy = *reinterpret_cast<const float4 *>(dy + t * d + c);
-        const float4 vo = *reinterpret_cast<const float4 *>(out_sorted + r * d + c);
+        const float4 vo = stream_load4(reinterpret_cast<const float4 *>(out_sorted + r * d + c));   // read once here
         dot = fmaf(vy.x, vo.x, dot); dot = fmaf(vy.y, vo.y, dot);
         dot = fmaf(vy.z, vo.z, dot); dot = fmaf(vy.w, vo.w, dot);
         *reinterpret_cast<float4 *>(dout + r * d + c) = make_float4(g * vy.x, g * vy.y, g * vy.z, g * vy.w);

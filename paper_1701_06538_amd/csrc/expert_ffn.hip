@@ -221,8 +221,8 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
         for (int i = tid; i < TM * U4; i += 512) {
             const int r = i / U4, cc = i % U4;
             if (r < rows)
-                *reinterpret_cast<uint4 *>(p.xs_out + (size_t)(row0 + r) * D + 8 * cc) =
-                    *reinterpret_cast<const uint4 *>(lds + (size_t)r * XS + 8 * cc);
+                MOE_STREAM_STORE(*reinterpret_cast<const v4u *>(lds + (size_t)r * XS + 8 * cc),   // kept for the backward pass: written once
+                                 reinterpret_cast<v4u *>(p.xs_out + (size_t)(row0 + r) * D + 8 * cc));
         }
     }
 
@@ -259,8 +259,8 @@ __global__ __launch_bounds__(512) void ffn_bf16_kernel(FfnArgs p) {
         for (int i = tid; i < TM * U4; i += 512) {
             const int r = i / U4, cc = i % U4;
             if (r < rows)
-                *reinterpret_cast<uint4 *>(p.hid_out + (size_t)(row0 + r) * H + 8 * cc) =
-                    *reinterpret_cast<const uint4 *>(lds + (size_t)r * HS + 8 * cc);
+                MOE_STREAM_STORE(*reinterpret_cast<const v4u *>(lds + (size_t)r * HS + 8 * cc),   // kept for the backward pass: written once
+                                 reinterpret_cast<v4u *>(p.hid_out + (size_t)(row0 + r) * H + 8 * cc));
         }
     }
 
@@ -421,8 +421,8 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
         for (int i = tid; i < TM * U4; i += 256) {
             const int r = i / U4, cc = i % U4;
             if (r < rows)
-                *reinterpret_cast<uint4 *>(p.xs_out + (size_t)(row0 + r) * D + 8 * cc) =
-                    *reinterpret_cast<const uint4 *>(lds + (size_t)r * XS + 8 * cc);
+                MOE_STREAM_STORE(*reinterpret_cast<const v4u *>(lds + (size_t)r * XS + 8 * cc),   // kept for the backward pass: written once
+                                 reinterpret_cast<v4u *>(p.xs_out + (size_t)(row0 + r) * D + 8 * cc));
         }
     }
 
@@ -460,8 +460,8 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
         for (int i = tid; i < TM * U4; i += 256) {
             const int r = i / U4, cc = i % U4;
             if (r < rows)
-                *reinterpret_cast<uint4 *>(p.hid_out + (size_t)(row0 + r) * H + 8 * cc) =
-                    *reinterpret_cast<const uint4 *>(lds + (size_t)r * HS + 8 * cc);
+                MOE_STREAM_STORE(*reinterpret_cast<const v4u *>(lds + (size_t)r * HS + 8 * cc),   // kept for the backward pass: written once
+                                 reinterpret_cast<v4u *>(p.hid_out + (size_t)(row0 + r) * H + 8 * cc));
         }
     }
     {
