@@ -47,8 +47,8 @@ enum { MOE_DTYPE_F32 = 0, MOE_DTYPE_BF16 = 1 };
  * Supported: d % 32 == 0; bf16 experts: d and h multiples of 128 (the paper's 512 x 1024 expert
  * runs on a fused kernel that keeps the hidden layer on chip, other shapes on a plain two-GEMM
  * path with the hidden layer in the workspace); fp32 experts: d and h multiples of 4;
- * 1 <= k <= min(n, 8) (per level when hierarchical); n <= 16384, at most 2048 experts per
- * gating level; T*k < 2^31.  moe_layer_backward: n a multiple of 4; bf16 experts with d and h
+ * 1 <= k <= min(n, 8) (per level when hierarchical); n <= 16384 (flat, or a*b with either level up
+ * to 16384); T*k < 2^31.  moe_layer_backward: n a multiple of 4; bf16 experts with d and h
  * multiples of 256, or fp32 experts. */
 typedef struct moe_config {
     int32_t T;             /* tokens in the batch */

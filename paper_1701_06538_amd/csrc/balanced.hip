@@ -616,7 +616,7 @@ static int softmax_gate_check(const moe_config *cfg) {
     int st = check_config(cfg);
     if (st != MOE_OK) return st;
     if (cfg->a != 0) return MOE_EINVAL;
-    if (cfg->n > kMaxGateExperts) return MOE_EUNSUPPORTED;
+    if (cfg->n > kMaxBalancedExperts) return MOE_EUNSUPPORTED;
     if (cfg->d > 2048) return MOE_EUNSUPPORTED;                        // combine: 8 float4 per lane
     return MOE_OK;
 }

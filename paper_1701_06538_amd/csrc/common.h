@@ -55,7 +55,8 @@ int check_gate_level(int64_t T, int d, int n, int k);
 constexpr int kGateBM = 128;       // rows per block tile of the logits kernel
 constexpr int kMaxK = 8;
 constexpr int kMaxExperts = 16384;   // route histograms live in 64 KB of LDS
-constexpr int kMaxGateExperts = 2048;  // experts of one gating level (top-k kernel accumulators)
+constexpr int kMaxGateExperts = 16384;  // experts of one gating level (the wide top-k kernel walks 2048-column chunks)
+constexpr int kMaxBalancedExperts = 2048;  // strictly balanced gating: one column-selection workgroup per expert, softmax rows in registers
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 

@@ -554,14 +554,17 @@ __global__ __launch_bounds__(256, 2) void gate_topk_kernel(TopkArgs p) {
     }
 }
 
-// Long rows (n > 1024): the four wavefronts of a workgroup share one row, a quarter each, so a lane
-// holds at most NCH = n/256 logits (the one-wave-per-row kernel would need 32 and spills).  Each
+// Long rows (n > 1024): the four wavefronts of a workgroup share one row; a row is NCK chunks of
+// 2048 columns and a wave owns a quarter of every chunk, so a lane holds NCH = 8 logits at a time
+// (the one-wave-per-row kernel would need 32 and spills).  Rows of up to 2048 experts are one chunk
+// that stays in registers for both passes; longer rows walk their chunks twice.  Each
 // wave finds the k+1 best of its quarter, the 4(k+1) candidates meet in LDS, every wave merges
 // them (identically) into the row's k+1 best, and then evaluates P(x,i) on its own quarter.  A
 // wave keeps the same columns for every row of the workgroup, so the Load sums need no exchange
 // at all; Importance is added by the first wave alone, row after row.
-template <int L, int NCH>
+template <int L, int NCH, int NCK>   // NCK chunks of 256 * NCH columns cover the row
 __global__ __launch_bounds__(256, 2) void gate_topk_wide_kernel(TopkArgs p) {
+    constexpr int CW = 256 * NCH;                 // columns of one chunk
     extern __shared__ float lds_imp[];            // Importance of the block [n]
     __shared__ uint64_t cand[2][4][L];            // per row parity, per wave
     const int tid = threadIdx.x, lane = tid & 63;
@@ -584,10 +587,12 @@ __global__ __launch_bounds__(256, 2) void gate_topk_wide_kernel(TopkArgs p) {
         re = min(rb + RPB, p.R);
     }
     const int kp1 = (k < n) ? k + 1 : k;
-    const int col_base = wave * 64 * NCH;         // this wave's quarter of the row
-    float acc_load[NCH];
+    const int col_base = wave * 64 * NCH;         // this wave's quarter of every chunk
+    float acc_load[NCK][NCH];
 #pragma unroll
-    for (int q = 0; q < NCH; ++q) acc_load[q] = 0.f;
+    for (int cb = 0; cb < NCK; ++cb)
+#pragma unroll
+        for (int q = 0; q < NCH; ++q) acc_load[cb][q] = 0.f;
     for (int i = tid; i < n; i += 256) lds_imp[i] = 0.f;
     __syncthreads();
 
@@ -599,38 +604,45 @@ __global__ __launch_bounds__(256, 2) void gate_topk_wide_kernel(TopkArgs p) {
         const int64_t orow = p.row_map ? p.row_map[r] : r;
         const float *e_row = p.eps ? uniform_ptr(p.eps + orow * n) : nullptr;
 
+        // one chunk of this wave's columns: clean, Softplus and H (unconditional clamped loads)
         float cv[NCH], sv[NCH], hv[NCH];
+        auto load_chunk = [&](int cb) {
 #pragma unroll
-        for (int q = 0; q < NCH; ++q) {
-            const unsigned i = min((unsigned)(col_base + lane + 64 * q), (unsigned)(n - 1));
-            cv[q] = c_row[i];
-            sv[q] = s_row[i];
-        }
-        if (e_row) {
+            for (int q = 0; q < NCH; ++q) {
+                const unsigned i = min((unsigned)(cb * CW + col_base + lane + 64 * q), (unsigned)(n - 1));
+                cv[q] = c_row[i];
+                sv[q] = s_row[i];
+            }
+            if (e_row) {
 #pragma unroll
-            for (int q = 0; q < NCH; ++q)
-                hv[q] = e_row[min((unsigned)(col_base + lane + 64 * q), (unsigned)(n - 1))];
+                for (int q = 0; q < NCH; ++q)
+                    hv[q] = e_row[min((unsigned)(cb * CW + col_base + lane + 64 * q), (unsigned)(n - 1))];
 #pragma unroll
-            for (int q = 0; q < NCH; ++q) hv[q] = __fmaf_rn(hv[q], sv[q], cv[q]);
-        } else {
+                for (int q = 0; q < NCH; ++q) hv[q] = __fmaf_rn(hv[q], sv[q], cv[q]);
+            } else {
 #pragma unroll
-            for (int q = 0; q < NCH; ++q) hv[q] = cv[q];
-        }
+                for (int q = 0; q < NCH; ++q) hv[q] = cv[q];
+            }
+        };
 
-        // the quarter's k+1 best: per-lane sorted lists, then wave-wide maxima
+        // this wave's k+1 best over all its chunks: per-lane sorted lists, then wave-wide maxima
         uint64_t lk[L];
 #pragma unroll
         for (int j = 0; j < L; ++j) lk[j] = 0;
+#pragma unroll 1
+        for (int cb = 0; cb < NCK; ++cb) {
+            load_chunk(cb);
 #pragma unroll
-        for (int q = 0; q < NCH; ++q) {
-            const int i = col_base + lane + 64 * q;
-            uint64_t key = i < n ? sel_key(hv[q], i) : 0;
+            for (int q = 0; q < NCH; ++q) {
+                const int i = cb * CW + col_base + lane + 64 * q;
+                uint64_t key = i < n ? sel_key(hv[q], i) : 0;
 #pragma unroll
-            for (int j = 0; j < L; ++j) {
-                const bool up = key > lk[j];
-                const uint64_t lo = up ? lk[j] : key;
-                lk[j] = up ? key : lk[j];
-                key = lo;
+                for (int j = 0; j < L; ++j) {
+                    const bool up = key > lk[j];
+                    const uint64_t lo = up ? lk[j] : key;
+                    lk[j] = up ? key : lk[j];
+                    key = lo;
+                }
             }
         }
         uint64_t mine = 0;   // lane j keeps the quarter's j-th best
@@ -699,28 +711,37 @@ __global__ __launch_bounds__(256, 2) void gate_topk_wide_kernel(TopkArgs p) {
             }
             if (lane == 0 && p.next_idx) p.next_idx[orow] = nxt;
         }
-        // Eq.(9) on this wave's quarter
+        // Eq.(9) on this wave's columns.  A single chunk is still in registers; several chunks are
+        // fetched again (the same loads and the same fused multiply-add give the same H).
         if (k < n) {
+#pragma unroll 1
+            for (int cb = 0; cb < NCK; ++cb) {
+                if (NCK > 1) load_chunk(cb);
 #pragma unroll
-            for (int q = 0; q < NCH; ++q) {
-                const int i = col_base + lane + 64 * q;
-                const float u = (cv[q] - (hv[q] >= thr_out ? thr_in : thr_out)) * load_inv_sigma(sv[q]);
-                const float P = normal_cdf(u);
-                acc_load[q] += i < n ? P : 0.f;
+                for (int q = 0; q < NCH; ++q) {
+                    const int i = cb * CW + col_base + lane + 64 * q;
+                    const float u = (cv[q] - (hv[q] >= thr_out ? thr_in : thr_out)) * load_inv_sigma(sv[q]);
+                    const float P = normal_cdf(u);
+                    acc_load[cb][q] += i < n ? P : 0.f;
+                }
             }
         } else {
 #pragma unroll
-            for (int q = 0; q < NCH; ++q) acc_load[q] += (col_base + lane + 64 * q) < n ? 1.0f : 0.f;
+            for (int cb = 0; cb < NCK; ++cb)
+#pragma unroll
+                for (int q = 0; q < NCH; ++q) acc_load[cb][q] += (cb * CW + col_base + lane + 64 * q) < n ? 1.0f : 0.f;
         }
     }
     __syncthreads();
     float *out = p.partials + (size_t)blockIdx.x * 2 * n;
     for (int i = tid; i < n; i += 256) out[i] = lds_imp[i];
 #pragma unroll
-    for (int q = 0; q < NCH; ++q) {
-        const int i = col_base + lane + 64 * q;
-        if (i < n) out[n + i] = acc_load[q];
-    }
+    for (int cb = 0; cb < NCK; ++cb)
+#pragma unroll
+        for (int q = 0; q < NCH; ++q) {
+            const int i = cb * CW + col_base + lane + 64 * q;
+            if (i < n) out[n + i] = acc_load[cb][q];
+        }
 }
 
 // Eq.(12): global expert id and gate product for every (token, primary slot, secondary slot)
@@ -776,19 +797,28 @@ int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
 }
 
 template <int L>
-static void launch_topk_nch(const TopkArgs &a, unsigned blocks, size_t lds, hipStream_t st) {
+static int launch_topk_nch(const TopkArgs &a, unsigned blocks, size_t lds, hipStream_t st) {
+    const size_t wide_lds = (size_t)a.n * sizeof(float);
     if (a.n <= 256) hipLaunchKernelGGL((gate_topk_kernel<L, 4>), dim3(blocks), dim3(256), lds, st, a);
     else if (a.n <= 512) hipLaunchKernelGGL((gate_topk_kernel<L, 8>), dim3(blocks), dim3(256), lds, st, a);
     else if (a.n <= 1024) hipLaunchKernelGGL((gate_topk_kernel<L, 16>), dim3(blocks), dim3(256), lds, st, a);
-    else hipLaunchKernelGGL((gate_topk_wide_kernel<L, 8>), dim3(blocks), dim3(256), (size_t)a.n * sizeof(float), st, a);
+    else if (a.n <= 2048) hipLaunchKernelGGL((gate_topk_wide_kernel<L, 8, 1>), dim3(blocks), dim3(256), wide_lds, st, a);
+    else if (a.n <= 4096) hipLaunchKernelGGL((gate_topk_wide_kernel<L, 8, 2>), dim3(blocks), dim3(256), wide_lds, st, a);
+    else if (a.n <= 8192) hipLaunchKernelGGL((gate_topk_wide_kernel<L, 8, 4>), dim3(blocks), dim3(256), wide_lds, st, a);
+    else {
+        static LdsLimitOnce lds_once;   // 64 KB of Importance sums beside the candidate exchange
+        MOE_TRY(lds_once.set((const void *)gate_topk_wide_kernel<L, 8, 8>, wide_lds));
+        hipLaunchKernelGGL((gate_topk_wide_kernel<L, 8, 8>), dim3(blocks), dim3(256), wide_lds, st, a);
+    }
+    return MOE_OK;
 }
 
 int launch_gate_topk(const TopkArgs &a, int64_t blocks, hipStream_t st) {
     if (blocks <= 0) return MOE_OK;
     const size_t lds = (size_t)5 * a.n * sizeof(float);
-    if (a.k + 1 <= 3) launch_topk_nch<3>(a, (unsigned)blocks, lds, st);
-    else if (a.k + 1 <= 5) launch_topk_nch<5>(a, (unsigned)blocks, lds, st);
-    else launch_topk_nch<9>(a, (unsigned)blocks, lds, st);
+    if (a.k + 1 <= 3) MOE_TRY(launch_topk_nch<3>(a, (unsigned)blocks, lds, st));
+    else if (a.k + 1 <= 5) MOE_TRY(launch_topk_nch<5>(a, (unsigned)blocks, lds, st));
+    else MOE_TRY(launch_topk_nch<9>(a, (unsigned)blocks, lds, st));
     MOE_LAUNCH_CHECK();
     return MOE_OK;
 }

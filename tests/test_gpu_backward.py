@@ -81,6 +81,7 @@ CASES = [
     # fp32 experts: every GEMM on the fp32 matrix cores
     ("cfg0_f32", dict(T=256, n=16, k=4, expert_dtype="f32"), False, 0),
     ("f32_ragged", dict(T=150, d=64, h=96, n=8, k=2, expert_dtype="f32"), True, 0),
+    ("n4096_f32", dict(T=96, d=64, h=64, n=4096, k=2, expert_dtype="f32"), False, 0),   # a flat gate wider than 2048 experts
 ]
 TOL_F32_EXPERTS = 1e-5
 

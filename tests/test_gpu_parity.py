@@ -155,6 +155,13 @@ WIDE_CASES = [
     ("n2047_k1_noise_free", 2047, 1, 75, True, False),
     ("n2047_k3", 2047, 3, 140, True, True),
     ("n2047_k8", 2047, 8, 50, False, True),
+    # more than 2048 experts in one gating level: rows walked as chunks of 2048 columns (2, 4 and 8
+    # chunks, the last one partly or wholly past the end of the row)
+    ("n4096_k4", 4096, 4, 70, False, True),
+    ("n5000_k8", 5000, 8, 40, True, True),
+    ("n8192_k2_noise_free", 8192, 2, 33, False, False),
+    ("n12345_k4", 12345, 4, 24, True, True),
+    ("n16384_k8", 16384, 8, 20, False, True),
 ]
 
 
@@ -167,7 +174,9 @@ def test_gate_wide_rows(api, name, n, k, T, with_bias, noise):
     x, W_g, W_noise, eps, bias = G.flat_inputs(shape, with_bias)
     # in-row ties: duplicated gate columns (same clean and raw logit) with the same noise draw give
     # equal H at different experts, some of them across the quarters the four waves own
-    for src, dst in ((3, 700), (3, n - 1), (510, 511), (1023, 1024)):
+    for src, dst in ((3, 700), (3, n - 1), (510, 511), (1023, 1024), (2047, 2048), (5, n // 2 + 1)):
+        if max(src, dst) >= n:
+            continue
         W_g[:, dst], W_noise[:, dst], eps[:, dst] = W_g[:, src], W_noise[:, src], eps[:, src]
         if bias is not None:
             bias[dst] = bias[src]
