@@ -46,6 +46,16 @@ def check_device_weights(shape, W1, W2, experts):
         assert torch.equal(W2[e].cpu(), W.expert_weights(shape, 1, int(e))), e
 
 
+def weight_fn_for(shape, W1, W2, many=512):
+    """The oracle's expert matrices: from the host generator for layers of fewer than `many`
+    experts, else from the generator's device tensors (checked against the host generator on three
+    experts): regenerating a thousand 512 x 1024 pairs on the host takes half a minute."""
+    if shape.n < many:
+        return oracle_weight_fn(shape)
+    check_device_weights(shape, W1, W2, [0, shape.n // 2 + 1, shape.n - 1])
+    return device_weight_fn(shape, W1, W2, block=16)
+
+
 def oracle_flat(shape, x, W_g, W_noise, eps, bias):
     from oracle import moe_oracle as O
     lg = O.noisy_logits_f32(x, W_g, W_noise, eps, bias)

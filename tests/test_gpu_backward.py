@@ -94,7 +94,7 @@ def test_backward_parity(api, name, ov, with_bias, flags):
     say("case backward", name, shape)
     dy = W.upstream_grad(shape)
     shape, inputs, run, out, call = run_backward(api, shape, with_bias, dy, flags=flags)
-    fw, gr = oracle_backward(shape, inputs, dy)
+    fw, gr = oracle_backward(shape, inputs, dy, weight_fn=G.weight_fn_for(shape, run.W1, run.W2))
     assert np.array_equal(run.topk_idx.cpu().numpy(), fw.idx)
     errs = dict(dx=G.rel_errors(out["dx"].cpu().numpy(), gr.dx)[0],
                 dW_g=fro_rel(out["dW_g"].cpu().numpy(), gr.dW_g),

@@ -71,7 +71,7 @@ def test_hier_layer_parity(api, name, ov):
     run = G.HierRun(api, shape, inputs, W1, W2)
     run.forward()
     check_hier_gate(run, hf, shape)
-    y_ref = O.moe_output(inputs[0], hf.idx, hf.gates, G.oracle_weight_fn(shape), shape.n)
+    y_ref = O.moe_output(inputs[0], hf.idx, hf.gates, G.weight_fn_for(shape, W1, W2), shape.n)
     row, mx = G.rel_errors(run.y.cpu().numpy(), y_ref)
     say("  y errors: row-rel %.3e max-abs-rel %.3e" % (row, mx))
     assert row <= TOL_BF16 and mx <= TOL_BF16

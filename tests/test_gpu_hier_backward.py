@@ -57,10 +57,10 @@ def run_hier_backward(api, shape, dy, gate_std=0.02, flags=0):
     return inputs, run, out, call
 
 
-def oracle_hier_backward(shape, inputs, dy, experts_for_dW=None):
+def oracle_hier_backward(shape, inputs, dy, experts_for_dW=None, weight_fn=None):
     x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s = inputs
     return O.hier_backward(x, Wg_p, Wn_p, eps_p, Wg_s, Wn_s, eps_s, shape.k_primary, shape.k_secondary,
-                           G.oracle_weight_fn(shape), dy, shape.w_importance, shape.w_load,
+                           weight_fn or G.oracle_weight_fn(shape), dy, shape.w_importance, shape.w_load,
                            experts_for_dW=experts_for_dW, expert_input=O.round_to_bf16(x))
 
 
@@ -91,7 +91,7 @@ def test_hier_backward_parity(api, name, ov, std, wl):
     inputs, run, out, call = run_hier_backward(api, shape, dy, std, flags)
     hf = O.hier_gate_and_losses(*inputs, shape.k_primary, shape.k_secondary, shape.w_importance, shape.w_load)
     assert np.array_equal(run.topk_idx.cpu().numpy(), hf.idx)
-    gr = oracle_hier_backward(shape, inputs, dy)
+    gr = oracle_hier_backward(shape, inputs, dy, weight_fn=G.weight_fn_for(shape, run.W1, run.W2, many=2048))
     errs = dict(dx=G.rel_errors(out["dx"].cpu().numpy(), gr.dx)[0],
                 dWg_p=fro_rel(out["dWg_p"].cpu().numpy(), gr.dWg_p),
                 dWn_p=fro_rel(out["dWn_p"].cpu().numpy(), gr.dWn_p),
