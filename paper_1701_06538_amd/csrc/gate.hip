@@ -799,7 +799,9 @@ int launch_gate_logits(const LogitsArgs &a, int64_t row_tiles, hipStream_t st) {
 template <int L>
 static int launch_topk_nch(const TopkArgs &a, unsigned blocks, size_t lds, hipStream_t st) {
     const size_t wide_lds = (size_t)a.n * sizeof(float);
-    if (a.n <= 256) hipLaunchKernelGGL((gate_topk_kernel<L, 4>), dim3(blocks), dim3(256), lds, st, a);
+    if (a.n <= 64) hipLaunchKernelGGL((gate_topk_kernel<L, 1>), dim3(blocks), dim3(256), lds, st, a);
+    else if (a.n <= 128) hipLaunchKernelGGL((gate_topk_kernel<L, 2>), dim3(blocks), dim3(256), lds, st, a);
+    else if (a.n <= 256) hipLaunchKernelGGL((gate_topk_kernel<L, 4>), dim3(blocks), dim3(256), lds, st, a);
     else if (a.n <= 512) hipLaunchKernelGGL((gate_topk_kernel<L, 8>), dim3(blocks), dim3(256), lds, st, a);
     else if (a.n <= 1024) hipLaunchKernelGGL((gate_topk_kernel<L, 16>), dim3(blocks), dim3(256), lds, st, a);
     else if (a.n <= 2048) hipLaunchKernelGGL((gate_topk_wide_kernel<L, 8, 1>), dim3(blocks), dim3(256), wide_lds, st, a);
