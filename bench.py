@@ -377,6 +377,28 @@ def run_workload(cfg_index, args, hip, K, warmup):
                             "algorithmic_bytes": opt_bytes, "bound": "hbm",
                             "achieved": opt_bytes / (opt_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": opt_bytes / (opt_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    if args.epilogue and not balanced:
+        # the combine with the layer's tail fused in (sigmoid, dropout, residual), on the rows and
+        # gate values the last step left in the workspace; own event pairs, outside the timed region
+        drop = 0.4
+        keep = G.dev(W.dropout_keep(shape, drop))
+        view = lambda off, count, dt: ws[off:off + count * 4].view(dt)
+        rows = view(lay.out_sorted, A * shape.d, torch.float32)
+        inv = view(lay.inv_perm, A, torch.int32)
+        y2 = torch.empty((shape.T, shape.d), **f32)
+        epi_ev = [(hip.create(), hip.create()) for _ in range(reps + 2)]
+        for e0, e1 in epi_ev:
+            hip.record(e0)
+            api.moe_combine_epilogue(run.cfg, rows, run.topk_gate, inv, run.x, keep, drop, y2)
+            hip.record(e1)
+        torch.cuda.synchronize()
+        epi_ms = float(np.median([hip.elapsed_ms(a, b) for a, b in epi_ev[2:]]))
+        # expert rows and y as in the combine, plus the residual input (fp32) and the dropout draw (bytes)
+        epi_bytes = comb_bytes + shape.T * shape.d * 4 + shape.T * shape.d
+        out["combine_epilogue"] = {"kernel": "moe_combine_epilogue (sigmoid, dropout %.1f, residual)" % drop,
+                                   "ms": epi_ms, "algorithmic_bytes": epi_bytes, "bound": "hbm",
+                                   "achieved": epi_bytes / (epi_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                                   "unit": "GB/s", "frac": epi_bytes / (epi_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     if not args.no_cpu_baseline:
         sample = args.cpu_sample
         if balanced:
@@ -402,6 +424,8 @@ def main():
                          "(flat forward configs only; needs --config)")
     ap.add_argument("--backward", action="store_true",
                     help="hierarchical config, or --gating balanced: time forward + backward per step")
+    ap.add_argument("--epilogue", action="store_true",
+                    help="also time moe_combine_epilogue (combine + sigmoid, dropout, residual) on the step's rows")
     ap.add_argument("--optimizer", action="store_true",
                     help="training config: also time the factored-second-moment Adam step of the expert "
                          "matrices (outside the timed region; reported under \"optimizer\")")

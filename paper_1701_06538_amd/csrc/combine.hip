@@ -35,11 +35,17 @@ __global__ __launch_bounds__(256) void combine_epilogue_kernel(const float4 *__r
         g[s] = s < k ? gate[t * k + s] : 0.f;
     }
     for (int c = lane; c < d4; c += 64) {
+        // the mask and the residual are requested first, so that they travel with the expert rows
+        // instead of after the arithmetic on them; rows, mask and y are touched once: streaming
+        uint32_t m = 0xffffffffu;
+        float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (keep) m = __builtin_nontemporal_load(keep + t * d4 + c);   // four mask bytes
+        if (x) r = x[t * d4 + c];
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int s = 0; s < kMaxK; ++s) {
             if (s < k) {
-                const float4 v = out_sorted[(int64_t)rows[s] * d4 + c];
+                const float4 v = stream_load4(out_sorted + (int64_t)rows[s] * d4 + c);
                 acc.x = fmaf(g[s], v.x, acc.x);
                 acc.y = fmaf(g[s], v.y, acc.y);
                 acc.z = fmaf(g[s], v.z, acc.z);
@@ -51,18 +57,11 @@ __global__ __launch_bounds__(256) void combine_epilogue_kernel(const float4 *__r
         o.y = inv_keep_prob / (1.0f + expf(-acc.y));
         o.z = inv_keep_prob / (1.0f + expf(-acc.z));
         o.w = inv_keep_prob / (1.0f + expf(-acc.w));
-        if (keep) {
-            const uint32_t m = keep[t * d4 + c];          // four mask bytes
-            o.x = (m & 0xffu) ? o.x : 0.f;
-            o.y = (m & 0xff00u) ? o.y : 0.f;
-            o.z = (m & 0xff0000u) ? o.z : 0.f;
-            o.w = (m & 0xff000000u) ? o.w : 0.f;
-        }
-        if (x) {
-            const float4 r = x[t * d4 + c];
-            o.x += r.x; o.y += r.y; o.z += r.z; o.w += r.w;
-        }
-        y[t * d4 + c] = o;
+        o.x = ((m & 0xffu) ? o.x : 0.f) + r.x;
+        o.y = ((m & 0xff00u) ? o.y : 0.f) + r.y;
+        o.z = ((m & 0xff0000u) ? o.z : 0.f) + r.z;
+        o.w = ((m & 0xff000000u) ? o.w : 0.f) + r.w;
+        stream_store4(y + t * d4 + c, o);
     }
 }
 

@@ -288,6 +288,58 @@ __device__ __forceinline__ void cv2_body(const double *__restrict__ sums64, int 
 // ---------------------------------------------------------------------------------------
 // combine (Eq.(1)): block `block` handles tokens 4*block .. 4*block+3, one wavefront each
 // ---------------------------------------------------------------------------------------
+// One token with k = KC known at compile time (KC = 0: any k up to kMaxK, slot by slot): the row
+// loads of a column are all issued before the first multiply-add waits for one of them.
+template <int KC>
+__device__ __forceinline__ void combine_token(const float4 *__restrict__ out_sorted,
+                                              const float *__restrict__ gate,
+                                              const int32_t *__restrict__ inv_perm,
+                                              float4 *__restrict__ y, int64_t t, int d4, int k, int lane) {
+    constexpr int KN = KC ? KC : kMaxK;
+    int rows[KN];
+    float g[KN];
+#pragma unroll
+    for (int s = 0; s < KN; ++s) {
+        rows[s] = s < k ? inv_perm[t * k + s] : 0;
+        g[s] = s < k ? gate[t * k + s] : 0.f;
+    }
+    auto column = [&](int c) {
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (KC) {
+            float4 v[KN];
+#pragma unroll
+            for (int s = 0; s < KN; ++s)   // every expert output row is read exactly once: streaming loads
+                v[s] = stream_load4(out_sorted + (int64_t)rows[s] * d4 + c);
+#pragma unroll
+            for (int s = 0; s < KN; ++s) {
+                acc.x = fmaf(g[s], v[s].x, acc.x);
+                acc.y = fmaf(g[s], v[s].y, acc.y);
+                acc.z = fmaf(g[s], v[s].z, acc.z);
+                acc.w = fmaf(g[s], v[s].w, acc.w);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < KN; ++s) {
+                if (s < k) {
+                    const float4 v = stream_load4(out_sorted + (int64_t)rows[s] * d4 + c);
+                    acc.x = fmaf(g[s], v.x, acc.x);
+                    acc.y = fmaf(g[s], v.y, acc.y);
+                    acc.z = fmaf(g[s], v.z, acc.z);
+                    acc.w = fmaf(g[s], v.w, acc.w);
+                }
+            }
+        }
+        stream_store4(y + t * d4 + c, acc);
+    };
+    if (d4 == 128) {
+        // the paper's d = 512: both 16-byte columns of a lane at once
+#pragma unroll
+        for (int i = 0; i < 2; ++i) column(lane + 64 * i);
+    } else {
+        for (int c = lane; c < d4; c += 64) column(c);
+    }
+}
+
 __device__ __forceinline__ void combine_body(const float4 *__restrict__ out_sorted,
                                              const float *__restrict__ gate,
                                              const int32_t *__restrict__ inv_perm,
@@ -296,28 +348,11 @@ __device__ __forceinline__ void combine_body(const float4 *__restrict__ out_sort
     const int lane = threadIdx.x & 63;
     const int64_t t = block * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
-    int rows[kMaxK];
-    float g[kMaxK];
-#pragma unroll
-    for (int s = 0; s < kMaxK; ++s) {
-        rows[s] = s < k ? inv_perm[t * k + s] : 0;
-        g[s] = s < k ? gate[t * k + s] : 0.f;
-    }
-    for (int c = lane; c < d4; c += 64) {
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int s = 0; s < kMaxK; ++s) {
-            if (s < k) {
-                // every expert output row is read exactly once: a streaming load
-                const float4 v = stream_load4(out_sorted + (int64_t)rows[s] * d4 + c);
-                acc.x = fmaf(g[s], v.x, acc.x);
-                acc.y = fmaf(g[s], v.y, acc.y);
-                acc.z = fmaf(g[s], v.z, acc.z);
-                acc.w = fmaf(g[s], v.w, acc.w);
-            }
-        }
-        stream_store4(y + t * d4 + c, acc);
-    }
+    // slots in ascending order in every form: the same sequence of fused multiply-adds
+    if (k == 4) combine_token<4>(out_sorted, gate, inv_perm, y, t, d4, k, lane);
+    else if (k == 2) combine_token<2>(out_sorted, gate, inv_perm, y, t, d4, k, lane);
+    else if (k == 1) combine_token<1>(out_sorted, gate, inv_perm, y, t, d4, k, lane);
+    else combine_token<0>(out_sorted, gate, inv_perm, y, t, d4, k, lane);
 }
 
 }  // namespace moe
