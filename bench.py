@@ -404,9 +404,9 @@ def run_workload(cfg_index, args, hip, K, warmup):
         if balanced:
             out["cpu_baseline"] = cpu_baseline_balanced(shape, inputs, W1, W2, sample or 8192)
         elif shape.hierarchical:
-            out["cpu_baseline"] = cpu_baseline_hier(shape, inputs, W1, W2, dy, sample or 256, backward)
+            out["cpu_baseline"] = cpu_baseline_hier(shape, inputs, W1, W2, dy, sample or 1024, backward)
         else:
-            default = {0: 256, 1: 8192, 2: 512, 4: 1024}.get(cfg_index, 1024)
+            default = {0: 256, 1: 8192, 2: 8192, 4: 16384}.get(cfg_index, 1024)
             out["cpu_baseline"] = cpu_baseline_flat(shape, inputs, W1, W2, dy, sample or default)
     return out
 
@@ -431,7 +431,7 @@ def main():
                          "matrices (outside the timed region; reported under \"optimizer\")")
     ap.add_argument("--cpu-sample", type=int, default=None,
                     help="tokens of the workload the oracle is timed on (default per workload: 256 / 8192 / "
-                         "512 / 256 / 1024, a few seconds of host time each)")
+                         "8192 / 1024 / 16384 for configs 0 ... 4, up to ten seconds of host time each)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel, so that rocprofv3 --pmc "
