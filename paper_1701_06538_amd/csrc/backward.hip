@@ -761,7 +761,7 @@ static int bwd_layout(const moe_config *cfg, BwdLayout *L) {
     if (ks < 1) ks = 1;
     L->ksplit = ks;
     L->wpart = take((size_t)ks * 2 * d * n * 4);
-    const size_t MT = (size_t)ceil_div((int64_t)A, GBM) + n + 8;
+    const size_t MT = (size_t)ceil_div((int64_t)A, kFfnBwdTileRows) + n + 8;   // the shortest tiles any kernel here asks for
     L->tile_expert = take(MT * 4);
     L->tile_row0 = take(MT * 4);
     L->num_tiles = take(16);
@@ -911,6 +911,19 @@ static int run_expert_backward(const moe_config *cfg, const ExpertBwd &b, hipStr
         GGRows g1{xs, (const uint16_t *)b.W1, b.hid, nullptr, d, h, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
         if ((st = launch_gg_rows128(g1, true, EPI_RELU_BF16, max_tiles, s)) != MOE_OK) return st;
         hid = b.hid;
+    }
+    if (ffn_bwd_rows_applies(cfg)) {
+        // about one tile of rows per expert: both row products in one launch that streams the
+        // expert's matrices once (the forward kernel's regime, run backwards)
+        if ((st = launch_build_tiles(b.offsets, n, kFfnBwdTileRows, b.tile_expert, b.tile_row0, b.num_tiles, s)) != MOE_OK)
+            return st;
+        FfnBwdRows fr{b.dout, hid, b.W1, b.W2, b.dz, b.dxs, b.offsets, b.tile_expert, b.tile_row0, b.num_tiles};
+        if ((st = launch_ffn_bwd_rows(fr, ceil_div(A, kFfnBwdTileRows) + n, s)) != MOE_OK) return st;
+        if ((st = launch_expert_order(b.offsets, n, b.order, s)) != MOE_OK) return st;
+        GGWgrad w2{hid, b.dout, b.dW2, h, d, b.offsets, b.order, b.mom[2], b.mom[3]};
+        if ((st = launch_gg_wgrad(w2, n, s)) != MOE_OK) return st;
+        GGWgrad w1{xs, b.dz, b.dW1, d, h, b.offsets, b.order, b.mom[0], b.mom[1]};
+        return launch_gg_wgrad(w1, n, s);
     }
     // the two compute-bound GEMMs of the expert backward run on 256-row tiles
     if ((st = launch_build_tiles(b.offsets, n, 256, b.tile_expert, b.tile_row0, b.num_tiles, s)) != MOE_OK) return st;
@@ -1257,7 +1270,7 @@ static void hier_bwd_layout(const moe_config *cfg, HierBwdLayout *L) {
     L->dgate = take(A * 4);
     L->gI = take(n * 4);
     L->gL = take(n * 4);
-    const size_t MT = (size_t)ceil_div((int64_t)A, GBM) + n + 8;
+    const size_t MT = (size_t)ceil_div((int64_t)A, kFfnBwdTileRows) + n + 8;   // the shortest tiles any kernel here asks for
     L->tile_expert = take(MT * 4);
     L->tile_row0 = take(MT * 4);
     L->num_tiles = take(16);

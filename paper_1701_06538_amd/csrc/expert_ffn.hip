@@ -59,7 +59,8 @@ __device__ __forceinline__ int xcd_tile(int bid, int num_tiles) {
 struct TileCoord {
     int e, row0, rows;
 };
-__device__ __forceinline__ bool load_tile(const FfnArgs &p, int TM, TileCoord &t) {
+template <class Args>
+__device__ __forceinline__ bool load_tile(const Args &p, int TM, TileCoord &t) {
     const int num = *p.num_tiles;
     const int tile = xcd_tile(blockIdx.x, num);
     if (tile < 0) return false;
@@ -482,6 +483,201 @@ __global__ __launch_bounds__(256) void ffn_bf16_w4_kernel(FfnArgs p) {
                 store_out4(dst + 4, v4f{acc[0][rt][4][r], acc[0][rt][5][r], acc[0][rt][6][r], acc[0][rt][7][r]});
             }
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Backward through the two layers of an expert for routed rows, where experts hold about one tile
+// of rows (the forward pass's four-wave regime): dz = (dout W2^T) * [hid > 0] (bf16, kept for the
+// weight gradient) and dxs = dz W1^T in ONE launch that streams both matrices once per tile, the
+// dz tile staying in LDS between the products -- the forward kernel run backwards.  Both products
+// contract over the CONTIGUOUS index of the row-major weight matrices, so a lane's 16-byte load
+// is a matrix-core operand as it stands (no register transpose): the weights are the A operand
+// (16 weight rows x 32 k per instruction), the tile's rows the B operand, and a lane ends up with
+// four consecutive output columns of one tile row.
+// ---------------------------------------------------------------------------------------
+// Cache policy of the backward kernel's weight loads (measured on 16384 experts of 16 rows:
+// 6.3-6.8 ms from process to process with plain loads or with the first-level cache bypassed alike,
+// 7.7 ms non-temporal: the half lines a wave instruction fetches must find their line again).
+#ifndef FFNB_AUX
+#define FFNB_AUX 1
+#endif
+template <int K, int LD, int STAGES, int NB>   // NB blocks of 16 weight rows per wave, row pitch LD
+struct WeightRowsStream {
+    // A wave instruction fetches 64 bytes of each of 16 weight rows (four lanes per row), half a
+    // cache line: the stream therefore moves in steps of 64 k, the two halves of every line
+    // requested back to back, so that the second is served by the first one's fill instead of
+    // fetching the line again after a streaming load has let go of it.
+    static constexpr int NSUPER = K / 64;
+    v4u f[STAGES][NB][2];
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t lane_off;
+
+    __device__ __forceinline__ void load(int s, int jj, int k0) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            f[s][jj][u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off, (uint32_t)(16 * jj * LD + k0 + 32 * u) * 2u,
+                                                                FFNB_AUX);
+    }
+    // W: the matrix (bytes long); this wave's rows start at wrow0; lane (m, g) reads row wrow0 + 16 jj + m
+    __device__ __forceinline__ void start(const uint16_t *W, uint32_t bytes, int wrow0, int m, int g) {
+        rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(W), 0, bytes, 0x00020000);
+        lane_off = (uint32_t)((wrow0 + m) * LD + 8 * g) * 2u;
+#pragma unroll
+        for (int s = 0; s < STAGES; ++s)
+#pragma unroll
+            for (int jj = 0; jj < NB; ++jj) load(s, jj, 64 * s);
+    }
+    // acc[jj][rt] (+)= W[wrow0 + 16 jj + (0..15), 0:K] * A[16 rt + (0..15), 0:K]^T   (A bf16 in LDS, row stride lda)
+    __device__ __forceinline__ void run(v4f (&acc)[NB][4], const uint16_t *A_lds, int lda, int c, int g) {
+        const uint16_t *ap = A_lds + (size_t)c * lda + 8 * g;
+#pragma unroll
+        for (int ss = 0; ss < NSUPER; ++ss) {
+            const int s = ss % STAGES, kk = 64 * ss;
+            const bool reload = ss + STAGES < NSUPER;
+            v8bf b[2][4];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int rt = 0; rt < 4; ++rt)
+                    b[u][rt] = __builtin_bit_cast(
+                        v8bf, *reinterpret_cast<const uint4 *>(ap + (size_t)(16 * rt) * lda + kk + 32 * u));
+#pragma unroll
+            for (int j0 = 0; j0 < NB; j0 += 8) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int jj = j0; jj < j0 + 8; ++jj) {
+                        const v8bf a = __builtin_bit_cast(v8bf, f[s][jj][u]);
+#pragma unroll
+                        for (int rt = 0; rt < 4; ++rt)
+                            acc[jj][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[u][rt], acc[jj][rt], 0, 0, 0);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+                // the sixteen fragments just multiplied are refilled at once: STAGES steps to arrive
+                if (reload) {
+#pragma unroll
+                    for (int jj = j0; jj < j0 + 8; ++jj) load(s, jj, kk + 64 * STAGES);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+};
+
+#ifndef FFNB_STAGES1
+#define FFNB_STAGES1 1
+#define FFNB_STAGES2 3
+#endif
+
+template <int D, int H>
+__global__ __launch_bounds__(256) void ffn_bwd_rows_w4_kernel(FfnBwdRows p) {
+    constexpr int TM = kFfnTM;
+    constexpr int XS = D + 8, HS = H + 8;
+    static_assert(H == 4 * 256 && D == 4 * 128, "four waves: 256 hidden / 128 input columns each");
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+
+    TileCoord tc;
+    if (!load_tile(p, TM, tc)) return;
+    const int e = tc.e, row0 = tc.row0, rows = tc.rows;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const uint16_t *W1 = (const uint16_t *)p.W1 + (size_t)e * D * H;   // [D][H]: row = input column
+    const uint16_t *W2 = (const uint16_t *)p.W2 + (size_t)e * H * D;   // [H][D]: row = hidden unit
+
+    // first product: dz_pre[row, j] = sum_c dout[row, c] W2[j, c]; this wave's hidden units 256 wave ..
+    WeightRowsStream<D, D, FFNB_STAGES1, 16> s1;
+    s1.start(W2, (uint32_t)(D * H * 2), 256 * wave, c, g);
+    {
+        // the tile's dout rows (bf16, adjacent in the sorted order) into LDS; rows past the end as zeros
+        constexpr int CH = D / 8;                       // 16-byte pieces per row
+        constexpr int PASSES = TM * CH / 256, HALF = PASSES / 2;
+        static_assert(TM * CH % 512 == 0, "two equal halves of whole passes");
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb) {
+            v4u v[HALF];
+#pragma unroll
+            for (int i = 0; i < HALF; ++i) {
+                const int idx = tid + 256 * (hb * HALF + i), r = idx / CH, ch = idx % CH;
+                v[i] = MOE_STREAM_LOAD(reinterpret_cast<const v4u *>(p.dout + (size_t)(row0 + min(r, rows - 1)) * D + 8 * ch));
+            }
+#pragma unroll
+            for (int i = 0; i < HALF; ++i) {
+                const int idx = tid + 256 * (hb * HALF + i), r = idx / CH, ch = idx % CH;
+                *reinterpret_cast<v4u *>(lds + (size_t)r * XS + 8 * ch) = r < rows ? v[i] : v4u{0u, 0u, 0u, 0u};
+            }
+        }
+    }
+    __syncthreads();
+
+    WeightRowsStream<H, H, FFNB_STAGES2, 8> s2;
+    {
+        v4f acc[16][4];
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) acc[jj][rt] = v4f{0.f, 0.f, 0.f, 0.f};
+        s1.run(acc, lds, XS, c, g);
+        // second product: dxs[row, cc] = sum_j dz[row, j] W1[cc, j]; this wave's input columns 128 wave ..
+        s2.start(W1, (uint32_t)(D * H * 2), 128 * wave, c, g);
+        __syncthreads();  // the dz tile overwrites the dout tile
+        // lane (row c of block rt, g) holds hidden units 256 wave + 16 jj + 4 g + (0..3) of its row
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt)
+                *reinterpret_cast<uint2 *>(lds + (size_t)(16 * rt + c) * HS + 256 * wave + 16 * jj + 4 * g) =
+                    make_uint2(pack_bf16x2(acc[jj][rt][0], acc[jj][rt][1]), pack_bf16x2(acc[jj][rt][2], acc[jj][rt][3]));
+        __syncthreads();
+    }
+    {
+        // ReLU'(z) = [hid > 0] (hid is the ReLU's output: positive or +0), applied to whole rows as
+        // they leave for the weight-gradient kernel; the masked tile stays in LDS for the second product
+        constexpr int CH = H / 8;
+        for (int i = tid; i < rows * CH; i += 256) {
+            const int r = i / CH, ch = i % CH;
+            const v4u hv = MOE_STREAM_LOAD(reinterpret_cast<const v4u *>(p.hid + (size_t)(row0 + r) * H + 8 * ch));
+            v4u zv = *reinterpret_cast<const v4u *>(lds + (size_t)r * HS + 8 * ch);
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                zv[w] &= ((hv[w] & 0x7fffu) ? 0xffffu : 0u) | ((hv[w] & 0x7fff0000u) ? 0xffff0000u : 0u);
+            *reinterpret_cast<v4u *>(lds + (size_t)r * HS + 8 * ch) = zv;
+            *reinterpret_cast<v4u *>(p.dz + (size_t)(row0 + r) * H + 8 * ch) = zv;
+        }
+        __syncthreads();
+    }
+    {
+        v4f acc[8][4];
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) acc[cc][rt] = v4f{0.f, 0.f, 0.f, 0.f};
+        s2.run(acc, lds, HS, c, g);
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            const int row = 16 * rt + c;
+            if (row >= rows) continue;
+#pragma unroll
+            for (int cc = 0; cc < 8; ++cc)
+                store_out4(p.dxs + (size_t)(row0 + row) * D + 128 * wave + 16 * cc + 4 * g, acc[cc][rt]);
+        }
+    }
+}
+
+static_assert(kFfnBwdTileRows == kFfnTM, "the backward kernel uses the forward kernel's tile height");
+bool ffn_bwd_rows_applies(const moe_config *cfg) {
+    return cfg->expert_dtype == MOE_DTYPE_BF16 && cfg->d == 512 && cfg->h == 1024 &&
+           (int64_t)cfg->T * cfg->k <= (int64_t)cfg->n * kFfnTM;
+}
+
+int launch_ffn_bwd_rows(const FfnBwdRows &a, int64_t max_tiles, hipStream_t st) {
+    if (max_tiles <= 0) return MOE_OK;
+    static LdsLimitOnce lds_once;
+    constexpr size_t lds = (size_t)kFfnTM * (1024 + 8) * sizeof(uint16_t);
+    MOE_TRY(lds_once.set((const void *)ffn_bwd_rows_w4_kernel<512, 1024>, lds));
+    const unsigned grid = (unsigned)(ceil_div(max_tiles, 8) * 8);
+    hipLaunchKernelGGL((ffn_bwd_rows_w4_kernel<512, 1024>), dim3(grid), dim3(256), lds, st, a);
+    MOE_LAUNCH_CHECK();
+    return MOE_OK;
 }
 
 // ---------------------------------------------------------------------------------------

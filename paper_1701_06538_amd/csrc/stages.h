@@ -127,6 +127,19 @@ int launch_combine_losses(const float *out_sorted, const float *gate, const int3
                           int64_t T, int d, int k, int64_t prow, int n, double *aux_ws, float w_imp,
                           float w_load, float *importance, float *load, float *losses, hipStream_t st);
 int launch_expert_ffn(const moe_config *cfg, const FfnArgs &a, int64_t max_tiles, hipStream_t st);
+// Backward through both layers of the fused experts for routed rows, one launch (experts with about
+// one 64-row tile of rows, 512 x 1024 bf16 experts): dz = (dout W2^T) * [hid > 0], dxs = dz W1^T.
+struct FfnBwdRows {
+    const uint16_t *dout;   // [A, d] bf16, sorted rows
+    const uint16_t *hid;    // [A, h] bf16 hidden activations (the ReLU's output)
+    const void *W1, *W2;    // [n, d, h], [n, h, d] bf16
+    uint16_t *dz;           // out [A, h] bf16
+    float *dxs;             // out [A, d] fp32
+    const int32_t *offsets, *tile_expert, *tile_row0, *num_tiles;   // 64-row tile table
+};
+constexpr int kFfnBwdTileRows = 64;
+bool ffn_bwd_rows_applies(const moe_config *cfg);
+int launch_ffn_bwd_rows(const FfnBwdRows &a, int64_t max_tiles, hipStream_t st);
 int expert_ffn_with_hidden(const moe_config *cfg, const float *x, const int32_t *perm,
                            const int32_t *offsets, const int32_t *tile_expert,
                            const int32_t *tile_row0, const int32_t *num_tiles, const void *W1,
